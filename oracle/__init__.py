@@ -1,0 +1,267 @@
+"""fp64 CPU oracle for the conv-GLU + CTC training path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes marshalling around ``w2l_oracle.c`` (plain C loops, double precision)
+plus :func:`train_step`, which strings those definitions together in the order of
+the paper's training loop (Sec. 2.3: network forward, criterion, backward).
+
+Only tests, the smoke check and the bench's ``cpu_baseline`` leg may import this
+package.  It shares nothing with the HIP library and never imports it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "w2l_oracle.c")
+_LIB = os.path.join(_HERE, "libw2l_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP over independent outputs)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+    return _lib
+
+
+def _d(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def _i(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int))
+
+
+def _ll(a):
+    a = np.ascontiguousarray(a, dtype=np.int64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_longlong))
+
+
+def out_len(T: int, stride: int) -> int:
+    return (T + stride - 1) // stride
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+# ----------------------------------------------------------------------------- conv
+def conv1d_fwd(x, w, bias, stride=1):
+    """y[b,t',co] = bias[co] + sum_{j,ci} w[co,j,ci] x[b, s t' + j - p, ci]."""
+    B, T, Cin = x.shape
+    Cout, k, Cin2 = w.shape
+    assert Cin2 == Cin and k % 2 == 1
+    x, px = _d(x)
+    w, pw = _d(w)
+    pb = None
+    if bias is not None:
+        bias, pb = _d(bias)
+    y = np.empty((B, out_len(T, stride), Cout))
+    _load().orc_conv1d_fwd(px, pw, pb, y.ctypes.data_as(C.POINTER(C.c_double)),
+                           B, T, Cin, Cout, k, stride)
+    return y
+
+
+def conv1d_fwd_at(x, w, bias, idx, stride=1):
+    B, T, Cin = x.shape
+    Cout, k, _ = w.shape
+    x, px = _d(x)
+    w, pw = _d(w)
+    pb = None
+    if bias is not None:
+        bias, pb = _d(bias)
+    idx, pi = _ll(idx)
+    out = np.empty(idx.size)
+    _load().orc_conv1d_fwd_at(px, pw, pb, pi, idx.size, out.ctypes.data_as(C.POINTER(C.c_double)),
+                              B, T, Cin, Cout, k, stride)
+    return out
+
+
+def conv1d_bwd_data(dy, w, T, stride=1):
+    """dx = transpose of x -> conv(x, w) applied to dy; T is the input length."""
+    B, Tp, Cout = dy.shape
+    Cout2, k, Cin = w.shape
+    assert Cout2 == Cout and Tp == out_len(T, stride)
+    dy, pdy = _d(dy)
+    w, pw = _d(w)
+    dx = np.empty((B, T, Cin))
+    _load().orc_conv1d_bwd_data(pdy, pw, dx.ctypes.data_as(C.POINTER(C.c_double)),
+                                B, T, Cin, Cout, k, stride)
+    return dx
+
+
+def conv1d_bwd_data_at(dy, w, T, idx, stride=1):
+    B, Tp, Cout = dy.shape
+    _, k, Cin = w.shape
+    dy, pdy = _d(dy)
+    w, pw = _d(w)
+    idx, pi = _ll(idx)
+    out = np.empty(idx.size)
+    _load().orc_conv1d_bwd_data_at(pdy, pw, pi, idx.size, out.ctypes.data_as(C.POINTER(C.c_double)),
+                                   B, T, Cin, Cout, k, stride)
+    return out
+
+
+def conv1d_bwd_weight(x, dy, k, stride=1, want_dbias=True):
+    B, T, Cin = x.shape
+    B2, Tp, Cout = dy.shape
+    assert B2 == B and Tp == out_len(T, stride)
+    x, px = _d(x)
+    dy, pdy = _d(dy)
+    dw = np.empty((Cout, k, Cin))
+    db = np.empty(Cout) if want_dbias else None
+    _load().orc_conv1d_bwd_weight(px, pdy, dw.ctypes.data_as(C.POINTER(C.c_double)),
+                                  db.ctypes.data_as(C.POINTER(C.c_double)) if want_dbias else None,
+                                  B, T, Cin, Cout, k, stride)
+    return dw, db
+
+
+def conv1d_bwd_weight_at(x, dy, k, idx, stride=1):
+    B, T, Cin = x.shape
+    _, _, Cout = dy.shape
+    x, px = _d(x)
+    dy, pdy = _d(dy)
+    idx, pi = _ll(idx)
+    out = np.empty(idx.size)
+    _load().orc_conv1d_bwd_weight_at(px, pdy, pi, idx.size, out.ctypes.data_as(C.POINTER(C.c_double)),
+                                     B, T, Cin, Cout, k, stride)
+    return out
+
+
+# ----------------------------------------------------------------------------- elementwise
+def glu_fwd(y):
+    """h = y[..., :C/2] * sigmoid(y[..., C/2:])."""
+    Cout = y.shape[-1]
+    assert Cout % 2 == 0
+    y, py = _d(y)
+    h = np.empty(y.shape[:-1] + (Cout // 2,))
+    _load().orc_glu_fwd(py, h.ctypes.data_as(C.POINTER(C.c_double)),
+                        C.c_longlong(y.size // Cout), Cout)
+    return h
+
+
+def glu_bwd(y, dh):
+    Cout = y.shape[-1]
+    y, py = _d(y)
+    dh, pdh = _d(dh)
+    dy = np.empty(y.shape)
+    _load().orc_glu_bwd(py, pdh, dy.ctypes.data_as(C.POINTER(C.c_double)),
+                        C.c_longlong(y.size // Cout), Cout)
+    return dy
+
+
+def logsoftmax_fwd(z):
+    Cc = z.shape[-1]
+    z, pz = _d(z)
+    lp = np.empty(z.shape)
+    _load().orc_logsoftmax_fwd(pz, lp.ctypes.data_as(C.POINTER(C.c_double)),
+                               C.c_longlong(z.size // Cc), Cc)
+    return lp
+
+
+def logsoftmax_bwd(lp, dlp):
+    Cc = lp.shape[-1]
+    lp, plp = _d(lp)
+    dlp, pd = _d(dlp)
+    dz = np.empty(lp.shape)
+    _load().orc_logsoftmax_bwd(plp, pd, dz.ctypes.data_as(C.POINTER(C.c_double)),
+                               C.c_longlong(lp.size // Cc), Cc)
+    return dz
+
+
+# ----------------------------------------------------------------------------- CTC
+def ctc(lp, targets, in_len, tgt_len, blank=0, want_lattice=False):
+    """Per-utterance CTC loss and d(sum_b loss_b)/d lp (= -G), from log-probabilities.
+
+    Returns (loss[B], grad_lp[B,Tp,C]) and, if ``want_lattice``, also the alpha
+    and beta lattices [B,Tp,2*Lmax+1] (-inf where unused).
+    """
+    B, Tp, Cc = lp.shape
+    targets = np.asarray(targets, dtype=np.int32).reshape(B, -1)
+    Lmax = targets.shape[1]
+    if Lmax == 0:
+        targets = np.zeros((B, 1), dtype=np.int32)
+        Lmax = 1
+    lp, plp = _d(lp)
+    targets, pt = _i(targets)
+    in_len, pil = _i(in_len)
+    tgt_len, ptl = _i(tgt_len)
+    loss = np.empty(B)
+    grad = np.empty((B, Tp, Cc))
+    al = be = None
+    pal = pbe = None
+    if want_lattice:
+        al = np.empty((B, Tp, 2 * Lmax + 1))
+        be = np.empty((B, Tp, 2 * Lmax + 1))
+        pal = al.ctypes.data_as(C.POINTER(C.c_double))
+        pbe = be.ctypes.data_as(C.POINTER(C.c_double))
+    rc = _load().orc_ctc(plp, pt, pil, ptl, loss.ctypes.data_as(C.POINTER(C.c_double)),
+                         grad.ctypes.data_as(C.POINTER(C.c_double)), pal, pbe,
+                         B, Tp, Cc, Lmax, blank)
+    if rc != 0:
+        raise ValueError("invalid CTC target or length")
+    if want_lattice:
+        return loss, grad, al, be
+    return loss, grad
+
+
+def ctc_from_logits(z, targets, in_len, tgt_len, blank=0, grad_scale=1.0):
+    """log-softmax then CTC; returns (loss[B], lp, d(grad_scale * sum_b loss_b)/dz)."""
+    lp = logsoftmax_fwd(z)
+    loss, dlp = ctc(lp, targets, in_len, tgt_len, blank)
+    dz = logsoftmax_bwd(lp, dlp) * grad_scale
+    return loss, lp, dz
+
+
+# ----------------------------------------------------------------------------- train step
+def train_step(layers, weights, biases, x, in_len, targets, tgt_len, grad_scale=1.0, blank=0,
+               keep_activations=False):
+    """Forward + backward of the conv-GLU network with the CTC criterion.
+
+    ``layers`` is a list of dicts {k, stride, cin, cout, glu}.  ``in_len`` counts
+    valid input frames per utterance (frames beyond it are expected to be zero in
+    ``x``); the criterion sees ceil(in_len / total stride) frames.  Returns a dict
+    with loss[B], logits, lp, dlogits, dw (list), db (list) and optionally the
+    per-layer activations.  Gradients are those of grad_scale * sum_b loss_b.
+    """
+    h = np.asarray(x, dtype=np.float64)
+    saved_in, saved_pre = [], []
+    tot_stride = 1
+    for L, w, b in zip(layers, weights, biases):
+        saved_in.append(h)
+        y = conv1d_fwd(h, w, b, L["stride"])
+        saved_pre.append(y)
+        h = glu_fwd(y) if L["glu"] else y
+        tot_stride *= L["stride"]
+    logits = h
+    crit_len = np.array([out_len(int(n), tot_stride) for n in in_len], dtype=np.int32)
+    loss, lp, dz = ctc_from_logits(logits, targets, crit_len, tgt_len, blank, grad_scale)
+    dws, dbs = [None] * len(layers), [None] * len(layers)
+    dh = dz
+    for i in range(len(layers) - 1, -1, -1):
+        L = layers[i]
+        dy = glu_bwd(saved_pre[i], dh) if L["glu"] else dh
+        dws[i], dbs[i] = conv1d_bwd_weight(saved_in[i], dy, L["k"], L["stride"])
+        if i > 0:
+            dh = conv1d_bwd_data(dy, weights[i], saved_in[i].shape[1], L["stride"])
+    out = dict(loss=loss, logits=logits, lp=lp, dlogits=dz, dw=dws, db=dbs, crit_len=crit_len)
+    if keep_activations:
+        out["inputs"] = saved_in
+        out["pre"] = saved_pre
+    return out
