@@ -1,0 +1,173 @@
+/*
+ * w2l.h -- C ABI of libw2l: the forward/backward training step of the paper's
+ * all-convolutional grapheme acoustic model with the CTC criterion, as HIP kernels
+ * for gfx950 (MI355X), one GPU.
+ *
+ * The paper (wav2letter++) splits every model into a *network* -- a function of
+ * the input only -- and a *criterion* -- a function of the network output and the
+ * target transcription (Sec. 2.3).  Here the network is a stack of 1-D temporal
+ * convolutions (Sec. 2.3, Sec. 4.1) with bias and gated linear units followed by a
+ * per-frame log-softmax, and the criterion is CTC (Sec. 2.3).  The paper names
+ * these operations without printing formulas; the exact arithmetic and layout
+ * conventions are stated on each entry point below.
+ *
+ * Conventions common to every call
+ *  - All tensor pointers are DEVICE pointers owned by the caller, dense,
+ *    row-major ("channels last": x[b][t][c]) and 16-byte aligned.  The library
+ *    never allocates or frees device memory; scratch space comes from the
+ *    caller's `workspace` (device pointer, 256-byte aligned) whose minimum size
+ *    the matching *_workspace_bytes() query returns.  Inputs are never modified.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *    enqueue work and return; they never synchronise with the host.  Outputs,
+ *    including losses, stay on the device.
+ *  - dtype: W2L_F32 or W2L_BF16 (bf16 = upper 16 bits of an IEEE float,
+ *    round-to-nearest-even on store).  Accumulation is always fp32; bias, weight
+ *    gradients, bias gradients, log-probabilities, losses and CTC gradients are
+ *    always fp32.
+ *  - Every function returns W2L_OK (0) or a negative w2l_status.  Arguments are
+ *    validated on the host before anything is launched; on error nothing is
+ *    launched.  The library never throws, aborts or prints.
+ *  - Time: T input frames, stride s >= 1, odd kernel width k, symmetric zero
+ *    padding p = (k-1)/2, output frames T' = ceil(T/s).
+ */
+#ifndef W2L_H
+#define W2L_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    W2L_OK = 0,
+    W2L_ERR_NULL = -1,      /* a required pointer is NULL */
+    W2L_ERR_SHAPE = -2,     /* non-positive size, even k, odd Cout with GLU, size over a limit */
+    W2L_ERR_DTYPE = -3,     /* unknown or unsupported dtype combination */
+    W2L_ERR_ALIGN = -4,     /* a pointer is not 16-byte aligned */
+    W2L_ERR_WORKSPACE = -5, /* workspace NULL or smaller than *_workspace_bytes() */
+    W2L_ERR_TARGET = -6,    /* (host validation helper) bad label or length */
+    W2L_ERR_LAUNCH = -7     /* HIP reported an error; see w2l_last_hip_error() */
+} w2l_status;
+
+typedef enum { W2L_F32 = 0, W2L_BF16 = 1 } w2l_dtype;
+
+/* One network layer: conv1d(k, stride, cin -> cout) + bias, then GLU if glu != 0
+ * (which halves the channel count seen by the next layer). */
+typedef struct {
+    int k, stride, cin, cout, glu;
+} w2l_layer;
+
+int w2l_version(void);
+const char *w2l_status_str(int status);
+/* hipError_t value of the most recent failed HIP call made by this library (0 if none). */
+int w2l_last_hip_error(void);
+
+/* ---- temporal convolution (Sec. 2.3 "1D convolutions"; Sec. 4.1) ------------------
+ * Cross-correlation:
+ *   y[b,t',co] = bias[co] + sum_{j<k} sum_{ci<Cin} w[co,j,ci] * x[b, s*t' + j - p, ci]
+ * with x = 0 outside 0 <= t < T.   x: [B,T,Cin] (dtype);  w: [Cout,k,Cin] (dtype);
+ * bias: [Cout] fp32 or NULL;  y: [B,T',Cout] (y_dtype; W2L_F32 is allowed with bf16
+ * operands, e.g. for logits).  workspace may be NULL when the query returns 0. */
+size_t w2l_conv1d_fwd_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype);
+int w2l_conv1d_fwd(const void *x, const void *w, const float *bias, void *y,
+                   int B, int T, int Cin, int Cout, int k, int stride,
+                   int dtype, int y_dtype, void *workspace, size_t ws_bytes, void *stream);
+
+/* Gradient with respect to the input (transpose of x -> y):
+ *   dx[b,t,ci] = sum_j sum_co w[co,j,ci] * dy[b,(t+p-j)/s,co]
+ * over taps j with (t+p-j) divisible by s and 0 <= (t+p-j)/s < T'.
+ * dy: [B,T',Cout] (dy_dtype);  w: [Cout,k,Cin] (dtype);  dx: [B,T,Cin] (dtype). */
+size_t w2l_conv1d_bwd_data_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype);
+int w2l_conv1d_bwd_data(const void *dy, const void *w, void *dx,
+                        int B, int T, int Cin, int Cout, int k, int stride,
+                        int dtype, int dy_dtype, void *workspace, size_t ws_bytes, void *stream);
+
+/* Gradient with respect to weights and bias (transpose of w -> y):
+ *   dw[co,j,ci] = sum_b sum_t' dy[b,t',co] * x[b, s*t' + j - p, ci]
+ *   dbias[co]   = sum_b sum_t' dy[b,t',co]
+ * x: [B,T,Cin] (dtype);  dy: [B,T',Cout] (dy_dtype);  dw: [Cout,k,Cin] fp32;
+ * dbias: [Cout] fp32 or NULL.  accumulate = 0 overwrites dw/dbias, 1 adds to them.
+ * Reductions run in a fixed order: results are bit-reproducible run to run. */
+size_t w2l_conv1d_bwd_weight_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype);
+int w2l_conv1d_bwd_weight(const void *x, const void *dy, float *dw, float *dbias,
+                          int B, int T, int Cin, int Cout, int k, int stride,
+                          int dtype, int dy_dtype, int accumulate,
+                          void *workspace, size_t ws_bytes, void *stream);
+
+/* ---- gated linear unit (the gated convnet of Sec. 4.1) -----------------------------
+ * y: [rows,Cout], Cout even.  Value half a = y[:, :Cout/2], gate half g = y[:, Cout/2:].
+ *   fwd:  h = a * sigmoid(g)                          h: [rows,Cout/2]
+ *   bwd:  dy[:, :Cout/2] = dh * sigmoid(g)
+ *         dy[:, Cout/2:] = dh * a * sigmoid(g) * (1 - sigmoid(g))
+ * All tensors share `dtype`; the arithmetic is fp32. */
+int w2l_glu_fwd(const void *y, void *h, long long rows, int Cout, int dtype, void *stream);
+int w2l_glu_bwd(const void *y, const void *dh, void *dy, long long rows, int Cout, int dtype,
+                void *stream);
+
+/* ---- per-frame log-softmax (normalised scores for the criterion, Sec. 2.3) ---------
+ *   fwd:  lp[r,c] = z[r,c] - max_c z[r,:] - log sum_c exp(z[r,c] - max_c z[r,:])
+ *   bwd:  dz[r,c] = dlp[r,c] - exp(lp[r,c]) * sum_c dlp[r,:]
+ * z: [rows,C] (z_dtype);  lp, dlp, dz: [rows,C] fp32.  1 <= C <= 4096. */
+int w2l_logsoftmax_fwd(const void *z, float *lp, long long rows, int C, int z_dtype, void *stream);
+int w2l_logsoftmax_bwd(const float *lp, const float *dlp, float *dz, long long rows, int C,
+                       void *stream);
+
+/* ---- CTC criterion (Sec. 2.3, after Graves et al. 2006) ---------------------------
+ * For utterance b with T_b = in_len[b] valid frames and target l (L_b = tgt_len[b]
+ * labels), over the extended sequence l' = (blank, l_1, blank, ..., l_L, blank):
+ *   loss[b] = -log sum over all frame labellings that collapse to l of
+ *             prod_{t<T_b} exp(lp[b,t,pi_t])            (natural log)
+ * computed with the log-space alpha/beta recursions, and
+ *   G[b,t,c] = posterior probability that frame t carries class c given l.
+ * in:  input [B,Tp,C] fp32 -- log-probabilities (is_logits = 0) or unnormalised
+ *      logits (is_logits = 1: a log-softmax is applied inside);
+ *      targets [B,Lmax] int32 (row b uses its first tgt_len[b] entries),
+ *      in_len [B] int32 (0..Tp), tgt_len [B] int32 (0..Lmax); blank in [0,C).
+ * out: loss [B] fp32;  grad [B,Tp,C] fp32 = grad_scale * d(sum_b loss_b)/d input, i.e.
+ *      -grad_scale*G (is_logits = 0) or grad_scale*(softmax - G) (is_logits = 1);
+ *      rows t >= in_len[b] are 0.
+ * An utterance with no valid alignment gets loss +inf and zero gradient.  A label
+ * equal to blank or outside [0,C), or a length outside its range, cannot be
+ * reported by an asynchronous call: that utterance gets loss NaN and zero
+ * gradient (w2l_ctc_check_targets_host() validates host copies beforehand).
+ * Limits: C <= 4096, Lmax <= 4000. */
+size_t w2l_ctc_workspace_bytes(int B, int Tp, int C, int Lmax);
+int w2l_ctc_fwd_bwd(const float *input, int is_logits, const int *targets, const int *in_len,
+                    const int *tgt_len, float *loss, float *grad,
+                    int B, int Tp, int C, int Lmax, int blank, float grad_scale,
+                    void *workspace, size_t ws_bytes, void *stream);
+/* HOST pointers.  Returns W2L_ERR_TARGET for a label == blank or outside [0,C),
+ * in_len outside [0,Tp] or tgt_len outside [0,Lmax]. */
+int w2l_ctc_check_targets_host(const int *targets, const int *in_len, const int *tgt_len,
+                               int B, int Tp, int C, int Lmax, int blank);
+
+/* ---- one training step: network forward, criterion, backward (Sec. 2.3, Sec. 4.1) --
+ * layers[0..n_layers): layer i maps [B,T_i,cin_i] to [B,ceil(T_i/stride_i),cout_i or
+ * cout_i/2]; cin_0 is the feature dimension, cin_{i+1} must equal layer i's output
+ * channels and the last layer's output channels are the C classes (last layer: glu = 0).
+ * x: [B,T,cin_0] (dtype), frames t >= in_len[b] must be zero (the network runs on the
+ * padded batch; no re-masking between layers).  The criterion sees
+ * ceil(in_len[b] / prod_i stride_i) frames of utterance b.
+ * weights[i]: [cout,k,cin] (dtype);  biases[i]: [cout] fp32 (NULL entry = no bias);
+ * dweights[i]: [cout,k,cin] fp32, dbiases[i]: [cout] fp32 (NULL entry = not wanted);
+ * both are overwritten with the gradient of grad_scale * sum_b loss[b].
+ * loss: [B] fp32.  logits (nullable): [B,T_last,C] fp32 copy of the network output.
+ * The four pointer tables are HOST arrays of DEVICE pointers; x, in_len, targets,
+ * tgt_len, loss, logits are device pointers.  With W2L_BF16, activations and
+ * gradients between layers are stored as bf16, the last layer's output (logits), the
+ * log-softmax and CTC are fp32. */
+size_t w2l_train_step_workspace_bytes(const w2l_layer *layers, int n_layers, int B, int T,
+                                      int Lmax, int dtype);
+int w2l_train_step(const w2l_layer *layers, int n_layers,
+                   const void *const *weights, const float *const *biases,
+                   float *const *dweights, float *const *dbiases,
+                   const void *x, const int *in_len, const int *targets, const int *tgt_len,
+                   float *loss, float *logits,
+                   int B, int T, int Lmax, int blank, int dtype, float grad_scale,
+                   void *workspace, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W2L_H */

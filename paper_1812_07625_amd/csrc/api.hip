@@ -1,0 +1,119 @@
+// C-ABI entry points for the temporal convolution and the library's bookkeeping calls.
+// Argument checks happen here, on the host, before any launch; the kernels assume
+// the shapes they are given.
+#include "common.h"
+
+namespace w2l {
+static thread_local int g_last_hip_error = 0;
+void note_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+}  // namespace w2l
+
+using namespace w2l;
+
+extern "C" int w2l_version(void) { return 100; }
+
+extern "C" int w2l_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" const char* w2l_status_str(int s)
+{
+    switch (s) {
+        case W2L_OK: return "ok";
+        case W2L_ERR_NULL: return "null pointer";
+        case W2L_ERR_SHAPE: return "bad shape";
+        case W2L_ERR_DTYPE: return "bad dtype";
+        case W2L_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case W2L_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case W2L_ERR_TARGET: return "bad target label or length";
+        case W2L_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+namespace {
+int check_conv_shape(int B, int T, int Cin, int Cout, int k, int s)
+{
+    if (B <= 0 || T <= 0 || Cin <= 0 || Cout <= 0 || k <= 0 || s <= 0) return W2L_ERR_SHAPE;
+    if ((k & 1) == 0) return W2L_ERR_SHAPE;
+    if ((long long)B * T > (1LL << 30) || (long long)k * Cin > (1LL << 30) || (long long)k * Cout > (1LL << 30))
+        return W2L_ERR_SHAPE;
+    return W2L_OK;
+}
+bool ws_ok(void* ws, size_t have, size_t need)
+{
+    if (need == 0) return true;
+    return ws && have >= need && (reinterpret_cast<uintptr_t>(ws) & 255u) == 0;
+}
+}  // namespace
+
+extern "C" size_t w2l_conv1d_fwd_workspace_bytes(int, int, int, int, int, int, int) { return 0; }
+
+extern "C" int w2l_conv1d_fwd(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin,
+                              int Cout, int k, int stride, int dtype, int y_dtype, void* workspace,
+                              size_t ws_bytes, void* stream)
+{
+    if (!x || !w || !y) return W2L_ERR_NULL;
+    int rc = check_conv_shape(B, T, Cin, Cout, k, stride);
+    if (rc) return rc;
+    if (!valid_dtype(dtype) || !valid_dtype(y_dtype) || (dtype == W2L_F32 && y_dtype != W2L_F32))
+        return W2L_ERR_DTYPE;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || (bias && !aligned16(bias))) return W2L_ERR_ALIGN;
+    if (!ws_ok(workspace, ws_bytes, w2l_conv1d_fwd_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
+        return W2L_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == W2L_BF16 && conv_fwd_mfma_ok(B, T, Cin, Cout, k, stride))
+        return conv_fwd_mfma(x, w, bias, y, B, T, Cin, Cout, k, stride, y_dtype, st);
+    return conv_fwd_generic(x, w, bias, y, B, T, Cin, Cout, k, stride, dtype, y_dtype, st);
+}
+
+extern "C" size_t w2l_conv1d_bwd_data_workspace_bytes(int, int, int, int, int, int, int) { return 0; }
+
+extern "C" int w2l_conv1d_bwd_data(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout,
+                                   int k, int stride, int dtype, int dy_dtype, void* workspace, size_t ws_bytes,
+                                   void* stream)
+{
+    if (!dy || !w || !dx) return W2L_ERR_NULL;
+    int rc = check_conv_shape(B, T, Cin, Cout, k, stride);
+    if (rc) return rc;
+    if (!valid_dtype(dtype) || !valid_dtype(dy_dtype) || (dtype == W2L_F32 && dy_dtype != W2L_F32))
+        return W2L_ERR_DTYPE;
+    if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return W2L_ERR_ALIGN;
+    if (!ws_ok(workspace, ws_bytes, w2l_conv1d_bwd_data_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
+        return W2L_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == W2L_BF16 && dy_dtype == W2L_BF16 && conv_dgrad_mfma_ok(B, T, Cin, Cout, k, stride))
+        return conv_dgrad_mfma(dy, w, dx, B, T, Cin, Cout, k, stride, st);
+    return conv_dgrad_generic(dy, w, dx, B, T, Cin, Cout, k, stride, dtype, dy_dtype, st);
+}
+
+extern "C" size_t w2l_conv1d_bwd_weight_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride,
+                                                        int dtype)
+{
+    (void)dtype;
+    if (B <= 0 || T <= 0 || Cin <= 0 || Cout <= 0 || k <= 0 || stride <= 0) return 0;
+    return round_up((size_t)DBIAS_CHUNKS * Cout * 4, 256) + conv_wgrad_mfma_workspace(B, T, Cin, Cout, k, stride);
+}
+
+extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, float* dbias, int B, int T,
+                                     int Cin, int Cout, int k, int stride, int dtype, int dy_dtype,
+                                     int accumulate, void* workspace, size_t ws_bytes, void* stream)
+{
+    if (!x || !dy || !dw) return W2L_ERR_NULL;
+    int rc = check_conv_shape(B, T, Cin, Cout, k, stride);
+    if (rc) return rc;
+    if (!valid_dtype(dtype) || !valid_dtype(dy_dtype) || (dtype == W2L_F32 && dy_dtype != W2L_F32))
+        return W2L_ERR_DTYPE;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || (dbias && !aligned16(dbias))) return W2L_ERR_ALIGN;
+    if (!ws_ok(workspace, ws_bytes, w2l_conv1d_bwd_weight_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
+        return W2L_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int Tp = out_len(T, stride);
+    float* scratch = static_cast<float*>(workspace);
+    void* ws2 = static_cast<unsigned char*>(workspace) + round_up((size_t)DBIAS_CHUNKS * Cout * 4, 256);
+    if (dbias) {
+        rc = dbias_reduce(dy, dbias, (long long)B * Tp, Cout, dy_dtype, accumulate, scratch, st);
+        if (rc) return rc;
+    }
+    if (dtype == W2L_BF16 && dy_dtype == W2L_BF16 && conv_wgrad_mfma_ok(B, T, Cin, Cout, k, stride))
+        return conv_wgrad_mfma(x, dy, dw, B, T, Cin, Cout, k, stride, accumulate, ws2, st);
+    return conv_wgrad_generic(x, dy, dw, B, T, Cin, Cout, k, stride, dtype, dy_dtype, accumulate, st);
+}

@@ -1,0 +1,257 @@
+// Shape-agnostic temporal-convolution kernels (fp32 or bf16 operands, fp32 accumulation).
+//
+// These back every shape the MFMA kernels do not take (fp32 tensors, channel counts
+// that are not multiples of 8, strided data gradients).  Each of the three passes is
+// the GEMM C[m,n] = sum_r A(m,r) * B(r,n) over a 64x64 output tile per workgroup,
+// 16-deep LDS panels, 4x4 outputs per thread; the operand functors fold the
+// convolution's indexing (tap offset, stride, zero padding) into the loads, so no
+// unfolded copy of the input is ever made.
+//
+// Definitions (the paper names the op in Sec. 2.3 without a formula):
+//   fwd   y[b,t',co]  = bias[co] + sum_{j,ci} w[co,j,ci] * x[b, s t' + j - p, ci]
+//   dgrad dx[b,t,ci]  = sum_{j,co} w[co,j,ci] * dy[b,(t+p-j)/s,co]   (divisible, in range)
+//   wgrad dw[co,j,ci] = sum_{b,t'} dy[b,t',co] * x[b, s t' + j - p, ci]
+#include "common.h"
+
+namespace w2l {
+namespace {
+
+constexpr int TM = 64, TN = 64, TK = 16;
+
+template <class AF, class BF, class EP, bool A_RFAST, bool B_RFAST>
+__global__ __launch_bounds__(256) void gemm_tiled(AF af, BF bf, EP ep, int M, int N, int R)
+{
+    __shared__ float As[TK][TM + 1];
+    __shared__ float Bs[TK][TN + 1];
+    const int tid = threadIdx.x;
+    const int tx = tid % 16, ty = tid / 16;
+    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+    for (int r0 = 0; r0 < R; r0 += TK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + i * 256;
+            int rr, mm;
+            if (A_RFAST) { rr = e % TK; mm = e / TK; } else { mm = e % TM; rr = e / TM; }
+            const int m = m0 + mm, r = r0 + rr;
+            As[rr][mm] = (m < M && r < R) ? af(m, r) : 0.f;
+            int nn;
+            if (B_RFAST) { rr = e % TK; nn = e / TK; } else { nn = e % TN; rr = e / TN; }
+            const int n = n0 + nn;
+            const int r2 = r0 + rr;
+            Bs[rr][nn] = (n < N && r2 < R) ? bf(r2, n) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int rr = 0; rr < TK; ++rr) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[rr][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[rr][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (m < M && n < N) ep(m, n, acc[i][j]);
+        }
+}
+
+// ---- operand functors ------------------------------------------------------------
+template <typename T>
+struct XWindow {  // A(m=(b,t'), r=(j,ci)) = x[b, s t' + j - p, ci]
+    const T* x; int T_, Tp, Cin, s, p;
+    __device__ float operator()(int m, int r) const {
+        const int b = m / Tp, tp = m - b * Tp;
+        const int j = r / Cin, ci = r - j * Cin;
+        const int t = s * tp + j - p;
+        if (t < 0 || t >= T_) return 0.f;
+        return Elem<T>::load(x, ((size_t)b * T_ + t) * Cin + ci);
+    }
+};
+template <typename T>
+struct WRows {  // B(r=(j,ci), n=co) = w[co, j, ci]
+    const T* w; int KC;
+    __device__ float operator()(int r, int n) const { return Elem<T>::load(w, (size_t)n * KC + r); }
+};
+template <typename T>
+struct DyWindow {  // A(m=(b,t), r=(j,co)) = dy[b, (t+p-j)/s, co]
+    const T* dy; int T_, Tp, Cout, s, p;
+    __device__ float operator()(int m, int r) const {
+        const int b = m / T_, t = m - b * T_;
+        const int j = r / Cout, co = r - j * Cout;
+        const int u = t + p - j;
+        if (u < 0) return 0.f;
+        const int tp = u / s;
+        if (tp * s != u || tp >= Tp) return 0.f;
+        return Elem<T>::load(dy, ((size_t)b * Tp + tp) * Cout + co);
+    }
+};
+template <typename T>
+struct WCols {  // B(r=(j,co), n=ci) = w[co, j, ci]
+    const T* w; int Cin, Cout, k;
+    __device__ float operator()(int r, int n) const {
+        const int j = r / Cout, co = r - j * Cout;
+        return Elem<T>::load(w, ((size_t)co * k + j) * Cin + n);
+    }
+};
+template <typename T>
+struct DyT {  // A(m=co, r=(b,t')) = dy[b,t',co]
+    const T* dy; int Cout;
+    __device__ float operator()(int m, int r) const { return Elem<T>::load(dy, (size_t)r * Cout + m); }
+};
+template <typename T>
+struct XShift {  // B(r=(b,t'), n=(j,ci)) = x[b, s t' + j - p, ci]
+    const T* x; int T_, Tp, Cin, s, p;
+    __device__ float operator()(int r, int n) const {
+        const int b = r / Tp, tp = r - b * Tp;
+        const int j = n / Cin, ci = n - j * Cin;
+        const int t = s * tp + j - p;
+        if (t < 0 || t >= T_) return 0.f;
+        return Elem<T>::load(x, ((size_t)b * T_ + t) * Cin + ci);
+    }
+};
+template <typename T>
+struct StoreBias {
+    T* y; const float* bias; int N;
+    __device__ void operator()(int m, int n, float v) const {
+        Elem<T>::store(y, (size_t)m * N + n, v + (bias ? bias[n] : 0.f));
+    }
+};
+struct StoreAcc {
+    float* d; int N; int accumulate;
+    __device__ void operator()(int m, int n, float v) const {
+        const size_t i = (size_t)m * N + n;
+        d[i] = accumulate ? d[i] + v : v;
+    }
+};
+
+template <class AF, class BF, class EP, bool AR, bool BR>
+int launch(AF af, BF bf, EP ep, long long M, long long N, long long R, hipStream_t st)
+{
+    const long long gy = (M + TM - 1) / TM, gx = (N + TN - 1) / TN;
+    if (gy > 65535 || gx > 2147483647LL || M * 1 > 2147483647LL || R > 2147483647LL) return W2L_ERR_SHAPE;
+    hipLaunchKernelGGL((gemm_tiled<AF, BF, EP, AR, BR>), dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st,
+                       af, bf, ep, (int)M, (int)N, (int)R);
+    return launch_status();
+}
+
+template <typename TI, typename TO>
+int fwd_t(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin, int Cout, int k,
+          int s, hipStream_t st)
+{
+    const int Tp = out_len(T, s), p = (k - 1) / 2;
+    XWindow<TI> af{(const TI*)x, T, Tp, Cin, s, p};
+    WRows<TI> bf{(const TI*)w, k * Cin};
+    StoreBias<TO> ep{(TO*)y, bias, Cout};
+    return launch<XWindow<TI>, WRows<TI>, StoreBias<TO>, true, true>(af, bf, ep, (long long)B * Tp, Cout,
+                                                                      (long long)k * Cin, st);
+}
+template <typename TW, typename TDY>
+int dgrad_t(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout, int k, int s,
+            hipStream_t st)
+{
+    const int Tp = out_len(T, s), p = (k - 1) / 2;
+    DyWindow<TDY> af{(const TDY*)dy, T, Tp, Cout, s, p};
+    WCols<TW> bf{(const TW*)w, Cin, Cout, k};
+    StoreBias<TW> ep{(TW*)dx, nullptr, Cin};
+    return launch<DyWindow<TDY>, WCols<TW>, StoreBias<TW>, true, false>(af, bf, ep, (long long)B * T, Cin,
+                                                                         (long long)k * Cout, st);
+}
+template <typename TX, typename TDY>
+int wgrad_t(const void* x, const void* dy, float* dw, int B, int T, int Cin, int Cout, int k, int s,
+            int accumulate, hipStream_t st)
+{
+    const int Tp = out_len(T, s), p = (k - 1) / 2;
+    DyT<TDY> af{(const TDY*)dy, Cout};
+    XShift<TX> bf{(const TX*)x, T, Tp, Cin, s, p};
+    StoreAcc ep{dw, k * Cin, accumulate};
+    return launch<DyT<TDY>, XShift<TX>, StoreAcc, false, false>(af, bf, ep, Cout, (long long)k * Cin,
+                                                                 (long long)B * Tp, st);
+}
+
+// ---- dbias: deterministic two-stage column sum -------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_stage1(const T* dy, float* part, long long rows, int Cout)
+{
+    // block: 64 columns x 4 row lanes; grid.y = row chunks
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int rl = threadIdx.x >> 6;
+    const long long per = (rows + gridDim.y - 1) / gridDim.y;
+    const long long r0 = per * blockIdx.y, r1 = (r0 + per < rows) ? r0 + per : rows;
+    float acc = 0.f;
+    if (c < Cout)
+        for (long long r = r0 + rl; r < r1; r += 4) acc += Elem<T>::load(dy, (size_t)r * Cout + c);
+    __shared__ float sm[4][64];
+    sm[rl][threadIdx.x & 63] = acc;
+    __syncthreads();
+    if (rl == 0 && c < Cout)
+        part[(size_t)blockIdx.y * Cout + c] = (sm[0][threadIdx.x] + sm[1][threadIdx.x]) +
+                                              (sm[2][threadIdx.x] + sm[3][threadIdx.x]);
+}
+__global__ void colsum_stage2(const float* part, float* dbias, int chunks, int Cout, int accumulate)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= Cout) return;
+    float acc = 0.f;
+    for (int i = 0; i < chunks; ++i) acc += part[(size_t)i * Cout + c];
+    dbias[c] = accumulate ? dbias[c] + acc : acc;
+}
+
+}  // namespace
+
+int conv_fwd_generic(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin,
+                     int Cout, int k, int s, int dt, int ydt, hipStream_t st)
+{
+    if (dt == W2L_F32 && ydt == W2L_F32) return fwd_t<float, float>(x, w, bias, y, B, T, Cin, Cout, k, s, st);
+    if (dt == W2L_BF16 && ydt == W2L_BF16) return fwd_t<bf16_t, bf16_t>(x, w, bias, y, B, T, Cin, Cout, k, s, st);
+    if (dt == W2L_BF16 && ydt == W2L_F32) return fwd_t<bf16_t, float>(x, w, bias, y, B, T, Cin, Cout, k, s, st);
+    return W2L_ERR_DTYPE;
+}
+int conv_dgrad_generic(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout, int k,
+                       int s, int dt, int dydt, hipStream_t st)
+{
+    if (dt == W2L_F32 && dydt == W2L_F32) return dgrad_t<float, float>(dy, w, dx, B, T, Cin, Cout, k, s, st);
+    if (dt == W2L_BF16 && dydt == W2L_BF16) return dgrad_t<bf16_t, bf16_t>(dy, w, dx, B, T, Cin, Cout, k, s, st);
+    if (dt == W2L_BF16 && dydt == W2L_F32) return dgrad_t<bf16_t, float>(dy, w, dx, B, T, Cin, Cout, k, s, st);
+    return W2L_ERR_DTYPE;
+}
+int conv_wgrad_generic(const void* x, const void* dy, float* dw, int B, int T, int Cin, int Cout, int k,
+                       int s, int dt, int dydt, int accumulate, hipStream_t st)
+{
+    if (dt == W2L_F32 && dydt == W2L_F32) return wgrad_t<float, float>(x, dy, dw, B, T, Cin, Cout, k, s, accumulate, st);
+    if (dt == W2L_BF16 && dydt == W2L_BF16) return wgrad_t<bf16_t, bf16_t>(x, dy, dw, B, T, Cin, Cout, k, s, accumulate, st);
+    if (dt == W2L_BF16 && dydt == W2L_F32) return wgrad_t<bf16_t, float>(x, dy, dw, B, T, Cin, Cout, k, s, accumulate, st);
+    return W2L_ERR_DTYPE;
+}
+int dbias_reduce(const void* dy, float* dbias, long long rows, int Cout, int dydt, int accumulate,
+                 float* scratch, hipStream_t st)
+{
+    const dim3 g1((Cout + 63) / 64, DBIAS_CHUNKS);
+    if (dydt == W2L_F32)
+        hipLaunchKernelGGL(colsum_stage1<float>, g1, dim3(256), 0, st, (const float*)dy, scratch, rows, Cout);
+    else if (dydt == W2L_BF16)
+        hipLaunchKernelGGL(colsum_stage1<bf16_t>, g1, dim3(256), 0, st, (const bf16_t*)dy, scratch, rows, Cout);
+    else
+        return W2L_ERR_DTYPE;
+    int rc = launch_status();
+    if (rc) return rc;
+    hipLaunchKernelGGL(colsum_stage2, dim3((Cout + 255) / 256), dim3(256), 0, st, scratch, dbias,
+                       (int)DBIAS_CHUNKS, Cout, accumulate);
+    return launch_status();
+}
+
+}  // namespace w2l

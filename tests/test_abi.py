@@ -1,0 +1,95 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol that
+include/w2l.h declares, and rejects bad arguments on the host before launching anything."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_1812_07625_amd", "libw2l.so")
+
+
+def declared_symbols():
+    src = open(os.path.join(ROOT, "include", "w2l.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(w2l_[a-z0-9_]+)\s*\(", src)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.fail("libw2l.so is not built: run `python -m paper_1812_07625_amd.build`")
+    return C.CDLL(LIB)
+
+
+def test_exports_every_declared_symbol(lib):
+    names = declared_symbols()
+    assert len(names) >= 18
+    for n in names:
+        assert hasattr(lib, n), "missing export %s" % n
+
+
+def test_binding_names_match_header():
+    import paper_1812_07625_amd as P
+    for n in declared_symbols():
+        assert hasattr(P, n), "binding lacks %s" % n
+
+
+def test_status_strings(lib):
+    lib.w2l_status_str.restype = C.c_char_p
+    seen = set()
+    for s in range(0, -8, -1):
+        seen.add(lib.w2l_status_str(s))
+    assert len(seen) == 8
+    assert lib.w2l_version() >= 100
+
+
+def test_host_side_argument_checks():
+    import paper_1812_07625_amd as P
+    r = P.raw
+    NULL, OK = None, 0
+    fake = 0x1000  # never dereferenced: checks fail before any launch
+    assert r.w2l_conv1d_fwd(NULL, fake, NULL, fake, 1, 8, 8, 8, 3, 1, 0, 0, NULL, 0, NULL) == -1
+    assert r.w2l_conv1d_fwd(fake, fake, NULL, fake, 1, 8, 8, 8, 4, 1, 0, 0, NULL, 0, NULL) == -2  # even k
+    assert r.w2l_conv1d_fwd(fake, fake, NULL, fake, 0, 8, 8, 8, 3, 1, 0, 0, NULL, 0, NULL) == -2
+    assert r.w2l_conv1d_fwd(fake, fake, NULL, fake, 1, 8, 8, 8, 3, 0, 0, 0, NULL, 0, NULL) == -2
+    assert r.w2l_conv1d_fwd(fake, fake, NULL, fake, 1, 8, 8, 8, 3, 1, 7, 0, NULL, 0, NULL) == -3
+    assert r.w2l_conv1d_fwd(fake, fake, NULL, fake, 1, 8, 8, 8, 3, 1, 0, 1, NULL, 0, NULL) == -3  # f32 in, bf16 out
+    assert r.w2l_conv1d_fwd(fake + 4, fake, NULL, fake, 1, 8, 8, 8, 3, 1, 0, 0, NULL, 0, NULL) == -4
+    assert r.w2l_conv1d_bwd_data(fake, NULL, fake, 1, 8, 8, 8, 3, 1, 0, 0, NULL, 0, NULL) == -1
+    assert r.w2l_conv1d_bwd_weight(fake, fake, fake, NULL, 1, 8, 8, 8, 3, 1, 0, 0, 0, NULL, 0, NULL) == -5
+    assert r.w2l_conv1d_bwd_weight_workspace_bytes(1, 8, 8, 8, 3, 1, 0) > 0
+    assert r.w2l_glu_fwd(fake, fake, 4, 7, 0, NULL) == -2  # odd channel count
+    assert r.w2l_glu_bwd(fake, NULL, fake, 4, 8, 0, NULL) == -1
+    assert r.w2l_logsoftmax_fwd(fake, fake, 4, 5000, 0, NULL) == -2
+    assert r.w2l_logsoftmax_bwd(fake, fake, fake, 0, 5, NULL) == -2
+    assert r.w2l_ctc_fwd_bwd(fake, 0, fake, fake, fake, fake, fake, 2, 10, 5, 3, 5, 1.0, fake, 1 << 30, NULL) == -2
+    assert r.w2l_ctc_fwd_bwd(fake, 0, fake, fake, fake, fake, fake, 2, 10, 5, 3, 0, 1.0, NULL, 0, NULL) == -5
+    assert r.w2l_ctc_fwd_bwd(fake, 0, fake, fake, fake, fake, fake, 2, 10, 5, 3, 0, 1.0, 0x1100, 16, NULL) == -5
+    assert r.w2l_ctc_workspace_bytes(2, 10, 5, 3) >= 2 * 2 * 10 * 7 * 8
+
+
+def test_ctc_host_validation():
+    import paper_1812_07625_amd as P
+    t = np.array([[1, 2, 3], [4, 4, 0]], np.int32)
+    assert P.w2l_ctc_check_targets_host(t, [10, 10], [3, 2], 10, 5) == 0
+    assert P.w2l_ctc_check_targets_host(t, [10, 10], [3, 3], 10, 5) == -6   # label 0 = blank
+    assert P.w2l_ctc_check_targets_host(t, [10, 11], [3, 2], 10, 5) == -6   # in_len > Tp
+    assert P.w2l_ctc_check_targets_host(t, [10, 10], [4, 2], 10, 5) == -6   # tgt_len > Lmax
+    assert P.w2l_ctc_check_targets_host(t, [10, 10], [3, 2], 10, 4) == -6   # label >= C
+
+
+def test_train_step_plan_checks():
+    import paper_1812_07625_amd as P
+    import workloads as W
+    lay = W.layers_105m()
+    n = P.w2l_train_step_workspace_bytes(lay, 8, 1500, 150, P.W2L_BF16)
+    assert n > 8 * 750 * 1536 * 2 * 9
+    bad = [dict(l) for l in lay]
+    bad[3]["cin"] = 700   # does not match the previous layer's output channels
+    assert P.w2l_train_step_workspace_bytes(bad, 8, 1500, 150, P.W2L_BF16) == 0
+    bad = [dict(l) for l in lay]
+    bad[-1]["glu"] = 1
+    assert P.w2l_train_step_workspace_bytes(bad, 8, 1500, 150, P.W2L_BF16) == 0

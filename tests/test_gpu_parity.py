@@ -1,0 +1,269 @@
+"""GPU-vs-oracle parity, element by element, on identical seeded inputs, through the C ABI.
+
+Tolerances (written here, derived from the arithmetic):
+  * bf16 tensors (conv outputs and gradients): relative L2 error <= 2e-2
+  * fp32 conv / GLU / log-softmax: relative L2 error <= 1e-5
+  * CTC: per-utterance relative loss error <= 1e-4, gradient relative L2 <= 1e-4
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+from gpu_util import DEV, empty, rel_l2, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+TOL_CTC = 1e-4
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_1812_07625_amd as P
+    return P
+
+
+def _grid(a, dtype):
+    a = a.astype(np.float32)
+    return W.round_to_bf16(a) if dtype == "bf16" else a
+
+
+CONV_SHAPES = [
+    # B, T, Cin, Cout, k, s
+    (2, 100, 40, 128, 5, 1),
+    (3, 70, 24, 72, 11, 1),      # ragged against 64-wide tiles
+    (2, 131, 40, 64, 13, 2),     # strided, odd T
+    (1, 37, 7, 5, 3, 3),         # odd channel counts, stride 3
+    (2, 64, 64, 29, 1, 1),       # 1x1 onto the class dimension
+    (4, 257, 128, 256, 11, 1),   # several tiles in every dimension, ragged tail in M
+    (2, 300, 80, 192, 13, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_three_passes(P, shape, dtype):
+    B, T, Cin, Cout, k, s = shape
+    rng = np.random.default_rng(hash(shape) % 2**31)
+    Tp = oracle.out_len(T, s)
+    x = _grid(rng.standard_normal((B, T, Cin)), dtype)
+    w = _grid(rng.standard_normal((Cout, k, Cin)) / np.sqrt(k * Cin), dtype)
+    bias = rng.standard_normal(Cout).astype(np.float32)
+    dy = _grid(rng.standard_normal((B, Tp, Cout)), dtype)
+
+    xd, wd, bd, dyd = to_dev(x, dtype), to_dev(w, dtype), to_dev(bias), to_dev(dy, dtype)
+    y = P.w2l_conv1d_fwd(xd, wd, bd, empty((B, Tp, Cout), dtype), s)
+    assert rel_l2(to_host(y), oracle.conv1d_fwd(x, w, bias, s)) <= TOL[dtype]
+    y0 = P.w2l_conv1d_fwd(xd, wd, None, empty((B, Tp, Cout), dtype), s)
+    assert rel_l2(to_host(y0), oracle.conv1d_fwd(x, w, None, s)) <= TOL[dtype]
+
+    dx = P.w2l_conv1d_bwd_data(dyd, wd, empty((B, T, Cin), dtype), s)
+    assert rel_l2(to_host(dx), oracle.conv1d_bwd_data(dy, w, T, s)) <= TOL[dtype]
+
+    ws = P.workspace(P.w2l_conv1d_bwd_weight_workspace_bytes(B, T, Cin, Cout, k, s, P.W2L_BF16 if dtype == "bf16" else 0))
+    dw, db = P.w2l_conv1d_bwd_weight(xd, dyd, empty((Cout, k, Cin)), empty((Cout,)), s, False, ws)
+    dw_o, db_o = oracle.conv1d_bwd_weight(x, dy, k, s)
+    tol_w = 1e-5 if dtype == "f32" else 1e-4  # operands are exact on both sides; only the fp32 summation differs
+    assert rel_l2(to_host(dw), dw_o) <= tol_w
+    assert rel_l2(to_host(db), db_o) <= tol_w
+    # accumulate = 1 adds onto what is there; run twice -> bit-identical (fixed reduction order)
+    dw2 = dw.clone()
+    db2 = db.clone()
+    P.w2l_conv1d_bwd_weight(xd, dyd, dw2, db2, s, True, ws)
+    assert rel_l2(to_host(dw2), 2 * dw_o) <= tol_w
+    assert rel_l2(to_host(db2), 2 * db_o) <= tol_w
+    dw3, db3 = P.w2l_conv1d_bwd_weight(xd, dyd, empty((Cout, k, Cin)), empty((Cout,)), s, False, ws)
+    assert torch.equal(dw3, dw) and torch.equal(db3, db)
+
+
+def test_conv_mixed_output_dtypes(P):
+    # bf16 operands with fp32 y (logits) and fp32 dy (gradient of the logits)
+    B, T, Cin, Cout, k, s = 2, 90, 64, 29, 1, 1
+    rng = np.random.default_rng(77)
+    x = _grid(rng.standard_normal((B, T, Cin)), "bf16")
+    w = _grid(rng.standard_normal((Cout, k, Cin)) / 8, "bf16")
+    dy = rng.standard_normal((B, T, Cout)).astype(np.float32)
+    xd, wd, dyd = to_dev(x, "bf16"), to_dev(w, "bf16"), to_dev(dy)
+    y = P.w2l_conv1d_fwd(xd, wd, None, empty((B, T, Cout)), s)
+    assert rel_l2(to_host(y), oracle.conv1d_fwd(x, w, None, s)) <= 1e-5
+    dx = P.w2l_conv1d_bwd_data(dyd, wd, empty((B, T, Cin), "bf16"), s)
+    assert rel_l2(to_host(dx), oracle.conv1d_bwd_data(dy, w, T, s)) <= TOL["bf16"]
+    ws = P.workspace(P.w2l_conv1d_bwd_weight_workspace_bytes(B, T, Cin, Cout, k, s, 1))
+    dw, db = P.w2l_conv1d_bwd_weight(xd, dyd, empty((Cout, k, Cin)), empty((Cout,)), s, False, ws)
+    dw_o, db_o = oracle.conv1d_bwd_weight(x, dy, k, s)
+    assert rel_l2(to_host(dw), dw_o) <= 1e-5 and rel_l2(to_host(db), db_o) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,Cout", [(200, 128), (77, 1536), (33, 30), (5, 2), (1000, 2048)])
+def test_glu(P, rows, Cout, dtype):
+    rng = np.random.default_rng(rows + Cout)
+    y = _grid(rng.standard_normal((rows, Cout)) * 2, dtype)
+    dh = _grid(rng.standard_normal((rows, Cout // 2)), dtype)
+    h = P.w2l_glu_fwd(to_dev(y, dtype), empty((rows, Cout // 2), dtype))
+    tol = 1e-5 if dtype == "f32" else 4e-3   # one bf16 rounding of the result: <= 2^-9 per element
+    assert rel_l2(to_host(h), oracle.glu_fwd(y)) <= tol
+    dy = P.w2l_glu_bwd(to_dev(y, dtype), to_dev(dh, dtype), empty((rows, Cout), dtype))
+    assert rel_l2(to_host(dy), oracle.glu_bwd(y, dh)) <= tol
+
+
+@pytest.mark.parametrize("rows,Cc", [(24000, 29), (100, 1), (37, 100), (9, 4096)])
+def test_logsoftmax(P, rows, Cc):
+    rng = np.random.default_rng(rows)
+    z = (rng.standard_normal((rows, Cc)) * 3).astype(np.float32)
+    dlp = rng.standard_normal((rows, Cc)).astype(np.float32)
+    lp = P.w2l_logsoftmax_fwd(to_dev(z), empty((rows, Cc)))
+    lp_o = oracle.logsoftmax_fwd(z)
+    assert rel_l2(to_host(lp), lp_o) <= 1e-5 if Cc > 1 else np.all(to_host(lp) == 0)
+    dz = P.w2l_logsoftmax_bwd(lp, to_dev(dlp), empty((rows, Cc)))
+    ref = oracle.logsoftmax_bwd(to_host(lp), dlp)
+    assert np.linalg.norm(to_host(dz) - ref) <= 1e-5 * max(np.linalg.norm(ref), 1.0)
+    zb = W.round_to_bf16(z)
+    lpb = P.w2l_logsoftmax_fwd(to_dev(zb, "bf16"), empty((rows, Cc)))
+    assert np.linalg.norm(to_host(lpb) - oracle.logsoftmax_fwd(zb)) <= 1e-5 * max(np.linalg.norm(lp_o), 1.0)
+
+
+def _run_ctc(P, inp, is_logits, targets, in_len, tgt_len, blank=0, scale=1.0):
+    B, Tp, Cc = inp.shape
+    Lmax = targets.shape[1]
+    ws = P.workspace(P.w2l_ctc_workspace_bytes(B, Tp, Cc, Lmax))
+    loss, grad = P.w2l_ctc_fwd_bwd(to_dev(inp), is_logits, to_dev(targets), to_dev(in_len), to_dev(tgt_len),
+                                   empty((B,)), empty((B, Tp, Cc)), blank, scale, ws)
+    torch.cuda.synchronize()
+    return loss.cpu().numpy().astype(np.float64), grad.cpu().numpy().astype(np.float64)
+
+
+def _check_ctc(loss, grad, loss_o, grad_o):
+    fin = np.isfinite(loss_o)
+    assert np.array_equal(np.isfinite(loss), fin)
+    assert np.all(np.abs(loss[fin] - loss_o[fin]) <= TOL_CTC * np.abs(loss_o[fin]))
+    assert np.all(loss[~fin] == loss_o[~fin])
+    assert np.all(np.isfinite(grad))
+    for b in range(len(loss)):
+        den = np.linalg.norm(grad_o[b])
+        err = np.linalg.norm(grad[b] - grad_o[b])
+        assert err <= TOL_CTC * den if den > 0 else err == 0, (b, err, den)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(B=4, T=60, in_lo=40, in_hi=60, l_lo=3, l_hi=15),
+    dict(B=6, T=200, in_lo=150, in_hi=200, l_lo=30, l_hi=70),     # S spans > 1 wavefront
+    dict(B=3, T=97, in_lo=1, in_hi=97, l_lo=0, l_hi=1, Cc=5),
+    dict(),                                                         # the full benchmark shape
+])
+def test_ctc_from_logits(P, kw):
+    cfg = W.config2(seed=2, **kw)
+    loss, grad = _run_ctc(P, cfg["logits"], 1, cfg["targets"], cfg["in_len"], cfg["tgt_len"], 0, 1.0)
+    loss_o, _, dz_o = oracle.ctc_from_logits(cfg["logits"].astype(np.float64), cfg["targets"], cfg["in_len"],
+                                             cfg["tgt_len"])
+    _check_ctc(loss, grad, loss_o, dz_o)
+    for b in range(cfg["B"]):
+        assert np.all(grad[b, cfg["in_len"][b]:] == 0)
+
+
+def test_ctc_from_logprobs_scale_blank_and_edges(P):
+    rng = np.random.default_rng(9)
+    B, Tp, Cc, Lmax = 7, 50, 6, 8
+    z = rng.standard_normal((B, Tp, Cc)) * 1.5
+    lp = oracle.logsoftmax_fwd(z).astype(np.float32)
+    blank = 2
+    tg = rng.integers(0, 2, size=(B, Lmax)).astype(np.int32)  # classes {0,1}: many adjacent repeats
+    tg[3] = [3, 4, 5, 3, 4, 5, 3, 4]
+    in_len = np.array([50, 31, 0, 8, 50, 9, 1], np.int32)
+    tgt_len = np.array([8, 5, 0, 8, 0, 8, 1], np.int32)   # b=2: T=0,L=0 ; b=3: T=L ; b=5: likely infeasible
+    loss, grad = _run_ctc(P, lp, 0, tg, in_len, tgt_len, blank, 0.25)
+    loss_o, g_o = oracle.ctc(lp.astype(np.float64), tg, in_len, tgt_len, blank)
+    assert np.isinf(loss_o[5])
+    _check_ctc(loss, grad, loss_o, 0.25 * g_o)
+
+
+def test_ctc_bad_label_gives_nan_loss_and_zero_grad(P):
+    cfg = W.config2(seed=5, B=3, T=40, in_lo=30, in_hi=40, l_lo=3, l_hi=6)
+    tg = cfg["targets"].copy()
+    tg[1, 0] = 0          # blank inside a target
+    loss, grad = _run_ctc(P, cfg["logits"], 1, tg, cfg["in_len"], cfg["tgt_len"])
+    assert np.isnan(loss[1]) and np.all(grad[1] == 0)
+    assert np.isfinite(loss[0]) and np.isfinite(loss[2]) and np.all(np.isfinite(grad))
+    il = cfg["in_len"].copy()
+    il[2] = 41            # longer than the padded length
+    loss, grad = _run_ctc(P, cfg["logits"], 1, cfg["targets"], il, cfg["tgt_len"])
+    assert np.isnan(loss[2]) and np.all(grad[2] == 0) and np.isfinite(loss[0])
+
+
+def test_ctc_is_deterministic(P):
+    cfg = W.config2(seed=6, B=4, T=120, in_lo=100, in_hi=120, l_lo=10, l_hi=40)
+    a = _run_ctc(P, cfg["logits"], 1, cfg["targets"], cfg["in_len"], cfg["tgt_len"])
+    b = _run_ctc(P, cfg["logits"], 1, cfg["targets"], cfg["in_len"], cfg["tgt_len"])
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+# ----------------------------------------------------------------------------- train step
+def run_train_step(P, cfg, grad_scale=1.0, want_logits=True):
+    dt = cfg["dtype"]
+    layers = cfg["layers"]
+    B, T = cfg["B"], cfg["T"]
+    xd = to_dev(cfg["x"], dt)
+    wd = [to_dev(w, dt) for w in cfg["weights"]]
+    bd = [to_dev(b) for b in cfg["biases"]]
+    dwd = [empty(w.shape) for w in cfg["weights"]]
+    dbd = [empty(b.shape) for b in cfg["biases"]]
+    tg, il, tl = to_dev(cfg["targets"]), to_dev(cfg["in_len"]), to_dev(cfg["tgt_len"])
+    Lmax = cfg["targets"].shape[1]
+    code = P.W2L_BF16 if dt == "bf16" else P.W2L_F32
+    ws = P.workspace(P.w2l_train_step_workspace_bytes(layers, B, T, Lmax, code))
+    loss = empty((B,))
+    Tl = T
+    for L in layers:
+        Tl = oracle.out_len(Tl, L["stride"])
+    logits = empty((B, Tl, layers[-1]["cout"])) if want_logits else None
+    P.w2l_train_step(layers, wd, bd, dwd, dbd, xd, il, tg, tl, loss, logits, cfg["blank"], grad_scale, ws)
+    torch.cuda.synchronize()
+    return dict(loss=to_host(loss), logits=to_host(logits) if want_logits else None,
+                dw=[to_host(t) for t in dwd], db=[to_host(t) for t in dbd])
+
+
+def oracle_train_step(cfg, grad_scale=1.0):
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    return oracle.train_step(cfg["layers"], [f64(w) for w in cfg["weights"]], [f64(b) for b in cfg["biases"]],
+                             f64(cfg["x"]), cfg["in_len"], cfg["targets"], cfg["tgt_len"], grad_scale,
+                             cfg["blank"])
+
+
+def check_train_step(got, ref, dtype):
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    assert np.all(np.abs(got["loss"] - ref["loss"]) <= (1e-4 if dtype == "f32" else 2e-2) * np.abs(ref["loss"]))
+    assert rel_l2(got["logits"], ref["logits"]) <= tol
+    for i, (a, b) in enumerate(zip(got["dw"], ref["dw"])):
+        assert rel_l2(a, b) <= tol, "dw of layer %d" % i
+    for i, (a, b) in enumerate(zip(got["db"], ref["db"])):
+        assert rel_l2(a, b) <= tol, "db of layer %d" % i
+
+
+def test_train_step_tiny_fp32(P):
+    cfg = W.config0()
+    check_train_step(run_train_step(P, cfg), oracle_train_step(cfg), "f32")
+    cfg = W.config0(seed=10, zero_bias=False)
+    check_train_step(run_train_step(P, cfg, 0.5), oracle_train_step(cfg, 0.5), "f32")
+
+
+def test_train_step_small_bf16_ragged(P):
+    layers = [dict(k=7, stride=2, cin=40, cout=96, glu=1), dict(k=5, stride=1, cin=48, cout=128, glu=1),
+              dict(k=3, stride=1, cin=64, cout=80, glu=1), dict(k=1, stride=1, cin=40, cout=29, glu=0)]
+    cfg = W.small_model(21, 5, 90, 171, 40, layers, True, 4, 20)
+    check_train_step(run_train_step(P, cfg), oracle_train_step(cfg), "bf16")
+
+
+def test_train_step_10m_model_reduced_batch(P):
+    # the ~10M-parameter bf16 configuration with the batch cut to 4 so the fp64 oracle takes seconds
+    cfg = W.config3(B=4)
+    check_train_step(run_train_step(P, cfg), oracle_train_step(cfg), "bf16")
+
+
+def test_train_step_is_deterministic(P):
+    cfg = W.config0(seed=3)
+    a, b = run_train_step(P, cfg), run_train_step(P, cfg)
+    assert np.array_equal(a["loss"], b["loss"])
+    for u, v in zip(a["dw"] + a["db"], b["dw"] + b["db"]):
+        assert np.array_equal(u, v)
