@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the conv-GLU + CTC training step on one MI355X.
+
+One "step" = one full forward + criterion + backward pass (w2l_train_step) of the
+~105M-parameter bf16 model over one synthetic batch (B=8, T_b ~ U[1000,1500] padded to
+1500, 80-dim features; seed 4), inputs resident in HBM before the timed region.
+Prints ONE JSON line: training frames/s (valid input frames per second), ms/step, the
+roofline of the dominant kernel measured live with events on the launch stream, and the
+fp64 CPU oracle timed on the host cores on a bounded sample (a baseline, not the target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA = 2.5e15   # dense bf16 MFMA, FLOP/s (MI355X published)
+PEAK_HBM = 8.0e12         # B/s
+
+
+def event_time_ms(fn, iters, warmup=2):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-iters", type=int, default=20)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_1812_07625_amd as P
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import to_dev, empty
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = W.config4()
+    layers, B, T = cfg["layers"], cfg["B"], cfg["T"]
+    xd = to_dev(cfg["x"], "bf16")
+    wd = [to_dev(w, "bf16") for w in cfg["weights"]]
+    bd = [to_dev(b) for b in cfg["biases"]]
+    dwd = [empty(w.shape) for w in cfg["weights"]]
+    dbd = [empty(b.shape) for b in cfg["biases"]]
+    tg, il, tl = to_dev(cfg["targets"]), to_dev(cfg["in_len"]), to_dev(cfg["tgt_len"])
+    Lmax = cfg["targets"].shape[1]
+    ws = P.workspace(P.w2l_train_step_workspace_bytes(layers, B, T, Lmax, P.W2L_BF16))
+    loss = empty((B,))
+
+    def step():
+        P.w2l_train_step(layers, wd, bd, dwd, dbd, xd, il, tg, tl, loss, None, 0, 1.0, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    lv = loss.cpu().numpy()
+    assert np.all(np.isfinite(lv)), "non-finite loss in the benchmark step"
+
+    frames = int(cfg["in_len"].sum())
+    flops = W.step_flops(layers, B, T)
+
+    # ---- per-kernel roofline at the body-layer shape (k=11, 768 -> 1536, M = B*T' = 6000)
+    L = layers[1]
+    Tp = (T + layers[0]["stride"] - 1) // layers[0]["stride"]
+    rng = np.random.default_rng(0)
+    hx = to_dev(W.round_to_bf16(rng.standard_normal((B, Tp, L["cin"])).astype(np.float32)), "bf16")
+    hdy = to_dev(W.round_to_bf16(rng.standard_normal((B, Tp, L["cout"])).astype(np.float32)), "bf16")
+    hy = empty((B, Tp, L["cout"]), "bf16")
+    hdx = empty((B, Tp, L["cin"]), "bf16")
+    hdw = empty(cfg["weights"][1].shape)
+    wws = P.workspace(P.w2l_conv1d_bwd_weight_workspace_bytes(B, Tp, L["cin"], L["cout"], L["k"], 1, 1))
+    gf = 2.0 * B * Tp * L["k"] * L["cin"] * L["cout"]
+    kern = {}
+    kern["conv1d_fwd"] = event_time_ms(lambda: P.w2l_conv1d_fwd(hx, wd[1], bd[1], hy, 1), args.kernel_iters)
+    kern["conv1d_bwd_data"] = event_time_ms(lambda: P.w2l_conv1d_bwd_data(hdy, wd[1], hdx, 1), args.kernel_iters)
+    kern["conv1d_bwd_weight"] = event_time_ms(
+        lambda: P.w2l_conv1d_bwd_weight(hx, hdy, hdw, None, 1, False, wws), args.kernel_iters)
+    dom = max(kern, key=kern.get)
+    achieved = gf / (kern[dom] * 1e-3)
+
+    # bandwidth-bound kernels at the same layer's shape
+    rows = B * Tp
+    hh = empty((rows, L["cout"] // 2), "bf16")
+    t_glu = event_time_ms(lambda: P.w2l_glu_fwd(hy, hh), args.kernel_iters)
+    glu_bytes = rows * L["cout"] * 2 + rows * (L["cout"] // 2) * 2
+    hdh = to_dev(W.round_to_bf16(rng.standard_normal((rows, L["cout"] // 2)).astype(np.float32)), "bf16")
+    hdy2 = empty((rows, L["cout"]), "bf16")
+    P.w2l_conv1d_fwd(hx, wd[1], bd[1], hy, 1)
+    t_glub = event_time_ms(lambda: P.w2l_glu_bwd(hy, hdh, hdy2), args.kernel_iters)
+    glub_bytes = rows * L["cout"] * 2 * 2 + rows * (L["cout"] // 2) * 2
+
+    # CTC alone at the criterion benchmark shape (B=32, T=750, C=29)
+    c2 = W.config2()
+    cz, ct, ci, cl = to_dev(c2["logits"]), to_dev(c2["targets"]), to_dev(c2["in_len"]), to_dev(c2["tgt_len"])
+    cws = P.workspace(P.w2l_ctc_workspace_bytes(32, 750, 29, c2["targets"].shape[1]))
+    closs, cgrad = empty((32,)), empty((32, 750, 29))
+    t_ctc = event_time_ms(lambda: P.w2l_ctc_fwd_bwd(cz, 1, ct, ci, cl, closs, cgrad, 0, 1.0, cws),
+                          args.kernel_iters)
+    cells = int(np.sum(c2["in_len"].astype(np.int64) * (2 * c2["tgt_len"].astype(np.int64) + 1)))
+    ctc_bytes = 2 * 32 * 750 * 29 * 4 + 2 * 4 * cells
+
+    out = {
+        "metric": "training frames/sec (fwd+bwd) for 105M conv-GLU CTC model",
+        "value": frames / dt,
+        "unit": "frames/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "config4: 105M-param conv-GLU CTC model, B=8, T_b~U[1000,1500] padded to 1500, "
+                        "80-dim features, seed 4; full fwd+criterion+bwd step",
+            "params": W.num_params(layers),
+            "valid_frames_per_step": frames,
+            "padded_frames_per_step": B * T,
+            "gflop_per_step": flops / 1e9,
+        },
+        "padded_frames_per_s": B * T / dt,
+        "step_tflops": flops / dt / 1e12,
+        "step_frac_of_bf16_mfma_peak": flops / dt / PEAK_BF16_MFMA,
+        "roofline": {
+            "bound": "mfma",
+            "kernel": dom + " (k=11, 768->1536, B*T'=6000)",
+            "achieved": achieved / 1e12,
+            "peak": PEAK_BF16_MFMA / 1e12,
+            "unit": "TFLOP/s",
+            "frac": achieved / PEAK_BF16_MFMA,
+            "traffic": None,
+            "avg_launch_ms": kern[dom],
+        },
+        "kernels": {
+            **{k: {"ms": v, "tflops": gf / (v * 1e-3) / 1e12, "frac_mfma_peak": gf / (v * 1e-3) / PEAK_BF16_MFMA}
+               for k, v in kern.items()},
+            "glu_fwd": {"ms": t_glu, "GBps": glu_bytes / (t_glu * 1e-3) / 1e9,
+                        "frac_hbm_peak": glu_bytes / (t_glu * 1e-3) / PEAK_HBM},
+            "glu_bwd": {"ms": t_glub, "GBps": glub_bytes / (t_glub * 1e-3) / 1e9,
+                        "frac_hbm_peak": glub_bytes / (t_glub * 1e-3) / PEAK_HBM},
+            "ctc_fwd_bwd(config2)": {"ms": t_ctc, "GBps": ctc_bytes / (t_ctc * 1e-3) / 1e9,
+                                     "frac_hbm_peak": ctc_bytes / (t_ctc * 1e-3) / PEAK_HBM,
+                                     "serial_steps": int(c2["in_len"].max()),
+                                     "us_per_serial_step": t_ctc * 1e3 / int(c2["in_len"].max())},
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        f64 = lambda a: np.asarray(a, dtype=np.float64)
+        b0 = 0
+        t1 = time.perf_counter()
+        oracle.train_step(layers, [f64(w) for w in cfg["weights"]], [f64(b) for b in cfg["biases"]],
+                          f64(cfg["x"][b0:b0 + 1]), cfg["in_len"][b0:b0 + 1], cfg["targets"][b0:b0 + 1],
+                          cfg["tgt_len"][b0:b0 + 1])
+        t_cpu = time.perf_counter() - t1
+        out["cpu_baseline"] = {
+            "value": float(cfg["in_len"][b0]) / t_cpu,
+            "unit": "frames/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "one utterance (b=0, %d valid frames, padded to %d) of the same batch through the same "
+                      "11 layers, fp64 oracle train step, %.1f s" % (int(cfg["in_len"][b0]), T, t_cpu),
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
