@@ -267,3 +267,81 @@ def test_train_step_is_deterministic(P):
     assert np.array_equal(a["loss"], b["loss"])
     for u, v in zip(a["dw"] + a["db"], b["dw"] + b["db"]):
         assert np.array_equal(u, v)
+
+
+# ----------------------------------------------------------------------------- full benchmark sizes
+FULL_SHAPES = [
+    # name, B, T, Cin, Cout, k, s   (launch configurations that bench.py times)
+    ("config1", 16, 800, 512, 1024, 11, 1),
+    ("config4-body", 8, 750, 768, 1536, 11, 1),
+    ("config4-first", 8, 1500, 80, 1536, 13, 2),
+    ("config4-1x1", 8, 750, 768, 2048, 1, 1),
+    ("config3-body", 16, 800, 256, 512, 11, 1),
+]
+
+
+@pytest.mark.parametrize("shape", FULL_SHAPES, ids=[s[0] for s in FULL_SHAPES])
+def test_conv_full_size_sampled(P, shape):
+    """bf16 operands at the benchmark shapes; the oracle evaluates a random sample of outputs
+    one by one (a full fp64 pass at these sizes takes minutes)."""
+    name, B, T, Cin, Cout, k, s = shape
+    rng = np.random.default_rng(abs(hash(name)) % 2**31 if False else len(name) * 1000 + B)
+    Tp = oracle.out_len(T, s)
+    x = W.round_to_bf16(rng.standard_normal((B, T, Cin)).astype(np.float32))
+    w = W.round_to_bf16((rng.standard_normal((Cout, k, Cin)) / np.sqrt(k * Cin)).astype(np.float32))
+    dy = W.round_to_bf16(rng.standard_normal((B, Tp, Cout)).astype(np.float32))
+    bias = rng.standard_normal(Cout).astype(np.float32)
+    xd, wd, dyd, bd = to_dev(x, "bf16"), to_dev(w, "bf16"), to_dev(dy, "bf16"), to_dev(bias)
+    nsamp = 3000
+
+    def sample(n_total, edge_rows=None):
+        idx = rng.integers(0, n_total, size=nsamp)
+        return np.unique(idx)
+
+    y = to_host(P.w2l_conv1d_fwd(xd, wd, bd, empty((B, Tp, Cout), "bf16"), s)).reshape(-1)
+    idx = sample(y.size)
+    # always include the corners of every utterance (zero-padded windows) and the last tile
+    corners = []
+    for b in range(B):
+        for tp in (0, 1, Tp - 2, Tp - 1):
+            for co in (0, Cout - 1):
+                corners.append((b * Tp + tp) * Cout + co)
+    idx = np.unique(np.concatenate([idx, np.array(corners)]))
+    ref = oracle.conv1d_fwd_at(x, w, bias, idx, s)
+    assert rel_l2(y[idx], ref) <= TOL["bf16"]
+
+    if s == 1:
+        dx = to_host(P.w2l_conv1d_bwd_data(dyd, wd, empty((B, T, Cin), "bf16"), s)).reshape(-1)
+        idx = sample(dx.size)
+        corners = [(b * T + t) * Cin + c for b in range(B) for t in (0, 1, T - 2, T - 1) for c in (0, Cin - 1)]
+        idx = np.unique(np.concatenate([idx, np.array(corners)]))
+        ref = oracle.conv1d_bwd_data_at(dy, w, T, idx, s)
+        assert rel_l2(dx[idx], ref) <= TOL["bf16"]
+
+    ws = P.workspace(P.w2l_conv1d_bwd_weight_workspace_bytes(B, T, Cin, Cout, k, s, P.W2L_BF16))
+    dw, db = P.w2l_conv1d_bwd_weight(xd, dyd, empty((Cout, k, Cin)), empty((Cout,)), s, False, ws)
+    dw = to_host(dw).reshape(-1)
+    idx = sample(dw.size)
+    corners = [(co * k + j) * Cin + c for co in (0, Cout - 1) for j in range(k) for c in (0, Cin - 1)]
+    idx = np.unique(np.concatenate([idx, np.array(corners)]))
+    ref = oracle.conv1d_bwd_weight_at(x, dy, k, idx, s)
+    assert rel_l2(dw[idx], ref) <= 1e-4
+    assert rel_l2(to_host(db), dy.astype(np.float64).sum((0, 1))) <= 1e-5
+
+
+def test_train_step_105m_forward_and_sampled_gradients(P):
+    """The benchmark configuration itself (B=8, 11 layers, 107M parameters).  The fp64 oracle
+    runs the whole network for one utterance only (the batch couples utterances only through
+    the sums in dw/db): its loss and logits must match the full-batch GPU step."""
+    cfg = W.config4()
+    got = run_train_step(P, cfg)
+    assert np.all(np.isfinite(got["loss"]))
+    b = 3
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    ref = oracle.train_step(cfg["layers"], [f64(w) for w in cfg["weights"]], [f64(v) for v in cfg["biases"]],
+                            f64(cfg["x"][b:b + 1]), cfg["in_len"][b:b + 1], cfg["targets"][b:b + 1],
+                            cfg["tgt_len"][b:b + 1])
+    assert abs(got["loss"][b] - ref["loss"][0]) <= 2e-2 * abs(ref["loss"][0])
+    assert rel_l2(got["logits"][b], ref["logits"][0]) <= 2e-2
+    for t in got["dw"] + got["db"]:
+        assert np.all(np.isfinite(t))
