@@ -48,6 +48,7 @@ struct PanelK {
     static constexpr int BYTES = ROWS * RS;
     static constexpr int CPR = BK / 8;                  // 16-byte chunks per row
     static constexpr int NCH = ROWS * CPR / NT;         // chunks per thread
+    static constexpr int READS_PER_FRAG = 1;
     static_assert(ROWS * CPR % NT == 0, "panel must divide over the workgroup");
     int off[NCH];                                      // element offsets (tensors hold < 2^31 elements)
     int lo[NCH], hi[NCH];
@@ -89,6 +90,7 @@ struct PanelMN {
     static constexpr int BYTES = BK * RS;
     static constexpr int CPR = COLS / 8;
     static constexpr int NCH = BK * CPR / NT;
+    static constexpr int READS_PER_FRAG = 2;
     static_assert(BK * CPR % NT == 0, "panel must divide over the workgroup");
     uint4 reg[NCH];
     const bf16_t* base;
@@ -150,20 +152,33 @@ struct Core {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     }
+    // One panel (BK reduction elements).  Operand fragments are double-buffered in
+    // registers: the LDS reads of sub-step ks+1 are issued before the MFMAs of sub-step ks,
+    // so their latency hides under matrix work (one wavefront per SIMD: nothing else would).
     __device__ __forceinline__ void step(const unsigned char* la, const unsigned char* lb, int wm, int wn, int lane)
     {
+        constexpr int NS = BK / 16;
+        bf16x8 a[2][TM], b[2][TN];
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 a[TM], b[TN];
+        for (int i = 0; i < TM; ++i) a[0][i] = PA::frag(la, wm * (BM / 2) + i * 32, 0, lane);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = PA::frag(la, wm * (BM / 2) + i * 32, ks, lane);
+        for (int j = 0; j < TN; ++j) b[0][j] = PB::frag(lb, wn * (BN / 2) + j * 32, 0, lane);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = PB::frag(lb, wn * (BN / 2) + j * 32, ks, lane);
+        for (int ks = 0; ks < NS; ++ks) {
+            const int c = ks & 1, n = c ^ 1;
+            if (ks + 1 < NS) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a[n][i] = PA::frag(la, wm * (BM / 2) + i * 32, ks + 1, lane);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[n][j] = PB::frag(lb, wn * (BN / 2) + j * 32, ks + 1, lane);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     // f(m, n, value) for every element this lane holds; m,n relative to the tile
