@@ -11,14 +11,22 @@
 //   wgrad  m=co      n=(j,ci)  r=(b,t')   A = dy (m-contiguous)         B = x window (n-contiguous)
 //
 // One workgroup = 4 wavefronts (2x2) computes a BM x BN tile; each wavefront owns a
-// (BM/2)x(BN/2) sub-tile of 32x32 MFMA blocks held in registers.  Operand panels of
-// BK reduction steps are fetched global -> registers -> LDS (double buffered, one
-// barrier per step).  r-contiguous panels are stored [row][BK] with a 16-byte row pad
-// and read with one 16-byte LDS read per MFMA operand; m/n-contiguous panels are
-// stored [BK][row] and read through the LDS transpose read (ds_read_b64_tr_b16), which
-// hands each lane the 4 consecutive reduction elements of its row.  Zero padding at
-// the utterance edges, ragged tiles and the reduction tail are all handled by
-// predicating the 16-byte global loads; stores are predicated on the tile bounds.
+// (BM/2)x(BN/2) sub-tile of 32x32 MFMA blocks held in accumulation registers.
+//
+// Data movement.  Operand panels of BKT reduction elements go global -> LDS directly
+// (global_load_lds_dwordx4: no staging registers, no LDS store instructions) into a ring
+// of STAGES panels, so the loads of panel st+STAGES-1 are in flight while panel st is
+// multiplied; one barrier per panel.  Each load instruction fills 1 KB of LDS (lane i ->
+// bytes 16i..16i+15), so the LDS image is dense; bank conflicts are avoided by an XOR
+// swizzle of the 16-byte chunk index within each row, applied on the global-address
+// side when loading and on the LDS-address side when reading.  r-contiguous panels are
+// stored [row][BKT] and read with one 16-byte LDS read per MFMA operand; m/n-contiguous
+// panels are stored [BKT][row] and read through the LDS transpose read
+// (ds_read_b64_tr_b16), which hands each lane the 4 consecutive reduction elements of
+// its row.  Zero padding at the utterance edges, ragged tiles and the reduction tail
+// are handled by pointing the load of an out-of-range chunk at a 16-byte block of
+// zeros (every lane always loads: the number of loads in flight is a constant, which
+// the hand-placed s_waitcnt counts rely on); stores are predicated on the tile bounds.
 #include "common.h"
 
 namespace w2l {
@@ -29,106 +37,124 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
-constexpr int NT = 256;       // threads per workgroup
-constexpr int BK = 64;        // reduction elements per panel
-constexpr int KPAD = 16;      // bytes of padding per r-contiguous LDS row
-constexpr int MNPAD = 64;     // bytes of padding per m/n-contiguous LDS row
+constexpr int NT = 256;  // threads per workgroup (4 wavefronts)
+
+__device__ __align__(16) unsigned int g_zero16[4];  // source of every out-of-range chunk
 
 struct ConvGeom {
     int B, T, Tp, Cin, Cout, k, s, p;
 };
 
-// ---- r-contiguous panel: ROWS rows x BK elements -------------------------------------
-// Row i of the tile is a run of memory starting at element offset `off` (may point
+// 16 bytes per lane, global -> LDS at lds_addr + 16*lane (lds_addr wave-uniform).  Written
+// as asm so that the compiler does not serialise later LDS reads behind it; completion is
+// tracked by hand with wait_vmcnt<>.
+__device__ __forceinline__ void dma16(const void* g, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr)
+                 : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// ---- r-contiguous panel: ROWS rows x BKT elements, dense [row][BKT] --------------------
+// Row i of the tile is a run of memory starting at element offset off[i] (may point
 // before the tensor for halo rows); reduction index r is valid in [lo, hi).
-template <int ROWS>
+template <int ROWS, int BKT>
 struct PanelK {
-    static constexpr int RS = BK * 2 + KPAD;            // LDS row stride in bytes
-    static constexpr int BYTES = ROWS * RS;
-    static constexpr int CPR = BK / 8;                  // 16-byte chunks per row
-    static constexpr int NCH = ROWS * CPR / NT;         // chunks per thread
-    static constexpr int READS_PER_FRAG = 1;
-    static_assert(ROWS * CPR % NT == 0, "panel must divide over the workgroup");
-    int off[NCH];                                      // element offsets (tensors hold < 2^31 elements)
-    int lo[NCH], hi[NCH];
-    uint4 reg[NCH];
-    int c8;                                             // this thread's element offset inside a row
+    static constexpr int ROWB = BKT * 2;               // bytes per LDS row
+    static constexpr int BYTES = ROWS * ROWB;
+    static constexpr int CPR = BKT / 8;                // 16-byte chunks per row
+    static constexpr int RPB = 64 / CPR;               // rows filled by one load instruction
+    static constexpr int NI = BYTES / 1024 / 4;        // load instructions per wavefront per panel
+    static_assert(BYTES % 4096 == 0, "panel must split into 1 KB blocks over 4 wavefronts");
+    static_assert(BKT == 64 || BKT == 32, "swizzles are written for 64- and 128-byte rows");
+    int off[NI];                                       // element offsets (tensors hold < 2^31 elements)
+    int lo[NI], hi[NI];
+    int c8;                                            // element offset inside a row of the chunk this lane loads
     const bf16_t* base;
 
-    __device__ __forceinline__ int row_of(int i) const { return (threadIdx.x + i * NT) / CPR; }
-    __device__ __forceinline__ void issue(int r0)
+    // chunk swizzle: rows that one LDS read instruction touches together land on distinct banks
+    static __device__ __forceinline__ int swz(int row)
+    {
+        if (BKT == 64) return (row & 7) ^ ((row >> 3) & 1);
+        return (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1);
+    }
+    static __device__ __forceinline__ int row_of(int i)
+    {
+        return ((threadIdx.x >> 6) + 4 * i) * RPB + (threadIdx.x & 63) / CPR;
+    }
+    __device__ __forceinline__ void init(const bf16_t* b)
+    {
+        base = b;
+        c8 = (((threadIdx.x & 63) % CPR) ^ swz(row_of(0))) * 8;  // swz(row_of(i)) is the same for every i
+    }
+    // panel whose first reduction index is r0, into the stage at LDS address lds_stage
+    __device__ __forceinline__ void issue(int r0, unsigned lds_stage) const
     {
         const int r = r0 + c8;
+        const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (r >= lo[i] && r < hi[i]) v = *reinterpret_cast<const uint4*>(base + off[i] + r);
-            reg[i] = v;
+        for (int i = 0; i < NI; ++i) {
+            const void* src = (r >= lo[i] && r < hi[i]) ? (const void*)(base + off[i] + r) : (const void*)g_zero16;
+            dma16(src, wbase + i * 4096);
         }
     }
-    __device__ __forceinline__ void commit(unsigned char* lds) const
-    {
-#pragma unroll
-        for (int i = 0; i < NCH; ++i)
-            *reinterpret_cast<uint4*>(lds + row_of(i) * RS + c8 * 2) = reg[i];
-    }
-    // 32 rows starting at row0, reduction sub-step ks (16 elements): lane holds row l%32, r = 8*(l/32)..+7
+    // 32 rows starting at row0, sub-step ks (16 elements): lane holds row l%32, r = 8*(l/32)..+7
     static __device__ __forceinline__ bf16x8 frag(const unsigned char* lds, int row0, int ks, int lane)
     {
-        const unsigned char* p = lds + (row0 + (lane & 31)) * RS + (ks * 16 + 8 * (lane >> 5)) * 2;
-        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const s16x8*>(p));
+        const int row = row0 + (lane & 31);
+        const int slot = (2 * ks + (lane >> 5)) ^ swz(row);
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const s16x8*>(lds + row * ROWB + slot * 16));
     }
 };
 
-// ---- m/n-contiguous panel: BK reduction rows x COLS elements ---------------------------
-// Reduction row i (of this step) starts at element offset rowoff(i); columns valid in
-// [lo, hi).  The caller supplies the per-step row addressing to issue().
-template <int COLS>
+// ---- m/n-contiguous panel: BKT reduction rows x COLS elements, dense [BKT][COLS] --------
+template <int COLS, int BKT>
 struct PanelMN {
-    static constexpr int RS = COLS * 2 + MNPAD;
-    static constexpr int BYTES = BK * RS;
+    static constexpr int RS = COLS * 2;
+    static constexpr int BYTES = BKT * RS;
     static constexpr int CPR = COLS / 8;
-    static constexpr int NCH = BK * CPR / NT;
-    static constexpr int READS_PER_FRAG = 2;
-    static_assert(BK * CPR % NT == 0, "panel must divide over the workgroup");
-    uint4 reg[NCH];
+    static constexpr int NI = BYTES / 1024 / 4;
+    static_assert(BYTES % 4096 == 0, "panel must split into 1 KB blocks over 4 wavefronts");
+    static_assert(CPR % 8 == 0, "swizzle flips chunk-index bits 2 and 3");
     const bf16_t* base;
 
     __device__ __forceinline__ void init(const bf16_t* b) { base = b; }
-    static __device__ __forceinline__ int row_of(int i) { return (threadIdx.x + i * NT) / CPR; }
-    static __device__ __forceinline__ int col_of(int i) { return ((threadIdx.x + i * NT) % CPR) * 8; }
-    // f(row, off, lo, hi): element offset of the row's column 0 of this tile and the valid
-    // column range; the 16-byte chunk at column c is loaded iff lo <= c < hi
+    static __device__ __forceinline__ int chunk_of(int i) { return ((threadIdx.x >> 6) + 4 * i) * 64 + (threadIdx.x & 63); }
+    // f(row, off, lo, hi): element offset of the row's column 0 of this tile and its valid
+    // column range; the 16-byte chunk at column c is real data iff lo <= c < hi
     template <class F>
-    __device__ __forceinline__ void issue(F f)
+    __device__ __forceinline__ void issue(F f, unsigned lds_stage) const
     {
+        const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
+        for (int i = 0; i < NI; ++i) {
+            const int q = chunk_of(i);
+            const int row = q / CPR, slot = q - row * CPR;
+            const int c8 = (slot ^ ((row & 3) << 2)) * 8;
             long long off;
             int lo, hi;
-            const int c8 = col_of(i);
-            f(row_of(i), off, lo, hi);
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (c8 >= lo && c8 < hi) v = *reinterpret_cast<const uint4*>(base + off + c8);
-            reg[i] = v;
+            f(row, off, lo, hi);
+            const void* src = (c8 >= lo && c8 < hi) ? (const void*)(base + off + c8) : (const void*)g_zero16;
+            dma16(src, wbase + i * 4096);
         }
     }
-    __device__ __forceinline__ void commit(unsigned char* lds) const
-    {
-#pragma unroll
-        for (int i = 0; i < NCH; ++i)
-            *reinterpret_cast<uint4*>(lds + row_of(i) * RS + col_of(i) * 2) = reg[i];
-    }
-    // same fragment as PanelK::frag, gathered with two transpose reads: within each group of
-    // 16 lanes, lane i supplies the address of row (i/4), columns 4*(i%4)..+3 and receives
-    // column i of rows 0..3
+    // Same fragment as PanelK::frag, gathered with two transpose reads: within each group of
+    // 16 lanes, lane i supplies the address of row (i/4), columns 4*(i%4)..+3, and receives
+    // column i of rows 0..3.
     static __device__ __forceinline__ bf16x8 frag(const unsigned char* lds, int col0, int ks, int lane)
     {
         const int q = lane >> 4, i = lane & 15;
         const int col = col0 + 16 * (q & 1) + 4 * (i & 3);
         const int r = ks * 16 + 8 * (q >> 1) + (i >> 2);
-        const unsigned char* p = lds + r * RS + col * 2;
+        const int slot = (col >> 3) ^ ((r & 3) << 2);           // (r+4)&3 == r&3: both reads share it
+        const unsigned char* p = lds + r * RS + slot * 16 + (col & 7) * 2;
         const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
         const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * RS));
         s16x8 v;
@@ -139,7 +165,7 @@ struct PanelMN {
 };
 
 // ---- the 2x2-wavefront MFMA core ----------------------------------------------------
-template <int BM, int BN, class PA, class PB>
+template <int BM, int BN, int BKT, class PA, class PB>
 struct Core {
     static constexpr int TM = BM / 2 / 32, TN = BN / 2 / 32;  // 32x32 blocks per wavefront
     f32x16 acc[TM][TN];
@@ -152,12 +178,12 @@ struct Core {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     }
-    // One panel (BK reduction elements).  Operand fragments are double-buffered in
-    // registers: the LDS reads of sub-step ks+1 are issued before the MFMAs of sub-step ks,
-    // so their latency hides under matrix work (one wavefront per SIMD: nothing else would).
+    // One panel.  Operand fragments are double-buffered in registers: the LDS reads of
+    // sub-step ks+1 are issued before the MFMAs of sub-step ks, so their latency hides
+    // under matrix work (one wavefront per SIMD: nothing else would hide it).
     __device__ __forceinline__ void step(const unsigned char* la, const unsigned char* lb, int wm, int wn, int lane)
     {
-        constexpr int NS = BK / 16;
+        constexpr int NS = BKT / 16;
         bf16x8 a[2][TM], b[2][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i) a[0][i] = PA::frag(la, wm * (BM / 2) + i * 32, 0, lane);
@@ -198,6 +224,37 @@ struct Core {
     }
 };
 
+// The panel ring shared by the three kernels.  issue(st, lds_addr) starts the loads of panel
+// st; every wavefront issues exactly NL load instructions per panel.
+template <int STAGES, int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
+__device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int wm, int wn,
+                                             int lane)
+{
+    static_assert(STAGES == 3 || STAGES == 4, "ring depth");
+    static_assert((STAGES - 2) * NL < 64, "loads in flight must fit the vmcnt counter");
+    const unsigned lds0 = (unsigned)(size_t)(lds_byte*)lds;
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < nsteps) issue(s, lds0 + s * STAGE_BYTES);
+    int slot = 0;  // ring slot of panel st
+    for (int st = 0; st < nsteps; ++st) {
+        // panels st+1 .. st+STAGES-2 may stay in flight; panel st must have landed
+        const int newer = nsteps - 1 - st;
+        if (STAGES == 4 && newer >= 2) wait_vmcnt<(STAGES == 4 ? 2 : 1) * NL>();
+        else if (newer >= 1) wait_vmcnt<NL>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();  // everyone's share of panel st is in LDS; everyone is done reading panel st-1
+        asm volatile("" ::: "memory");  // no LDS read of panel st may be hoisted above the barrier
+        const int pre = st + STAGES - 1;
+        int pslot = slot - 1;          // the slot panel st-1 occupied
+        if (pslot < 0) pslot += STAGES;
+        if (pre < nsteps) issue(pre, lds0 + pslot * STAGE_BYTES);
+        const unsigned char* cur = lds + slot * STAGE_BYTES;
+        core.step(cur, cur + A_BYTES, wm, wn, lane);
+        slot = (slot + 1 == STAGES) ? 0 : slot + 1;
+    }
+}
+
 // Workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own
 // L2); give each XCD a contiguous run of tiles, ordered with the shorter grid dimension
 // fastest, so that the tiles sharing an L2 cover a compact block of operand panels.
@@ -212,14 +269,14 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
 }
 
 // =============================== forward ================================================
-template <int BM, int BN, typename TO>
+template <int BM, int BN, int BKT, int STAGES, typename TO>
 __global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
                                                  const float* __restrict__ bias, TO* __restrict__ y, ConvGeom g)
 {
-    using PA = PanelK<BM>;
-    using PB = PanelK<BN>;
-    extern __shared__ __align__(16) unsigned char lds[];
-    constexpr int STAGE = PA::BYTES + PB::BYTES;  // stage i holds [A panel | B panel]
+    using PA = PanelK<BM, BKT>;
+    using PB = PanelK<BN, BKT>;
+    extern __shared__ __align__(1024) unsigned char lds[];
+    constexpr int STAGE = PA::BYTES + PB::BYTES;
     const int M = g.B * g.Tp, N = g.Cout, K = g.k * g.Cin;
     int tm, tn;
     tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
@@ -228,13 +285,11 @@ __global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, c
 
     PA pa;
     PB pb;
-    pa.base = x;
-    pb.base = w;
-    pa.c8 = (threadIdx.x % PA::CPR) * 8;
-    pb.c8 = pa.c8;
+    pa.init(x);
+    pb.init(w);
 #pragma unroll
-    for (int i = 0; i < PA::NCH; ++i) {
-        const int m = m0 + pa.row_of(i);
+    for (int i = 0; i < PA::NI; ++i) {
+        const int m = m0 + PA::row_of(i);
         const int b = m / g.Tp, tp = m - b * g.Tp;
         const int t0 = g.s * tp - g.p;                  // first frame of the window (may be < 0)
         pa.off[i] = (b * g.T + t0) * g.Cin;
@@ -243,28 +298,22 @@ __global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, c
         pa.hi[i] = (m < M) ? (last < g.k ? last : g.k) * g.Cin : 0;
     }
 #pragma unroll
-    for (int i = 0; i < PB::NCH; ++i) {
-        const int n = n0 + pb.row_of(i);
+    for (int i = 0; i < PB::NI; ++i) {
+        const int n = n0 + PB::row_of(i);
         pb.off[i] = n * K;
         pb.lo[i] = 0;
         pb.hi[i] = (n < N) ? K : 0;
     }
-    Core<BM, BN, PA, PB> core;
+    Core<BM, BN, BKT, PA, PB> core;
     core.zero();
-    const int nsteps = (K + BK - 1) / BK;
-    pa.issue(0);
-    pb.issue(0);
-    pa.commit(lds);
-    pb.commit(lds + PA::BYTES);
-    __syncthreads();
-    for (int st = 0; st < nsteps; ++st) {
-        unsigned char* cur = lds + (st & 1) * STAGE;
-        unsigned char* nxt = lds + ((st & 1) ^ 1) * STAGE;
-        if (st + 1 < nsteps) { pa.issue((st + 1) * BK); pb.issue((st + 1) * BK); }
-        core.step(cur, cur + PA::BYTES, wm, wn, lane);
-        if (st + 1 < nsteps) { pa.commit(nxt); pb.commit(nxt + PA::BYTES); }
-        __syncthreads();
-    }
+    const int nsteps = (K + BKT - 1) / BKT;
+    run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
+        core, lds, nsteps,
+        [&](int st, unsigned dst) {
+            pa.issue(st * BKT, dst);
+            pb.issue(st * BKT, dst + PA::BYTES);
+        },
+        wm, wn, lane);
     core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
         const int m = m0 + mm, n = n0 + nn;
         if (m < M && n < N) Elem<TO>::store(y, (size_t)m * N + n, v + (bias ? bias[n] : 0.f));
@@ -273,14 +322,14 @@ __global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, c
 
 // =============================== data gradient (stride 1) =============================
 // dx[b,t,ci] = sum_{j',co} dy[b, t-p+j', co] * w[co, k-1-j', ci]
-template <int BM, int BN>
+template <int BM, int BN, int BKT, int STAGES>
 __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
                                                    bf16_t* __restrict__ dx, ConvGeom g)
 {
-    using PA = PanelK<BM>;
-    using PB = PanelMN<BN>;
-    extern __shared__ __align__(16) unsigned char lds[];
-    constexpr int STAGE = PA::BYTES + PB::BYTES;  // stage i holds [A panel | B panel]
+    using PA = PanelK<BM, BKT>;
+    using PB = PanelMN<BN, BKT>;
+    extern __shared__ __align__(1024) unsigned char lds[];
+    constexpr int STAGE = PA::BYTES + PB::BYTES;
     const int M = g.B * g.T, N = g.Cin, K = g.k * g.Cout;
     int tm, tn;
     tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
@@ -289,12 +338,11 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
 
     PA pa;
     PB pb;
-    pa.base = dy;
-    pa.c8 = (threadIdx.x % PA::CPR) * 8;
+    pa.init(dy);
     pb.init(w);
 #pragma unroll
-    for (int i = 0; i < PA::NCH; ++i) {
-        const int m = m0 + pa.row_of(i);
+    for (int i = 0; i < PA::NI; ++i) {
+        const int m = m0 + PA::row_of(i);
         const int b = m / g.T, t = m - b * g.T;
         const int t0 = t - g.p;
         pa.off[i] = (b * g.Tp + t0) * g.Cout;
@@ -302,34 +350,26 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
         const int last = g.Tp - t0;
         pa.hi[i] = (m < M) ? (last < g.k ? last : g.k) * g.Cout : 0;
     }
-    // reduction row r = (j', co): Cout is a multiple of BK, so a step stays inside one tap
-    auto wrow = [&](int st) {
-        const int r0 = st * BK;
-        const int jp = r0 / g.Cout, co0 = r0 - jp * g.Cout;
-        const long long tapoff = (long long)(g.k - 1 - jp) * g.Cin + n0;
-        const int ncols = N - n0;
-        return [=](int rr, long long& off, int& lo, int& hi) {
-            off = (long long)(co0 + rr) * g.k * g.Cin + tapoff;
-            lo = 0;
-            hi = ncols;  // chunk columns are multiples of 8 and N % 8 == 0
-        };
-    };
-    Core<BM, BN, PA, PB> core;
+    Core<BM, BN, BKT, PA, PB> core;
     core.zero();
-    const int nsteps = K / BK;
-    pa.issue(0);
-    pb.issue(wrow(0));
-    pa.commit(lds);
-    pb.commit(lds + PA::BYTES);
-    __syncthreads();
-    for (int st = 0; st < nsteps; ++st) {
-        unsigned char* cur = lds + (st & 1) * STAGE;
-        unsigned char* nxt = lds + ((st & 1) ^ 1) * STAGE;
-        if (st + 1 < nsteps) { pa.issue((st + 1) * BK); pb.issue(wrow(st + 1)); }
-        core.step(cur, cur + PA::BYTES, wm, wn, lane);
-        if (st + 1 < nsteps) { pa.commit(nxt); pb.commit(nxt + PA::BYTES); }
-        __syncthreads();
-    }
+    const int nsteps = K / BKT;  // Cout is a multiple of BKT: a panel stays inside one tap
+    run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
+        core, lds, nsteps,
+        [&](int st, unsigned dst) {
+            pa.issue(st * BKT, dst);
+            const int r0 = st * BKT;
+            const int jp = r0 / g.Cout, co0 = r0 - jp * g.Cout;
+            const long long tapoff = (long long)(g.k - 1 - jp) * g.Cin + n0;
+            const int ncols = N - n0;
+            pb.issue(
+                [=](int rr, long long& off, int& lo, int& hi) {
+                    off = (long long)(co0 + rr) * g.k * g.Cin + tapoff;
+                    lo = 0;
+                    hi = ncols;  // chunk columns are multiples of 8 and N % 8 == 0
+                },
+                dst + PA::BYTES);
+        },
+        wm, wn, lane);
     core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
         const int m = m0 + mm, n = n0 + nn;
         if (m < M && n < N) dx[(size_t)m * N + n] = f32_to_bf16(v);
@@ -338,15 +378,15 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
 
 // =============================== weight gradient ========================================
 // dw[co, (j,ci)] = sum_{b,t'} dy[b,t',co] * x[b, s t' - p + j, ci]; the reduction walks
-// utterance by utterance in BK-frame steps (the last step of an utterance is masked).
-template <int BM, int BN>
+// utterance by utterance in BKT-frame panels (the last panel of an utterance is masked).
+template <int BM, int BN, int BKT, int STAGES>
 __global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
                                                    float* __restrict__ dw, ConvGeom g, int accumulate)
 {
-    using PA = PanelMN<BM>;
-    using PB = PanelMN<BN>;
-    extern __shared__ __align__(16) unsigned char lds[];
-    constexpr int STAGE = PA::BYTES + PB::BYTES;  // stage i holds [A panel | B panel]
+    using PA = PanelMN<BM, BKT>;
+    using PB = PanelMN<BN, BKT>;
+    extern __shared__ __align__(1024) unsigned char lds[];
+    constexpr int STAGE = PA::BYTES + PB::BYTES;
     const int M = g.Cout, N = g.k * g.Cin;
     int tm, tn;
     tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
@@ -357,47 +397,38 @@ __global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x,
     PB pb;
     pa.init(dy);
     pb.init(x);
-    const int spb = (g.Tp + BK - 1) / BK;  // steps per utterance
+    const int spb = (g.Tp + BKT - 1) / BKT;  // panels per utterance
     const int nsteps = g.B * spb;
-    auto arow = [&](int st) {
-        const int b = st / spb, tp0 = (st - b * spb) * BK;
-        const long long boff = ((long long)b * g.Tp + tp0) * g.Cout + m0;
-        const int left = g.Tp - tp0, ncols = M - m0;
-        return [=](int rr, long long& off, int& lo, int& hi) {
-            off = boff + (long long)rr * g.Cout;
-            lo = 0;
-            hi = (rr < left) ? ncols : 0;
-        };
-    };
-    auto brow = [&](int st) {
-        const int b = st / spb, tp0 = (st - b * spb) * BK;
-        const int left = g.Tp - tp0;
-        return [=](int rr, long long& off, int& lo, int& hi) {
-            const int t0 = g.s * (tp0 + rr) - g.p;               // frame under tap 0
-            off = ((long long)b * g.T + t0) * g.Cin + n0;
-            // tile column c <-> tap-major index n0 + c ; valid taps: 0 <= t0 + j < T
-            const int jlo = t0 < 0 ? -t0 : 0;
-            const int jhi = (g.T - t0) < g.k ? (g.T - t0) : g.k;
-            lo = jlo * g.Cin - n0;
-            hi = (rr < left) ? jhi * g.Cin - n0 : lo;
-            if (hi > N - n0) hi = N - n0;
-        };
-    };
-    Core<BM, BN, PA, PB> core;
+    Core<BM, BN, BKT, PA, PB> core;
     core.zero();
-    pa.issue(arow(0));
-    pb.issue(brow(0));
-    pa.commit(lds);
-    pb.commit(lds + PA::BYTES);
-    __syncthreads();
-    for (int st = 0; st < nsteps; ++st) {
-        unsigned char* cur = lds + (st & 1) * STAGE;
-        unsigned char* nxt = lds + ((st & 1) ^ 1) * STAGE;
-        if (st + 1 < nsteps) { pa.issue(arow(st + 1)); pb.issue(brow(st + 1)); }
-        core.step(cur, cur + PA::BYTES, wm, wn, lane);
-        if (st + 1 < nsteps) { pa.commit(nxt); pb.commit(nxt + PA::BYTES); }
-        __syncthreads();
-    }
+    run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
+        core, lds, nsteps,
+        [&](int st, unsigned dst) {
+            const int b = st / spb, tp0 = (st - b * spb) * BKT;
+            const int left = g.Tp - tp0;
+            const long long boff = ((long long)b * g.Tp + tp0) * g.Cout + m0;
+            const int mcols = M - m0;
+            pa.issue(
+                [=](int rr, long long& off, int& lo, int& hi) {
+                    off = boff + (long long)rr * g.Cout;
+                    lo = 0;
+                    hi = (rr < left) ? mcols : 0;
+                },
+                dst);
+            pb.issue(
+                [=](int rr, long long& off, int& lo, int& hi) {
+                    const int t0 = g.s * (tp0 + rr) - g.p;          // frame under tap 0
+                    off = ((long long)b * g.T + t0) * g.Cin + n0;
+                    // tile column c <-> tap-major index n0 + c ; valid taps: 0 <= t0 + j < T
+                    const int jlo = t0 < 0 ? -t0 : 0;
+                    const int jhi = (g.T - t0) < g.k ? (g.T - t0) : g.k;
+                    lo = jlo * g.Cin - n0;
+                    hi = (rr < left) ? jhi * g.Cin - n0 : lo;
+                    if (hi > N - n0) hi = N - n0;
+                },
+                dst + PA::BYTES);
+        },
+        wm, wn, lane);
     core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
         const int m = m0 + mm, n = n0 + nn;
         if (m < M && n < N) {
@@ -406,9 +437,6 @@ __global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x,
         }
     });
 }
-
-template <int BM, int BN, class PA, class PB>
-constexpr int lds_bytes() { return 2 * (PA::BYTES + PB::BYTES); }
 
 template <class K>
 int set_lds(K kern, int bytes)
@@ -441,15 +469,17 @@ bool common_ok(int B, int T, int Cin, int Cout, int k, int s)
     if (Cin % 8 || Cout % 8) return false;
     if ((long long)k * Cin > 32767 * 8LL || (long long)k * Cout > 32767 * 8LL) return false;
     if ((long long)B * T * Cin >= (1LL << 31) || (long long)B * out_len(T, s) * Cout >= (1LL << 31)) return false;
+    if ((long long)Cout * k * Cin >= (1LL << 31)) return false;
     return true;
 }
 
-#define W2L_TILE_DISPATCH(CALL)                          \
-    if (tc.bm == 256 && tc.bn == 256) { CALL(256, 256); } \
-    else if (tc.bm == 192 && tc.bn == 192) { CALL(192, 192); } \
-    else if (tc.bm == 256 && tc.bn == 128) { CALL(256, 128); } \
-    else if (tc.bm == 128 && tc.bn == 256) { CALL(128, 256); } \
-    else { CALL(128, 128); }
+// tile -> (panel depth, ring depth): 3 x 48 KB for the tiles that fit, 4 x 32 KB for 256x256
+#define W2L_TILE_DISPATCH(CALL)                                          \
+    if (tc.bm == 256 && tc.bn == 256) { CALL(256, 256, 32, 4); }         \
+    else if (tc.bm == 192 && tc.bn == 192) { CALL(192, 192, 64, 3); }    \
+    else if (tc.bm == 256 && tc.bn == 128) { CALL(256, 128, 64, 3); }    \
+    else if (tc.bm == 128 && tc.bn == 256) { CALL(128, 256, 64, 3); }    \
+    else { CALL(128, 128, 64, 3); }
 
 }  // namespace
 
@@ -465,19 +495,19 @@ int conv_fwd_mfma(const void* x, const void* w, const float* bias, void* y, int 
     const long long M = (long long)B * g.Tp, N = Cout;
     const TileChoice tc = choose_tile(M, N);
     int rc = W2L_OK;
-#define CALL(BM_, BN_)                                                                                   \
-    {                                                                                                    \
-        constexpr int bytes = lds_bytes<BM_, BN_, PanelK<BM_>, PanelK<BN_>>();                           \
-        const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                 \
-        if (ydt == W2L_BF16) {                                                                           \
-            rc = set_lds(conv_fwd_k<BM_, BN_, bf16_t>, bytes);                                           \
-            if (!rc) hipLaunchKernelGGL((conv_fwd_k<BM_, BN_, bf16_t>), dim3(grid), dim3(NT), bytes, st, \
-                                        (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g);        \
-        } else {                                                                                         \
-            rc = set_lds(conv_fwd_k<BM_, BN_, float>, bytes);                                            \
-            if (!rc) hipLaunchKernelGGL((conv_fwd_k<BM_, BN_, float>), dim3(grid), dim3(NT), bytes, st,  \
-                                        (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g);         \
-        }                                                                                                \
+#define CALL(BM_, BN_, BK_, ST_)                                                                              \
+    {                                                                                                         \
+        constexpr int bytes = ST_ * (PanelK<BM_, BK_>::BYTES + PanelK<BN_, BK_>::BYTES);                      \
+        const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                      \
+        if (ydt == W2L_BF16) {                                                                                \
+            rc = set_lds(conv_fwd_k<BM_, BN_, BK_, ST_, bf16_t>, bytes);                                      \
+            if (!rc) hipLaunchKernelGGL((conv_fwd_k<BM_, BN_, BK_, ST_, bf16_t>), dim3(grid), dim3(NT), bytes, st, \
+                                        (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g);             \
+        } else {                                                                                              \
+            rc = set_lds(conv_fwd_k<BM_, BN_, BK_, ST_, float>, bytes);                                       \
+            if (!rc) hipLaunchKernelGGL((conv_fwd_k<BM_, BN_, BK_, ST_, float>), dim3(grid), dim3(NT), bytes, st, \
+                                        (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g);              \
+        }                                                                                                     \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
@@ -486,7 +516,7 @@ int conv_fwd_mfma(const void* x, const void* w, const float* bias, void* y, int 
 
 bool conv_dgrad_mfma_ok(int B, int T, int Cin, int Cout, int k, int s)
 {
-    return s == 1 && common_ok(B, T, Cin, Cout, k, s) && Cout % BK == 0 && Cin >= 64 && (long long)B * T >= 128;
+    return s == 1 && common_ok(B, T, Cin, Cout, k, s) && Cout % 64 == 0 && Cin >= 64 && (long long)B * T >= 128;
 }
 
 int conv_dgrad_mfma(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout, int k, int s,
@@ -496,13 +526,13 @@ int conv_dgrad_mfma(const void* dy, const void* w, void* dx, int B, int T, int C
     const long long M = (long long)B * T, N = Cin;
     const TileChoice tc = choose_tile(M, N);
     int rc = W2L_OK;
-#define CALL(BM_, BN_)                                                                               \
-    {                                                                                                \
-        constexpr int bytes = lds_bytes<BM_, BN_, PanelK<BM_>, PanelMN<BN_>>();                      \
-        const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));             \
-        rc = set_lds(conv_dgrad_k<BM_, BN_>, bytes);                                                 \
-        if (!rc) hipLaunchKernelGGL((conv_dgrad_k<BM_, BN_>), dim3(grid), dim3(NT), bytes, st,       \
-                                    (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g);            \
+#define CALL(BM_, BN_, BK_, ST_)                                                                          \
+    {                                                                                                     \
+        constexpr int bytes = ST_ * (PanelK<BM_, BK_>::BYTES + PanelMN<BN_, BK_>::BYTES);                 \
+        const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                  \
+        rc = set_lds(conv_dgrad_k<BM_, BN_, BK_, ST_>, bytes);                                            \
+        if (!rc) hipLaunchKernelGGL((conv_dgrad_k<BM_, BN_, BK_, ST_>), dim3(grid), dim3(NT), bytes, st,  \
+                                    (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g);                 \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
@@ -523,13 +553,13 @@ int conv_wgrad_mfma(const void* x, const void* dy, float* dw, int B, int T, int 
     const long long M = Cout, N = (long long)k * Cin;
     const TileChoice tc = choose_tile(M, N);
     int rc = W2L_OK;
-#define CALL(BM_, BN_)                                                                                \
-    {                                                                                                 \
-        constexpr int bytes = lds_bytes<BM_, BN_, PanelMN<BM_>, PanelMN<BN_>>();                      \
-        const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));              \
-        rc = set_lds(conv_wgrad_k<BM_, BN_>, bytes);                                                  \
-        if (!rc) hipLaunchKernelGGL((conv_wgrad_k<BM_, BN_>), dim3(grid), dim3(NT), bytes, st,        \
-                                    (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate);          \
+#define CALL(BM_, BN_, BK_, ST_)                                                                          \
+    {                                                                                                     \
+        constexpr int bytes = ST_ * (PanelMN<BM_, BK_>::BYTES + PanelMN<BN_, BK_>::BYTES);                \
+        const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                  \
+        rc = set_lds(conv_wgrad_k<BM_, BN_, BK_, ST_>, bytes);                                            \
+        if (!rc) hipLaunchKernelGGL((conv_wgrad_k<BM_, BN_, BK_, ST_>), dim3(grid), dim3(NT), bytes, st,  \
+                                    (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate);              \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
