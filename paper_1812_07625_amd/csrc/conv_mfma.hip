@@ -94,16 +94,14 @@ struct PanelK {
         base = b;
         c8 = (((threadIdx.x & 63) % CPR) ^ swz(row_of(0))) * 8;  // swz(row_of(i)) is the same for every i
     }
-    // panel whose first reduction index is r0, into the stage at LDS address lds_stage
-    __device__ __forceinline__ void issue(int r0, unsigned lds_stage) const
+    // load instruction i (of NI) of the panel whose first reduction index is r0, into the
+    // stage at LDS address lds_stage
+    __device__ __forceinline__ void issue(int i, int r0, unsigned lds_stage) const
     {
         const int r = r0 + c8;
         const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const void* src = (r >= lo[i] && r < hi[i]) ? (const void*)(base + off[i] + r) : (const void*)g_zero16;
-            dma16(src, wbase + i * 4096);
-        }
+        const void* src = (r >= lo[i] && r < hi[i]) ? (const void*)(base + off[i] + r) : (const void*)g_zero16;
+        dma16(src, wbase + i * 4096);
     }
     // 32 rows starting at row0, sub-step ks (16 elements): lane holds row l%32, r = 8*(l/32)..+7
     static __device__ __forceinline__ bf16x8 frag(const unsigned char* lds, int row0, int ks, int lane)
@@ -130,20 +128,17 @@ struct PanelMN {
     // f(row, off, lo, hi): element offset of the row's column 0 of this tile and its valid
     // column range; the 16-byte chunk at column c is real data iff lo <= c < hi
     template <class F>
-    __device__ __forceinline__ void issue(F f, unsigned lds_stage) const
+    __device__ __forceinline__ void issue(int i, F f, unsigned lds_stage) const
     {
         const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int q = chunk_of(i);
-            const int row = q / CPR, slot = q - row * CPR;
-            const int c8 = (slot ^ ((row & 3) << 2)) * 8;
-            long long off;
-            int lo, hi;
-            f(row, off, lo, hi);
-            const void* src = (c8 >= lo && c8 < hi) ? (const void*)(base + off + c8) : (const void*)g_zero16;
-            dma16(src, wbase + i * 4096);
-        }
+        const int q = chunk_of(i);
+        const int row = q / CPR, slot = q - row * CPR;
+        const int c8 = (slot ^ ((row & 3) << 2)) * 8;
+        long long off;
+        int lo, hi;
+        f(row, off, lo, hi);
+        const void* src = (c8 >= lo && c8 < hi) ? (const void*)(base + off + c8) : (const void*)g_zero16;
+        dma16(src, wbase + i * 4096);
     }
     // Same fragment as PanelK::frag, gathered with two transpose reads: within each group of
     // 16 lanes, lane i supplies the address of row (i/4), columns 4*(i%4)..+3, and receives
@@ -180,8 +175,14 @@ struct Core {
     }
     // One panel.  Operand fragments are double-buffered in registers: the LDS reads of
     // sub-step ks+1 are issued before the MFMAs of sub-step ks, so their latency hides
-    // under matrix work (one wavefront per SIMD: nothing else would hide it).
-    __device__ __forceinline__ void step(const unsigned char* la, const unsigned char* lb, int wm, int wn, int lane)
+    // under matrix work (one wavefront per SIMD: nothing else would hide it).  hook(g) runs
+    // after the g-th MFMA of the panel: the caller hangs the next panel's load instructions
+    // there, so their address arithmetic issues in the shadow of the matrix pipe instead of
+    // in front of it.
+    static constexpr int GROUPS = (BKT / 16) * TM * TN;
+    template <class Hook>
+    __device__ __forceinline__ void step(const unsigned char* la, const unsigned char* lb, int wm, int wn, int lane,
+                                         Hook hook)
     {
         constexpr int NS = BKT / 16;
         bf16x8 a[2][TM], b[2][TN];
@@ -202,9 +203,12 @@ struct Core {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    hook((ks * TM + i) * TN + j);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
         }
     }
     // f(m, n, value) for every element this lane holds; m,n relative to the tile
@@ -224,35 +228,36 @@ struct Core {
     }
 };
 
-// The panel ring shared by the three kernels.  issue(st, lds_addr) starts the loads of panel
-// st; every wavefront issues exactly NL load instructions per panel.
+// The panel ring shared by the three kernels.  issue(i, p, lds_addr) starts load instruction
+// i (of NL per wavefront) of panel p; for p >= nsteps it must load zeros (the ring keeps
+// prefetching past the end so that the number of loads in flight never changes).
 template <int STAGES, int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
 __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int wm, int wn,
                                              int lane)
 {
     static_assert(STAGES == 3 || STAGES == 4, "ring depth");
     static_assert((STAGES - 2) * NL < 64, "loads in flight must fit the vmcnt counter");
+    static_assert(NL <= CoreT::GROUPS, "one load instruction per MFMA");
     const unsigned lds0 = (unsigned)(size_t)(lds_byte*)lds;
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < nsteps) issue(s, lds0 + s * STAGE_BYTES);
+    for (int s = 0; s < STAGES - 1; ++s) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) issue(i, s, lds0 + s * STAGE_BYTES);
+    }
     int slot = 0;  // ring slot of panel st
     for (int st = 0; st < nsteps; ++st) {
-        // panels st+1 .. st+STAGES-2 may stay in flight; panel st must have landed
-        const int newer = nsteps - 1 - st;
-        if (STAGES == 4 && newer >= 2) wait_vmcnt<(STAGES == 4 ? 2 : 1) * NL>();
-        else if (newer >= 1) wait_vmcnt<NL>();
-        else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();  // everyone's share of panel st is in LDS; everyone is done reading panel st-1
-        asm volatile("" ::: "memory");  // no LDS read of panel st may be hoisted above the barrier
+        wait_vmcnt<(STAGES - 2) * NL>();  // panels st+1 .. st+STAGES-2 stay in flight; panel st has landed
+        __builtin_amdgcn_s_barrier();     // everyone's share of panel st is in LDS; everyone is done reading panel st-1
+        asm volatile("" ::: "memory");    // no LDS read of panel st may be hoisted above the barrier
         const int pre = st + STAGES - 1;
-        int pslot = slot - 1;          // the slot panel st-1 occupied
+        int pslot = slot - 1;             // the slot panel st-1 occupied
         if (pslot < 0) pslot += STAGES;
-        if (pre < nsteps) issue(pre, lds0 + pslot * STAGE_BYTES);
+        const unsigned dst = lds0 + pslot * STAGE_BYTES;
         const unsigned char* cur = lds + slot * STAGE_BYTES;
-        core.step(cur, cur + A_BYTES, wm, wn, lane);
+        core.step(cur, cur + A_BYTES, wm, wn, lane, [&](int grp) { if (grp < NL) issue(grp, pre, dst); });
         slot = (slot + 1 == STAGES) ? 0 : slot + 1;
     }
+    wait_vmcnt<0>();  // the trailing zero-panels must land before the LDS allocation is released
 }
 
 // Workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own
@@ -309,9 +314,9 @@ __global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, c
     const int nsteps = (K + BKT - 1) / BKT;
     run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
-        [&](int st, unsigned dst) {
-            pa.issue(st * BKT, dst);
-            pb.issue(st * BKT, dst + PA::BYTES);
+        [&](int i, int st, unsigned dst) {
+            if (i < PA::NI) pa.issue(i, st * BKT, dst);
+            else pb.issue(i - PA::NI, st * BKT, dst + PA::BYTES);
         },
         wm, wn, lane);
     core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
@@ -355,17 +360,17 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
     const int nsteps = K / BKT;  // Cout is a multiple of BKT: a panel stays inside one tap
     run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
-        [&](int st, unsigned dst) {
-            pa.issue(st * BKT, dst);
+        [&](int i, int st, unsigned dst) {
+            if (i < PA::NI) { pa.issue(i, st * BKT, dst); return; }
             const int r0 = st * BKT;
             const int jp = r0 / g.Cout, co0 = r0 - jp * g.Cout;
             const long long tapoff = (long long)(g.k - 1 - jp) * g.Cin + n0;
             const int ncols = N - n0;
-            pb.issue(
+            pb.issue(i - PA::NI,
                 [=](int rr, long long& off, int& lo, int& hi) {
                     off = (long long)(co0 + rr) * g.k * g.Cin + tapoff;
                     lo = 0;
-                    hi = ncols;  // chunk columns are multiples of 8 and N % 8 == 0
+                    hi = (st < nsteps) ? ncols : 0;  // chunk columns are multiples of 8 and N % 8 == 0
                 },
                 dst + PA::BYTES);
         },
@@ -403,19 +408,22 @@ __global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x,
     core.zero();
     run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
-        [&](int st, unsigned dst) {
+        [&](int i, int st, unsigned dst) {
             const int b = st / spb, tp0 = (st - b * spb) * BKT;
-            const int left = g.Tp - tp0;
-            const long long boff = ((long long)b * g.Tp + tp0) * g.Cout + m0;
-            const int mcols = M - m0;
-            pa.issue(
-                [=](int rr, long long& off, int& lo, int& hi) {
-                    off = boff + (long long)rr * g.Cout;
-                    lo = 0;
-                    hi = (rr < left) ? mcols : 0;
-                },
-                dst);
-            pb.issue(
+            const int left = (st < nsteps) ? g.Tp - tp0 : 0;  // past the end: every row masked
+            if (i < PA::NI) {
+                const long long boff = ((long long)b * g.Tp + tp0) * g.Cout + m0;
+                const int mcols = M - m0;
+                pa.issue(i,
+                    [=](int rr, long long& off, int& lo, int& hi) {
+                        off = boff + (long long)rr * g.Cout;
+                        lo = 0;
+                        hi = (rr < left) ? mcols : 0;
+                    },
+                    dst);
+                return;
+            }
+            pb.issue(i - PA::NI,
                 [=](int rr, long long& off, int& lo, int& hi) {
                     const int t0 = g.s * (tp0 + rr) - g.p;          // frame under tap 0
                     off = ((long long)b * g.T + t0) * g.Cin + n0;
