@@ -173,42 +173,55 @@ struct Core {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     }
-    // One panel.  Operand fragments are double-buffered in registers: the LDS reads of
-    // sub-step ks+1 are issued before the MFMAs of sub-step ks, so their latency hides
-    // under matrix work (one wavefront per SIMD: nothing else would hide it).  hook(g) runs
-    // after the g-th MFMA of the panel: the caller hangs the next panel's load instructions
-    // there, so their address arithmetic issues in the shadow of the matrix pipe instead of
-    // in front of it.
-    static constexpr int GROUPS = (BKT / 16) * TM * TN;
-    template <class Hook>
-    __device__ __forceinline__ void step(const unsigned char* la, const unsigned char* lb, int wm, int wn, int lane,
-                                         Hook hook)
+    // Operand fragments are double-buffered in registers: the LDS reads of sub-step ks+1 are
+    // issued before the MFMAs of sub-step ks, so their latency hides under matrix work (one
+    // wavefront per SIMD: nothing else would hide it) -- and this carries across panels: the
+    // first fragments of the next panel are read before the last MFMAs of the current one.
+    static constexpr int NS = BKT / 16;
+    static constexpr int GROUPS = NS * TM * TN;      // MFMAs per panel
+    static constexpr int EARLY = (NS - 1) * TM * TN;  // MFMAs issued before the hand-over point
+    bf16x8 fa[2][TM], fb[2][TN];
+    __device__ __forceinline__ void load_frags(int set, const unsigned char* la, const unsigned char* lb, int ks,
+                                               int wm, int wn, int lane)
     {
-        constexpr int NS = BKT / 16;
-        bf16x8 a[2][TM], b[2][TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[0][i] = PA::frag(la, wm * (BM / 2) + i * 32, 0, lane);
+        for (int i = 0; i < TM; ++i) fa[set][i] = PA::frag(la, wm * (BM / 2) + i * 32, ks, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[0][j] = PB::frag(lb, wn * (BN / 2) + j * 32, 0, lane);
+        for (int j = 0; j < TN; ++j) fb[set][j] = PB::frag(lb, wn * (BN / 2) + j * 32, ks, lane);
+    }
+    template <class Hook>
+    __device__ __forceinline__ void mfmas(int ks, Hook hook)
+    {
+        const int c = ks & 1;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], fb[c][j], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                hook((ks * TM + i) * TN + j);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    }
+    // One panel whose ks=0 fragments are already in register set 0.  hook(g) runs after the
+    // g-th MFMA (the caller hangs the prefetch loads there, off the matrix pipe's critical
+    // path); handover() runs before the last sub-step's MFMAs and must make the next panel
+    // readable; the next panel's ks=0 fragments are then read from (na, nb) into set 0.
+    template <class Hook, class Handover>
+    __device__ __forceinline__ void step(const unsigned char* la, const unsigned char* lb, const unsigned char* na,
+                                         const unsigned char* nb, int wm, int wn, int lane, Hook hook,
+                                         Handover handover)
+    {
 #pragma unroll
         for (int ks = 0; ks < NS; ++ks) {
-            const int c = ks & 1, n = c ^ 1;
             if (ks + 1 < NS) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) a[n][i] = PA::frag(la, wm * (BM / 2) + i * 32, ks + 1, lane);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) b[n][j] = PB::frag(lb, wn * (BN / 2) + j * 32, ks + 1, lane);
+                load_frags((ks + 1) & 1, la, lb, ks + 1, wm, wn, lane);
+            } else {
+                handover();
+                load_frags(0, na, nb, 0, wm, wn, lane);
             }
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    hook((ks * TM + i) * TN + j);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+            mfmas(ks, hook);
         }
     }
     // f(m, n, value) for every element this lane holds; m,n relative to the tile
@@ -231,31 +244,51 @@ struct Core {
 // The panel ring shared by the three kernels.  issue(i, p, lds_addr) starts load instruction
 // i (of NL per wavefront) of panel p; for p >= nsteps it must load zeros (the ring keeps
 // prefetching past the end so that the number of loads in flight never changes).
+//
+// Per panel st, per wavefront, in program order:
+//   MFMAs of sub-steps 0..NS-2, interleaved with the NL loads of panel st+STAGES-1 (they go
+//     into the slot panel st-1 occupied; the barrier passed during panel st-1 freed it);
+//   wait until this wavefront's loads of panel st+1 have landed, then barrier: now every
+//     wavefront's share of panel st+1 is in LDS and nobody will read panel st again from
+//     LDS (its last fragments are already in registers);
+//   read the first fragments of panel st+1; MFMAs of the last sub-step of panel st.
 template <int STAGES, int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
 __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int wm, int wn,
                                              int lane)
 {
     static_assert(STAGES == 3 || STAGES == 4, "ring depth");
     static_assert((STAGES - 2) * NL < 64, "loads in flight must fit the vmcnt counter");
-    static_assert(NL <= CoreT::GROUPS, "one load instruction per MFMA");
+    static_assert(NL <= CoreT::EARLY, "the prefetch loads must all be issued before the hand-over point");
     const unsigned lds0 = (unsigned)(size_t)(lds_byte*)lds;
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) issue(i, s, lds0 + s * STAGE_BYTES);
     }
+    wait_vmcnt<(STAGES - 2) * NL>();  // panel 0 has landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    core.load_frags(0, lds, lds + A_BYTES, 0, wm, wn, lane);
     int slot = 0;  // ring slot of panel st
     for (int st = 0; st < nsteps; ++st) {
-        wait_vmcnt<(STAGES - 2) * NL>();  // panels st+1 .. st+STAGES-2 stay in flight; panel st has landed
-        __builtin_amdgcn_s_barrier();     // everyone's share of panel st is in LDS; everyone is done reading panel st-1
-        asm volatile("" ::: "memory");    // no LDS read of panel st may be hoisted above the barrier
         const int pre = st + STAGES - 1;
         int pslot = slot - 1;             // the slot panel st-1 occupied
         if (pslot < 0) pslot += STAGES;
+        const int nslot = (slot + 1 == STAGES) ? 0 : slot + 1;
         const unsigned dst = lds0 + pslot * STAGE_BYTES;
         const unsigned char* cur = lds + slot * STAGE_BYTES;
-        core.step(cur, cur + A_BYTES, wm, wn, lane, [&](int grp) { if (grp < NL) issue(grp, pre, dst); });
-        slot = (slot + 1 == STAGES) ? 0 : slot + 1;
+        const unsigned char* nxt = lds + nslot * STAGE_BYTES;
+        core.step(
+            cur, cur + A_BYTES, nxt, nxt + A_BYTES, wm, wn, lane,
+            [&](int g) { if (g < NL) issue(g, pre, dst); },
+            [&]() {
+                // in flight, oldest first: panels st+1 .. st+STAGES-1; the first must have landed
+                wait_vmcnt<(STAGES - 2) * NL>();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wavefront's reads of panel st are done
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");  // no LDS read of panel st+1 may be hoisted above the barrier
+            });
+        slot = nslot;
     }
     wait_vmcnt<0>();  // the trailing zero-panels must land before the LDS allocation is released
 }
