@@ -45,6 +45,35 @@ bool ws_ok(void* ws, size_t have, size_t need)
 }
 }  // namespace
 
+namespace w2l {
+
+int conv_fwd(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int dt, int ydt,
+             hipStream_t st)
+{
+    if (dt == W2L_BF16 && conv_fwd_mfma_ok(d)) return conv_fwd_mfma(d, x, w, bias, y, ydt, st);
+    return conv_fwd_generic(d, x, w, bias, y, dt, ydt, st);
+}
+
+int conv_dgrad(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st)
+{
+    if (dt == W2L_BF16 && dydt == W2L_BF16 && conv_dgrad_mfma_ok(d)) return conv_dgrad_mfma(d, dy, w, dx, st);
+    return conv_dgrad_generic(d, dy, w, dx, dt, dydt, st);
+}
+
+int conv_wgrad(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int dt, int dydt,
+               int accumulate, float* dbias_scratch, hipStream_t st)
+{
+    if (dbias) {
+        // halo frames hold zeros, so summing every frame of the allocation is the same sum
+        const int rc = dbias_reduce(dy, dbias, (long long)d.B * d.y_pitch, d.Cout, dydt, accumulate, dbias_scratch, st);
+        if (rc) return rc;
+    }
+    if (dt == W2L_BF16 && dydt == W2L_BF16 && conv_wgrad_mfma_ok(d)) return conv_wgrad_mfma(d, x, dy, dw, accumulate, st);
+    return conv_wgrad_generic(d, x, dy, dw, dt, dydt, accumulate, st);
+}
+
+}  // namespace w2l
+
 extern "C" size_t w2l_conv1d_fwd_workspace_bytes(int, int, int, int, int, int, int) { return 0; }
 
 extern "C" int w2l_conv1d_fwd(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin,
@@ -59,10 +88,7 @@ extern "C" int w2l_conv1d_fwd(const void* x, const void* w, const float* bias, v
     if (!aligned16(x) || !aligned16(w) || !aligned16(y) || (bias && !aligned16(bias))) return W2L_ERR_ALIGN;
     if (!ws_ok(workspace, ws_bytes, w2l_conv1d_fwd_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
         return W2L_ERR_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    if (dtype == W2L_BF16 && conv_fwd_mfma_ok(B, T, Cin, Cout, k, stride))
-        return conv_fwd_mfma(x, w, bias, y, B, T, Cin, Cout, k, stride, y_dtype, st);
-    return conv_fwd_generic(x, w, bias, y, B, T, Cin, Cout, k, stride, dtype, y_dtype, st);
+    return conv_fwd(dense_desc(B, T, Cin, Cout, k, stride), x, w, bias, y, dtype, y_dtype, (hipStream_t)stream);
 }
 
 extern "C" size_t w2l_conv1d_bwd_data_workspace_bytes(int, int, int, int, int, int, int) { return 0; }
@@ -79,10 +105,7 @@ extern "C" int w2l_conv1d_bwd_data(const void* dy, const void* w, void* dx, int 
     if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return W2L_ERR_ALIGN;
     if (!ws_ok(workspace, ws_bytes, w2l_conv1d_bwd_data_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
         return W2L_ERR_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    if (dtype == W2L_BF16 && dy_dtype == W2L_BF16 && conv_dgrad_mfma_ok(B, T, Cin, Cout, k, stride))
-        return conv_dgrad_mfma(dy, w, dx, B, T, Cin, Cout, k, stride, st);
-    return conv_dgrad_generic(dy, w, dx, B, T, Cin, Cout, k, stride, dtype, dy_dtype, st);
+    return conv_dgrad(dense_desc(B, T, Cin, Cout, k, stride), dy, w, dx, dtype, dy_dtype, (hipStream_t)stream);
 }
 
 extern "C" size_t w2l_conv1d_bwd_weight_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride,
@@ -90,7 +113,7 @@ extern "C" size_t w2l_conv1d_bwd_weight_workspace_bytes(int B, int T, int Cin, i
 {
     (void)dtype;
     if (B <= 0 || T <= 0 || Cin <= 0 || Cout <= 0 || k <= 0 || stride <= 0) return 0;
-    return round_up((size_t)DBIAS_CHUNKS * Cout * 4, 256) + conv_wgrad_mfma_workspace(B, T, Cin, Cout, k, stride);
+    return round_up((size_t)DBIAS_CHUNKS * Cout * 4, 256);
 }
 
 extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, float* dbias, int B, int T,
@@ -105,15 +128,6 @@ extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, f
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || (dbias && !aligned16(dbias))) return W2L_ERR_ALIGN;
     if (!ws_ok(workspace, ws_bytes, w2l_conv1d_bwd_weight_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
         return W2L_ERR_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    const int Tp = out_len(T, stride);
-    float* scratch = static_cast<float*>(workspace);
-    void* ws2 = static_cast<unsigned char*>(workspace) + round_up((size_t)DBIAS_CHUNKS * Cout * 4, 256);
-    if (dbias) {
-        rc = dbias_reduce(dy, dbias, (long long)B * Tp, Cout, dy_dtype, accumulate, scratch, st);
-        if (rc) return rc;
-    }
-    if (dtype == W2L_BF16 && dy_dtype == W2L_BF16 && conv_wgrad_mfma_ok(B, T, Cin, Cout, k, stride))
-        return conv_wgrad_mfma(x, dy, dw, B, T, Cin, Cout, k, stride, accumulate, ws2, st);
-    return conv_wgrad_generic(x, dy, dw, B, T, Cin, Cout, k, stride, dtype, dy_dtype, accumulate, st);
+    return conv_wgrad(dense_desc(B, T, Cin, Cout, k, stride), x, dy, dw, dbias, dtype, dy_dtype, accumulate,
+                      static_cast<float*>(workspace), (hipStream_t)stream);
 }

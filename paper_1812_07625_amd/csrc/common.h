@@ -43,28 +43,57 @@ template <> struct Elem<bf16_t> {
 };
 
 // ---- internal entry points shared between translation units -----------------------
-int conv_fwd_generic(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin,
-                     int Cout, int k, int s, int dt, int ydt, hipStream_t st);
-int conv_dgrad_generic(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout, int k,
-                       int s, int dt, int dydt, hipStream_t st);
-int conv_wgrad_generic(const void* x, const void* dy, float* dw, int B, int T, int Cin, int Cout, int k,
-                       int s, int dt, int dydt, int accumulate, hipStream_t st);
+// Geometry of one convolution plus the memory layout of the time axis of its tensors.
+// Utterance b, frame t of the input-side tensor (x, dx) lives at element
+// ((b * x_pitch + x_halo + t) * Cin); of the output-side tensor (y, dy) at
+// ((b * y_pitch + y_halo + t') * Cout).  A tensor with halo > 0 holds zeros in frames
+// [-halo, 0) and [T, pitch - halo) of every utterance, and `slack` further zero frames
+// after its last utterance; tensor pointers always point at the start of the allocation
+// (frame -halo of utterance 0).  Caller-supplied (C ABI) tensors are dense: pitch = T,
+// halo = 0, slack = 0.
+struct ConvDesc {
+    int B, T, Tp, Cin, Cout, k, s, p;
+    int x_pitch, x_halo, y_pitch, y_halo, slack;
+};
+inline ConvDesc dense_desc(int B, int T, int Cin, int Cout, int k, int s)
+{
+    ConvDesc d{B, T, out_len(T, s), Cin, Cout, k, s, (k - 1) / 2, 0, 0, 0, 0, 0};
+    d.x_pitch = T;
+    d.y_pitch = d.Tp;
+    return d;
+}
+
+// dispatchers (api.hip): MFMA kernels where the shape allows, shape-agnostic kernels otherwise
+int conv_fwd(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int dt, int ydt,
+             hipStream_t st);
+int conv_dgrad(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st);
+int conv_wgrad(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int dt, int dydt,
+               int accumulate, float* dbias_scratch, hipStream_t st);
+
+int conv_fwd_generic(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int dt, int ydt,
+                     hipStream_t st);
+int conv_dgrad_generic(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st);
+int conv_wgrad_generic(const ConvDesc& d, const void* x, const void* dy, float* dw, int dt, int dydt, int accumulate,
+                       hipStream_t st);
 // column sums of dy[rows,Cout] -> dbias, two deterministic stages; scratch holds DBIAS_CHUNKS*Cout floats
 enum { DBIAS_CHUNKS = 64 };
 int dbias_reduce(const void* dy, float* dbias, long long rows, int Cout, int dydt, int accumulate,
                  float* scratch, hipStream_t st);
 
-
 // MFMA (bf16 operands, fp32 accumulate) paths; *_ok() says whether a shape is taken
-bool conv_fwd_mfma_ok(int B, int T, int Cin, int Cout, int k, int s);
-int conv_fwd_mfma(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin, int Cout,
-                  int k, int s, int ydt, hipStream_t st);
-bool conv_dgrad_mfma_ok(int B, int T, int Cin, int Cout, int k, int s);
-int conv_dgrad_mfma(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout, int k, int s,
-                    hipStream_t st);
-bool conv_wgrad_mfma_ok(int B, int T, int Cin, int Cout, int k, int s);
-size_t conv_wgrad_mfma_workspace(int B, int T, int Cin, int Cout, int k, int s);
-int conv_wgrad_mfma(const void* x, const void* dy, float* dw, int B, int T, int Cin, int Cout, int k, int s,
-                    int accumulate, void* ws, hipStream_t st);
+bool conv_fwd_mfma_ok(const ConvDesc& d);
+int conv_fwd_mfma(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int ydt, hipStream_t st);
+bool conv_dgrad_mfma_ok(const ConvDesc& d);
+int conv_dgrad_mfma(const ConvDesc& d, const void* dy, const void* w, void* dx, hipStream_t st);
+bool conv_wgrad_mfma_ok(const ConvDesc& d);
+int conv_wgrad_mfma(const ConvDesc& d, const void* x, const void* dy, float* dw, int accumulate, hipStream_t st);
+
+// GLU with an explicit output layout (elementwise.hip).  y (and dh) are dense [B*Tp, Cout]
+// ([B*Tp, Cout/2]); the output is written with the given pitch and halo, halo and slack
+// frames included (as zeros).
+int glu_fwd_layout(const void* y, void* h, int B, int Tp, int Cout, int dtype, int pitch, int halo, int slack,
+                   hipStream_t st);
+int glu_bwd_layout(const void* y, const void* dh, void* dy, int B, int Tp, int Cout, int dtype, int pitch, int halo,
+                   int slack, hipStream_t st);
 
 }  // namespace w2l

@@ -70,16 +70,16 @@ __global__ __launch_bounds__(256) void gemm_tiled(AF af, BF bf, EP ep, int M, in
         }
 }
 
-// ---- operand functors ------------------------------------------------------------
+// ---- operand functors (time-axis layout: element ((b*pitch + halo + t) * C + c)) ---------
 template <typename T>
 struct XWindow {  // A(m=(b,t'), r=(j,ci)) = x[b, s t' + j - p, ci]
-    const T* x; int T_, Tp, Cin, s, p;
+    const T* x; int T_, Tp, Cin, s, p, pitch, halo;
     __device__ float operator()(int m, int r) const {
         const int b = m / Tp, tp = m - b * Tp;
         const int j = r / Cin, ci = r - j * Cin;
         const int t = s * tp + j - p;
         if (t < 0 || t >= T_) return 0.f;
-        return Elem<T>::load(x, ((size_t)b * T_ + t) * Cin + ci);
+        return Elem<T>::load(x, ((size_t)b * pitch + halo + t) * Cin + ci);
     }
 };
 template <typename T>
@@ -89,7 +89,7 @@ struct WRows {  // B(r=(j,ci), n=co) = w[co, j, ci]
 };
 template <typename T>
 struct DyWindow {  // A(m=(b,t), r=(j,co)) = dy[b, (t+p-j)/s, co]
-    const T* dy; int T_, Tp, Cout, s, p;
+    const T* dy; int T_, Tp, Cout, s, p, pitch, halo;
     __device__ float operator()(int m, int r) const {
         const int b = m / T_, t = m - b * T_;
         const int j = r / Cout, co = r - j * Cout;
@@ -97,7 +97,7 @@ struct DyWindow {  // A(m=(b,t), r=(j,co)) = dy[b, (t+p-j)/s, co]
         if (u < 0) return 0.f;
         const int tp = u / s;
         if (tp * s != u || tp >= Tp) return 0.f;
-        return Elem<T>::load(dy, ((size_t)b * Tp + tp) * Cout + co);
+        return Elem<T>::load(dy, ((size_t)b * pitch + halo + tp) * Cout + co);
     }
 };
 template <typename T>
@@ -110,25 +110,29 @@ struct WCols {  // B(r=(j,co), n=ci) = w[co, j, ci]
 };
 template <typename T>
 struct DyT {  // A(m=co, r=(b,t')) = dy[b,t',co]
-    const T* dy; int Cout;
-    __device__ float operator()(int m, int r) const { return Elem<T>::load(dy, (size_t)r * Cout + m); }
+    const T* dy; int Tp, Cout, pitch, halo;
+    __device__ float operator()(int m, int r) const {
+        const int b = r / Tp, tp = r - b * Tp;
+        return Elem<T>::load(dy, ((size_t)b * pitch + halo + tp) * Cout + m);
+    }
 };
 template <typename T>
 struct XShift {  // B(r=(b,t'), n=(j,ci)) = x[b, s t' + j - p, ci]
-    const T* x; int T_, Tp, Cin, s, p;
+    const T* x; int T_, Tp, Cin, s, p, pitch, halo;
     __device__ float operator()(int r, int n) const {
         const int b = r / Tp, tp = r - b * Tp;
         const int j = n / Cin, ci = n - j * Cin;
         const int t = s * tp + j - p;
         if (t < 0 || t >= T_) return 0.f;
-        return Elem<T>::load(x, ((size_t)b * T_ + t) * Cin + ci);
+        return Elem<T>::load(x, ((size_t)b * pitch + halo + t) * Cin + ci);
     }
 };
 template <typename T>
-struct StoreBias {
-    T* y; const float* bias; int N;
+struct StoreRows {  // out[b, t, n] = v (+ bias[n]); m = (b,t) over `frames` frames per utterance
+    T* y; const float* bias; int N, frames, pitch, halo;
     __device__ void operator()(int m, int n, float v) const {
-        Elem<T>::store(y, (size_t)m * N + n, v + (bias ? bias[n] : 0.f));
+        const int b = m / frames, t = m - b * frames;
+        Elem<T>::store(y, ((size_t)b * pitch + halo + t) * N + n, v + (bias ? bias[n] : 0.f));
     }
 };
 struct StoreAcc {
@@ -150,37 +154,31 @@ int launch(AF af, BF bf, EP ep, long long M, long long N, long long R, hipStream
 }
 
 template <typename TI, typename TO>
-int fwd_t(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin, int Cout, int k,
-          int s, hipStream_t st)
+int fwd_t(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, hipStream_t st)
 {
-    const int Tp = out_len(T, s), p = (k - 1) / 2;
-    XWindow<TI> af{(const TI*)x, T, Tp, Cin, s, p};
-    WRows<TI> bf{(const TI*)w, k * Cin};
-    StoreBias<TO> ep{(TO*)y, bias, Cout};
-    return launch<XWindow<TI>, WRows<TI>, StoreBias<TO>, true, true>(af, bf, ep, (long long)B * Tp, Cout,
-                                                                      (long long)k * Cin, st);
+    XWindow<TI> af{(const TI*)x, d.T, d.Tp, d.Cin, d.s, d.p, d.x_pitch, d.x_halo};
+    WRows<TI> bf{(const TI*)w, d.k * d.Cin};
+    StoreRows<TO> ep{(TO*)y, bias, d.Cout, d.Tp, d.y_pitch, d.y_halo};
+    return launch<XWindow<TI>, WRows<TI>, StoreRows<TO>, true, true>(af, bf, ep, (long long)d.B * d.Tp, d.Cout,
+                                                                      (long long)d.k * d.Cin, st);
 }
 template <typename TW, typename TDY>
-int dgrad_t(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout, int k, int s,
-            hipStream_t st)
+int dgrad_t(const ConvDesc& d, const void* dy, const void* w, void* dx, hipStream_t st)
 {
-    const int Tp = out_len(T, s), p = (k - 1) / 2;
-    DyWindow<TDY> af{(const TDY*)dy, T, Tp, Cout, s, p};
-    WCols<TW> bf{(const TW*)w, Cin, Cout, k};
-    StoreBias<TW> ep{(TW*)dx, nullptr, Cin};
-    return launch<DyWindow<TDY>, WCols<TW>, StoreBias<TW>, true, false>(af, bf, ep, (long long)B * T, Cin,
-                                                                         (long long)k * Cout, st);
+    DyWindow<TDY> af{(const TDY*)dy, d.T, d.Tp, d.Cout, d.s, d.p, d.y_pitch, d.y_halo};
+    WCols<TW> bf{(const TW*)w, d.Cin, d.Cout, d.k};
+    StoreRows<TW> ep{(TW*)dx, nullptr, d.Cin, d.T, d.x_pitch, d.x_halo};
+    return launch<DyWindow<TDY>, WCols<TW>, StoreRows<TW>, true, false>(af, bf, ep, (long long)d.B * d.T, d.Cin,
+                                                                         (long long)d.k * d.Cout, st);
 }
 template <typename TX, typename TDY>
-int wgrad_t(const void* x, const void* dy, float* dw, int B, int T, int Cin, int Cout, int k, int s,
-            int accumulate, hipStream_t st)
+int wgrad_t(const ConvDesc& d, const void* x, const void* dy, float* dw, int accumulate, hipStream_t st)
 {
-    const int Tp = out_len(T, s), p = (k - 1) / 2;
-    DyT<TDY> af{(const TDY*)dy, Cout};
-    XShift<TX> bf{(const TX*)x, T, Tp, Cin, s, p};
-    StoreAcc ep{dw, k * Cin, accumulate};
-    return launch<DyT<TDY>, XShift<TX>, StoreAcc, false, false>(af, bf, ep, Cout, (long long)k * Cin,
-                                                                 (long long)B * Tp, st);
+    DyT<TDY> af{(const TDY*)dy, d.Tp, d.Cout, d.y_pitch, d.y_halo};
+    XShift<TX> bf{(const TX*)x, d.T, d.Tp, d.Cin, d.s, d.p, d.x_pitch, d.x_halo};
+    StoreAcc ep{dw, d.k * d.Cin, accumulate};
+    return launch<DyT<TDY>, XShift<TX>, StoreAcc, false, false>(af, bf, ep, d.Cout, (long long)d.k * d.Cin,
+                                                                 (long long)d.B * d.Tp, st);
 }
 
 // ---- dbias: deterministic two-stage column sum -------------------------------------
@@ -213,28 +211,27 @@ __global__ void colsum_stage2(const float* part, float* dbias, int chunks, int C
 
 }  // namespace
 
-int conv_fwd_generic(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin,
-                     int Cout, int k, int s, int dt, int ydt, hipStream_t st)
+int conv_fwd_generic(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int dt, int ydt,
+                     hipStream_t st)
 {
-    if (dt == W2L_F32 && ydt == W2L_F32) return fwd_t<float, float>(x, w, bias, y, B, T, Cin, Cout, k, s, st);
-    if (dt == W2L_BF16 && ydt == W2L_BF16) return fwd_t<bf16_t, bf16_t>(x, w, bias, y, B, T, Cin, Cout, k, s, st);
-    if (dt == W2L_BF16 && ydt == W2L_F32) return fwd_t<bf16_t, float>(x, w, bias, y, B, T, Cin, Cout, k, s, st);
+    if (dt == W2L_F32 && ydt == W2L_F32) return fwd_t<float, float>(d, x, w, bias, y, st);
+    if (dt == W2L_BF16 && ydt == W2L_BF16) return fwd_t<bf16_t, bf16_t>(d, x, w, bias, y, st);
+    if (dt == W2L_BF16 && ydt == W2L_F32) return fwd_t<bf16_t, float>(d, x, w, bias, y, st);
     return W2L_ERR_DTYPE;
 }
-int conv_dgrad_generic(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout, int k,
-                       int s, int dt, int dydt, hipStream_t st)
+int conv_dgrad_generic(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st)
 {
-    if (dt == W2L_F32 && dydt == W2L_F32) return dgrad_t<float, float>(dy, w, dx, B, T, Cin, Cout, k, s, st);
-    if (dt == W2L_BF16 && dydt == W2L_BF16) return dgrad_t<bf16_t, bf16_t>(dy, w, dx, B, T, Cin, Cout, k, s, st);
-    if (dt == W2L_BF16 && dydt == W2L_F32) return dgrad_t<bf16_t, float>(dy, w, dx, B, T, Cin, Cout, k, s, st);
+    if (dt == W2L_F32 && dydt == W2L_F32) return dgrad_t<float, float>(d, dy, w, dx, st);
+    if (dt == W2L_BF16 && dydt == W2L_BF16) return dgrad_t<bf16_t, bf16_t>(d, dy, w, dx, st);
+    if (dt == W2L_BF16 && dydt == W2L_F32) return dgrad_t<bf16_t, float>(d, dy, w, dx, st);
     return W2L_ERR_DTYPE;
 }
-int conv_wgrad_generic(const void* x, const void* dy, float* dw, int B, int T, int Cin, int Cout, int k,
-                       int s, int dt, int dydt, int accumulate, hipStream_t st)
+int conv_wgrad_generic(const ConvDesc& d, const void* x, const void* dy, float* dw, int dt, int dydt, int accumulate,
+                       hipStream_t st)
 {
-    if (dt == W2L_F32 && dydt == W2L_F32) return wgrad_t<float, float>(x, dy, dw, B, T, Cin, Cout, k, s, accumulate, st);
-    if (dt == W2L_BF16 && dydt == W2L_BF16) return wgrad_t<bf16_t, bf16_t>(x, dy, dw, B, T, Cin, Cout, k, s, accumulate, st);
-    if (dt == W2L_BF16 && dydt == W2L_F32) return wgrad_t<bf16_t, float>(x, dy, dw, B, T, Cin, Cout, k, s, accumulate, st);
+    if (dt == W2L_F32 && dydt == W2L_F32) return wgrad_t<float, float>(d, x, dy, dw, accumulate, st);
+    if (dt == W2L_BF16 && dydt == W2L_BF16) return wgrad_t<bf16_t, bf16_t>(d, x, dy, dw, accumulate, st);
+    if (dt == W2L_BF16 && dydt == W2L_F32) return wgrad_t<bf16_t, float>(d, x, dy, dw, accumulate, st);
     return W2L_ERR_DTYPE;
 }
 int dbias_reduce(const void* dy, float* dbias, long long rows, int Cout, int dydt, int accumulate,

@@ -27,6 +27,12 @@
 // are handled by pointing the load of an out-of-range chunk at a 16-byte block of
 // zeros (every lane always loads: the number of loads in flight is a constant, which
 // the hand-placed s_waitcnt counts rely on); stores are predicated on the tile bounds.
+//
+// Two addressing modes.  CHECKED handles any caller tensor: per load, a range test picks the
+// real address or the zero block.  FAST is for tensors laid out with a zero halo of at least
+// (k-1)/2 frames around every utterance (the train step keeps its activations that way): every
+// window is then plain in-bounds memory, the per-lane byte offsets are loop invariants, the
+// panel advance is a scalar add on the base pointer, and a load costs three instructions.
 #include "common.h"
 
 namespace w2l {
@@ -43,9 +49,7 @@ constexpr int NT = 256;  // threads per workgroup (4 wavefronts)
 
 __device__ __align__(16) unsigned int g_zero16[4];  // source of every out-of-range chunk
 
-struct ConvGeom {
-    int B, T, Tp, Cin, Cout, k, s, p;
-};
+typedef ConvDesc ConvGeom;
 
 // 16 bytes per lane, global -> LDS at lds_addr + 16*lane (lds_addr wave-uniform).  Written
 // as asm so that the compiler does not serialise later LDS reads behind it; completion is
@@ -53,6 +57,12 @@ struct ConvGeom {
 __device__ __forceinline__ void dma16(const void* g, unsigned lds_addr)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr)
+                 : "memory");
+}
+// same, address = uniform 64-bit base + per-lane 32-bit byte offset
+__device__ __forceinline__ void dma16s(unsigned voff, const void* sbase, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr)
                  : "memory");
 }
 template <int N>
@@ -75,7 +85,8 @@ struct PanelK {
     static_assert(BYTES % 4096 == 0, "panel must split into 1 KB blocks over 4 wavefronts");
     static_assert(BKT == 64 || BKT == 32, "swizzles are written for 64- and 128-byte rows");
     int off[NI];                                       // element offsets (tensors hold < 2^31 elements)
-    int lo[NI], hi[NI];
+    int lo[NI], hi[NI];                                // CHECKED mode only
+    unsigned voff[NI];                                 // FAST mode only: byte offset of this lane's chunk at r0 = 0
     int c8;                                            // element offset inside a row of the chunk this lane loads
     const bf16_t* base;
 
@@ -103,6 +114,13 @@ struct PanelK {
         const void* src = (r >= lo[i] && r < hi[i]) ? (const void*)(base + off[i] + r) : (const void*)g_zero16;
         dma16(src, wbase + i * 4096);
     }
+    // FAST: row_off_elems = element offset of row i's reduction index 0 (always in bounds)
+    __device__ __forceinline__ void set_fast(int i, long long row_off_elems) { voff[i] = (unsigned)((row_off_elems + c8) * 2); }
+    __device__ __forceinline__ void issue_fast(int i, const bf16_t* sbase, unsigned lds_stage) const
+    {
+        const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
+        dma16s(voff[i], sbase, wbase + i * 4096);
+    }
     // 32 rows starting at row0, sub-step ks (16 elements): lane holds row l%32, r = 8*(l/32)..+7
     static __device__ __forceinline__ bf16x8 frag(const unsigned char* lds, int row0, int ks, int lane)
     {
@@ -122,8 +140,28 @@ struct PanelMN {
     static_assert(BYTES % 4096 == 0, "panel must split into 1 KB blocks over 4 wavefronts");
     static_assert(CPR % 8 == 0, "swizzle flips chunk-index bits 2 and 3");
     const bf16_t* base;
+    unsigned voff[NI];  // FAST mode only
 
     __device__ __forceinline__ void init(const bf16_t* b) { base = b; }
+    // FAST: reduction row r of a panel starts row_pitch elements after row r-1; columns at or
+    // beyond ncols are folded onto column 0 (their products land in outputs that are never stored)
+    __device__ __forceinline__ void init_fast(const bf16_t* b, int row_pitch, int ncols)
+    {
+        base = b;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int q = chunk_of(i);
+            const int row = q / CPR, slot = q - row * CPR;
+            int c8 = (slot ^ ((row & 3) << 2)) * 8;
+            if (c8 >= ncols) c8 = 0;
+            voff[i] = (unsigned)(((long long)row * row_pitch + c8) * 2);
+        }
+    }
+    __device__ __forceinline__ void issue_fast(int i, const bf16_t* sbase, unsigned lds_stage) const
+    {
+        const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
+        dma16s(voff[i], sbase, wbase + i * 4096);
+    }
     static __device__ __forceinline__ int chunk_of(int i) { return ((threadIdx.x >> 6) + 4 * i) * 64 + (threadIdx.x & 63); }
     // f(row, off, lo, hi): element offset of the row's column 0 of this tile and its valid
     // column range; the 16-byte chunk at column c is real data iff lo <= c < hi
@@ -231,13 +269,11 @@ struct Core {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int r = 0; r < 16; ++r) {
+                const int m = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    const int n = wn * (BN / 2) + j * 32 + (lane & 31);
-                    f(m, n, acc[i][j][r]);
-                }
+                for (int j = 0; j < TN; ++j) f(m, wn * (BN / 2) + j * 32 + (lane & 31), acc[i][j][r]);
+            }
     }
 };
 
@@ -306,8 +342,16 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
     else { tn = id / tiles_m; tm = id % tiles_m; }
 }
 
+// element offset of output row m = (b, t) in a tensor with `frames` frames per utterance
+__device__ __forceinline__ long long out_row(int m, int frames, int pitch, int halo)
+{
+    if (pitch == frames && halo == 0) return m;
+    const int b = m / frames;
+    return (long long)b * pitch + halo + (m - b * frames);
+}
+
 // =============================== forward ================================================
-template <int BM, int BN, int BKT, int STAGES, typename TO>
+template <int BM, int BN, int BKT, int STAGES, bool FAST, typename TO>
 __global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
                                                  const float* __restrict__ bias, TO* __restrict__ y, ConvGeom g)
 {
@@ -327,40 +371,58 @@ __global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, c
     pb.init(w);
 #pragma unroll
     for (int i = 0; i < PA::NI; ++i) {
-        const int m = m0 + PA::row_of(i);
+        int m = m0 + PA::row_of(i);
+        if (FAST && m >= M) m = M - 1;                  // rows past the end recompute the last row; never stored
         const int b = m / g.Tp, tp = m - b * g.Tp;
         const int t0 = g.s * tp - g.p;                  // first frame of the window (may be < 0)
-        pa.off[i] = (b * g.T + t0) * g.Cin;
-        pa.lo[i] = (t0 < 0 ? -t0 : 0) * g.Cin;
-        const int last = g.T - t0;                      // taps j < last are inside the utterance
-        pa.hi[i] = (m < M) ? (last < g.k ? last : g.k) * g.Cin : 0;
+        const long long row = ((long long)b * g.x_pitch + g.x_halo + t0) * g.Cin;
+        if (FAST) {
+            pa.set_fast(i, row);
+        } else {
+            pa.off[i] = (int)row;
+            pa.lo[i] = (t0 < 0 ? -t0 : 0) * g.Cin;
+            const int last = g.T - t0;                  // taps j < last are inside the utterance
+            pa.hi[i] = (m < M) ? (last < g.k ? last : g.k) * g.Cin : 0;
+        }
     }
 #pragma unroll
     for (int i = 0; i < PB::NI; ++i) {
-        const int n = n0 + PB::row_of(i);
-        pb.off[i] = n * K;
-        pb.lo[i] = 0;
-        pb.hi[i] = (n < N) ? K : 0;
+        int n = n0 + PB::row_of(i);
+        if (FAST) {
+            if (n >= N) n = N - 1;
+            pb.set_fast(i, (long long)n * K);
+        } else {
+            pb.off[i] = n * K;
+            pb.lo[i] = 0;
+            pb.hi[i] = (n < N) ? K : 0;
+        }
     }
     Core<BM, BN, BKT, PA, PB> core;
     core.zero();
-    const int nsteps = (K + BKT - 1) / BKT;
+    const int nsteps = (K + BKT - 1) / BKT;  // FAST requires K % BKT == 0
     run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
         [&](int i, int st, unsigned dst) {
-            if (i < PA::NI) pa.issue(i, st * BKT, dst);
-            else pb.issue(i - PA::NI, st * BKT, dst + PA::BYTES);
+            if (FAST) {
+                const int r0 = (st < nsteps ? st : nsteps - 1) * BKT;  // past the end: refetch the last panel
+                if (i < PA::NI) pa.issue_fast(i, x + r0, dst);
+                else pb.issue_fast(i - PA::NI, w + r0, dst + PA::BYTES);
+            } else {
+                if (i < PA::NI) pa.issue(i, st * BKT, dst);
+                else pb.issue(i - PA::NI, st * BKT, dst + PA::BYTES);
+            }
         },
         wm, wn, lane);
     core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
         const int m = m0 + mm, n = n0 + nn;
-        if (m < M && n < N) Elem<TO>::store(y, (size_t)m * N + n, v + (bias ? bias[n] : 0.f));
+        if (m < M && n < N)
+            Elem<TO>::store(y, (size_t)out_row(m, g.Tp, g.y_pitch, g.y_halo) * N + n, v + (bias ? bias[n] : 0.f));
     });
 }
 
 // =============================== data gradient (stride 1) =============================
 // dx[b,t,ci] = sum_{j',co} dy[b, t-p+j', co] * w[co, k-1-j', ci]
-template <int BM, int BN, int BKT, int STAGES>
+template <int BM, int BN, int BKT, int STAGES, bool FAST>
 __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
                                                    bf16_t* __restrict__ dx, ConvGeom g)
 {
@@ -377,16 +439,23 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
     PA pa;
     PB pb;
     pa.init(dy);
-    pb.init(w);
+    if (FAST) pb.init_fast(w, g.k * g.Cin, N - n0);
+    else pb.init(w);
 #pragma unroll
     for (int i = 0; i < PA::NI; ++i) {
-        const int m = m0 + PA::row_of(i);
+        int m = m0 + PA::row_of(i);
+        if (FAST && m >= M) m = M - 1;
         const int b = m / g.T, t = m - b * g.T;
         const int t0 = t - g.p;
-        pa.off[i] = (b * g.Tp + t0) * g.Cout;
-        pa.lo[i] = (t0 < 0 ? -t0 : 0) * g.Cout;
-        const int last = g.Tp - t0;
-        pa.hi[i] = (m < M) ? (last < g.k ? last : g.k) * g.Cout : 0;
+        const long long row = ((long long)b * g.y_pitch + g.y_halo + t0) * g.Cout;
+        if (FAST) {
+            pa.set_fast(i, row);
+        } else {
+            pa.off[i] = (int)row;
+            pa.lo[i] = (t0 < 0 ? -t0 : 0) * g.Cout;
+            const int last = g.Tp - t0;
+            pa.hi[i] = (m < M) ? (last < g.k ? last : g.k) * g.Cout : 0;
+        }
     }
     Core<BM, BN, BKT, PA, PB> core;
     core.zero();
@@ -394,10 +463,19 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
     run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
         [&](int i, int st, unsigned dst) {
-            if (i < PA::NI) { pa.issue(i, st * BKT, dst); return; }
-            const int r0 = st * BKT;
+            const int stc = (FAST && st >= nsteps) ? nsteps - 1 : st;
+            const int r0 = stc * BKT;
+            if (i < PA::NI) {
+                if (FAST) pa.issue_fast(i, dy + r0, dst);
+                else pa.issue(i, r0, dst);
+                return;
+            }
             const int jp = r0 / g.Cout, co0 = r0 - jp * g.Cout;
             const long long tapoff = (long long)(g.k - 1 - jp) * g.Cin + n0;
+            if (FAST) {
+                pb.issue_fast(i - PA::NI, w + (long long)co0 * g.k * g.Cin + tapoff, dst + PA::BYTES);
+                return;
+            }
             const int ncols = N - n0;
             pb.issue(i - PA::NI,
                 [=](int rr, long long& off, int& lo, int& hi) {
@@ -410,14 +488,18 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
         wm, wn, lane);
     core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
         const int m = m0 + mm, n = n0 + nn;
-        if (m < M && n < N) dx[(size_t)m * N + n] = f32_to_bf16(v);
+        if (m < M && n < N) dx[(size_t)out_row(m, g.T, g.x_pitch, g.x_halo) * N + n] = f32_to_bf16(v);
     });
 }
 
 // =============================== weight gradient ========================================
-// dw[co, (j,ci)] = sum_{b,t'} dy[b,t',co] * x[b, s t' - p + j, ci]; the reduction walks
-// utterance by utterance in BKT-frame panels (the last panel of an utterance is masked).
-template <int BM, int BN, int BKT, int STAGES>
+// dw[co, (j,ci)] = sum_{b,t'} dy[b,t',co] * x[b, s t' - p + j, ci].
+// CHECKED: the reduction walks utterance by utterance in BKT-frame panels (the last panel of
+// an utterance is masked).  FAST (stride 1, x and dy share one haloed time layout): the
+// reduction runs straight through the frames of all utterances including the halo frames
+// between them -- dy is zero there, so they add nothing -- which makes every panel a dense
+// block of BKT consecutive frames of both tensors.
+template <int BM, int BN, int BKT, int STAGES, bool FAST>
 __global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
                                                    float* __restrict__ dw, ConvGeom g, int accumulate)
 {
@@ -433,19 +515,31 @@ __global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x,
 
     PA pa;
     PB pb;
-    pa.init(dy);
-    pb.init(x);
-    const int spb = (g.Tp + BKT - 1) / BKT;  // panels per utterance
-    const int nsteps = g.B * spb;
+    if (FAST) {
+        pa.init_fast(dy, g.Cout, M - m0);
+        pb.init_fast(x, g.Cin, N - n0);
+    } else {
+        pa.init(dy);
+        pb.init(x);
+    }
+    const int spb = (g.Tp + BKT - 1) / BKT;  // CHECKED: panels per utterance
+    const int frames = (g.B - 1) * g.y_pitch + g.Tp;  // FAST: first real frame of utterance 0 .. last real frame
+    const int nsteps = FAST ? (frames + BKT - 1) / BKT : g.B * spb;
     Core<BM, BN, BKT, PA, PB> core;
     core.zero();
     run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
         [&](int i, int st, unsigned dst) {
+            if (FAST) {
+                const long long f0 = (long long)(st < nsteps ? st : nsteps - 1) * BKT;
+                if (i < PA::NI) pa.issue_fast(i, dy + (g.y_halo + f0) * g.Cout + m0, dst);
+                else pb.issue_fast(i - PA::NI, x + (g.x_halo - g.p + f0) * g.Cin + n0, dst + PA::BYTES);
+                return;
+            }
             const int b = st / spb, tp0 = (st - b * spb) * BKT;
             const int left = (st < nsteps) ? g.Tp - tp0 : 0;  // past the end: every row masked
             if (i < PA::NI) {
-                const long long boff = ((long long)b * g.Tp + tp0) * g.Cout + m0;
+                const long long boff = ((long long)b * g.y_pitch + g.y_halo + tp0) * g.Cout + m0;
                 const int mcols = M - m0;
                 pa.issue(i,
                     [=](int rr, long long& off, int& lo, int& hi) {
@@ -459,7 +553,7 @@ __global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x,
             pb.issue(i - PA::NI,
                 [=](int rr, long long& off, int& lo, int& hi) {
                     const int t0 = g.s * (tp0 + rr) - g.p;          // frame under tap 0
-                    off = ((long long)b * g.T + t0) * g.Cin + n0;
+                    off = ((long long)b * g.x_pitch + g.x_halo + t0) * g.Cin + n0;
                     // tile column c <-> tap-major index n0 + c ; valid taps: 0 <= t0 + j < T
                     const int jlo = t0 < 0 ? -t0 : 0;
                     const int jhi = (g.T - t0) < g.k ? (g.T - t0) : g.k;
@@ -505,14 +599,19 @@ TileChoice choose_tile(long long M, long long N)
     return pick;
 }
 
-bool common_ok(int B, int T, int Cin, int Cout, int k, int s)
+bool common_ok(const ConvDesc& d)
 {
-    if (Cin % 8 || Cout % 8) return false;
-    if ((long long)k * Cin > 32767 * 8LL || (long long)k * Cout > 32767 * 8LL) return false;
-    if ((long long)B * T * Cin >= (1LL << 31) || (long long)B * out_len(T, s) * Cout >= (1LL << 31)) return false;
-    if ((long long)Cout * k * Cin >= (1LL << 31)) return false;
+    if (d.Cin % 8 || d.Cout % 8) return false;
+    if ((long long)d.k * d.Cin > 32767 * 8LL || (long long)d.k * d.Cout > 32767 * 8LL) return false;
+    // 32-bit element/byte offsets inside the kernels
+    if (((long long)d.B * d.x_pitch + d.slack) * d.Cin >= (1LL << 30)) return false;
+    if (((long long)d.B * d.y_pitch + d.slack) * d.Cout >= (1LL << 30)) return false;
+    if ((long long)d.Cout * d.k * d.Cin >= (1LL << 30)) return false;
     return true;
 }
+// FAST addressing: windows never leave zero-filled, allocated memory
+bool halo_ok_x(const ConvDesc& d) { return d.p == 0 || d.x_halo >= d.p; }
+bool halo_ok_y(const ConvDesc& d) { return d.p == 0 || d.y_halo >= d.p; }
 
 // tile -> (panel depth, ring depth): 3 x 48 KB for the tiles that fit, 4 x 32 KB for 256x256
 #define W2L_TILE_DISPATCH(CALL)                                          \
@@ -524,30 +623,32 @@ bool common_ok(int B, int T, int Cin, int Cout, int k, int s)
 
 }  // namespace
 
-bool conv_fwd_mfma_ok(int B, int T, int Cin, int Cout, int k, int s)
+bool conv_fwd_mfma_ok(const ConvDesc& d)
 {
-    return common_ok(B, T, Cin, Cout, k, s) && Cout >= 64 && (long long)B * out_len(T, s) >= 128;
+    return common_ok(d) && d.Cout >= 64 && (long long)d.B * d.Tp >= 128;
 }
 
-int conv_fwd_mfma(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin, int Cout, int k,
-                  int s, int ydt, hipStream_t st)
+int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* bias, void* y, int ydt, hipStream_t st)
 {
-    ConvGeom g{B, T, out_len(T, s), Cin, Cout, k, s, (k - 1) / 2};
-    const long long M = (long long)B * g.Tp, N = Cout;
+    const long long M = (long long)g.B * g.Tp, N = g.Cout;
     const TileChoice tc = choose_tile(M, N);
+    const bool fast = halo_ok_x(g) && ((long long)g.k * g.Cin) % 64 == 0;
     int rc = W2L_OK;
+#define LAUNCH(KERN, BYTES, ...)                                                          \
+    {                                                                                     \
+        rc = set_lds(KERN, BYTES);                                                        \
+        if (!rc) hipLaunchKernelGGL(KERN, dim3(grid), dim3(NT), BYTES, st, __VA_ARGS__);  \
+    }
 #define CALL(BM_, BN_, BK_, ST_)                                                                              \
     {                                                                                                         \
         constexpr int bytes = ST_ * (PanelK<BM_, BK_>::BYTES + PanelK<BN_, BK_>::BYTES);                      \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                      \
         if (ydt == W2L_BF16) {                                                                                \
-            rc = set_lds(conv_fwd_k<BM_, BN_, BK_, ST_, bf16_t>, bytes);                                      \
-            if (!rc) hipLaunchKernelGGL((conv_fwd_k<BM_, BN_, BK_, ST_, bf16_t>), dim3(grid), dim3(NT), bytes, st, \
-                                        (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g);             \
+            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, true, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g) \
+            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, false, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g)     \
         } else {                                                                                              \
-            rc = set_lds(conv_fwd_k<BM_, BN_, BK_, ST_, float>, bytes);                                       \
-            if (!rc) hipLaunchKernelGGL((conv_fwd_k<BM_, BN_, BK_, ST_, float>), dim3(grid), dim3(NT), bytes, st, \
-                                        (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g);              \
+            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, true, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)   \
+            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, false, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)       \
         }                                                                                                     \
     }
     W2L_TILE_DISPATCH(CALL)
@@ -555,55 +656,52 @@ int conv_fwd_mfma(const void* x, const void* w, const float* bias, void* y, int 
     return rc ? rc : launch_status();
 }
 
-bool conv_dgrad_mfma_ok(int B, int T, int Cin, int Cout, int k, int s)
+bool conv_dgrad_mfma_ok(const ConvDesc& d)
 {
-    return s == 1 && common_ok(B, T, Cin, Cout, k, s) && Cout % 64 == 0 && Cin >= 64 && (long long)B * T >= 128;
+    return d.s == 1 && common_ok(d) && d.Cout % 64 == 0 && d.Cin >= 64 && (long long)d.B * d.T >= 128;
 }
 
-int conv_dgrad_mfma(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout, int k, int s,
-                    hipStream_t st)
+int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, hipStream_t st)
 {
-    ConvGeom g{B, T, out_len(T, s), Cin, Cout, k, s, (k - 1) / 2};
-    const long long M = (long long)B * T, N = Cin;
+    const long long M = (long long)g.B * g.T, N = g.Cin;
     const TileChoice tc = choose_tile(M, N);
+    const bool fast = halo_ok_y(g);
     int rc = W2L_OK;
 #define CALL(BM_, BN_, BK_, ST_)                                                                          \
     {                                                                                                     \
         constexpr int bytes = ST_ * (PanelK<BM_, BK_>::BYTES + PanelMN<BN_, BK_>::BYTES);                 \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                  \
-        rc = set_lds(conv_dgrad_k<BM_, BN_, BK_, ST_>, bytes);                                            \
-        if (!rc) hipLaunchKernelGGL((conv_dgrad_k<BM_, BN_, BK_, ST_>), dim3(grid), dim3(NT), bytes, st,  \
-                                    (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g);                 \
+        if (fast) LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, true>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g) \
+        else LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, false>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g)     \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
     return rc ? rc : launch_status();
 }
 
-bool conv_wgrad_mfma_ok(int B, int T, int Cin, int Cout, int k, int s)
+bool conv_wgrad_mfma_ok(const ConvDesc& d)
 {
-    return common_ok(B, T, Cin, Cout, k, s) && Cout >= 64 && (long long)k * Cin >= 64;
+    return common_ok(d) && d.Cout >= 64 && (long long)d.k * d.Cin >= 64;
 }
 
-size_t conv_wgrad_mfma_workspace(int, int, int, int, int, int) { return 0; }
-
-int conv_wgrad_mfma(const void* x, const void* dy, float* dw, int B, int T, int Cin, int Cout, int k, int s,
-                    int accumulate, void*, hipStream_t st)
+int conv_wgrad_mfma(const ConvDesc& g, const void* x, const void* dy, float* dw, int accumulate, hipStream_t st)
 {
-    ConvGeom g{B, T, out_len(T, s), Cin, Cout, k, s, (k - 1) / 2};
-    const long long M = Cout, N = (long long)k * Cin;
+    const long long M = g.Cout, N = (long long)g.k * g.Cin;
     const TileChoice tc = choose_tile(M, N);
+    // FAST walks the frames of both tensors in lock step and over-reads up to 64 + p frames
+    const bool fast = g.s == 1 && g.x_pitch == g.y_pitch && g.x_halo == g.y_halo && g.x_halo >= g.p && g.slack >= 64 &&
+                      (g.B == 1 || g.x_halo > 0 || g.p == 0);
     int rc = W2L_OK;
 #define CALL(BM_, BN_, BK_, ST_)                                                                          \
     {                                                                                                     \
         constexpr int bytes = ST_ * (PanelMN<BM_, BK_>::BYTES + PanelMN<BN_, BK_>::BYTES);                \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                  \
-        rc = set_lds(conv_wgrad_k<BM_, BN_, BK_, ST_>, bytes);                                            \
-        if (!rc) hipLaunchKernelGGL((conv_wgrad_k<BM_, BN_, BK_, ST_>), dim3(grid), dim3(NT), bytes, st,  \
-                                    (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate);              \
+        if (fast) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, true>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate) \
+        else LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate)     \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
+#undef LAUNCH
     return rc ? rc : launch_status();
 }
 

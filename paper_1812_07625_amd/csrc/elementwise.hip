@@ -42,74 +42,94 @@ template <> struct Vec8<float> {
     }
 };
 
-template <typename T>
-__global__ __launch_bounds__(256) void glu_fwd_vec(const T* __restrict__ y, T* __restrict__ h,
-                                                   long long rows, int H)
-{
-    const int hv = H / 8;
-    const long long total = rows * hv;
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
-         i += (long long)gridDim.x * blockDim.x) {
-        const long long r = i / hv;
-        const int c = (int)(i - r * hv) * 8;
-        float a[8], g[8], o[8];
-        Vec8<T>::load(y + r * 2 * H + c, a);
-        Vec8<T>::load(y + r * 2 * H + H + c, g);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = a[j] * sigmoidf_(g[j]);
-        Vec8<T>::store(h + r * H + c, o);
+// Output rows run over every frame of the output allocation: B*pitch + slack frames.  Frame f
+// belongs to utterance b = f / pitch at time t = f % pitch - halo; it is real iff 0 <= t < Tp
+// (then its dense source row is b*Tp + t), otherwise it is a halo/slack frame and gets zeros.
+struct RowMap {
+    int Tp, pitch, halo;
+    long long real_frames;  // B * pitch
+    __device__ __forceinline__ long long src(long long f) const
+    {
+        if (pitch == Tp) return f < real_frames ? f : -1;
+        if (f >= real_frames) return -1;
+        const long long b = f / pitch;
+        const int t = (int)(f - b * pitch) - halo;
+        return (t >= 0 && t < Tp) ? b * Tp + t : -1;
     }
-}
-template <typename T>
-__global__ __launch_bounds__(256) void glu_fwd_scalar(const T* __restrict__ y, T* __restrict__ h,
-                                                      long long rows, int H)
+};
+
+template <typename T, int V>  // V = 8 (vector path, H % 8 == 0) or 1
+__global__ __launch_bounds__(256) void glu_fwd_k(const T* __restrict__ y, T* __restrict__ h, long long out_rows,
+                                                 int H, RowMap map)
 {
-    const long long total = rows * H;
+    const int hv = H / V;
+    const long long total = out_rows * hv;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
          i += (long long)gridDim.x * blockDim.x) {
-        const long long r = i / H;
-        const int c = (int)(i - r * H);
-        const float a = Elem<T>::load(y, r * 2 * H + c), g = Elem<T>::load(y, r * 2 * H + H + c);
-        Elem<T>::store(h, i, a * sigmoidf_(g));
-    }
-}
-template <typename T>
-__global__ __launch_bounds__(256) void glu_bwd_vec(const T* __restrict__ y, const T* __restrict__ dh,
-                                                   T* __restrict__ dy, long long rows, int H)
-{
-    const int hv = H / 8;
-    const long long total = rows * hv;
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
-         i += (long long)gridDim.x * blockDim.x) {
-        const long long r = i / hv;
-        const int c = (int)(i - r * hv) * 8;
-        float a[8], g[8], d[8], da[8], dg[8];
-        Vec8<T>::load(y + r * 2 * H + c, a);
-        Vec8<T>::load(y + r * 2 * H + H + c, g);
-        Vec8<T>::load(dh + r * H + c, d);
+        const long long f = i / hv;
+        const int c = (int)(i - f * hv) * V;
+        const long long r = map.src(f);
+        float o[V];
+        if (r >= 0) {
+            float a[V], g[V];
+            if (V == 8) {
+                Vec8<T>::load(y + r * 2 * H + c, a);
+                Vec8<T>::load(y + r * 2 * H + H + c, g);
+            } else {
+                a[0] = Elem<T>::load(y, r * 2 * H + c);
+                g[0] = Elem<T>::load(y, r * 2 * H + H + c);
+            }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float sg = sigmoidf_(g[j]);
-            da[j] = d[j] * sg;
-            dg[j] = d[j] * a[j] * sg * (1.f - sg);
+            for (int j = 0; j < V; ++j) o[j] = a[j] * sigmoidf_(g[j]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) o[j] = 0.f;
         }
-        Vec8<T>::store(dy + r * 2 * H + c, da);
-        Vec8<T>::store(dy + r * 2 * H + H + c, dg);
+        if (V == 8) Vec8<T>::store(h + f * H + c, o);
+        else Elem<T>::store(h, f * H + c, o[0]);
     }
 }
-template <typename T>
-__global__ __launch_bounds__(256) void glu_bwd_scalar(const T* __restrict__ y, const T* __restrict__ dh,
-                                                      T* __restrict__ dy, long long rows, int H)
+
+template <typename T, int V>
+__global__ __launch_bounds__(256) void glu_bwd_k(const T* __restrict__ y, const T* __restrict__ dh,
+                                                 T* __restrict__ dy, long long out_rows, int H, RowMap map)
 {
-    const long long total = rows * H;
+    const int hv = H / V;
+    const long long total = out_rows * hv;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
          i += (long long)gridDim.x * blockDim.x) {
-        const long long r = i / H;
-        const int c = (int)(i - r * H);
-        const float a = Elem<T>::load(y, r * 2 * H + c), g = Elem<T>::load(y, r * 2 * H + H + c);
-        const float d = Elem<T>::load(dh, i), sg = sigmoidf_(g);
-        Elem<T>::store(dy, r * 2 * H + c, d * sg);
-        Elem<T>::store(dy, r * 2 * H + H + c, d * a * sg * (1.f - sg));
+        const long long f = i / hv;
+        const int c = (int)(i - f * hv) * V;
+        const long long r = map.src(f);
+        float da[V], dg[V];
+        if (r >= 0) {
+            float a[V], g[V], d[V];
+            if (V == 8) {
+                Vec8<T>::load(y + r * 2 * H + c, a);
+                Vec8<T>::load(y + r * 2 * H + H + c, g);
+                Vec8<T>::load(dh + r * H + c, d);
+            } else {
+                a[0] = Elem<T>::load(y, r * 2 * H + c);
+                g[0] = Elem<T>::load(y, r * 2 * H + H + c);
+                d[0] = Elem<T>::load(dh, r * H + c);
+            }
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const float sg = sigmoidf_(g[j]);
+                da[j] = d[j] * sg;
+                dg[j] = d[j] * a[j] * sg * (1.f - sg);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) { da[j] = 0.f; dg[j] = 0.f; }
+        }
+        if (V == 8) {
+            Vec8<T>::store(dy + f * 2 * H + c, da);
+            Vec8<T>::store(dy + f * 2 * H + H + c, dg);
+        } else {
+            Elem<T>::store(dy, f * 2 * H + c, da[0]);
+            Elem<T>::store(dy, f * 2 * H + H + c, dg[0]);
+        }
     }
 }
 
@@ -175,47 +195,63 @@ __global__ __launch_bounds__(256) void logsoftmax_bwd_k(const float* __restrict_
 
 using namespace w2l;
 
+namespace w2l {
+
+int glu_fwd_layout(const void* y, void* h, int B, int Tp, int Cout, int dtype, int pitch, int halo, int slack,
+                   hipStream_t st)
+{
+    const int H = Cout / 2;
+    const bool vec = (H % 8) == 0;
+    const long long out_rows = (long long)B * pitch + slack;
+    const RowMap map{Tp, pitch, halo, (long long)B * pitch};
+    const dim3 g(grid_for(vec ? out_rows * (H / 8) : out_rows * H)), b(256);
+    if (dtype == W2L_BF16) {
+        if (vec) hipLaunchKernelGGL((glu_fwd_k<bf16_t, 8>), g, b, 0, st, (const bf16_t*)y, (bf16_t*)h, out_rows, H, map);
+        else hipLaunchKernelGGL((glu_fwd_k<bf16_t, 1>), g, b, 0, st, (const bf16_t*)y, (bf16_t*)h, out_rows, H, map);
+    } else {
+        if (vec) hipLaunchKernelGGL((glu_fwd_k<float, 8>), g, b, 0, st, (const float*)y, (float*)h, out_rows, H, map);
+        else hipLaunchKernelGGL((glu_fwd_k<float, 1>), g, b, 0, st, (const float*)y, (float*)h, out_rows, H, map);
+    }
+    return launch_status();
+}
+
+int glu_bwd_layout(const void* y, const void* dh, void* dy, int B, int Tp, int Cout, int dtype, int pitch, int halo,
+                   int slack, hipStream_t st)
+{
+    const int H = Cout / 2;
+    const bool vec = (H % 8) == 0;
+    const long long out_rows = (long long)B * pitch + slack;
+    const RowMap map{Tp, pitch, halo, (long long)B * pitch};
+    const dim3 g(grid_for(vec ? out_rows * (H / 8) : out_rows * H)), b(256);
+    if (dtype == W2L_BF16) {
+        if (vec) hipLaunchKernelGGL((glu_bwd_k<bf16_t, 8>), g, b, 0, st, (const bf16_t*)y, (const bf16_t*)dh, (bf16_t*)dy, out_rows, H, map);
+        else hipLaunchKernelGGL((glu_bwd_k<bf16_t, 1>), g, b, 0, st, (const bf16_t*)y, (const bf16_t*)dh, (bf16_t*)dy, out_rows, H, map);
+    } else {
+        if (vec) hipLaunchKernelGGL((glu_bwd_k<float, 8>), g, b, 0, st, (const float*)y, (const float*)dh, (float*)dy, out_rows, H, map);
+        else hipLaunchKernelGGL((glu_bwd_k<float, 1>), g, b, 0, st, (const float*)y, (const float*)dh, (float*)dy, out_rows, H, map);
+    }
+    return launch_status();
+}
+
+}  // namespace w2l
+
 extern "C" int w2l_glu_fwd(const void* y, void* h, long long rows, int Cout, int dtype, void* stream)
 {
     if (!y || !h) return W2L_ERR_NULL;
-    if (rows <= 0 || Cout <= 0 || (Cout & 1)) return W2L_ERR_SHAPE;
+    if (rows <= 0 || rows > 2147483647LL || Cout <= 0 || (Cout & 1)) return W2L_ERR_SHAPE;
     if (!valid_dtype(dtype)) return W2L_ERR_DTYPE;
     if (!aligned16(y) || !aligned16(h)) return W2L_ERR_ALIGN;
-    hipStream_t st = (hipStream_t)stream;
-    const int H = Cout / 2;
-    const bool vec = (H % 8) == 0;
-    const long long items = vec ? rows * (H / 8) : rows * H;
-    const dim3 g(grid_for(items)), b(256);
-    if (dtype == W2L_BF16) {
-        if (vec) hipLaunchKernelGGL(glu_fwd_vec<bf16_t>, g, b, 0, st, (const bf16_t*)y, (bf16_t*)h, rows, H);
-        else hipLaunchKernelGGL(glu_fwd_scalar<bf16_t>, g, b, 0, st, (const bf16_t*)y, (bf16_t*)h, rows, H);
-    } else {
-        if (vec) hipLaunchKernelGGL(glu_fwd_vec<float>, g, b, 0, st, (const float*)y, (float*)h, rows, H);
-        else hipLaunchKernelGGL(glu_fwd_scalar<float>, g, b, 0, st, (const float*)y, (float*)h, rows, H);
-    }
-    return launch_status();
+    return glu_fwd_layout(y, h, 1, (int)rows, Cout, dtype, (int)rows, 0, 0, (hipStream_t)stream);
 }
 
 extern "C" int w2l_glu_bwd(const void* y, const void* dh, void* dy, long long rows, int Cout, int dtype,
                            void* stream)
 {
     if (!y || !dh || !dy) return W2L_ERR_NULL;
-    if (rows <= 0 || Cout <= 0 || (Cout & 1)) return W2L_ERR_SHAPE;
+    if (rows <= 0 || rows > 2147483647LL || Cout <= 0 || (Cout & 1)) return W2L_ERR_SHAPE;
     if (!valid_dtype(dtype)) return W2L_ERR_DTYPE;
     if (!aligned16(y) || !aligned16(dh) || !aligned16(dy)) return W2L_ERR_ALIGN;
-    hipStream_t st = (hipStream_t)stream;
-    const int H = Cout / 2;
-    const bool vec = (H % 8) == 0;
-    const long long items = vec ? rows * (H / 8) : rows * H;
-    const dim3 g(grid_for(items)), b(256);
-    if (dtype == W2L_BF16) {
-        if (vec) hipLaunchKernelGGL(glu_bwd_vec<bf16_t>, g, b, 0, st, (const bf16_t*)y, (const bf16_t*)dh, (bf16_t*)dy, rows, H);
-        else hipLaunchKernelGGL(glu_bwd_scalar<bf16_t>, g, b, 0, st, (const bf16_t*)y, (const bf16_t*)dh, (bf16_t*)dy, rows, H);
-    } else {
-        if (vec) hipLaunchKernelGGL(glu_bwd_vec<float>, g, b, 0, st, (const float*)y, (const float*)dh, (float*)dy, rows, H);
-        else hipLaunchKernelGGL(glu_bwd_scalar<float>, g, b, 0, st, (const float*)y, (const float*)dh, (float*)dy, rows, H);
-    }
-    return launch_status();
+    return glu_bwd_layout(y, dh, dy, 1, (int)rows, Cout, dtype, (int)rows, 0, 0, (hipStream_t)stream);
 }
 
 extern "C" int w2l_logsoftmax_fwd(const void* z, float* lp, long long rows, int C, int z_dtype, void* stream)

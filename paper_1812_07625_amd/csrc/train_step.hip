@@ -12,14 +12,23 @@
 namespace w2l {
 namespace {
 
+// Activations that feed a convolution (GLU outputs h_i, and the gradients dy_i that feed
+// dgrad/wgrad) are kept with HALO zero frames around every utterance and SLACK zero frames
+// after the last one, so the convolution kernels can read every window as plain memory.
+// Tensors only read elementwise (pre-GLU outputs y_i, gradients dh_i) stay dense.
+constexpr int HALO = 8;
+constexpr int SLACK = 64;
+
 struct Plan {
     int n = 0, C = 0, Tlast = 0, tot_stride = 1;
     std::vector<int> Tin, Tout, outch;
-    std::vector<size_t> pre, post;  // workspace offsets of conv output and GLU output per layer
-    size_t dlogits = 0, crit_len = 0, gbuf0 = 0, gbuf1 = 0, ctc = 0, conv = 0, total = 0;
+    std::vector<size_t> pre, post;  // workspace offsets of conv output (dense) and GLU output (haloed) per layer
+    size_t dlogits = 0, crit_len = 0, gdy = 0, gdh = 0, ctc = 0, conv = 0, total = 0;
     size_t ctc_bytes = 0, conv_bytes = 0;
     int status = W2L_OK;
 };
+
+size_t haloed_bytes(int B, int frames, int ch, size_t es) { return ((size_t)B * (frames + 2 * HALO) + SLACK) * ch * es; }
 
 Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
 {
@@ -29,7 +38,7 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
     if (n <= 0 || n > 1024 || B <= 0 || T <= 0 || Lmax <= 0) { p.status = W2L_ERR_SHAPE; return p; }
     if (!valid_dtype(dtype)) { p.status = W2L_ERR_DTYPE; return p; }
     const size_t es = dtype_size(dtype);
-    size_t off = 0, gmax = 0;
+    size_t off = 0, dymax = 0, dhmax = 0;
     int t = T;
     for (int i = 0; i < n; ++i) {
         const w2l_layer& l = L[i];
@@ -47,13 +56,14 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
         off += round_up((size_t)B * to * l.cout * oes, 256);
         if (l.glu) {
             p.post.push_back(off);
-            off += round_up((size_t)B * to * (l.cout / 2) * es, 256);
+            off += round_up(haloed_bytes(B, to, l.cout / 2, es), 256);
+            const size_t g1 = haloed_bytes(B, to, l.cout, es);
+            dymax = g1 > dymax ? g1 : dymax;
         } else {
             p.post.push_back(p.pre.back());
         }
-        const size_t g1 = (size_t)B * to * l.cout * 4, g2 = (size_t)B * t * l.cin * 4;
-        gmax = g1 > gmax ? g1 : gmax;
-        gmax = g2 > gmax ? g2 : gmax;
+        const size_t g2 = (size_t)B * t * l.cin * es;
+        dhmax = g2 > dhmax ? g2 : dhmax;
         const size_t cw = w2l_conv1d_bwd_weight_workspace_bytes(B, t, l.cin, l.cout, l.k, l.stride, dtype);
         p.conv_bytes = cw > p.conv_bytes ? cw : p.conv_bytes;
         t = to;
@@ -62,8 +72,8 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
     p.C = L[n - 1].cout;
     p.dlogits = off; off += round_up((size_t)B * p.Tlast * p.C * 4, 256);
     p.crit_len = off; off += round_up((size_t)B * 4, 256);
-    p.gbuf0 = off; off += round_up(gmax, 256);
-    p.gbuf1 = off; off += round_up(gmax, 256);
+    p.gdy = off; off += round_up(dymax, 256);
+    p.gdh = off; off += round_up(dhmax, 256);
     p.ctc_bytes = w2l_ctc_workspace_bytes(B, p.Tlast, p.C, Lmax);
     p.ctc = off; off += round_up(p.ctc_bytes, 256);
     p.conv = off; off += round_up(p.conv_bytes, 256);
@@ -112,16 +122,24 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
     const int n = n_layers;
     int rc;
 
-    // ---- network forward
+    // geometry of layer i; its input is the caller's dense x (i = 0) or the haloed h_{i-1}
+    auto desc = [&](int i) {
+        const w2l_layer& l = layers[i];
+        ConvDesc d = dense_desc(B, p.Tin[i], l.cin, l.cout, l.k, l.stride);
+        if (i > 0) { d.x_pitch = p.Tin[i] + 2 * HALO; d.x_halo = HALO; d.slack = SLACK; }
+        return d;
+    };
+
+    // ---- network forward: y_i = conv(h_{i-1}) + bias (dense), h_i = GLU(y_i) (haloed)
     const void* h = x;
     for (int i = 0; i < n; ++i) {
         const w2l_layer& l = layers[i];
         const int ydt = (i == n - 1) ? W2L_F32 : dtype;
-        rc = w2l_conv1d_fwd(h, weights[i], biases[i], ws + p.pre[i], B, p.Tin[i], l.cin, l.cout, l.k, l.stride,
-                            dtype, ydt, nullptr, 0, stream);
+        rc = conv_fwd(desc(i), h, weights[i], biases[i], ws + p.pre[i], dtype, ydt, st);
         if (rc) return rc;
         if (l.glu) {
-            rc = w2l_glu_fwd(ws + p.pre[i], ws + p.post[i], (long long)B * p.Tout[i], l.cout, dtype, stream);
+            rc = glu_fwd_layout(ws + p.pre[i], ws + p.post[i], B, p.Tout[i], l.cout, dtype, p.Tout[i] + 2 * HALO, HALO,
+                                SLACK, st);
             if (rc) return rc;
         }
         h = ws + p.post[i];
@@ -142,36 +160,38 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
                          ws + p.ctc, p.ctc_bytes, stream);
     if (rc) return rc;
 
-    // ---- backward
-    void* gb[2] = {ws + p.gbuf0, ws + p.gbuf1};
-    const void* dh = dz;  // gradient wrt layer i's (post-GLU) output
+    // ---- backward.  dh = gradient wrt layer i's output (dense); dy = gradient wrt its conv
+    // output: the haloed result of the GLU backward, or dh itself for a layer without GLU.
+    void* gdy = ws + p.gdy;
+    void* gdh = ws + p.gdh;
+    const void* dh = dz;
     int dh_dt = W2L_F32;
-    int cur = 0;          // buffer free to write next
     for (int i = n - 1; i >= 0; --i) {
         const w2l_layer& l = layers[i];
+        ConvDesc d = desc(i);
         const void* dy = dh;
         int dy_dt = dh_dt;
         if (l.glu) {
-            // dh arrives in the activation dtype for every GLU layer (it was written by a dgrad)
-            rc = w2l_glu_bwd(ws + p.pre[i], dh, gb[cur], (long long)B * p.Tout[i], l.cout, dtype, stream);
+            rc = glu_bwd_layout(ws + p.pre[i], dh, gdy, B, p.Tout[i], l.cout, dtype, p.Tout[i] + 2 * HALO, HALO, SLACK, st);
             if (rc) return rc;
-            dy = gb[cur];
+            dy = gdy;
             dy_dt = dtype;
-            cur ^= 1;
+            d.y_pitch = p.Tout[i] + 2 * HALO;
+            d.y_halo = HALO;
+        } else {
+            d.slack = 0;  // dy is dense here: nothing may be read past its end
         }
         const void* xin = (i == 0) ? x : (const void*)(ws + p.post[i - 1]);
-        rc = w2l_conv1d_bwd_weight(xin, dy, dweights[i], dbiases[i], B, p.Tin[i], l.cin, l.cout, l.k, l.stride,
-                                   dtype, dy_dt, 0, ws + p.conv, p.conv_bytes, stream);
+        rc = conv_wgrad(d, xin, dy, dweights[i], dbiases[i], dtype, dy_dt, 0, reinterpret_cast<float*>(ws + p.conv), st);
         if (rc) return rc;
         if (i > 0) {
-            // write into the buffer that does not hold dy
-            void* out = (dy == gb[0]) ? gb[1] : gb[0];
-            rc = w2l_conv1d_bwd_data(dy, weights[i], out, B, p.Tin[i], l.cin, l.cout, l.k, l.stride, dtype, dy_dt,
-                                     nullptr, 0, stream);
+            ConvDesc dd = d;   // dx = dh_{i-1} is written dense
+            dd.x_pitch = p.Tin[i];
+            dd.x_halo = 0;
+            rc = conv_dgrad(dd, dy, weights[i], gdh, dtype, dy_dt, st);
             if (rc) return rc;
-            dh = out;
+            dh = gdh;
             dh_dt = dtype;
-            cur = (out == gb[0]) ? 1 : 0;
         }
     }
     return W2L_OK;
