@@ -60,14 +60,23 @@ int conv_dgrad(const ConvDesc& d, const void* dy, const void* w, void* dx, int d
     return conv_dgrad_generic(d, dy, w, dx, dt, dydt, st);
 }
 
-int conv_wgrad(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int dt, int dydt,
-               int accumulate, float* dbias_scratch, hipStream_t st)
+size_t conv_wgrad_scratch_bytes(int Cin, int Cout, int k)
 {
+    return round_up((size_t)DBIAS_CHUNKS * Cout * 4, 256) + conv_wgrad_skinny_scratch(Cin, Cout, k);
+}
+
+int conv_wgrad(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int dt, int dydt,
+               int accumulate, void* scratch, hipStream_t st)
+{
+    float* dbias_scratch = static_cast<float*>(scratch);
+    float* skinny_scratch =
+        reinterpret_cast<float*>(static_cast<unsigned char*>(scratch) + round_up((size_t)DBIAS_CHUNKS * d.Cout * 4, 256));
     if (dbias) {
         // halo frames hold zeros, so summing every frame of the allocation is the same sum
         const int rc = dbias_reduce(dy, dbias, (long long)d.B * d.y_pitch, d.Cout, dydt, accumulate, dbias_scratch, st);
         if (rc) return rc;
     }
+    if (d.Cout <= 32) return conv_wgrad_skinny(d, x, dy, dw, dt, dydt, accumulate, skinny_scratch, st);
     if (dt == W2L_BF16 && dydt == W2L_BF16 && conv_wgrad_mfma_ok(d)) return conv_wgrad_mfma(d, x, dy, dw, accumulate, st);
     return conv_wgrad_generic(d, x, dy, dw, dt, dydt, accumulate, st);
 }
@@ -113,7 +122,7 @@ extern "C" size_t w2l_conv1d_bwd_weight_workspace_bytes(int B, int T, int Cin, i
 {
     (void)dtype;
     if (B <= 0 || T <= 0 || Cin <= 0 || Cout <= 0 || k <= 0 || stride <= 0) return 0;
-    return round_up((size_t)DBIAS_CHUNKS * Cout * 4, 256);
+    return conv_wgrad_scratch_bytes(Cin, Cout, k);
 }
 
 extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, float* dbias, int B, int T,
@@ -129,5 +138,5 @@ extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, f
     if (!ws_ok(workspace, ws_bytes, w2l_conv1d_bwd_weight_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
         return W2L_ERR_WORKSPACE;
     return conv_wgrad(dense_desc(B, T, Cin, Cout, k, stride), x, dy, dw, dbias, dtype, dy_dtype, accumulate,
-                      static_cast<float*>(workspace), (hipStream_t)stream);
+                      workspace, (hipStream_t)stream);
 }

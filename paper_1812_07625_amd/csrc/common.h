@@ -67,14 +67,21 @@ inline ConvDesc dense_desc(int B, int T, int Cin, int Cout, int k, int s)
 int conv_fwd(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int dt, int ydt,
              hipStream_t st);
 int conv_dgrad(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st);
+// scratch: conv_wgrad_scratch_bytes() bytes of device memory
+size_t conv_wgrad_scratch_bytes(int Cin, int Cout, int k);
 int conv_wgrad(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int dt, int dydt,
-               int accumulate, float* dbias_scratch, hipStream_t st);
+               int accumulate, void* scratch, hipStream_t st);
 
 int conv_fwd_generic(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int dt, int ydt,
                      hipStream_t st);
 int conv_dgrad_generic(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st);
 int conv_wgrad_generic(const ConvDesc& d, const void* x, const void* dy, float* dw, int dt, int dydt, int accumulate,
                        hipStream_t st);
+// narrow outputs (Cout <= 32): row-chunked reduction, SKINNY_CHUNKS partials summed in a fixed order
+enum { SKINNY_CHUNKS = 64 };
+size_t conv_wgrad_skinny_scratch(int Cin, int Cout, int k);
+int conv_wgrad_skinny(const ConvDesc& d, const void* x, const void* dy, float* dw, int dt, int dydt, int accumulate,
+                      float* scratch, hipStream_t st);
 // column sums of dy[rows,Cout] -> dbias, two deterministic stages; scratch holds DBIAS_CHUNKS*Cout floats
 enum { DBIAS_CHUNKS = 64 };
 int dbias_reduce(const void* dy, float* dbias, long long rows, int Cout, int dydt, int accumulate,

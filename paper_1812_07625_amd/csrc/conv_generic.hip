@@ -181,6 +181,65 @@ int wgrad_t(const ConvDesc& d, const void* x, const void* dy, float* dw, int acc
                                                                  (long long)d.B * d.Tp, st);
 }
 
+// ---- weight gradient for narrow outputs (Cout <= 32, e.g. the 29 grapheme classes) ---------
+// dw[co, n=(j,ci)] = sum_{r=(b,t')} dy[r,co] * x[b, s t' + j - p, ci].  A 64-wide GEMM tile would
+// leave all but one tile row empty and serialise the whole reduction in a handful of
+// workgroups; here the reduction is cut into SKINNY_CHUNKS row ranges (grid.y), every thread
+// owns one column n and keeps all Cout partial sums in registers, and a second pass adds the
+// chunks in a fixed order.
+constexpr int SKINNY_ROWS = 32;  // dy rows staged in LDS per pass
+
+template <typename TX, typename TDY>
+__global__ __launch_bounds__(256) void wgrad_skinny_stage1(const TX* __restrict__ x, const TDY* __restrict__ dy,
+                                                           float* __restrict__ part, ConvDesc d)
+{
+    __shared__ float dyt[SKINNY_ROWS][32];
+    const int N = d.k * d.Cin, R = d.B * d.Tp;
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    const int per = (R + gridDim.y - 1) / gridDim.y;
+    const int r_begin = per * blockIdx.y, r_end = (r_begin + per < R) ? r_begin + per : R;
+    const int j = (n < N) ? n / d.Cin : 0, ci = (n < N) ? n - j * d.Cin : 0;
+    float acc[32];
+#pragma unroll
+    for (int c = 0; c < 32; ++c) acc[c] = 0.f;
+    for (int r0 = r_begin; r0 < r_end; r0 += SKINNY_ROWS) {
+        for (int e = threadIdx.x; e < SKINNY_ROWS * 32; e += 256) {
+            const int rr = e >> 5, c = e & 31, r = r0 + rr;
+            float v = 0.f;
+            if (r < r_end && c < d.Cout) {
+                const int b = r / d.Tp, tp = r - b * d.Tp;
+                v = Elem<TDY>::load(dy, ((size_t)b * d.y_pitch + d.y_halo + tp) * d.Cout + c);
+            }
+            dyt[rr][c] = v;
+        }
+        __syncthreads();
+        if (n < N) {
+            const int rows = (r_end - r0 < SKINNY_ROWS) ? r_end - r0 : SKINNY_ROWS;
+            for (int rr = 0; rr < rows; ++rr) {
+                const int r = r0 + rr;
+                const int b = r / d.Tp, tp = r - b * d.Tp;
+                const int t = d.s * tp + j - d.p;
+                if (t < 0 || t >= d.T) continue;
+                const float xv = Elem<TX>::load(x, ((size_t)b * d.x_pitch + d.x_halo + t) * d.Cin + ci);
+#pragma unroll
+                for (int c = 0; c < 32; ++c) acc[c] = fmaf(dyt[rr][c], xv, acc[c]);
+            }
+        }
+        __syncthreads();
+    }
+    if (n < N)
+        for (int c = 0; c < d.Cout; ++c) part[((size_t)blockIdx.y * d.Cout + c) * N + n] = acc[c];
+}
+__global__ __launch_bounds__(256) void wgrad_skinny_stage2(const float* __restrict__ part, float* __restrict__ dw,
+                                                           int chunks, long long total, int accumulate)
+{
+    const long long i = blockIdx.x * 256LL + threadIdx.x;
+    if (i >= total) return;
+    float acc = 0.f;
+    for (int c = 0; c < chunks; ++c) acc += part[(size_t)c * total + i];
+    dw[i] = accumulate ? dw[i] + acc : acc;
+}
+
 // ---- dbias: deterministic two-stage column sum -------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_stage1(const T* dy, float* part, long long rows, int Cout)
@@ -233,6 +292,30 @@ int conv_wgrad_generic(const ConvDesc& d, const void* x, const void* dy, float* 
     if (dt == W2L_BF16 && dydt == W2L_BF16) return wgrad_t<bf16_t, bf16_t>(d, x, dy, dw, accumulate, st);
     if (dt == W2L_BF16 && dydt == W2L_F32) return wgrad_t<bf16_t, float>(d, x, dy, dw, accumulate, st);
     return W2L_ERR_DTYPE;
+}
+size_t conv_wgrad_skinny_scratch(int Cin, int Cout, int k)
+{
+    return Cout <= 32 ? round_up((size_t)SKINNY_CHUNKS * Cout * k * Cin * 4, 256) : 0;
+}
+int conv_wgrad_skinny(const ConvDesc& d, const void* x, const void* dy, float* dw, int dt, int dydt, int accumulate,
+                      float* scratch, hipStream_t st)
+{
+    const long long N = (long long)d.k * d.Cin;
+    const dim3 g1((unsigned)((N + 255) / 256), SKINNY_CHUNKS);
+    if (dt == W2L_F32 && dydt == W2L_F32)
+        hipLaunchKernelGGL((wgrad_skinny_stage1<float, float>), g1, dim3(256), 0, st, (const float*)x, (const float*)dy, scratch, d);
+    else if (dt == W2L_BF16 && dydt == W2L_BF16)
+        hipLaunchKernelGGL((wgrad_skinny_stage1<bf16_t, bf16_t>), g1, dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)dy, scratch, d);
+    else if (dt == W2L_BF16 && dydt == W2L_F32)
+        hipLaunchKernelGGL((wgrad_skinny_stage1<bf16_t, float>), g1, dim3(256), 0, st, (const bf16_t*)x, (const float*)dy, scratch, d);
+    else
+        return W2L_ERR_DTYPE;
+    int rc = launch_status();
+    if (rc) return rc;
+    const long long total = (long long)d.Cout * N;
+    hipLaunchKernelGGL(wgrad_skinny_stage2, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, scratch, dw,
+                       (int)SKINNY_CHUNKS, total, accumulate);
+    return launch_status();
 }
 int dbias_reduce(const void* dy, float* dbias, long long rows, int Cout, int dydt, int accumulate,
                  float* scratch, hipStream_t st)

@@ -625,7 +625,10 @@ bool halo_ok_y(const ConvDesc& d) { return d.p == 0 || d.y_halo >= d.p; }
 
 bool conv_fwd_mfma_ok(const ConvDesc& d)
 {
-    return common_ok(d) && d.Cout >= 64 && (long long)d.B * d.Tp >= 128;
+    // rows of w are fetched in 16-byte chunks along (j,ci): only Cin needs to be a multiple of 8
+    ConvDesc e = d;
+    e.Cout = (d.Cout + 7) / 8 * 8;
+    return d.Cin % 8 == 0 && common_ok(e) && d.Cout >= 16 && (long long)d.B * d.Tp >= 128;
 }
 
 int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* bias, void* y, int ydt, hipStream_t st)

@@ -161,7 +161,12 @@ __global__ void ctc_lattice(const float* __restrict__ lp, const int* __restrict_
                 if (e < chunk_elems) nxt[e] = pf[i];
             }
         }
-        __syncthreads();
+        // LDS-only hand-over: wait for this wavefront's LDS traffic, then barrier.  A full
+        // __syncthreads() would also wait for the lattice stores above, putting HBM write
+        // latency on the T-step dependency chain.
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
         double* tmp = prev; prev = cur; cur = tmp;
     }
     if (dir == 0 && tid == 0) {

@@ -182,7 +182,7 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
             d.slack = 0;  // dy is dense here: nothing may be read past its end
         }
         const void* xin = (i == 0) ? x : (const void*)(ws + p.post[i - 1]);
-        rc = conv_wgrad(d, xin, dy, dweights[i], dbiases[i], dtype, dy_dt, 0, reinterpret_cast<float*>(ws + p.conv), st);
+        rc = conv_wgrad(d, xin, dy, dweights[i], dbiases[i], dtype, dy_dt, 0, ws + p.conv, st);
         if (rc) return rc;
         if (i > 0) {
             ConvDesc dd = d;   // dx = dh_{i-1} is written dense
