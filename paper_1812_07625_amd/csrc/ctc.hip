@@ -22,13 +22,11 @@ namespace {
 
 constexpr double LOG2E = 1.4426950408889634074;
 constexpr double LN2 = 0.69314718055994530942;
-constexpr int PF = 8;           // prefetch registers per thread
-constexpr int MAX_CHUNK = 16;   // frames of scores staged per chunk
 constexpr int GRAD_ROWS = 16;   // frames per ctc_grad workgroup (4 per wavefront)
 
 struct CtcDims {
     int B, Tp, C, Lmax, blank;
-    int Sp;  // lattice row pitch = 2*Lmax+1
+    int Sp;  // lattice row pitch = 2*Lmax+2 (pairs of doubles, 16-byte aligned)
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -42,35 +40,56 @@ __device__ __forceinline__ double lse3_log2(double a, double b, double c)
     const float sum = fast_exp2((float)(a - m)) + fast_exp2((float)(b - m)) + fast_exp2((float)(c - m));
     return m + (double)fast_log2(sum);
 }
-
-__global__ void ctc_lattice(const float* __restrict__ lp, const int* __restrict__ targets,
-                            const int* __restrict__ in_len, const int* __restrict__ tgt_len,
-                            float* __restrict__ loss, double* __restrict__ logp2_out,
-                            double* __restrict__ alpha, double* __restrict__ beta, CtcDims d, int chunk)
+__device__ __forceinline__ double lse2_log2(double a, double b)
 {
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    const int dir = blockIdx.x, b = blockIdx.y;
-    const int tid = threadIdx.x, NT = blockDim.x;
-    const int T = in_len[b], L = tgt_len[b];
+    const double m = fmax(a, b);
+    if (m == -INFINITY) return -INFINITY;
+    const float sum = fast_exp2((float)(a - m)) + fast_exp2((float)(b - m));
+    return m + (double)fast_log2(sum);
+}
+
+// value of `v` held by the previous lane of the wavefront (lane 0 receives its own)
+__device__ __forceinline__ double from_prev_lane(double v)
+{
+    const unsigned long long u = __double_as_longlong(v);
+    const int lo = __shfl_up((int)(u & 0xffffffffu), 1, 64);
+    const int hi = __shfl_up((int)(u >> 32), 1, 64);
+    return __longlong_as_double(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+}
+
+constexpr int SCORE_AHEAD = 16;  // frames of scores held in registers ahead of the recursion
+
+// One workgroup per (utterance, direction).  The extended sequence is cut into pairs
+// (blank 2i, label 2i+1); a thread owns PPT consecutive pairs and keeps their alpha values in
+// registers, so per frame it needs exactly one value from outside: the label state of the
+// pair to its left, which comes from the neighbouring lane (or, across a wavefront boundary,
+// through a two-slot LDS mailbox and the one barrier of the step).  The scores lp[t, blank]
+// and lp[t, label] are fetched SCORE_AHEAD frames early into a register ring, off the
+// dependency chain.  beta is the same recursion on the reversed sequence and reversed time
+// (state index q counts from the end), stored in its own q order.
+template <int PPT>
+__global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp, const int* __restrict__ targets,
+                                                    const int* __restrict__ in_len, const int* __restrict__ tgt_len,
+                                                    float* __restrict__ loss, double* __restrict__ logp2_out,
+                                                    double* __restrict__ alpha, double* __restrict__ beta, CtcDims d)
+{
+    __shared__ double mailbox[2][16];
+    __shared__ double fin[2];
     __shared__ int bad_len, bad;
+    const int dir = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
+    const int T = in_len[b], L = tgt_len[b];
     if (tid == 0) {
         bad_len = (T < 0 || T > d.Tp || L < 0 || L > d.Lmax) ? 1 : 0;
         bad = 0;
+        fin[0] = -INFINITY;
+        fin[1] = -INFINITY;
     }
     __syncthreads();
     if (bad_len) {
         if (dir == 0 && tid == 0) { loss[b] = NAN; logp2_out[b] = NAN; }
         return;
     }
-    const int S = 2 * L + 1;
-    // LDS carve-up: two state vectors (2 leading -inf pads each), class of each state
-    // (bit 30 = "may skip from s-2"), two score chunks
-    double* st0 = reinterpret_cast<double*>(smem_raw);
-    double* st1 = st0 + (2 * d.Lmax + 3);
-    int* cls = reinterpret_cast<int*>(st1 + (2 * d.Lmax + 3));
-    float* sc0 = reinterpret_cast<float*>(cls + (2 * d.Lmax + 1));
-    float* sc1 = sc0 + (size_t)chunk * d.C;
-
     const int* lab = targets + (size_t)b * d.Lmax;
     for (int i = tid; i < L; i += NT) {
         const int l = lab[i];
@@ -81,21 +100,6 @@ __global__ void ctc_lattice(const float* __restrict__ lp, const int* __restrict_
         if (dir == 0 && tid == 0) { loss[b] = NAN; logp2_out[b] = NAN; }
         return;
     }
-    // state index q runs in this direction's own order; actual state s = dir ? S-1-q : q
-    for (int q = tid; q < S; q += NT) {
-        const int s = dir ? S - 1 - q : q;
-        int c = d.blank, skip = 0;
-        if (s & 1) {
-            c = lab[(s - 1) >> 1];
-            if (q >= 2) {
-                const int s2 = dir ? s + 2 : s - 2;
-                skip = (lab[(s2 - 1) >> 1] != c);
-            }
-        }
-        cls[q] = c | (skip << 30);
-    }
-    for (int q = tid; q < S + 2; q += NT) { st0[q] = -INFINITY; st1[q] = -INFINITY; }
-
     if (T == 0) {
         if (dir == 0 && tid == 0) {
             loss[b] = (L == 0) ? 0.f : INFINITY;
@@ -103,76 +107,104 @@ __global__ void ctc_lattice(const float* __restrict__ lp, const int* __restrict_
         }
         return;
     }
-
+    // pair i (in this direction's order) = states q = 2i (blank), 2i+1 (label i, absent for i = L)
+    int cls[PPT];      // class of the label state
+    bool has_l[PPT];   // label state exists
+    bool skip[PPT];    // label state may be entered from the label of the pair to the left
+    bool live[PPT];    // pair exists
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) {
+        const int i = tid * PPT + j;
+        live[j] = i <= L;
+        has_l[j] = i < L;
+        const int li = dir ? L - 1 - i : i;          // label index in the target
+        cls[j] = has_l[j] ? lab[li] : d.blank;
+        skip[j] = has_l[j] && i >= 1 && lab[dir ? li + 1 : li - 1] != cls[j];
+    }
     const float* lpb = lp + (size_t)b * d.Tp * d.C;
     double* lat = (dir ? beta : alpha) + (size_t)b * d.Tp * d.Sp;
-    const int rowsz = d.C;
-    const int chunk_elems = chunk * rowsz;
-    // frame visited at step i
-    auto frame = [&](int i) { return dir ? T - 1 - i : i; };
+    auto frame = [&](int step) { return dir ? T - 1 - step : step; };
 
-    // chunk 0 synchronously
-    for (int e = tid; e < chunk_elems; e += NT) {
-        const int r = e / rowsz, c = e - r * rowsz;
-        sc0[e] = (r < T) ? lpb[(size_t)frame(r) * rowsz + c] : 0.f;
-    }
-    __syncthreads();
-
-    double* prev = st0;
-    double* cur = st1;
-    float pf[PF];
-    for (int step = 0; step < T; ++step) {
-        const int cidx = step / chunk, within = step - cidx * chunk;
-        float* sc = (cidx & 1) ? sc1 : sc0;
-        if (within == 0) {  // start fetching the next chunk; consumed `chunk` steps from now
+    // score ring: sb[k] / sl[j][k] hold the scores of step (current block of SCORE_AHEAD) + k
+    float sb[SCORE_AHEAD], sl[PPT][SCORE_AHEAD];
 #pragma unroll
-            for (int i = 0; i < PF; ++i) {
-                const int e = tid + i * NT;
-                pf[i] = 0.f;
-                if (e < chunk_elems) {
-                    const int r = e / rowsz, c = e - r * rowsz;
-                    const int fs = (cidx + 1) * chunk + r;
-                    if (fs < T) pf[i] = lpb[(size_t)frame(fs) * rowsz + c];
+    for (int k = 0; k < SCORE_AHEAD; ++k) {
+        const int f = frame(k < T ? k : T - 1);
+        sb[k] = lpb[(size_t)f * d.C + d.blank];
+#pragma unroll
+        for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
+    }
+    double ab[PPT], al[PPT];
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) { ab[j] = -INFINITY; al[j] = -INFINITY; }
+    double left = -INFINITY;  // label state of the pair to the left of this thread's first pair, previous frame
+    const int nwaves = NT >> 6;
+
+    for (int t0 = 0; t0 < T; t0 += SCORE_AHEAD) {
+#pragma unroll
+        for (int k = 0; k < SCORE_AHEAD; ++k) {
+            const int step = t0 + k;
+            if (step >= T) break;
+            const double s_b = (double)sb[k] * LOG2E;
+            double s_l[PPT];
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) s_l[j] = (double)sl[j][k] * LOG2E;
+            {   // refill this ring slot for step + SCORE_AHEAD
+                const int nf = step + SCORE_AHEAD;
+                const int f = frame(nf < T ? nf : T - 1);
+                sb[k] = lpb[(size_t)f * d.C + d.blank];
+#pragma unroll
+                for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
+            }
+            double carry = left;  // label value (previous frame) of the pair to the left of pair j
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) {
+                const double ob = ab[j], ol = al[j];
+                double nb, nl;
+                if (step == 0) {
+                    const bool first = (tid * PPT + j) == 0;
+                    nb = first ? s_b : -INFINITY;
+                    nl = (first && has_l[j]) ? s_l[j] : -INFINITY;
+                } else {
+                    nb = lse2_log2(ob, carry) + s_b;
+                    nl = has_l[j] ? lse3_log2(ol, ob, skip[j] ? carry : -INFINITY) + s_l[j] : -INFINITY;
+                }
+                if (!live[j]) { nb = -INFINITY; nl = -INFINITY; }
+                carry = ol;
+                ab[j] = nb;
+                al[j] = nl;
+                if (live[j]) {
+                    double2 v2 = make_double2(nb, nl);
+                    *reinterpret_cast<double2*>(lat + (size_t)frame(step) * d.Sp + 2 * (tid * PPT + j)) = v2;
                 }
             }
-        }
-        const int t = frame(step);
-        const float* row = sc + (size_t)within * rowsz;
-        for (int q = tid; q < S; q += NT) {
-            const int cw = cls[q];
-            const int c = cw & 0x3fffffff;
-            const double sc2 = (double)row[c] * LOG2E;
-            double v;
-            if (step == 0) {
-                v = (q < 2) ? sc2 : -INFINITY;
-            } else {
-                const double a0 = prev[q + 2], a1 = prev[q + 1];
-                const double a2 = (cw >> 30) ? prev[q] : -INFINITY;
-                v = lse3_log2(a0, a1, a2) + sc2;
+            // hand this thread's last label value to the thread on its right
+            const double send = al[PPT - 1];
+            double recv = from_prev_lane(send);
+            if (nwaves > 1) {
+                if (lane == 63) mailbox[step & 1][wave] = send;
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if (lane == 0 && wave > 0) recv = mailbox[step & 1][wave - 1];
             }
-            cur[q + 2] = v;
-            lat[(size_t)t * d.Sp + (dir ? S - 1 - q : q)] = v;
+            left = (tid == 0) ? -INFINITY : recv;
         }
-        if (within == chunk - 1) {
-            float* nxt = (cidx & 1) ? sc0 : sc1;
-#pragma unroll
-            for (int i = 0; i < PF; ++i) {
-                const int e = tid + i * NT;
-                if (e < chunk_elems) nxt[e] = pf[i];
-            }
-        }
-        // LDS-only hand-over: wait for this wavefront's LDS traffic, then barrier.  A full
-        // __syncthreads() would also wait for the lattice stores above, putting HBM write
-        // latency on the T-step dependency chain.
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        double* tmp = prev; prev = cur; cur = tmp;
     }
-    if (dir == 0 && tid == 0) {
-        const double lp2 = lse3_log2(prev[S - 1 + 2], (S > 1) ? prev[S - 2 + 2] : -INFINITY, -INFINITY);
-        logp2_out[b] = lp2;
-        loss[b] = (lp2 == -INFINITY) ? INFINITY : (float)(-lp2 * LN2);
+    // log P = lse( alpha_{T-1}(S-1), alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1
+    if (dir == 0) {
+#pragma unroll
+        for (int j = 0; j < PPT; ++j) {
+            const int i = tid * PPT + j;
+            if (i == L) fin[0] = ab[j];
+            if (i == L - 1) fin[1] = al[j];
+        }
+        __syncthreads();
+        if (tid == 0) {
+            const double lp2 = lse2_log2(fin[0], fin[1]);
+            logp2_out[b] = lp2;
+            loss[b] = (lp2 == -INFINITY) ? INFINITY : (float)(-lp2 * LN2);
+        }
     }
 }
 
@@ -244,7 +276,7 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
         float z = 0.f, zb = 0.f;
         for (int s = lane; s < S; s += 64) {
             const int c = (s & 1) ? lab[(s - 1) >> 1] : d.blank;
-            const double a = ar[s], bt = br[s];
+            const double a = ar[s], bt = br[S - 1 - s];  // beta rows are stored in reversed state order
             float e = 0.f;
             if (a != -INFINITY && bt != -INFINITY)
                 e = fast_exp2((float)(a + bt - (double)lrow[c] * LOG2E - logp2));
@@ -271,26 +303,9 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
     }
 }
 
-size_t lattice_lds_bytes(int Lmax, int C, int chunk)
-{
-    return (size_t)2 * 8 * (2 * Lmax + 3) + (size_t)4 * (2 * Lmax + 1) + (size_t)2 * 4 * chunk * C;
-}
 size_t grad_lds_bytes(int Lmax, int C)
 {
-    return (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (2 * Lmax + 1);
-}
-void lattice_launch_shape(int Lmax, int C, int* nt, int* chunk)
-{
-    int need = 2 * Lmax + 1;
-    if ((C + PF - 1) / PF > need) need = (C + PF - 1) / PF;
-    int t = (need + 63) / 64 * 64;
-    if (t < 64) t = 64;
-    if (t > 1024) t = 1024;
-    int ch = PF * t / C;
-    if (ch > MAX_CHUNK) ch = MAX_CHUNK;
-    if (ch < 1) ch = 1;
-    *nt = t;
-    *chunk = ch;
+    return (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (2 * Lmax + 2);
 }
 
 struct WsLayout { size_t lp, logp, alpha, beta, total; };
@@ -300,7 +315,7 @@ WsLayout ws_layout(int B, int Tp, int C, int Lmax)
     size_t off = 0;
     w.lp = off; off += round_up((size_t)B * Tp * C * 4, 256);
     w.logp = off; off += round_up((size_t)B * 8, 256);
-    const size_t lat = round_up((size_t)B * Tp * (2 * (size_t)Lmax + 1) * 8, 256);
+    const size_t lat = round_up((size_t)B * Tp * (2 * (size_t)Lmax + 2) * 8, 256);
     w.alpha = off; off += lat;
     w.beta = off; off += lat;
     w.total = off;
@@ -356,23 +371,24 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     double* logp = reinterpret_cast<double*>(ws + w.logp);
     double* alpha = reinterpret_cast<double*>(ws + w.alpha);
     double* beta = reinterpret_cast<double*>(ws + w.beta);
-    CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 1};
+    CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 2};
 
-    int nt, chunk;
-    lattice_launch_shape(Lmax, C, &nt, &chunk);
-    const size_t lds1 = lattice_lds_bytes(Lmax, C, chunk), lds2 = grad_lds_bytes(Lmax, C);
-    if (lds1 > 160 * 1024 || lds2 > 160 * 1024) return W2L_ERR_SHAPE;
-    hipError_t e;
-    if (lds1 > 48 * 1024) {
-        e = hipFuncSetAttribute((const void*)ctc_lattice, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
-        if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }
-    }
+    const size_t lds2 = grad_lds_bytes(Lmax, C);
+    if (lds2 > 160 * 1024) return W2L_ERR_SHAPE;
     if (lds2 > 48 * 1024) {
-        e = hipFuncSetAttribute((const void*)ctc_grad, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+        hipError_t e = hipFuncSetAttribute((const void*)ctc_grad, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
         if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }
     }
-    hipLaunchKernelGGL(ctc_lattice, dim3(2, B), dim3(nt), lds1, st, lp, targets, in_len, tgt_len, loss, logp,
-                       alpha, beta, d, chunk);
+    // one thread per (blank,label) pair of the extended target; more pairs per thread only
+    // when a workgroup of 1024 cannot cover Lmax+1 pairs
+    const int pairs = Lmax + 1;
+    const int ppt = pairs <= 1024 ? 1 : (pairs <= 2048 ? 2 : 4);
+    int nt = ((pairs + ppt - 1) / ppt + 63) / 64 * 64;
+    if (nt > 1024) return W2L_ERR_SHAPE;
+    const dim3 g1(2, B), b1(nt);
+    if (ppt == 1) hipLaunchKernelGGL(ctc_lattice<1>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
+    else if (ppt == 2) hipLaunchKernelGGL(ctc_lattice<2>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
+    else hipLaunchKernelGGL(ctc_lattice<4>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
     int rc = launch_status();
     if (rc) return rc;
     hipLaunchKernelGGL(ctc_grad, dim3((Tp + GRAD_ROWS - 1) / GRAD_ROWS, B), dim3(256), lds2, st, lp, targets,

@@ -152,6 +152,7 @@ def _check_ctc(loss, grad, loss_o, grad_o):
     dict(B=6, T=200, in_lo=150, in_hi=200, l_lo=30, l_hi=70),     # S spans > 1 wavefront
     dict(B=3, T=97, in_lo=1, in_hi=97, l_lo=0, l_hi=1, Cc=5),
     dict(),                                                         # the full benchmark shape
+    dict(B=2, T=2300, in_lo=2250, in_hi=2300, l_lo=1030, l_hi=1100),  # > 1024 pairs: two pairs per thread
 ])
 def test_ctc_from_logits(P, kw):
     cfg = W.config2(seed=2, **kw)
