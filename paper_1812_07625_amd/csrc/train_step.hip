@@ -6,6 +6,7 @@
 //   criterion log-softmax + CTC on the fp32 logits; yields d loss / d logits directly
 //   backward  for each layer, last to first: [GLU bwd] -> wgrad(+dbias) -> dgrad
 //             (dgrad is skipped for layer 0: the features need no gradient)
+#include <mutex>
 #include <vector>
 #include "common.h"
 
@@ -19,11 +20,42 @@ namespace {
 constexpr int HALO = 8;
 constexpr int SLACK = 64;
 
+// A helper stream (default priority) on which the weight gradients run: wgrad of layer i needs
+// only dy_i and h_{i-1}, nothing downstream needs it before the step ends, and neither wgrad
+// nor dgrad fills all 256 CUs with its tile grid alone -- side by side they do.  Created once
+// per device on first use; no device memory is allocated.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    std::vector<hipEvent_t> ready, done;  // per layer: dy_i written (main) / wgrad_i finished (side)
+    bool ok = false;
+};
+SideStream* side_stream(int n_layers)
+{
+    static std::mutex mu;
+    static SideStream per_device[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    SideStream& s = per_device[dev];
+    if (!s.stream) {
+        if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) { s.stream = nullptr; return nullptr; }
+        s.ok = true;
+    }
+    while (s.ok && (int)s.ready.size() < n_layers) {
+        hipEvent_t a, b;
+        if (hipEventCreateWithFlags(&a, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&b, hipEventDisableTiming) != hipSuccess) { s.ok = false; break; }
+        s.ready.push_back(a);
+        s.done.push_back(b);
+    }
+    return s.ok ? &s : nullptr;
+}
+
 struct Plan {
     int n = 0, C = 0, Tlast = 0, tot_stride = 1;
     std::vector<int> Tin, Tout, outch;
     std::vector<size_t> pre, post;  // workspace offsets of conv output (dense) and GLU output (haloed) per layer
-    size_t dlogits = 0, crit_len = 0, gdy = 0, gdh = 0, ctc = 0, conv = 0, total = 0;
+    size_t dlogits = 0, crit_len = 0, gdy[2] = {0, 0}, gdh = 0, ctc = 0, conv = 0, total = 0;
     size_t ctc_bytes = 0, conv_bytes = 0;
     int status = W2L_OK;
 };
@@ -72,7 +104,8 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
     p.C = L[n - 1].cout;
     p.dlogits = off; off += round_up((size_t)B * p.Tlast * p.C * 4, 256);
     p.crit_len = off; off += round_up((size_t)B * 4, 256);
-    p.gdy = off; off += round_up(dymax, 256);
+    p.gdy[0] = off; off += round_up(dymax, 256);
+    p.gdy[1] = off; off += round_up(dymax, 256);
     p.gdh = off; off += round_up(dhmax, 256);
     p.ctc_bytes = w2l_ctc_workspace_bytes(B, p.Tlast, p.C, Lmax);
     p.ctc = off; off += round_up(p.ctc_bytes, 256);
@@ -162,7 +195,12 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
 
     // ---- backward.  dh = gradient wrt layer i's output (dense); dy = gradient wrt its conv
     // output: the haloed result of the GLU backward, or dh itself for a layer without GLU.
-    void* gdy = ws + p.gdy;
+    // Main stream: GLU bwd -> dgrad chain.  Side stream: wgrad (+dbias) of every layer, each
+    // started as soon as its dy exists.  dy buffers alternate so that layer i-1's GLU bwd does
+    // not overwrite what wgrad_i still reads; layer i-2's waits for wgrad_i.
+    SideStream* side = side_stream(n);
+    hipStream_t wst = side ? side->stream : st;
+    auto hip_ok = [&](hipError_t e) { if (e != hipSuccess) { note_hip_error(e); return false; } return true; };
     void* gdh = ws + p.gdh;
     const void* dh = dz;
     int dh_dt = W2L_F32;
@@ -172,6 +210,8 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
         const void* dy = dh;
         int dy_dt = dh_dt;
         if (l.glu) {
+            void* gdy = ws + p.gdy[i & 1];
+            if (side && i + 2 < n && !hip_ok(hipStreamWaitEvent(st, side->done[i + 2], 0))) return W2L_ERR_LAUNCH;
             rc = glu_bwd_layout(ws + p.pre[i], dh, gdy, B, p.Tout[i], l.cout, dtype, p.Tout[i] + 2 * HALO, HALO, SLACK, st);
             if (rc) return rc;
             dy = gdy;
@@ -181,9 +221,14 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
         } else {
             d.slack = 0;  // dy is dense here: nothing may be read past its end
         }
+        if (side) {
+            if (!hip_ok(hipEventRecord(side->ready[i], st)) || !hip_ok(hipStreamWaitEvent(wst, side->ready[i], 0)))
+                return W2L_ERR_LAUNCH;
+        }
         const void* xin = (i == 0) ? x : (const void*)(ws + p.post[i - 1]);
-        rc = conv_wgrad(d, xin, dy, dweights[i], dbiases[i], dtype, dy_dt, 0, ws + p.conv, st);
+        rc = conv_wgrad(d, xin, dy, dweights[i], dbiases[i], dtype, dy_dt, 0, ws + p.conv, wst);
         if (rc) return rc;
+        if (side && !hip_ok(hipEventRecord(side->done[i], wst))) return W2L_ERR_LAUNCH;
         if (i > 0) {
             ConvDesc dd = d;   // dx = dh_{i-1} is written dense
             dd.x_pitch = p.Tin[i];
@@ -194,5 +239,7 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
             dh_dt = dtype;
         }
     }
+    // join: the side stream is in order, so its last event covers every weight gradient
+    if (side && !hip_ok(hipStreamWaitEvent(st, side->done[0], 0))) return W2L_ERR_LAUNCH;
     return W2L_OK;
 }
