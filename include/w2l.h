@@ -68,7 +68,12 @@ int w2l_last_hip_error(void);
  *   y[b,t',co] = bias[co] + sum_{j<k} sum_{ci<Cin} w[co,j,ci] * x[b, s*t' + j - p, ci]
  * with x = 0 outside 0 <= t < T.   x: [B,T,Cin] (dtype);  w: [Cout,k,Cin] (dtype);
  * bias: [Cout] fp32 or NULL;  y: [B,T',Cout] (y_dtype; W2L_F32 is allowed with bf16
- * operands, e.g. for logits).  workspace may be NULL when the query returns 0. */
+ * operands, e.g. for logits).
+ * Workspace is optional for fwd and bwd_data: with NULL the kernels predicate every load
+ * against the utterance edges; given the queried number of bytes they first copy the
+ * window-read operand into a layout with a zero halo around every utterance (one extra
+ * bandwidth-bound pass) and then run the faster unpredicated kernel.  A non-NULL workspace
+ * smaller than the query is W2L_ERR_WORKSPACE. */
 size_t w2l_conv1d_fwd_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype);
 int w2l_conv1d_fwd(const void *x, const void *w, const float *bias, void *y,
                    int B, int T, int Cin, int Cout, int k, int stride,
@@ -88,7 +93,8 @@ int w2l_conv1d_bwd_data(const void *dy, const void *w, void *dx,
  *   dbias[co]   = sum_b sum_t' dy[b,t',co]
  * x: [B,T,Cin] (dtype);  dy: [B,T',Cout] (dy_dtype);  dw: [Cout,k,Cin] fp32;
  * dbias: [Cout] fp32 or NULL.  accumulate = 0 overwrites dw/dbias, 1 adds to them.
- * Reductions run in a fixed order: results are bit-reproducible run to run. */
+ * Reductions run in a fixed order: results are bit-reproducible run to run.
+ * The workspace is required here (reduction scratch, plus the haloed operand copies). */
 size_t w2l_conv1d_bwd_weight_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype);
 int w2l_conv1d_bwd_weight(const void *x, const void *dy, float *dw, float *dbias,
                           int B, int T, int Cin, int Cout, int k, int stride,

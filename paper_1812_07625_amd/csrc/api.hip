@@ -83,7 +83,22 @@ int conv_wgrad(const ConvDesc& d, const void* x, const void* dy, float* dw, floa
 
 }  // namespace w2l
 
-extern "C" size_t w2l_conv1d_fwd_workspace_bytes(int, int, int, int, int, int, int) { return 0; }
+namespace {
+// The C ABI takes dense tensors; the MFMA kernels run fastest on tensors with a zero halo
+// around every utterance.  Given workspace, the entry points first copy the window-read
+// operand(s) into that layout (one bandwidth-bound pass, a few percent of the GEMM).
+constexpr int ABI_HALO = 8, ABI_SLACK = 64;
+size_t haloed_bytes(int B, int frames, int C) { return round_up(((size_t)B * (frames + 2 * ABI_HALO) + ABI_SLACK) * C * 2, 256); }
+bool stage_fwd(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cin % 64 == 0 && Cout >= 16 && s >= 1; }
+bool stage_dgrad(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && s == 1 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cout % 64 == 0 && Cin % 8 == 0 && Cin >= 64; }
+bool stage_wgrad(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && s == 1 && (k - 1) / 2 <= ABI_HALO && Cin % 8 == 0 && Cout % 8 == 0 && Cout >= 64 && (long long)k * Cin >= 64; }
+}  // namespace
+
+extern "C" size_t w2l_conv1d_fwd_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype)
+{
+    if (check_conv_shape(B, T, Cin, Cout, k, stride)) return 0;
+    return stage_fwd(Cin, Cout, k, stride, dtype) ? haloed_bytes(B, T, Cin) : 0;
+}
 
 extern "C" int w2l_conv1d_fwd(const void* x, const void* w, const float* bias, void* y, int B, int T, int Cin,
                               int Cout, int k, int stride, int dtype, int y_dtype, void* workspace,
@@ -95,12 +110,26 @@ extern "C" int w2l_conv1d_fwd(const void* x, const void* w, const float* bias, v
     if (!valid_dtype(dtype) || !valid_dtype(y_dtype) || (dtype == W2L_F32 && y_dtype != W2L_F32))
         return W2L_ERR_DTYPE;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y) || (bias && !aligned16(bias))) return W2L_ERR_ALIGN;
-    if (!ws_ok(workspace, ws_bytes, w2l_conv1d_fwd_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
-        return W2L_ERR_WORKSPACE;
-    return conv_fwd(dense_desc(B, T, Cin, Cout, k, stride), x, w, bias, y, dtype, y_dtype, (hipStream_t)stream);
+    const size_t need = w2l_conv1d_fwd_workspace_bytes(B, T, Cin, Cout, k, stride, dtype);
+    if (workspace && !ws_ok(workspace, ws_bytes, need)) return W2L_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    ConvDesc d = dense_desc(B, T, Cin, Cout, k, stride);
+    if (workspace && need) {
+        rc = pad_layout_bf16(x, workspace, B, T, Cin, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK, st);
+        if (rc) return rc;
+        d.x_pitch = T + 2 * ABI_HALO;
+        d.x_halo = ABI_HALO;
+        d.slack = ABI_SLACK;
+        x = workspace;
+    }
+    return conv_fwd(d, x, w, bias, y, dtype, y_dtype, st);
 }
 
-extern "C" size_t w2l_conv1d_bwd_data_workspace_bytes(int, int, int, int, int, int, int) { return 0; }
+extern "C" size_t w2l_conv1d_bwd_data_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype)
+{
+    if (check_conv_shape(B, T, Cin, Cout, k, stride)) return 0;
+    return stage_dgrad(Cin, Cout, k, stride, dtype) ? haloed_bytes(B, out_len(T, stride), Cout) : 0;
+}
 
 extern "C" int w2l_conv1d_bwd_data(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout,
                                    int k, int stride, int dtype, int dy_dtype, void* workspace, size_t ws_bytes,
@@ -112,17 +141,28 @@ extern "C" int w2l_conv1d_bwd_data(const void* dy, const void* w, void* dx, int 
     if (!valid_dtype(dtype) || !valid_dtype(dy_dtype) || (dtype == W2L_F32 && dy_dtype != W2L_F32))
         return W2L_ERR_DTYPE;
     if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return W2L_ERR_ALIGN;
-    if (!ws_ok(workspace, ws_bytes, w2l_conv1d_bwd_data_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
-        return W2L_ERR_WORKSPACE;
-    return conv_dgrad(dense_desc(B, T, Cin, Cout, k, stride), dy, w, dx, dtype, dy_dtype, (hipStream_t)stream);
+    const size_t need = (dy_dtype == W2L_BF16) ? w2l_conv1d_bwd_data_workspace_bytes(B, T, Cin, Cout, k, stride, dtype) : 0;
+    if (workspace && !ws_ok(workspace, ws_bytes, need)) return W2L_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    ConvDesc d = dense_desc(B, T, Cin, Cout, k, stride);
+    if (workspace && need) {
+        rc = pad_layout_bf16(dy, workspace, B, d.Tp, Cout, d.Tp + 2 * ABI_HALO, ABI_HALO, ABI_SLACK, st);
+        if (rc) return rc;
+        d.y_pitch = d.Tp + 2 * ABI_HALO;
+        d.y_halo = ABI_HALO;
+        d.slack = ABI_SLACK;
+        dy = workspace;
+    }
+    return conv_dgrad(d, dy, w, dx, dtype, dy_dtype, st);
 }
 
 extern "C" size_t w2l_conv1d_bwd_weight_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride,
                                                         int dtype)
 {
-    (void)dtype;
-    if (B <= 0 || T <= 0 || Cin <= 0 || Cout <= 0 || k <= 0 || stride <= 0) return 0;
-    return conv_wgrad_scratch_bytes(Cin, Cout, k);
+    if (check_conv_shape(B, T, Cin, Cout, k, stride)) return 0;
+    size_t n = conv_wgrad_scratch_bytes(Cin, Cout, k);
+    if (stage_wgrad(Cin, Cout, k, stride, dtype)) n += haloed_bytes(B, T, Cin) + haloed_bytes(B, T, Cout);
+    return n;
 }
 
 extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, float* dbias, int B, int T,
@@ -137,6 +177,21 @@ extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, f
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || (dbias && !aligned16(dbias))) return W2L_ERR_ALIGN;
     if (!ws_ok(workspace, ws_bytes, w2l_conv1d_bwd_weight_workspace_bytes(B, T, Cin, Cout, k, stride, dtype)))
         return W2L_ERR_WORKSPACE;
-    return conv_wgrad(dense_desc(B, T, Cin, Cout, k, stride), x, dy, dw, dbias, dtype, dy_dtype, accumulate,
-                      workspace, (hipStream_t)stream);
+    hipStream_t st = (hipStream_t)stream;
+    ConvDesc d = dense_desc(B, T, Cin, Cout, k, stride);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    if (dy_dtype == W2L_BF16 && stage_wgrad(Cin, Cout, k, stride, dtype)) {
+        unsigned char* xp = ws + conv_wgrad_scratch_bytes(Cin, Cout, k);
+        unsigned char* dyp = xp + haloed_bytes(B, T, Cin);
+        rc = pad_layout_bf16(x, xp, B, T, Cin, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK, st);
+        if (rc) return rc;
+        rc = pad_layout_bf16(dy, dyp, B, T, Cout, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK, st);
+        if (rc) return rc;
+        d.x_pitch = d.y_pitch = T + 2 * ABI_HALO;
+        d.x_halo = d.y_halo = ABI_HALO;
+        d.slack = ABI_SLACK;
+        x = xp;
+        dy = dyp;
+    }
+    return conv_wgrad(d, x, dy, dw, dbias, dtype, dy_dtype, accumulate, workspace, st);
 }

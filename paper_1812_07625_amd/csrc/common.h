@@ -103,4 +103,7 @@ int glu_fwd_layout(const void* y, void* h, int B, int Tp, int Cout, int dtype, i
 int glu_bwd_layout(const void* y, const void* dh, void* dy, int B, int Tp, int Cout, int dtype, int pitch, int halo,
                    int slack, hipStream_t st);
 
+// dense bf16 [B*Tp, C] (C % 8 == 0) -> layout with the given pitch / halo / slack, zeros outside the real frames
+int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch, int halo, int slack, hipStream_t st);
+
 }  // namespace w2l

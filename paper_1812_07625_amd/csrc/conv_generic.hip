@@ -259,6 +259,42 @@ __global__ __launch_bounds__(256) void colsum_stage1(const T* dy, float* part, l
         part[(size_t)blockIdx.y * Cout + c] = (sm[0][threadIdx.x] + sm[1][threadIdx.x]) +
                                               (sm[2][threadIdx.x] + sm[3][threadIdx.x]);
 }
+// bf16, Cout % 8 == 0: one pass.  A workgroup owns 32 columns (4 lanes x 16-byte loads) and
+// 64 row lanes; the 64 partial sums per column are added in a fixed tree through LDS.
+__global__ __launch_bounds__(256) void colsum_bf16(const bf16_t* __restrict__ dy, float* __restrict__ dbias,
+                                                   long long rows, int Cout, int accumulate)
+{
+    const int cg = threadIdx.x & 3, rl = threadIdx.x >> 2;
+    const int c0 = blockIdx.x * 32 + cg * 8;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    if (c0 < Cout)
+        for (long long r = rl; r < rows; r += 64) {
+            const uint4 v = *reinterpret_cast<const uint4*>(dy + r * Cout + c0);
+            const unsigned u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[2 * j] += __uint_as_float(u[j] << 16);
+                acc[2 * j + 1] += __uint_as_float(u[j] & 0xffff0000u);
+            }
+        }
+    __shared__ float sm[64][33];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm[rl][cg * 8 + j] = acc[j];
+    __syncthreads();
+    for (int half = 32; half > 0; half >>= 1) {
+        for (int e = threadIdx.x; e < half * 32; e += 256) {
+            const int r = e >> 5, c = e & 31;
+            sm[r][c] += sm[r + half][c];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < 32) {
+        const int c = blockIdx.x * 32 + threadIdx.x;
+        if (c < Cout) dbias[c] = accumulate ? dbias[c] + sm[0][threadIdx.x] : sm[0][threadIdx.x];
+    }
+}
 __global__ void colsum_stage2(const float* part, float* dbias, int chunks, int Cout, int accumulate)
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
@@ -320,6 +356,11 @@ int conv_wgrad_skinny(const ConvDesc& d, const void* x, const void* dy, float* d
 int dbias_reduce(const void* dy, float* dbias, long long rows, int Cout, int dydt, int accumulate,
                  float* scratch, hipStream_t st)
 {
+    if (dydt == W2L_BF16 && Cout % 8 == 0) {
+        hipLaunchKernelGGL(colsum_bf16, dim3((Cout + 31) / 32), dim3(256), 0, st, (const bf16_t*)dy, dbias, rows, Cout,
+                           accumulate);
+        return launch_status();
+    }
     const dim3 g1((Cout + 63) / 64, DBIAS_CHUNKS);
     if (dydt == W2L_F32)
         hipLaunchKernelGGL(colsum_stage1<float>, g1, dim3(256), 0, st, (const float*)dy, scratch, rows, Cout);

@@ -144,7 +144,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
         for (int k = 0; k < SCORE_AHEAD; ++k) {
             const int step = t0 + k;
-            if (step >= T) break;
+            if (step < T) {  // uniform over the workgroup; written as a guard so the ring indices stay static
             const double s_b = (double)sb[k] * LOG2E;
             double s_l[PPT];
 #pragma unroll
@@ -189,6 +189,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                 if (lane == 0 && wave > 0) recv = mailbox[step & 1][wave - 1];
             }
             left = (tid == 0) ? -INFINITY : recv;
+            }
         }
     }
     // log P = lse( alpha_{T-1}(S-1), alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1

@@ -133,6 +133,23 @@ __global__ __launch_bounds__(256) void glu_bwd_k(const T* __restrict__ y, const 
     }
 }
 
+// dense [B*Tp, C] -> haloed layout (zeros in halo and slack frames); C % 8 == 0, bf16
+__global__ __launch_bounds__(256) void pad_layout_k(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                                    long long out_rows, int C, RowMap map)
+{
+    const int cv = C / 8;
+    const long long total = out_rows * cv;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long f = i / cv;
+        const int c = (int)(i - f * cv) * 8;
+        const long long r = map.src(f);
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r >= 0) v = *reinterpret_cast<const uint4*>(src + r * C + c);
+        *reinterpret_cast<uint4*>(dst + f * C + c) = v;
+    }
+}
+
 inline unsigned grid_for(long long items)
 {
     long long b = (items + 255) / 256;
@@ -233,6 +250,17 @@ int glu_bwd_layout(const void* y, const void* dh, void* dy, int B, int Tp, int C
     return launch_status();
 }
 
+}  // namespace w2l
+
+namespace w2l {
+int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch, int halo, int slack, hipStream_t st)
+{
+    const long long out_rows = (long long)B * pitch + slack;
+    const RowMap map{Tp, pitch, halo, (long long)B * pitch};
+    hipLaunchKernelGGL(pad_layout_k, dim3(grid_for(out_rows * (C / 8))), dim3(256), 0, st, (const bf16_t*)src,
+                       (bf16_t*)dst, out_rows, C, map);
+    return launch_status();
+}
 }  // namespace w2l
 
 extern "C" int w2l_glu_fwd(const void* y, void* h, long long rows, int Cout, int dtype, void* stream)

@@ -54,13 +54,20 @@ def test_conv_three_passes(P, shape, dtype):
     dy = _grid(rng.standard_normal((B, Tp, Cout)), dtype)
 
     xd, wd, bd, dyd = to_dev(x, dtype), to_dev(w, dtype), to_dev(bias), to_dev(dy, dtype)
-    y = P.w2l_conv1d_fwd(xd, wd, bd, empty((B, Tp, Cout), dtype), s)
-    assert rel_l2(to_host(y), oracle.conv1d_fwd(x, w, bias, s)) <= TOL[dtype]
-    y0 = P.w2l_conv1d_fwd(xd, wd, None, empty((B, Tp, Cout), dtype), s)
-    assert rel_l2(to_host(y0), oracle.conv1d_fwd(x, w, None, s)) <= TOL[dtype]
-
-    dx = P.w2l_conv1d_bwd_data(dyd, wd, empty((B, T, Cin), dtype), s)
-    assert rel_l2(to_host(dx), oracle.conv1d_bwd_data(dy, w, T, s)) <= TOL[dtype]
+    code = P.W2L_BF16 if dtype == "bf16" else P.W2L_F32
+    y_o, y0_o = oracle.conv1d_fwd(x, w, bias, s), oracle.conv1d_fwd(x, w, None, s)
+    dx_o = oracle.conv1d_bwd_data(dy, w, T, s)
+    # without workspace: loads predicated against the utterance edges; with the workspace the
+    # query asks for: operands staged into the zero-haloed layout first
+    for use_ws in (False, True):
+        wf = P.workspace(P.w2l_conv1d_fwd_workspace_bytes(B, T, Cin, Cout, k, s, code)) if use_ws else None
+        y = P.w2l_conv1d_fwd(xd, wd, bd, empty((B, Tp, Cout), dtype), s, wf)
+        assert rel_l2(to_host(y), y_o) <= TOL[dtype]
+        y0 = P.w2l_conv1d_fwd(xd, wd, None, empty((B, Tp, Cout), dtype), s, wf)
+        assert rel_l2(to_host(y0), y0_o) <= TOL[dtype]
+        wb = P.workspace(P.w2l_conv1d_bwd_data_workspace_bytes(B, T, Cin, Cout, k, s, code)) if use_ws else None
+        dx = P.w2l_conv1d_bwd_data(dyd, wd, empty((B, T, Cin), dtype), s, wb)
+        assert rel_l2(to_host(dx), dx_o) <= TOL[dtype]
 
     ws = P.workspace(P.w2l_conv1d_bwd_weight_workspace_bytes(B, T, Cin, Cout, k, s, P.W2L_BF16 if dtype == "bf16" else 0))
     dw, db = P.w2l_conv1d_bwd_weight(xd, dyd, empty((Cout, k, Cin)), empty((Cout,)), s, False, ws)
@@ -299,7 +306,8 @@ def test_conv_full_size_sampled(P, shape):
         idx = rng.integers(0, n_total, size=nsamp)
         return np.unique(idx)
 
-    y = to_host(P.w2l_conv1d_fwd(xd, wd, bd, empty((B, Tp, Cout), "bf16"), s)).reshape(-1)
+    wf = P.workspace(P.w2l_conv1d_fwd_workspace_bytes(B, T, Cin, Cout, k, s, P.W2L_BF16))
+    y = to_host(P.w2l_conv1d_fwd(xd, wd, bd, empty((B, Tp, Cout), "bf16"), s, wf)).reshape(-1)
     idx = sample(y.size)
     # always include the corners of every utterance (zero-padded windows) and the last tile
     corners = []
@@ -312,7 +320,8 @@ def test_conv_full_size_sampled(P, shape):
     assert rel_l2(y[idx], ref) <= TOL["bf16"]
 
     if s == 1:
-        dx = to_host(P.w2l_conv1d_bwd_data(dyd, wd, empty((B, T, Cin), "bf16"), s)).reshape(-1)
+        wb = P.workspace(P.w2l_conv1d_bwd_data_workspace_bytes(B, T, Cin, Cout, k, s, P.W2L_BF16))
+        dx = to_host(P.w2l_conv1d_bwd_data(dyd, wd, empty((B, T, Cin), "bf16"), s, wb)).reshape(-1)
         idx = sample(dx.size)
         corners = [(b * T + t) * Cin + c for b in range(B) for t in (0, 1, T - 2, T - 1) for c in (0, Cin - 1)]
         idx = np.unique(np.concatenate([idx, np.array(corners)]))
