@@ -26,24 +26,25 @@ constexpr int GRAD_ROWS = 16;   // frames per ctc_grad workgroup (4 per wavefron
 
 struct CtcDims {
     int B, Tp, C, Lmax, blank;
-    int Sp;  // lattice row pitch = 2*Lmax+2 (pairs of doubles, 16-byte aligned)
+    int Sp;  // lattice row pitch = 2*Lmax+4: pairs of doubles, the last pair is a spare; Tp+1 rows per utterance
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
-// log2( 2^a + 2^b + 2^c ), any of them may be -inf
+// log2( 2^a + 2^b + 2^c ), any of them may be -inf.  Branch-free: with every operand -inf the
+// reference point is moved to 0, the exponentials are 0 and log2(0) = -inf comes out by itself.
 __device__ __forceinline__ double lse3_log2(double a, double b, double c)
 {
-    const double m = fmax(a, fmax(b, c));
-    if (m == -INFINITY) return -INFINITY;
+    double m = fmax(a, fmax(b, c));
+    m = (m == -INFINITY) ? 0.0 : m;
     const float sum = fast_exp2((float)(a - m)) + fast_exp2((float)(b - m)) + fast_exp2((float)(c - m));
     return m + (double)fast_log2(sum);
 }
 __device__ __forceinline__ double lse2_log2(double a, double b)
 {
-    const double m = fmax(a, b);
-    if (m == -INFINITY) return -INFINITY;
+    double m = fmax(a, b);
+    m = (m == -INFINITY) ? 0.0 : m;
     const float sum = fast_exp2((float)(a - m)) + fast_exp2((float)(b - m));
     return m + (double)fast_log2(sum);
 }
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         skip[j] = has_l[j] && i >= 1 && lab[dir ? li + 1 : li - 1] != cls[j];
     }
     const float* lpb = lp + (size_t)b * d.Tp * d.C;
-    double* lat = (dir ? beta : alpha) + (size_t)b * d.Tp * d.Sp;
+    double* lat = (dir ? beta : alpha) + (size_t)b * (d.Tp + 1) * d.Sp;
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
 
     // score ring: sb[k] / sl[j][k] hold the scores of step (current block of SCORE_AHEAD) + k
@@ -134,17 +135,24 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
         for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
     }
-    double ab[PPT], al[PPT];
+    double ab[PPT], al[PPT], fin_b[PPT], fin_l[PPT];
 #pragma unroll
-    for (int j = 0; j < PPT; ++j) { ab[j] = -INFINITY; al[j] = -INFINITY; }
+    for (int j = 0; j < PPT; ++j) { ab[j] = -INFINITY; al[j] = -INFINITY; fin_b[j] = -INFINITY; fin_l[j] = -INFINITY; }
     double left = -INFINITY;  // label state of the pair to the left of this thread's first pair, previous frame
     const int nwaves = NT >> 6;
+    // Lattice slot of this thread's pair j; threads past the end of the target write to the
+    // spare pair at the end of the row, steps past the last frame to the spare row Tp: the step
+    // body below is straight-line code with a fixed number of memory operations, so that the
+    // compiler's counters can let the score prefetches and lattice stores stay in flight.
+    int slot[PPT];
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) slot[j] = 2 * (live[j] ? tid * PPT + j : d.Lmax + 1);
+    const int tblocks = (T + SCORE_AHEAD - 1) / SCORE_AHEAD;
 
-    for (int t0 = 0; t0 < T; t0 += SCORE_AHEAD) {
+    for (int tb = 0; tb < tblocks; ++tb) {
 #pragma unroll
         for (int k = 0; k < SCORE_AHEAD; ++k) {
-            const int step = t0 + k;
-            if (step < T) {  // uniform over the workgroup; written as a guard so the ring indices stay static
+            const int step = tb * SCORE_AHEAD + k;
             const double s_b = (double)sb[k] * LOG2E;
             double s_l[PPT];
 #pragma unroll
@@ -156,27 +164,24 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
                 for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
             }
+            const int row = step < T ? frame(step) : d.Tp;
             double carry = left;  // label value (previous frame) of the pair to the left of pair j
 #pragma unroll
             for (int j = 0; j < PPT; ++j) {
                 const double ob = ab[j], ol = al[j];
-                double nb, nl;
-                if (step == 0) {
-                    const bool first = (tid * PPT + j) == 0;
-                    nb = first ? s_b : -INFINITY;
-                    nl = (first && has_l[j]) ? s_l[j] : -INFINITY;
-                } else {
-                    nb = lse2_log2(ob, carry) + s_b;
-                    nl = has_l[j] ? lse3_log2(ol, ob, skip[j] ? carry : -INFINITY) + s_l[j] : -INFINITY;
-                }
-                if (!live[j]) { nb = -INFINITY; nl = -INFINITY; }
+                const bool first = (tid * PPT + j) == 0;
+                double nb = lse2_log2(ob, carry) + s_b;
+                double nl = lse3_log2(ol, ob, skip[j] ? carry : -INFINITY) + s_l[j];
+                nb = (step == 0) ? (first ? s_b : -INFINITY) : nb;
+                nl = (step == 0) ? (first ? s_l[j] : -INFINITY) : nl;
+                nb = live[j] ? nb : -INFINITY;
+                nl = has_l[j] ? nl : -INFINITY;
                 carry = ol;
                 ab[j] = nb;
                 al[j] = nl;
-                if (live[j]) {
-                    double2 v2 = make_double2(nb, nl);
-                    *reinterpret_cast<double2*>(lat + (size_t)frame(step) * d.Sp + 2 * (tid * PPT + j)) = v2;
-                }
+                fin_b[j] = (step == T - 1) ? nb : fin_b[j];
+                fin_l[j] = (step == T - 1) ? nl : fin_l[j];
+                *reinterpret_cast<double2*>(lat + (size_t)row * d.Sp + slot[j]) = make_double2(nb, nl);
             }
             // hand this thread's last label value to the thread on its right
             const double send = al[PPT - 1];
@@ -186,10 +191,10 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-                if (lane == 0 && wave > 0) recv = mailbox[step & 1][wave - 1];
+                const double mb = mailbox[step & 1][wave > 0 ? wave - 1 : 0];
+                recv = (lane == 0) ? mb : recv;
             }
             left = (tid == 0) ? -INFINITY : recv;
-            }
         }
     }
     // log P = lse( alpha_{T-1}(S-1), alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1
@@ -197,8 +202,8 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
         for (int j = 0; j < PPT; ++j) {
             const int i = tid * PPT + j;
-            if (i == L) fin[0] = ab[j];
-            if (i == L - 1) fin[1] = al[j];
+            if (i == L) fin[0] = fin_b[j];
+            if (i == L - 1) fin[1] = fin_l[j];
         }
         __syncthreads();
         if (tid == 0) {
@@ -271,8 +276,8 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
             for (int c = lane; c < d.C; c += 64) grow[c] = 0.f;
             continue;
         }
-        const double* ar = alpha + ((size_t)b * d.Tp + t) * d.Sp;
-        const double* br = beta + ((size_t)b * d.Tp + t) * d.Sp;
+        const double* ar = alpha + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
+        const double* br = beta + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
         const float* lrow = lpb + (size_t)t * d.C;
         float z = 0.f, zb = 0.f;
         for (int s = lane; s < S; s += 64) {
@@ -306,7 +311,7 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
 
 size_t grad_lds_bytes(int Lmax, int C)
 {
-    return (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (2 * Lmax + 2);
+    return (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (2 * Lmax + 4);
 }
 
 struct WsLayout { size_t lp, logp, alpha, beta, total; };
@@ -316,7 +321,7 @@ WsLayout ws_layout(int B, int Tp, int C, int Lmax)
     size_t off = 0;
     w.lp = off; off += round_up((size_t)B * Tp * C * 4, 256);
     w.logp = off; off += round_up((size_t)B * 8, 256);
-    const size_t lat = round_up((size_t)B * Tp * (2 * (size_t)Lmax + 2) * 8, 256);
+    const size_t lat = round_up((size_t)B * (Tp + 1) * (2 * (size_t)Lmax + 4) * 8, 256);
     w.alpha = off; off += lat;
     w.beta = off; off += lat;
     w.total = off;
@@ -372,7 +377,7 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     double* logp = reinterpret_cast<double*>(ws + w.logp);
     double* alpha = reinterpret_cast<double*>(ws + w.alpha);
     double* beta = reinterpret_cast<double*>(ws + w.beta);
-    CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 2};
+    CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 4};
 
     const size_t lds2 = grad_lds_bytes(Lmax, C);
     if (lds2 > 160 * 1024) return W2L_ERR_SHAPE;
