@@ -7,11 +7,13 @@
 //   2. ctc_lattice: one workgroup per (utterance, direction).  alpha runs forward in
 //      time, beta is the same recursion on the reversed label sequence and reversed
 //      time, so the two run concurrently and the serial chain is T_b steps, not 2 T_b.
-//      States live in LDS; scores are kept in the base-2 log domain so that the
-//      log-sum-exp maps onto the hardware exp2/log2 instructions; the running values
-//      are held in fp64 (their magnitude grows with t, the increments do not) while
-//      every transcendental is evaluated in fp32 on differences.  Score rows are
-//      prefetched into LDS a chunk of frames ahead, off the dependency chain;
+//      Scores are kept in the base-2 log domain so that the log-sum-exp maps onto the
+//      hardware exp2/log2 instructions.  States are fp32 values *relative to a running
+//      offset*: every 16 frames the workgroup's largest state is subtracted from all of
+//      them and added to a double-precision offset, so the fp32 values stay small (their
+//      rounding error does not grow with t) while the magnitude lives in the offset.
+//      "Log zero" is a large negative finite number, which keeps the recursion free of
+//      branches and NaNs;
 //   3. ctc_grad: one wavefront per frame combines alpha_t and beta_t into the state
 //      posteriors, normalises them per frame, and sums them per class in a fixed
 //      order given by a (class, position) sort of the target.
@@ -32,33 +34,29 @@ struct CtcDims {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
-// log2( 2^a + 2^b + 2^c ), any of them may be -inf.  Branch-free: with every operand -inf the
-// reference point is moved to 0, the exponentials are 0 and log2(0) = -inf comes out by itself.
-__device__ __forceinline__ double lse3_log2(double a, double b, double c)
+constexpr float NEG = -1.0e30f;      // log zero: absorbs every finite addend, never turns into NaN
+constexpr float NEG_TEST = -1.0e29f;  // anything below is "log zero"
+
+// log2( 2^a + 2^b [+ 2^c] ); operands may be NEG
+__device__ __forceinline__ float lse3_log2(float a, float b, float c)
 {
-    double m = fmax(a, fmax(b, c));
-    m = (m == -INFINITY) ? 0.0 : m;
-    const float sum = fast_exp2((float)(a - m)) + fast_exp2((float)(b - m)) + fast_exp2((float)(c - m));
-    return m + (double)fast_log2(sum);
+    const float m = fmaxf(a, fmaxf(b, c));
+    return m + fast_log2(fast_exp2(a - m) + fast_exp2(b - m) + fast_exp2(c - m));
 }
-__device__ __forceinline__ double lse2_log2(double a, double b)
+__device__ __forceinline__ float lse2_log2(float a, float b)
 {
-    double m = fmax(a, b);
-    m = (m == -INFINITY) ? 0.0 : m;
-    const float sum = fast_exp2((float)(a - m)) + fast_exp2((float)(b - m));
-    return m + (double)fast_log2(sum);
+    const float m = fmaxf(a, b);
+    return m + fast_log2(fast_exp2(a - m) + fast_exp2(b - m));
+}
+__device__ __forceinline__ float wave_max_f(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
 }
 
-// value of `v` held by the previous lane of the wavefront (lane 0 receives its own)
-__device__ __forceinline__ double from_prev_lane(double v)
-{
-    const unsigned long long u = __double_as_longlong(v);
-    const int lo = __shfl_up((int)(u & 0xffffffffu), 1, 64);
-    const int hi = __shfl_up((int)(u >> 32), 1, 64);
-    return __longlong_as_double(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
-}
-
-constexpr int SCORE_AHEAD = 16;  // frames of scores held in registers ahead of the recursion
+constexpr int SCORE_AHEAD = 16;  // frames of scores held in registers ahead of the recursion;
+                                 // also the renormalisation period
 
 // One workgroup per (utterance, direction).  The extended sequence is cut into pairs
 // (blank 2i, label 2i+1); a thread owns PPT consecutive pairs and keeps their alpha values in
@@ -67,15 +65,21 @@ constexpr int SCORE_AHEAD = 16;  // frames of scores held in registers ahead of 
 // through a two-slot LDS mailbox and the one barrier of the step).  The scores lp[t, blank]
 // and lp[t, label] are fetched SCORE_AHEAD frames early into a register ring, off the
 // dependency chain.  beta is the same recursion on the reversed sequence and reversed time
-// (state index q counts from the end), stored in its own q order.
+// (state index q counts from the end), stored in its own q order.  The step body is
+// straight-line code with a fixed number of memory operations (threads past the end of the
+// target write to a spare pair, steps past the last frame to a spare row), so the score
+// prefetches and lattice stores stay in flight across steps.
+// Stored per frame: the relative states (fp32) and the offset that applies to them (fp64).
 template <int PPT>
 __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp, const int* __restrict__ targets,
                                                     const int* __restrict__ in_len, const int* __restrict__ tgt_len,
                                                     float* __restrict__ loss, double* __restrict__ logp2_out,
-                                                    double* __restrict__ alpha, double* __restrict__ beta, CtcDims d)
+                                                    float* __restrict__ alpha, float* __restrict__ beta,
+                                                    double* __restrict__ aoff, double* __restrict__ boff, CtcDims d)
 {
-    __shared__ double mailbox[2][16];
-    __shared__ double fin[2];
+    __shared__ float mailbox[2][16];
+    __shared__ float wmax[16];
+    __shared__ float fin[2];
     __shared__ int bad_len, bad;
     const int dir = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
@@ -83,8 +87,8 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     if (tid == 0) {
         bad_len = (T < 0 || T > d.Tp || L < 0 || L > d.Lmax) ? 1 : 0;
         bad = 0;
-        fin[0] = -INFINITY;
-        fin[1] = -INFINITY;
+        fin[0] = NEG;
+        fin[1] = NEG;
     }
     __syncthreads();
     if (bad_len) {
@@ -113,6 +117,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     bool has_l[PPT];   // label state exists
     bool skip[PPT];    // label state may be entered from the label of the pair to the left
     bool live[PPT];    // pair exists
+    int slot[PPT];     // lattice position of the pair (the spare pair for threads past the end)
 #pragma unroll
     for (int j = 0; j < PPT; ++j) {
         const int i = tid * PPT + j;
@@ -121,12 +126,14 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         const int li = dir ? L - 1 - i : i;          // label index in the target
         cls[j] = has_l[j] ? lab[li] : d.blank;
         skip[j] = has_l[j] && i >= 1 && lab[dir ? li + 1 : li - 1] != cls[j];
+        slot[j] = 2 * (live[j] ? i : d.Lmax + 1);
     }
     const float* lpb = lp + (size_t)b * d.Tp * d.C;
-    double* lat = (dir ? beta : alpha) + (size_t)b * (d.Tp + 1) * d.Sp;
+    float* lat = (dir ? beta : alpha) + (size_t)b * (d.Tp + 1) * d.Sp;
+    double* offs = (dir ? boff : aoff) + (size_t)b * (d.Tp + 1);
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
+    const float log2e = (float)LOG2E;
 
-    // score ring: sb[k] / sl[j][k] hold the scores of step (current block of SCORE_AHEAD) + k
     float sb[SCORE_AHEAD], sl[PPT][SCORE_AHEAD];
 #pragma unroll
     for (int k = 0; k < SCORE_AHEAD; ++k) {
@@ -135,28 +142,23 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
         for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
     }
-    double ab[PPT], al[PPT], fin_b[PPT], fin_l[PPT];
+    float ab[PPT], al[PPT], fin_b[PPT], fin_l[PPT];
 #pragma unroll
-    for (int j = 0; j < PPT; ++j) { ab[j] = -INFINITY; al[j] = -INFINITY; fin_b[j] = -INFINITY; fin_l[j] = -INFINITY; }
-    double left = -INFINITY;  // label state of the pair to the left of this thread's first pair, previous frame
+    for (int j = 0; j < PPT; ++j) { ab[j] = NEG; al[j] = NEG; fin_b[j] = NEG; fin_l[j] = NEG; }
+    float left = NEG;   // label state of the pair to the left of this thread's first pair, previous frame
+    double offset = 0;  // true log2 value = relative value + offset
+    double fin_off = 0;
     const int nwaves = NT >> 6;
-    // Lattice slot of this thread's pair j; threads past the end of the target write to the
-    // spare pair at the end of the row, steps past the last frame to the spare row Tp: the step
-    // body below is straight-line code with a fixed number of memory operations, so that the
-    // compiler's counters can let the score prefetches and lattice stores stay in flight.
-    int slot[PPT];
-#pragma unroll
-    for (int j = 0; j < PPT; ++j) slot[j] = 2 * (live[j] ? tid * PPT + j : d.Lmax + 1);
     const int tblocks = (T + SCORE_AHEAD - 1) / SCORE_AHEAD;
 
     for (int tb = 0; tb < tblocks; ++tb) {
 #pragma unroll
         for (int k = 0; k < SCORE_AHEAD; ++k) {
             const int step = tb * SCORE_AHEAD + k;
-            const double s_b = (double)sb[k] * LOG2E;
-            double s_l[PPT];
+            const float s_b = sb[k] * log2e;
+            float s_l[PPT];
 #pragma unroll
-            for (int j = 0; j < PPT; ++j) s_l[j] = (double)sl[j][k] * LOG2E;
+            for (int j = 0; j < PPT; ++j) s_l[j] = sl[j][k] * log2e;
             {   // refill this ring slot for step + SCORE_AHEAD
                 const int nf = step + SCORE_AHEAD;
                 const int f = frame(nf < T ? nf : T - 1);
@@ -165,36 +167,59 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                 for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
             }
             const int row = step < T ? frame(step) : d.Tp;
-            double carry = left;  // label value (previous frame) of the pair to the left of pair j
+            float carry = left;  // label value (previous frame) of the pair to the left of pair j
 #pragma unroll
             for (int j = 0; j < PPT; ++j) {
-                const double ob = ab[j], ol = al[j];
+                const float ob = ab[j], ol = al[j];
                 const bool first = (tid * PPT + j) == 0;
-                double nb = lse2_log2(ob, carry) + s_b;
-                double nl = lse3_log2(ol, ob, skip[j] ? carry : -INFINITY) + s_l[j];
-                nb = (step == 0) ? (first ? s_b : -INFINITY) : nb;
-                nl = (step == 0) ? (first ? s_l[j] : -INFINITY) : nl;
-                nb = live[j] ? nb : -INFINITY;
-                nl = has_l[j] ? nl : -INFINITY;
+                float nb = lse2_log2(ob, carry) + s_b;
+                float nl = lse3_log2(ol, ob, skip[j] ? carry : NEG) + s_l[j];
+                nb = (step == 0) ? (first ? s_b : NEG) : nb;
+                nl = (step == 0) ? (first ? s_l[j] : NEG) : nl;
+                nb = live[j] ? nb : NEG;
+                nl = has_l[j] ? nl : NEG;
                 carry = ol;
                 ab[j] = nb;
                 al[j] = nl;
                 fin_b[j] = (step == T - 1) ? nb : fin_b[j];
                 fin_l[j] = (step == T - 1) ? nl : fin_l[j];
-                *reinterpret_cast<double2*>(lat + (size_t)row * d.Sp + slot[j]) = make_double2(nb, nl);
+                *reinterpret_cast<float2*>(lat + (size_t)row * d.Sp + slot[j]) = make_float2(nb, nl);
             }
+            if (tid == 0) offs[row] = offset;
+            fin_off = (step == T - 1) ? offset : fin_off;
             // hand this thread's last label value to the thread on its right
-            const double send = al[PPT - 1];
-            double recv = from_prev_lane(send);
+            const float send = al[PPT - 1];
+            float recv = __shfl_up(send, 1, 64);
             if (nwaves > 1) {
                 if (lane == 63) mailbox[step & 1][wave] = send;
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-                const double mb = mailbox[step & 1][wave > 0 ? wave - 1 : 0];
+                const float mb = mailbox[step & 1][wave > 0 ? wave - 1 : 0];
                 recv = (lane == 0) ? mb : recv;
             }
-            left = (tid == 0) ? -INFINITY : recv;
+            left = (tid == 0) ? NEG : recv;
+        }
+        // renormalise: move the workgroup's largest state into the offset
+        float m = NEG;
+#pragma unroll
+        for (int j = 0; j < PPT; ++j) m = fmaxf(m, fmaxf(ab[j], al[j]));
+        m = wave_max_f(m);
+        if (nwaves > 1) {
+            if (lane == 0) wmax[wave] = m;
+            __syncthreads();
+            m = wmax[0];
+            for (int w2 = 1; w2 < nwaves; ++w2) m = fmaxf(m, wmax[w2]);
+            __syncthreads();
+        }
+        if (m > NEG_TEST) {  // uniform over the workgroup
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) {
+                ab[j] = ab[j] > NEG_TEST ? ab[j] - m : NEG;
+                al[j] = al[j] > NEG_TEST ? al[j] - m : NEG;
+            }
+            left = left > NEG_TEST ? left - m : NEG;
+            offset += (double)m;
         }
     }
     // log P = lse( alpha_{T-1}(S-1), alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1
@@ -207,9 +232,11 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         }
         __syncthreads();
         if (tid == 0) {
-            const double lp2 = lse2_log2(fin[0], fin[1]);
+            const float rel = lse2_log2(fin[0], fin[1]);
+            const bool none = rel < NEG_TEST;
+            const double lp2 = none ? -INFINITY : (double)rel + fin_off;
             logp2_out[b] = lp2;
-            loss[b] = (lp2 == -INFINITY) ? INFINITY : (float)(-lp2 * LN2);
+            loss[b] = none ? INFINITY : (float)(-lp2 * LN2);
         }
     }
 }
@@ -226,8 +253,10 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
                                                 const int* __restrict__ tgt_len,
                                                 const float* __restrict__ loss,
                                                 const double* __restrict__ logp2_in,
-                                                const double* __restrict__ alpha,
-                                                const double* __restrict__ beta, float* __restrict__ grad,
+                                                const float* __restrict__ alpha,
+                                                const float* __restrict__ beta,
+                                                const double* __restrict__ aoff,
+                                                const double* __restrict__ boff, float* __restrict__ grad,
                                                 CtcDims d, int is_logits, float grad_scale)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -276,16 +305,17 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
             for (int c = lane; c < d.C; c += 64) grow[c] = 0.f;
             continue;
         }
-        const double* ar = alpha + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
-        const double* br = beta + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
+        const float* ar = alpha + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
+        const float* br = beta + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
         const float* lrow = lpb + (size_t)t * d.C;
+        // offsets of the two lattices at this frame minus log P: what every state's sum needs added
+        const float shift = (float)(aoff[(size_t)b * (d.Tp + 1) + t] + boff[(size_t)b * (d.Tp + 1) + t] - logp2);
         float z = 0.f, zb = 0.f;
         for (int s = lane; s < S; s += 64) {
             const int c = (s & 1) ? lab[(s - 1) >> 1] : d.blank;
-            const double a = ar[s], bt = br[S - 1 - s];  // beta rows are stored in reversed state order
+            const float a = ar[s], bt = br[S - 1 - s];  // beta rows are stored in reversed state order
             float e = 0.f;
-            if (a != -INFINITY && bt != -INFINITY)
-                e = fast_exp2((float)(a + bt - (double)lrow[c] * LOG2E - logp2));
+            if (a > NEG_TEST && bt > NEG_TEST) e = fast_exp2((a + bt) + (shift - lrow[c] * (float)LOG2E));
             ebuf[s] = e;
             z += e;
             if (!(s & 1)) zb += e;
@@ -314,16 +344,19 @@ size_t grad_lds_bytes(int Lmax, int C)
     return (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (2 * Lmax + 4);
 }
 
-struct WsLayout { size_t lp, logp, alpha, beta, total; };
+struct WsLayout { size_t lp, logp, alpha, beta, aoff, boff, total; };
 WsLayout ws_layout(int B, int Tp, int C, int Lmax)
 {
     WsLayout w;
     size_t off = 0;
     w.lp = off; off += round_up((size_t)B * Tp * C * 4, 256);
     w.logp = off; off += round_up((size_t)B * 8, 256);
-    const size_t lat = round_up((size_t)B * (Tp + 1) * (2 * (size_t)Lmax + 4) * 8, 256);
+    const size_t lat = round_up((size_t)B * (Tp + 1) * (2 * (size_t)Lmax + 4) * 4, 256);
     w.alpha = off; off += lat;
     w.beta = off; off += lat;
+    const size_t offs = round_up((size_t)B * (Tp + 1) * 8, 256);
+    w.aoff = off; off += offs;
+    w.boff = off; off += offs;
     w.total = off;
     return w;
 }
@@ -375,8 +408,10 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
         lp = lpw;
     }
     double* logp = reinterpret_cast<double*>(ws + w.logp);
-    double* alpha = reinterpret_cast<double*>(ws + w.alpha);
-    double* beta = reinterpret_cast<double*>(ws + w.beta);
+    float* alpha = reinterpret_cast<float*>(ws + w.alpha);
+    float* beta = reinterpret_cast<float*>(ws + w.beta);
+    double* aoff = reinterpret_cast<double*>(ws + w.aoff);
+    double* boff = reinterpret_cast<double*>(ws + w.boff);
     CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 4};
 
     const size_t lds2 = grad_lds_bytes(Lmax, C);
@@ -392,12 +427,12 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     int nt = ((pairs + ppt - 1) / ppt + 63) / 64 * 64;
     if (nt > 1024) return W2L_ERR_SHAPE;
     const dim3 g1(2, B), b1(nt);
-    if (ppt == 1) hipLaunchKernelGGL(ctc_lattice<1>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
-    else if (ppt == 2) hipLaunchKernelGGL(ctc_lattice<2>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
-    else hipLaunchKernelGGL(ctc_lattice<4>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
+    if (ppt == 1) hipLaunchKernelGGL(ctc_lattice<1>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, aoff, boff, d);
+    else if (ppt == 2) hipLaunchKernelGGL(ctc_lattice<2>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, aoff, boff, d);
+    else hipLaunchKernelGGL(ctc_lattice<4>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, aoff, boff, d);
     int rc = launch_status();
     if (rc) return rc;
     hipLaunchKernelGGL(ctc_grad, dim3((Tp + GRAD_ROWS - 1) / GRAD_ROWS, B), dim3(256), lds2, st, lp, targets,
-                       in_len, tgt_len, loss, logp, alpha, beta, grad, d, is_logits, grad_scale);
+                       in_len, tgt_len, loss, logp, alpha, beta, aoff, boff, grad, d, is_logits, grad_scale);
     return launch_status();
 }
