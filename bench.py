@@ -20,8 +20,15 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_MFMA = 2.5e15   # dense bf16 MFMA, FLOP/s (MI355X published)
 PEAK_HBM = 8.0e12         # B/s
 
+# HBM bytes per launch of the dominant kernel, from two `rocprofv3 --pmc` runs
+# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, scaled by the same counters' reading for a
+# device copy of known size).  The runs and the factor are recorded in
+# profiles/conv_dgrad_config4_body_pmc.txt; None until they have been taken.
+DOMINANT_KERNEL_HBM_BYTES = None
+
 
 def event_time_ms(fn, iters, warmup=2):
+    """Average milliseconds per call, HIP events on torch's current stream (the launch stream)."""
     import torch
     for _ in range(warmup):
         fn()
@@ -38,8 +45,8 @@ def event_time_ms(fn, iters, warmup=2):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=20)
     args = ap.parse_args()
@@ -85,7 +92,24 @@ def main():
     frames = int(cfg["in_len"].sum())
     flops = W.step_flops(layers, B, T)
 
-    # ---- per-kernel roofline at the body-layer shape (k=11, 768 -> 1536, M = B*T' = 6000)
+    # ---- measured ceilings: matrix pipe alone, and a plain device copy
+    sink = empty((2048 * 256,))
+    probe_flop = [0.0]
+
+    def probe():
+        probe_flop[0] = P.w2l_probe_mfma(sink, 2048, 2000)
+
+    t_probe = event_time_ms(probe, 3, 1)
+    mfma_ceiling = probe_flop[0] / (t_probe * 1e-3)
+    cbuf_a = torch.empty(1 << 29, dtype=torch.uint8, device="cuda:0")
+    cbuf_b = torch.empty_like(cbuf_a)
+    t_copy = event_time_ms(lambda: cbuf_b.copy_(cbuf_a), 5, 2)
+    copy_bw = 2.0 * cbuf_a.numel() / (t_copy * 1e-3)
+    del cbuf_a, cbuf_b
+
+    # ---- per-kernel figures at the body-layer shape (k=11, 768 -> 1536, M = B*T' = 6000),
+    # through the same entry points and kernels the train step launches (operands staged into
+    # the zero-haloed layout inside the call, as the step keeps them)
     L = layers[1]
     Tp = (T + layers[0]["stride"] - 1) // layers[0]["stride"]
     rng = np.random.default_rng(0)
@@ -94,13 +118,19 @@ def main():
     hy = empty((B, Tp, L["cout"]), "bf16")
     hdx = empty((B, Tp, L["cin"]), "bf16")
     hdw = empty(cfg["weights"][1].shape)
-    wws = P.workspace(P.w2l_conv1d_bwd_weight_workspace_bytes(B, Tp, L["cin"], L["cout"], L["k"], 1, 1))
+    shp = (B, Tp, L["cin"], L["cout"], L["k"], 1, P.W2L_BF16)
+    ws_f = P.workspace(P.w2l_conv1d_fwd_workspace_bytes(*shp))
+    ws_d = P.workspace(P.w2l_conv1d_bwd_data_workspace_bytes(*shp))
+    ws_w = P.workspace(P.w2l_conv1d_bwd_weight_workspace_bytes(*shp))
     gf = 2.0 * B * Tp * L["k"] * L["cin"] * L["cout"]
     kern = {}
-    kern["conv1d_fwd"] = event_time_ms(lambda: P.w2l_conv1d_fwd(hx, wd[1], bd[1], hy, 1), args.kernel_iters)
-    kern["conv1d_bwd_data"] = event_time_ms(lambda: P.w2l_conv1d_bwd_data(hdy, wd[1], hdx, 1), args.kernel_iters)
+    kern["conv1d_fwd"] = event_time_ms(lambda: P.w2l_conv1d_fwd(hx, wd[1], bd[1], hy, 1, ws_f), args.kernel_iters)
+    kern["conv1d_bwd_data"] = event_time_ms(lambda: P.w2l_conv1d_bwd_data(hdy, wd[1], hdx, 1, ws_d),
+                                            args.kernel_iters)
     kern["conv1d_bwd_weight"] = event_time_ms(
-        lambda: P.w2l_conv1d_bwd_weight(hx, hdy, hdw, None, 1, False, wws), args.kernel_iters)
+        lambda: P.w2l_conv1d_bwd_weight(hx, hdy, hdw, None, 1, False, ws_w), args.kernel_iters)
+    # the step runs 8 body layers x (fwd, dgrad, wgrad) + the 1x1 layers: the pass that costs
+    # the most per launch is the dominant kernel
     dom = max(kern, key=kern.get)
     achieved = gf / (kern[dom] * 1e-3)
 
@@ -111,7 +141,6 @@ def main():
     glu_bytes = rows * L["cout"] * 2 + rows * (L["cout"] // 2) * 2
     hdh = to_dev(W.round_to_bf16(rng.standard_normal((rows, L["cout"] // 2)).astype(np.float32)), "bf16")
     hdy2 = empty((rows, L["cout"]), "bf16")
-    P.w2l_conv1d_fwd(hx, wd[1], bd[1], hy, 1)
     t_glub = event_time_ms(lambda: P.w2l_glu_bwd(hy, hdh, hdy2), args.kernel_iters)
     glub_bytes = rows * L["cout"] * 2 * 2 + rows * (L["cout"] // 2) * 2
 
@@ -151,14 +180,17 @@ def main():
         "step_frac_of_bf16_mfma_peak": flops / dt / PEAK_BF16_MFMA,
         "roofline": {
             "bound": "mfma",
-            "kernel": dom + " (k=11, 768->1536, B*T'=6000)",
+            "kernel": dom + " (k=11, 768->1536, B*T'=6000; 155.7 GFLOP per launch)",
             "achieved": achieved / 1e12,
             "peak": PEAK_BF16_MFMA / 1e12,
             "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_MFMA,
-            "traffic": None,
+            "traffic": DOMINANT_KERNEL_HBM_BYTES,
             "avg_launch_ms": kern[dom],
+            "measured_mfma_only_ceiling_tflops": mfma_ceiling / 1e12,
+            "frac_of_measured_ceiling": achieved / mfma_ceiling,
         },
+        "measured_ceilings": {"mfma_bf16_tflops": mfma_ceiling / 1e12, "device_copy_GBps": copy_bw / 1e9},
         "kernels": {
             **{k: {"ms": v, "tflops": gf / (v * 1e-3) / 1e12, "frac_mfma_peak": gf / (v * 1e-3) / PEAK_BF16_MFMA}
                for k, v in kern.items()},

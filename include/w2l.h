@@ -173,6 +173,14 @@ int w2l_train_step(const w2l_layer *layers, int n_layers,
                    int B, int T, int Lmax, int blank, int dtype, float grad_scale,
                    void *workspace, size_t ws_bytes, void *stream);
 
+/* ---- measurement aid (not part of the training path) -----------------------------------
+ * Launches `blocks` workgroups of 4 wavefronts, each wavefront issuing 8*iters independent
+ * v_mfma_f32_32x32x16_bf16 (32768 FLOP each) and nothing else; out: [blocks*256] fp32 sink.
+ * Timed by the caller, it gives the bf16 MFMA rate the part sustains at its clocks under
+ * load -- the practical ceiling next to the published 2.5 PFLOP/s (Sec. 4 of the paper
+ * reports timings on its own hardware only; rooflines here are measured, not quoted). */
+int w2l_probe_mfma(float *out, int blocks, int iters, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

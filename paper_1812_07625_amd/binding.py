@@ -20,7 +20,8 @@ __all__ = [
     "w2l_conv1d_fwd", "w2l_conv1d_bwd_data", "w2l_conv1d_bwd_weight", "w2l_conv1d_fwd_workspace_bytes",
     "w2l_conv1d_bwd_data_workspace_bytes", "w2l_conv1d_bwd_weight_workspace_bytes", "w2l_glu_fwd", "w2l_glu_bwd",
     "w2l_logsoftmax_fwd", "w2l_logsoftmax_bwd", "w2l_ctc_workspace_bytes", "w2l_ctc_fwd_bwd",
-    "w2l_ctc_check_targets_host", "w2l_train_step_workspace_bytes", "w2l_train_step", "raw", "workspace",
+    "w2l_ctc_check_targets_host", "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_probe_mfma", "raw",
+    "workspace",
 ]
 
 
@@ -62,6 +63,7 @@ def _load():
         "w2l_ctc_workspace_bytes": (sz, [i] * 4),
         "w2l_ctc_fwd_bwd": (i, [vp, i, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]),
         "w2l_ctc_check_targets_host": (i, [vp, vp, vp, i, i, i, i, i]),
+        "w2l_probe_mfma": (i, [vp, i, i, vp]),
         "w2l_train_step_workspace_bytes": (sz, [C.POINTER(w2l_layer), i, i, i, i, i]),
         "w2l_train_step": (i, [C.POINTER(w2l_layer), i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                C.POINTER(vp), vp, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]),
@@ -217,6 +219,12 @@ def w2l_ctc_check_targets_host(targets, in_len, tgt_len, Tp, Cc, blank=0) -> int
     tl = np.ascontiguousarray(tgt_len, dtype=np.int32)
     return raw.w2l_ctc_check_targets_host(t.ctypes.data, il.ctypes.data, tl.ctypes.data, t.shape[0], Tp, Cc,
                                           t.shape[1], blank)
+
+
+def w2l_probe_mfma(out, blocks, iters, stream=None):
+    """Measurement aid: blocks*4 wavefronts each issue 8*iters MFMAs (32768 FLOP each)."""
+    _check(raw.w2l_probe_mfma(_p(out), blocks, iters, _stream(stream)), "w2l_probe_mfma")
+    return 2.0 * 32 * 32 * 16 * 8 * iters * blocks * 4
 
 
 def _layer_array(layers):

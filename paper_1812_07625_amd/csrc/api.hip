@@ -195,3 +195,33 @@ extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, f
     }
     return conv_wgrad(d, x, dy, dw, dbias, dtype, dy_dtype, accumulate, workspace, st);
 }
+
+// ---- measurement aid: what the matrix pipe sustains with nothing else going on -----------
+namespace {
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
+__global__ __launch_bounds__(256) void mfma_probe_k(float* out, int iters)
+{
+    probe_f32x16 acc[8];
+    for (int i = 0; i < 8; ++i)
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    probe_bf16x8 a, b;
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)((threadIdx.x + e) & 7); b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 3); }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 8; ++i)
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+}  // namespace
+
+extern "C" int w2l_probe_mfma(float* out, int blocks, int iters, void* stream)
+{
+    if (!out) return W2L_ERR_NULL;
+    if (blocks <= 0 || blocks > 65535 || iters <= 0) return W2L_ERR_SHAPE;
+    hipLaunchKernelGGL(mfma_probe_k, dim3(blocks), dim3(256), 0, (hipStream_t)stream, out, iters);
+    return launch_status();
+}

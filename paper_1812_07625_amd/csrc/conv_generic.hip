@@ -259,18 +259,22 @@ __global__ __launch_bounds__(256) void colsum_stage1(const T* dy, float* part, l
         part[(size_t)blockIdx.y * Cout + c] = (sm[0][threadIdx.x] + sm[1][threadIdx.x]) +
                                               (sm[2][threadIdx.x] + sm[3][threadIdx.x]);
 }
-// bf16, Cout % 8 == 0: one pass.  A workgroup owns 32 columns (4 lanes x 16-byte loads) and
-// 64 row lanes; the 64 partial sums per column are added in a fixed tree through LDS.
-__global__ __launch_bounds__(256) void colsum_bf16(const bf16_t* __restrict__ dy, float* __restrict__ dbias,
-                                                   long long rows, int Cout, int accumulate)
+// bf16, Cout % 8 == 0.  A workgroup owns 32 columns (4 lanes x 16-byte loads) of one of
+// DBIAS_VCHUNKS row ranges, 64 row lanes each; the 64 partial sums per column are added in a
+// fixed tree through LDS; colsum_stage2 then adds the chunks in order.
+constexpr int DBIAS_VCHUNKS = 16;
+__global__ __launch_bounds__(256) void colsum_bf16_stage1(const bf16_t* __restrict__ dy, float* __restrict__ part,
+                                                          long long rows, int Cout)
 {
     const int cg = threadIdx.x & 3, rl = threadIdx.x >> 2;
     const int c0 = blockIdx.x * 32 + cg * 8;
+    const long long per = (rows + gridDim.y - 1) / gridDim.y;
+    const long long r0 = per * blockIdx.y, r1 = (r0 + per < rows) ? r0 + per : rows;
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     if (c0 < Cout)
-        for (long long r = rl; r < rows; r += 64) {
+        for (long long r = r0 + rl; r < r1; r += 64) {
             const uint4 v = *reinterpret_cast<const uint4*>(dy + r * Cout + c0);
             const unsigned u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -292,7 +296,7 @@ __global__ __launch_bounds__(256) void colsum_bf16(const bf16_t* __restrict__ dy
     }
     if (threadIdx.x < 32) {
         const int c = blockIdx.x * 32 + threadIdx.x;
-        if (c < Cout) dbias[c] = accumulate ? dbias[c] + sm[0][threadIdx.x] : sm[0][threadIdx.x];
+        if (c < Cout) part[(size_t)blockIdx.y * Cout + c] = sm[0][threadIdx.x];
     }
 }
 __global__ void colsum_stage2(const float* part, float* dbias, int chunks, int Cout, int accumulate)
@@ -357,8 +361,12 @@ int dbias_reduce(const void* dy, float* dbias, long long rows, int Cout, int dyd
                  float* scratch, hipStream_t st)
 {
     if (dydt == W2L_BF16 && Cout % 8 == 0) {
-        hipLaunchKernelGGL(colsum_bf16, dim3((Cout + 31) / 32), dim3(256), 0, st, (const bf16_t*)dy, dbias, rows, Cout,
-                           accumulate);
+        hipLaunchKernelGGL(colsum_bf16_stage1, dim3((Cout + 31) / 32, DBIAS_VCHUNKS), dim3(256), 0, st,
+                           (const bf16_t*)dy, scratch, rows, Cout);
+        int rc = launch_status();
+        if (rc) return rc;
+        hipLaunchKernelGGL(colsum_stage2, dim3((Cout + 255) / 256), dim3(256), 0, st, scratch, dbias,
+                           (int)DBIAS_VCHUNKS, Cout, accumulate);
         return launch_status();
     }
     const dim3 g1((Cout + 63) / 64, DBIAS_CHUNKS);
