@@ -26,10 +26,9 @@ inline bool valid_dtype(int dt) { return dt == W2L_F32 || dt == W2L_BF16; }
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
 // round to nearest, ties to even; NaN stays NaN
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+    const unsigned u = __float_as_uint(f);
+    const unsigned r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (bf16_t)(((u & 0x7fffffffu) > 0x7f800000u) ? ((u >> 16) | 0x40u) : r);  // a select, not a branch
 }
 
 template <typename T> struct Elem;

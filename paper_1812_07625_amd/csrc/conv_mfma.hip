@@ -10,8 +10,12 @@
 //   dgrad  m=(b,t)   n=ci      r=(j',co)  A = dy window (r-contiguous)  B = w (n-contiguous), j'=k-1-j
 //   wgrad  m=co      n=(j,ci)  r=(b,t')   A = dy (m-contiguous)         B = x window (n-contiguous)
 //
-// One workgroup = 4 wavefronts (2x2) computes a BM x BN tile; each wavefront owns a
-// (BM/2)x(BN/2) sub-tile of 32x32 MFMA blocks held in accumulation registers.
+// One workgroup computes a BM x BN tile with KG groups of 4 wavefronts (2x2); a wavefront owns a
+// (BM/2)x(BN/2) sub-tile of 32x32 MFMA blocks held in accumulation registers.  With KG = 2 the
+// two groups split the reduction (alternate 16-element sub-steps of every panel) and their
+// accumulators are summed through LDS at the end: every SIMD then hosts two wavefronts, so one
+// can issue matrix instructions while the other issues loads or waits, and the register budget
+// per wavefront (256) still holds a 96x96 or 128x64 sub-tile.
 //
 // Data movement.  Operand panels of BKT reduction elements go global -> LDS directly
 // (global_load_lds_dwordx4: no staging registers, no LDS store instructions) into a ring
@@ -45,7 +49,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
-constexpr int NT = 256;  // threads per workgroup (4 wavefronts)
 
 __device__ __align__(16) unsigned int g_zero16[4];  // source of every out-of-range chunk
 
@@ -75,14 +78,14 @@ __device__ __forceinline__ void wait_vmcnt()
 // ---- r-contiguous panel: ROWS rows x BKT elements, dense [row][BKT] --------------------
 // Row i of the tile is a run of memory starting at element offset off[i] (may point
 // before the tensor for halo rows); reduction index r is valid in [lo, hi).
-template <int ROWS, int BKT>
+template <int ROWS, int BKT, int NW>
 struct PanelK {
     static constexpr int ROWB = BKT * 2;               // bytes per LDS row
     static constexpr int BYTES = ROWS * ROWB;
     static constexpr int CPR = BKT / 8;                // 16-byte chunks per row
     static constexpr int RPB = 64 / CPR;               // rows filled by one load instruction
-    static constexpr int NI = BYTES / 1024 / 4;        // load instructions per wavefront per panel
-    static_assert(BYTES % 4096 == 0, "panel must split into 1 KB blocks over 4 wavefronts");
+    static constexpr int NI = BYTES / 1024 / NW;       // load instructions per wavefront per panel
+    static_assert(BYTES % (1024 * NW) == 0, "panel must split into 1 KB blocks over the wavefronts");
     static_assert(BKT == 64 || BKT == 32, "swizzles are written for 64- and 128-byte rows");
     int off[NI];                                       // element offsets (tensors hold < 2^31 elements)
     int lo[NI], hi[NI];                                // CHECKED mode only
@@ -98,7 +101,7 @@ struct PanelK {
     }
     static __device__ __forceinline__ int row_of(int i)
     {
-        return ((threadIdx.x >> 6) + 4 * i) * RPB + (threadIdx.x & 63) / CPR;
+        return ((threadIdx.x >> 6) + NW * i) * RPB + (threadIdx.x & 63) / CPR;
     }
     __device__ __forceinline__ void init(const bf16_t* b)
     {
@@ -112,14 +115,14 @@ struct PanelK {
         const int r = r0 + c8;
         const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
         const void* src = (r >= lo[i] && r < hi[i]) ? (const void*)(base + off[i] + r) : (const void*)g_zero16;
-        dma16(src, wbase + i * 4096);
+        dma16(src, wbase + i * (1024 * NW));
     }
     // FAST: row_off_elems = element offset of row i's reduction index 0 (always in bounds)
     __device__ __forceinline__ void set_fast(int i, long long row_off_elems) { voff[i] = (unsigned)((row_off_elems + c8) * 2); }
     __device__ __forceinline__ void issue_fast(int i, const bf16_t* sbase, unsigned lds_stage) const
     {
         const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
-        dma16s(voff[i], sbase, wbase + i * 4096);
+        dma16s(voff[i], sbase, wbase + i * (1024 * NW));
     }
     // 32 rows starting at row0, sub-step ks (16 elements): lane holds row l%32, r = 8*(l/32)..+7
     static __device__ __forceinline__ bf16x8 frag(const unsigned char* lds, int row0, int ks, int lane)
@@ -131,13 +134,13 @@ struct PanelK {
 };
 
 // ---- m/n-contiguous panel: BKT reduction rows x COLS elements, dense [BKT][COLS] --------
-template <int COLS, int BKT>
+template <int COLS, int BKT, int NW>
 struct PanelMN {
     static constexpr int RS = COLS * 2;
     static constexpr int BYTES = BKT * RS;
     static constexpr int CPR = COLS / 8;
-    static constexpr int NI = BYTES / 1024 / 4;
-    static_assert(BYTES % 4096 == 0, "panel must split into 1 KB blocks over 4 wavefronts");
+    static constexpr int NI = BYTES / 1024 / NW;
+    static_assert(BYTES % (1024 * NW) == 0, "panel must split into 1 KB blocks over the wavefronts");
     static_assert(CPR % 8 == 0, "swizzle flips chunk-index bits 2 and 3");
     const bf16_t* base;
     unsigned voff[NI];  // FAST mode only
@@ -160,9 +163,9 @@ struct PanelMN {
     __device__ __forceinline__ void issue_fast(int i, const bf16_t* sbase, unsigned lds_stage) const
     {
         const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
-        dma16s(voff[i], sbase, wbase + i * 4096);
+        dma16s(voff[i], sbase, wbase + i * (1024 * NW));
     }
-    static __device__ __forceinline__ int chunk_of(int i) { return ((threadIdx.x >> 6) + 4 * i) * 64 + (threadIdx.x & 63); }
+    static __device__ __forceinline__ int chunk_of(int i) { return ((threadIdx.x >> 6) + NW * i) * 64 + (threadIdx.x & 63); }
     // f(row, off, lo, hi): element offset of the row's column 0 of this tile and its valid
     // column range; the 16-byte chunk at column c is real data iff lo <= c < hi
     template <class F>
@@ -176,7 +179,7 @@ struct PanelMN {
         int lo, hi;
         f(row, off, lo, hi);
         const void* src = (c8 >= lo && c8 < hi) ? (const void*)(base + off + c8) : (const void*)g_zero16;
-        dma16(src, wbase + i * 4096);
+        dma16(src, wbase + i * (1024 * NW));
     }
     // Same fragment as PanelK::frag, gathered with two transpose reads: within each group of
     // 16 lanes, lane i supplies the address of row (i/4), columns 4*(i%4)..+3, and receives
@@ -197,8 +200,9 @@ struct PanelMN {
     }
 };
 
-// ---- the 2x2-wavefront MFMA core ----------------------------------------------------
-template <int BM, int BN, int BKT, class PA, class PB>
+// ---- the MFMA core: KG groups of 2x2 wavefronts ----------------------------------------
+// Group kg multiplies the sub-steps ks = kg, kg + KG, ... of every panel.
+template <int BM, int BN, int BKT, int KG, class PA, class PB>
 struct Core {
     static constexpr int TM = BM / 2 / 32, TN = BN / 2 / 32;  // 32x32 blocks per wavefront
     f32x16 acc[TM][TN];
@@ -211,12 +215,13 @@ struct Core {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     }
-    // Operand fragments are double-buffered in registers: the LDS reads of sub-step ks+1 are
-    // issued before the MFMAs of sub-step ks, so their latency hides under matrix work (one
-    // wavefront per SIMD: nothing else would hide it) -- and this carries across panels: the
-    // first fragments of the next panel are read before the last MFMAs of the current one.
-    static constexpr int NS = BKT / 16;
-    static constexpr int GROUPS = NS * TM * TN;      // MFMAs per panel
+    // Operand fragments are double-buffered in registers: the LDS reads of this wavefront's next
+    // sub-step are issued before the MFMAs of the current one, so their latency hides under
+    // matrix work -- and this carries across panels: the first fragments of the next panel are
+    // read before the last MFMAs of the current one.
+    static constexpr int NS = BKT / 16 / KG;          // sub-steps per panel per wavefront
+    static_assert(NS >= 2 && (BKT / 16) % KG == 0, "each group needs two sub-steps per panel to double-buffer");
+    static constexpr int GROUPS = NS * TM * TN;      // MFMAs per panel per wavefront
     static constexpr int EARLY = (NS - 1) * TM * TN;  // MFMAs issued before the hand-over point
     bf16x8 fa[2][TM], fb[2][TN];
     __device__ __forceinline__ void load_frags(int set, const unsigned char* la, const unsigned char* lb, int ks,
@@ -228,38 +233,38 @@ struct Core {
         for (int j = 0; j < TN; ++j) fb[set][j] = PB::frag(lb, wn * (BN / 2) + j * 32, ks, lane);
     }
     template <class Hook>
-    __device__ __forceinline__ void mfmas(int ks, Hook hook)
+    __device__ __forceinline__ void mfmas(int u, Hook hook)
     {
-        const int c = ks & 1;
+        const int c = u & 1;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], fb[c][j], acc[i][j], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                hook((ks * TM + i) * TN + j);
+                hook((u * TM + i) * TN + j);
                 __builtin_amdgcn_sched_barrier(0);
             }
     }
-    // One panel whose ks=0 fragments are already in register set 0.  hook(g) runs after the
-    // g-th MFMA (the caller hangs the prefetch loads there, off the matrix pipe's critical
-    // path); handover() runs before the last sub-step's MFMAs and must make the next panel
-    // readable; the next panel's ks=0 fragments are then read from (na, nb) into set 0.
+    // One panel whose first fragments (sub-step kg) are already in register set 0.  hook(g) runs
+    // after this wavefront's g-th MFMA (the caller hangs the prefetch loads there, off the matrix
+    // pipe's critical path); handover() runs before the last sub-step's MFMAs and must make the
+    // next panel readable; the next panel's first fragments are then read from (na, nb) into set 0.
     template <class Hook, class Handover>
     __device__ __forceinline__ void step(const unsigned char* la, const unsigned char* lb, const unsigned char* na,
-                                         const unsigned char* nb, int wm, int wn, int lane, Hook hook,
+                                         const unsigned char* nb, int kg, int wm, int wn, int lane, Hook hook,
                                          Handover handover)
     {
 #pragma unroll
-        for (int ks = 0; ks < NS; ++ks) {
-            if (ks + 1 < NS) {
-                load_frags((ks + 1) & 1, la, lb, ks + 1, wm, wn, lane);
+        for (int u = 0; u < NS; ++u) {
+            if (u + 1 < NS) {
+                load_frags((u + 1) & 1, la, lb, kg + KG * (u + 1), wm, wn, lane);
             } else {
                 handover();
-                load_frags(0, na, nb, 0, wm, wn, lane);
+                load_frags(0, na, nb, kg, wm, wn, lane);
             }
             __builtin_amdgcn_sched_barrier(0);
-            mfmas(ks, hook);
+            mfmas(u, hook);
         }
     }
     // f(m, n, value) for every element this lane holds; m,n relative to the tile
@@ -275,22 +280,77 @@ struct Core {
                 for (int j = 0; j < TN; ++j) f(m, wn * (BN / 2) + j * 32 + (lane & 31), acc[i][j][r]);
             }
     }
+    // bf16 output tile staged in LDS as [rows][BN] (rows padded by 16 bytes so that the two row
+    // groups a wavefront writes at once fall on different banks): value + add[j], rounded.
+    // Wavefront rows are taken relative to row_base.
+    static constexpr int OPITCH = BN * 2 + 16;
+    __device__ __forceinline__ void stage_bf16(unsigned char* buf, const float (&add)[TN], int row_base, int wm, int wn,
+                                               int lane) const
+    {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) - row_base;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int n = wn * (BN / 2) + j * 32 + (lane & 31);
+                    *reinterpret_cast<bf16_t*>(buf + m * OPITCH + n * 2) = f32_to_bf16(acc[i][j][r] + add[j]);
+                }
+            }
+    }
+    // KG == 2: add group 1's accumulators into group 0's through LDS (buf: 4 * TM * TN * 4 KB,
+    // free of panel traffic).  Lane-contiguous 16-byte accesses; the sum order is fixed.
+    __device__ __forceinline__ void reduce_groups(unsigned char* buf, int kg, int w4, int lane)
+    {
+        static_assert(KG <= 2, "two reduction groups at most");
+        if (KG == 1) return;
+        typedef __attribute__((ext_vector_type(4))) float f32x4;
+        f32x4* q = reinterpret_cast<f32x4*>(buf) + (size_t)w4 * TM * TN * 4 * 64 + lane;
+        __syncthreads();  // every wavefront has finished reading operand panels
+        if (kg == 1) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        f32x4 v = {acc[i][j][4 * r4], acc[i][j][4 * r4 + 1], acc[i][j][4 * r4 + 2], acc[i][j][4 * r4 + 3]};
+                        q[((i * TN + j) * 4 + r4) * 64] = v;
+                    }
+        }
+        __syncthreads();
+        if (kg == 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const f32x4 v = q[((i * TN + j) * 4 + r4) * 64];
+                        acc[i][j][4 * r4] += v[0];
+                        acc[i][j][4 * r4 + 1] += v[1];
+                        acc[i][j][4 * r4 + 2] += v[2];
+                        acc[i][j][4 * r4 + 3] += v[3];
+                    }
+        }
+    }
 };
 
 // The panel ring shared by the three kernels.  issue(i, p, lds_addr) starts load instruction
-// i (of NL per wavefront) of panel p; for p >= nsteps it must load zeros (the ring keeps
-// prefetching past the end so that the number of loads in flight never changes).
+// i (of NL per wavefront) of panel p; for p >= nsteps it must load zeros or refetch valid data
+// (the ring keeps prefetching past the end so that the number of loads in flight never changes).
 //
 // Per panel st, per wavefront, in program order:
-//   MFMAs of sub-steps 0..NS-2, interleaved with the NL loads of panel st+STAGES-1 (they go
-//     into the slot panel st-1 occupied; the barrier passed during panel st-1 freed it);
+//   MFMAs of all but the last sub-step, interleaved with the NL loads of panel st+STAGES-1 (they
+//     go into the slot panel st-1 occupied; the barrier passed during panel st-1 freed it);
 //   wait until this wavefront's loads of panel st+1 have landed, then barrier: now every
 //     wavefront's share of panel st+1 is in LDS and nobody will read panel st again from
 //     LDS (its last fragments are already in registers);
 //   read the first fragments of panel st+1; MFMAs of the last sub-step of panel st.
 template <int STAGES, int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
-__device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int wm, int wn,
-                                             int lane)
+__device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int kg, int wm,
+                                             int wn, int lane)
 {
     static_assert(STAGES == 3 || STAGES == 4, "ring depth");
     static_assert((STAGES - 2) * NL < 64, "loads in flight must fit the vmcnt counter");
@@ -304,7 +364,7 @@ __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, in
     wait_vmcnt<(STAGES - 2) * NL>();  // panel 0 has landed
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    core.load_frags(0, lds, lds + A_BYTES, 0, wm, wn, lane);
+    core.load_frags(0, lds, lds + A_BYTES, kg, wm, wn, lane);
     int slot = 0;  // ring slot of panel st
     for (int st = 0; st < nsteps; ++st) {
         const int pre = st + STAGES - 1;
@@ -315,7 +375,7 @@ __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, in
         const unsigned char* cur = lds + slot * STAGE_BYTES;
         const unsigned char* nxt = lds + nslot * STAGE_BYTES;
         core.step(
-            cur, cur + A_BYTES, nxt, nxt + A_BYTES, wm, wn, lane,
+            cur, cur + A_BYTES, nxt, nxt + A_BYTES, kg, wm, wn, lane,
             [&](int g) { if (g < NL) issue(g, pre, dst); },
             [&]() {
                 // in flight, oldest first: panels st+1 .. st+STAGES-1; the first must have landed
@@ -326,7 +386,37 @@ __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, in
             });
         slot = nslot;
     }
-    wait_vmcnt<0>();  // the trailing zero-panels must land before the LDS allocation is released
+    wait_vmcnt<0>();  // the trailing panels must land before LDS is reused or released
+}
+
+// bf16 epilogue shared by the forward and data-gradient kernels: the accumulators (+ add[j] per
+// column block) go to LDS as a row-major tile and leave as 16-byte row segments, every thread
+// of the workgroup storing.  When the padded tile does not fit the panel ring (256x256) the
+// two wavefront rows go one after the other.  rowoff(m) = element row of output row m.
+template <int BM, int BN, int KG, int LDS_BYTES, class CoreT, class RowOff>
+__device__ __forceinline__ void store_tile_bf16(const CoreT& core, unsigned char* lds, const float (&add)[CoreT::TN],
+                                                bf16_t* __restrict__ out, int m0, int n0, int M, int N, int kg, int wm,
+                                                int wn, int lane, RowOff rowoff)
+{
+    constexpr int PITCH = CoreT::OPITCH, CPRW = BN / 8, NTHR = 256 * KG;
+    constexpr int PASSES = (BM * PITCH <= LDS_BYTES) ? 1 : 2;
+    constexpr int ROWS = BM / PASSES;
+    static_assert(ROWS * PITCH <= LDS_BYTES, "output tile staging must fit the panel ring");
+    static_assert((ROWS * CPRW) % NTHR == 0, "row segments split evenly over the threads");
+#pragma unroll
+    for (int h = 0; h < PASSES; ++h) {
+        __syncthreads();  // LDS is free: panels, group reduction or the previous pass are done with
+        if (kg == 0 && (PASSES == 1 || wm == h)) core.stage_bf16(lds, add, h * ROWS, wm, wn, lane);
+        __syncthreads();
+#pragma unroll
+        for (int c = threadIdx.x; c < ROWS * CPRW; c += NTHR) {
+            const int row = c / CPRW, cc = c - row * CPRW;
+            const int m = m0 + h * ROWS + row, n = n0 + cc * 8;
+            if (m < M && n < N)
+                *reinterpret_cast<uint4*>(out + (size_t)rowoff(m) * N + n) =
+                    *reinterpret_cast<const uint4*>(lds + row * PITCH + cc * 16);
+        }
+    }
 }
 
 // Workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own
@@ -351,19 +441,21 @@ __device__ __forceinline__ long long out_row(int m, int frames, int pitch, int h
 }
 
 // =============================== forward ================================================
-template <int BM, int BN, int BKT, int STAGES, bool FAST, typename TO>
-__global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
+template <int BM, int BN, int BKT, int STAGES, int KG, bool FAST, typename TO>
+__global__ __launch_bounds__(256 * KG) void conv_fwd_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
                                                  const float* __restrict__ bias, TO* __restrict__ y, ConvGeom g)
 {
-    using PA = PanelK<BM, BKT>;
-    using PB = PanelK<BN, BKT>;
+    using PA = PanelK<BM, BKT, 4 * KG>;
+    using PB = PanelK<BN, BKT, 4 * KG>;
     extern __shared__ __align__(1024) unsigned char lds[];
     constexpr int STAGE = PA::BYTES + PB::BYTES;
+    static_assert(KG == 1 || BM * BN * 4 <= STAGES * STAGE, "the group reduction reuses the panel ring");
     const int M = g.B * g.Tp, N = g.Cout, K = g.k * g.Cin;
     int tm, tn;
     tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
 
     PA pa;
     PB pb;
@@ -397,7 +489,7 @@ __global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, c
             pb.hi[i] = (n < N) ? K : 0;
         }
     }
-    Core<BM, BN, BKT, PA, PB> core;
+    Core<BM, BN, BKT, KG, PA, PB> core;
     core.zero();
     const int nsteps = (K + BKT - 1) / BKT;  // FAST requires K % BKT == 0
     run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
@@ -412,29 +504,52 @@ __global__ __launch_bounds__(NT) void conv_fwd_k(const bf16_t* __restrict__ x, c
                 else pb.issue(i - PA::NI, st * BKT, dst + PA::BYTES);
             }
         },
-        wm, wn, lane);
-    core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
-        const int m = m0 + mm, n = n0 + nn;
-        if (m < M && n < N)
-            Elem<TO>::store(y, (size_t)out_row(m, g.Tp, g.y_pitch, g.y_halo) * N + n, v + (bias ? bias[n] : 0.f));
-    });
+        kg, wm, wn, lane);
+    core.reduce_groups(lds, kg, w4, lane);
+    float bv[core.TN];
+#pragma unroll
+    for (int j = 0; j < core.TN; ++j) {
+        const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+        bv[j] = (bias && n < N) ? bias[n] : 0.f;
+    }
+    if (sizeof(TO) == 2 && N % 8 == 0) {
+        store_tile_bf16<BM, BN, KG, STAGES * STAGE>(core, lds, bv, reinterpret_cast<bf16_t*>(y), m0, n0, M, N, kg, wm, wn,
+                                                    lane, [&](int m) { return out_row(m, g.Tp, g.y_pitch, g.y_halo); });
+        return;
+    }
+    if (kg != 0) return;
+#pragma unroll
+    for (int i = 0; i < core.TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (m >= M) continue;
+            const size_t row = (size_t)out_row(m, g.Tp, g.y_pitch, g.y_halo) * N;
+#pragma unroll
+            for (int j = 0; j < core.TN; ++j) {
+                const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+                if (n < N) Elem<TO>::store(y, row + n, core.acc[i][j][r] + bv[j]);
+            }
+        }
 }
 
 // =============================== data gradient (stride 1) =============================
 // dx[b,t,ci] = sum_{j',co} dy[b, t-p+j', co] * w[co, k-1-j', ci]
-template <int BM, int BN, int BKT, int STAGES, bool FAST>
-__global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
+template <int BM, int BN, int BKT, int STAGES, int KG, bool FAST>
+__global__ __launch_bounds__(256 * KG) void conv_dgrad_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
                                                    bf16_t* __restrict__ dx, ConvGeom g)
 {
-    using PA = PanelK<BM, BKT>;
-    using PB = PanelMN<BN, BKT>;
+    using PA = PanelK<BM, BKT, 4 * KG>;
+    using PB = PanelMN<BN, BKT, 4 * KG>;
     extern __shared__ __align__(1024) unsigned char lds[];
     constexpr int STAGE = PA::BYTES + PB::BYTES;
+    static_assert(KG == 1 || BM * BN * 4 <= STAGES * STAGE, "the group reduction reuses the panel ring");
     const int M = g.B * g.T, N = g.Cin, K = g.k * g.Cout;
     int tm, tn;
     tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
 
     PA pa;
     PB pb;
@@ -457,7 +572,7 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
             pa.hi[i] = (m < M) ? (last < g.k ? last : g.k) * g.Cout : 0;
         }
     }
-    Core<BM, BN, BKT, PA, PB> core;
+    Core<BM, BN, BKT, KG, PA, PB> core;
     core.zero();
     const int nsteps = K / BKT;  // Cout is a multiple of BKT: a panel stays inside one tap
     run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
@@ -485,11 +600,13 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
                 },
                 dst + PA::BYTES);
         },
-        wm, wn, lane);
-    core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
-        const int m = m0 + mm, n = n0 + nn;
-        if (m < M && n < N) dx[(size_t)out_row(m, g.T, g.x_pitch, g.x_halo) * N + n] = f32_to_bf16(v);
-    });
+        kg, wm, wn, lane);
+    core.reduce_groups(lds, kg, w4, lane);
+    float zero[core.TN];
+#pragma unroll
+    for (int j = 0; j < core.TN; ++j) zero[j] = 0.f;
+    store_tile_bf16<BM, BN, KG, STAGES * STAGE>(core, lds, zero, dx, m0, n0, M, N, kg, wm, wn, lane,
+                                                [&](int m) { return out_row(m, g.T, g.x_pitch, g.x_halo); });
 }
 
 // =============================== weight gradient ========================================
@@ -499,19 +616,21 @@ __global__ __launch_bounds__(NT) void conv_dgrad_k(const bf16_t* __restrict__ dy
 // reduction runs straight through the frames of all utterances including the halo frames
 // between them -- dy is zero there, so they add nothing -- which makes every panel a dense
 // block of BKT consecutive frames of both tensors.
-template <int BM, int BN, int BKT, int STAGES, bool FAST>
-__global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
+template <int BM, int BN, int BKT, int STAGES, int KG, bool FAST>
+__global__ __launch_bounds__(256 * KG) void conv_wgrad_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
                                                    float* __restrict__ dw, ConvGeom g, int accumulate)
 {
-    using PA = PanelMN<BM, BKT>;
-    using PB = PanelMN<BN, BKT>;
+    using PA = PanelMN<BM, BKT, 4 * KG>;
+    using PB = PanelMN<BN, BKT, 4 * KG>;
     extern __shared__ __align__(1024) unsigned char lds[];
     constexpr int STAGE = PA::BYTES + PB::BYTES;
+    static_assert(KG == 1 || BM * BN * 4 <= STAGES * STAGE, "the group reduction reuses the panel ring");
     const int M = g.Cout, N = g.k * g.Cin;
     int tm, tn;
     tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
 
     PA pa;
     PB pb;
@@ -525,7 +644,7 @@ __global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x,
     const int spb = (g.Tp + BKT - 1) / BKT;  // CHECKED: panels per utterance
     const int frames = (g.B - 1) * g.y_pitch + g.Tp;  // FAST: first real frame of utterance 0 .. last real frame
     const int nsteps = FAST ? (frames + BKT - 1) / BKT : g.B * spb;
-    Core<BM, BN, BKT, PA, PB> core;
+    Core<BM, BN, BKT, KG, PA, PB> core;
     core.zero();
     run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
@@ -563,7 +682,9 @@ __global__ __launch_bounds__(NT) void conv_wgrad_k(const bf16_t* __restrict__ x,
                 },
                 dst + PA::BYTES);
         },
-        wm, wn, lane);
+        kg, wm, wn, lane);
+    core.reduce_groups(lds, kg, w4, lane);
+    if (kg != 0) return;
     core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
         const int m = m0 + mm, n = n0 + nn;
         if (m < M && n < N) {
@@ -614,12 +735,13 @@ bool halo_ok_x(const ConvDesc& d) { return d.p == 0 || d.x_halo >= d.p; }
 bool halo_ok_y(const ConvDesc& d) { return d.p == 0 || d.y_halo >= d.p; }
 
 // tile -> (panel depth, ring depth): 3 x 48 KB for the tiles that fit, 4 x 32 KB for 256x256
-#define W2L_TILE_DISPATCH(CALL)                                          \
-    if (tc.bm == 256 && tc.bn == 256) { CALL(256, 256, 32, 4); }         \
-    else if (tc.bm == 192 && tc.bn == 192) { CALL(192, 192, 64, 3); }    \
-    else if (tc.bm == 256 && tc.bn == 128) { CALL(256, 128, 64, 3); }    \
-    else if (tc.bm == 128 && tc.bn == 256) { CALL(128, 256, 64, 3); }    \
-    else { CALL(128, 128, 64, 3); }
+// and how many reduction groups of wavefronts (the 256x256 accumulators leave room for one)
+#define W2L_TILE_DISPATCH(CALL)                                             \
+    if (tc.bm == 256 && tc.bn == 256) { CALL(256, 256, 32, 4, 1); }         \
+    else if (tc.bm == 192 && tc.bn == 192) { CALL(192, 192, 64, 3, 2); }    \
+    else if (tc.bm == 256 && tc.bn == 128) { CALL(256, 128, 64, 3, 2); }    \
+    else if (tc.bm == 128 && tc.bn == 256) { CALL(128, 256, 64, 3, 2); }    \
+    else { CALL(128, 128, 64, 3, 2); }
 
 }  // namespace
 
@@ -640,18 +762,19 @@ int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* 
 #define LAUNCH(KERN, BYTES, ...)                                                          \
     {                                                                                     \
         rc = set_lds(KERN, BYTES);                                                        \
-        if (!rc) hipLaunchKernelGGL(KERN, dim3(grid), dim3(NT), BYTES, st, __VA_ARGS__);  \
+        if (!rc) hipLaunchKernelGGL(KERN, dim3(grid), dim3(nthreads), BYTES, st, __VA_ARGS__);  \
     }
-#define CALL(BM_, BN_, BK_, ST_)                                                                              \
+#define CALL(BM_, BN_, BK_, ST_, KG_)                                                                         \
     {                                                                                                         \
-        constexpr int bytes = ST_ * (PanelK<BM_, BK_>::BYTES + PanelK<BN_, BK_>::BYTES);                      \
+        constexpr int bytes = ST_ * (BM_ + BN_) * BK_ * 2;                                                    \
+        const unsigned nthreads = 256 * KG_;                                                                  \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                      \
         if (ydt == W2L_BF16) {                                                                                \
-            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, true, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g) \
-            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, false, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g)     \
+            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, true, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g) \
+            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, false, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g)     \
         } else {                                                                                              \
-            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, true, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)   \
-            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, false, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)       \
+            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, true, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)   \
+            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, false, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)       \
         }                                                                                                     \
     }
     W2L_TILE_DISPATCH(CALL)
@@ -670,12 +793,13 @@ int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, 
     const TileChoice tc = choose_tile(M, N);
     const bool fast = halo_ok_y(g);
     int rc = W2L_OK;
-#define CALL(BM_, BN_, BK_, ST_)                                                                          \
+#define CALL(BM_, BN_, BK_, ST_, KG_)                                                                     \
     {                                                                                                     \
-        constexpr int bytes = ST_ * (PanelK<BM_, BK_>::BYTES + PanelMN<BN_, BK_>::BYTES);                 \
+        constexpr int bytes = ST_ * (BM_ + BN_) * BK_ * 2;                                                \
+        const unsigned nthreads = 256 * KG_;                                                              \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                  \
-        if (fast) LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, true>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g) \
-        else LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, false>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g)     \
+        if (fast) LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, KG_, true>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g) \
+        else LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, KG_, false>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g)     \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
@@ -695,12 +819,13 @@ int conv_wgrad_mfma(const ConvDesc& g, const void* x, const void* dy, float* dw,
     const bool fast = g.s == 1 && g.x_pitch == g.y_pitch && g.x_halo == g.y_halo && g.x_halo >= g.p && g.slack >= 64 &&
                       (g.B == 1 || g.x_halo > 0 || g.p == 0);
     int rc = W2L_OK;
-#define CALL(BM_, BN_, BK_, ST_)                                                                          \
+#define CALL(BM_, BN_, BK_, ST_, KG_)                                                                     \
     {                                                                                                     \
-        constexpr int bytes = ST_ * (PanelMN<BM_, BK_>::BYTES + PanelMN<BN_, BK_>::BYTES);                \
+        constexpr int bytes = ST_ * (BM_ + BN_) * BK_ * 2;                                                \
+        const unsigned nthreads = 256 * KG_;                                                              \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                  \
-        if (fast) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, true>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate) \
-        else LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate)     \
+        if (fast) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, true>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate) \
+        else LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate)     \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
