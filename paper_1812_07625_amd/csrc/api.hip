@@ -87,7 +87,7 @@ namespace {
 // The C ABI takes dense tensors; the MFMA kernels run fastest on tensors with a zero halo
 // around every utterance.  Given workspace, the entry points first copy the window-read
 // operand(s) into that layout (one bandwidth-bound pass, a few percent of the GEMM).
-constexpr int ABI_HALO = 8, ABI_SLACK = 64;
+constexpr int ABI_HALO = 8, ABI_SLACK = 320;
 size_t haloed_bytes(int B, int frames, int C) { return round_up(((size_t)B * (frames + 2 * ABI_HALO) + ABI_SLACK) * C * 2, 256); }
 bool stage_fwd(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cin % 64 == 0 && Cout >= 16 && s >= 1; }
 bool stage_dgrad(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && s == 1 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cout % 64 == 0 && Cin % 8 == 0 && Cin >= 64; }

@@ -38,6 +38,10 @@
 // window is then plain in-bounds memory, the per-lane byte offsets are loop invariants, the
 // panel advance is a scalar add on the base pointer, and a load costs three instructions.
 #include "common.h"
+#include <cstdlib>
+#ifndef W2L_SPREAD_EXPR
+#define W2L_SPREAD_EXPR (CoreT::GROUPS / NL)
+#endif
 
 namespace w2l {
 namespace {
@@ -224,11 +228,12 @@ struct Core {
     static constexpr int GROUPS = NS * TM * TN;      // MFMAs per panel per wavefront
     static constexpr int EARLY = (NS - 1) * TM * TN;  // MFMAs issued before the hand-over point
     bf16x8 fa[2][TM], fb[2][TN];
+    // arow: row of the A panel that tile row 0 reads (non-zero when the panel is an activation slab)
     __device__ __forceinline__ void load_frags(int set, const unsigned char* la, const unsigned char* lb, int ks,
-                                               int wm, int wn, int lane)
+                                               int wm, int wn, int lane, int arow = 0)
     {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[set][i] = PA::frag(la, wm * (BM / 2) + i * 32, ks, lane);
+        for (int i = 0; i < TM; ++i) fa[set][i] = PA::frag(la, wm * (BM / 2) + i * 32 + arow, ks, lane);
 #pragma unroll
         for (int j = 0; j < TN; ++j) fb[set][j] = PB::frag(lb, wn * (BN / 2) + j * 32, ks, lane);
     }
@@ -253,19 +258,33 @@ struct Core {
     template <class Hook, class Handover>
     __device__ __forceinline__ void step(const unsigned char* la, const unsigned char* lb, const unsigned char* na,
                                          const unsigned char* nb, int kg, int wm, int wn, int lane, Hook hook,
-                                         Handover handover)
+                                         Handover handover, int arow = 0, int narow = 0)
     {
 #pragma unroll
         for (int u = 0; u < NS; ++u) {
             if (u + 1 < NS) {
-                load_frags((u + 1) & 1, la, lb, kg + KG * (u + 1), wm, wn, lane);
+                load_frags((u + 1) & 1, la, lb, kg + KG * (u + 1), wm, wn, lane, arow);
             } else {
                 handover();
-                load_frags(0, na, nb, kg, wm, wn, lane);
+                load_frags(0, na, nb, kg, wm, wn, lane, narow);
             }
             __builtin_amdgcn_sched_barrier(0);
             mfmas(u, hook);
         }
+    }
+    // Ping-pong form (KG == 2): a wavefront first reads all its fragments of a panel, then
+    // multiplies them; the two groups do this in opposite phases (see run_pingpong).
+    __device__ __forceinline__ void read_panel(const unsigned char* la, const unsigned char* lb, int kg, int wm, int wn,
+                                               int lane, int arow = 0)
+    {
+        static_assert(NS == 2, "one register set per sub-step");
+#pragma unroll
+        for (int u = 0; u < NS; ++u) load_frags(u, la, lb, kg + KG * u, wm, wn, lane, arow);
+    }
+    __device__ __forceinline__ void mfma_panel()
+    {
+#pragma unroll
+        for (int u = 0; u < NS; ++u) mfmas(u, [](int) {});
     }
     // f(m, n, value) for every element this lane holds; m,n relative to the tile
     template <class F>
@@ -354,7 +373,12 @@ __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, in
 {
     static_assert(STAGES == 3 || STAGES == 4, "ring depth");
     static_assert((STAGES - 2) * NL < 64, "loads in flight must fit the vmcnt counter");
-    static_assert(NL <= CoreT::EARLY, "the prefetch loads must all be issued before the hand-over point");
+    // one load after every SPREAD-th MFMA: a burst of loads would fill the memory pipeline's
+    // queue and stall the wavefront (and the MFMAs behind the load in program order) at issue
+    constexpr int SPREAD = W2L_SPREAD_EXPR;
+    static_assert((NL - 1) * SPREAD < CoreT::GROUPS, "the prefetch loads must all be issued within the panel");
+    // loads of the newest panel issued before the hand-over point
+    constexpr int E = (CoreT::EARLY + SPREAD - 1) / SPREAD < NL ? (CoreT::EARLY + SPREAD - 1) / SPREAD : NL;
     const unsigned lds0 = (unsigned)(size_t)(lds_byte*)lds;
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) {
@@ -376,10 +400,11 @@ __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, in
         const unsigned char* nxt = lds + nslot * STAGE_BYTES;
         core.step(
             cur, cur + A_BYTES, nxt, nxt + A_BYTES, kg, wm, wn, lane,
-            [&](int g) { if (g < NL) issue(g, pre, dst); },
+            [&](int g) { if (g % SPREAD == 0 && g / SPREAD < NL) issue(g / SPREAD, pre, dst); },
             [&]() {
-                // in flight, oldest first: panels st+1 .. st+STAGES-1; the first must have landed
-                wait_vmcnt<(STAGES - 2) * NL>();
+                // in flight, oldest first: panels st+1 .. st+STAGES-2 and the first E loads of
+                // panel st+STAGES-1; panel st+1 must have landed
+                wait_vmcnt<(STAGES - 3) * NL + E>();
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wavefront's reads of panel st are done
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");  // no LDS read of panel st+1 may be hoisted above the barrier
@@ -389,14 +414,161 @@ __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, in
     wait_vmcnt<0>();  // the trailing panels must land before LDS is reused or released
 }
 
+// Ping-pong schedule for two groups of wavefronts (KG == 2).  Time is cut into phases with one
+// workgroup barrier between consecutive phases.  In a "read" phase R(st) a wavefront starts its
+// share of the loads of panel st+2, reads all its fragments of panel st from LDS and waits for
+// its loads of panel st+1; in a "multiply" phase M(st) it only issues the MFMAs of panel st.
+//     phase:    0      1      2      3      4    ...
+//     group 0:  R(0)   M(0)   R(1)   M(1)   R(2) ...
+//     group 1:  -      R(0)   M(0)   R(1)   M(1) ...
+// so at any time one wavefront of every SIMD feeds the matrix pipe with nothing else in its
+// instruction stream while the other does all the LDS and memory work -- LDS reads in the
+// stream of a wavefront that is issuing MFMAs delay them, and two wavefronts that both
+// multiply at once are served oldest-first, i.e. one after the other, with the pipe draining at
+// every barrier.  Panel st is read in phases 2st and 2st+1; its ring slot is written again by
+// loads issued in phase 2st+2 or later, and panel st+1 has landed (every wavefront waited for
+// its own share at the end of a read phase no later than phase 2st+1) before phase 2st+2.
+template <int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
+__device__ __forceinline__ void run_pingpong(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int kg, int wm,
+                                             int wn, int lane)
+{
+    static_assert(NL < 64, "loads in flight must fit the vmcnt counter");
+    const unsigned lds0 = (unsigned)(size_t)(lds_byte*)lds;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) issue(i, s, lds0 + s * STAGE_BYTES);
+    }
+    wait_vmcnt<NL>();  // panel 0 has landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kg == 1) {  // phase 0: nothing to do for group 1
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
+    int slot = 0;
+    for (int st = 0; st < nsteps; ++st) {
+        int pslot = slot - 1;  // the slot panel st-1 occupied = the slot of panel st+2
+        if (pslot < 0) pslot += 3;
+        const unsigned dst = lds0 + pslot * STAGE_BYTES;
+        const unsigned char* cur = lds + slot * STAGE_BYTES;
+        // ---- R(st)
+#pragma unroll
+        for (int i = 0; i < NL; ++i) issue(i, st + 2, dst);
+        core.read_panel(cur, cur + A_BYTES, kg, wm, wn, lane);
+        wait_vmcnt<NL>();                                   // this wavefront's share of panel st+1 has landed
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // and its reads of panel st are done
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // ---- M(st)
+        __builtin_amdgcn_sched_barrier(0);
+        core.mfma_panel();
+        __builtin_amdgcn_sched_barrier(0);
+        if (kg == 0 || st + 1 < nsteps) {  // group 1's last multiply phase is the last phase
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
+        slot = (slot + 1 == 3) ? 0 : slot + 1;
+    }
+    wait_vmcnt<0>();  // the trailing panels must land before LDS is reused or released
+}
+
+template <int STAGES, int KG, int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
+__device__ __forceinline__ void run_ring(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int kg, int wm, int wn,
+                                         int lane)
+{
+    if constexpr (KG == 2) {
+        static_assert(STAGES == 3, "the ping-pong schedule uses a three-slot ring");
+        run_pingpong<NL, STAGE_BYTES, A_BYTES>(core, lds, nsteps, issue, kg, wm, wn, lane);
+    } else {
+        run_pipeline<STAGES, NL, STAGE_BYTES, A_BYTES>(core, lds, nsteps, issue, kg, wm, wn, lane);
+    }
+}
+
+// The ring of the stride-1 forward / data-gradient passes when the A operand is kept as an
+// activation slab: the reduction runs over channel blocks of 64 (outer) and taps (inner); the
+// frames a tile needs from one channel block -- BM + k - 1 consecutive frames -- are loaded once
+// into one of two slab buffers and serve all k taps (tap j reads the slab j rows further down),
+// so only the weight panels stream through the three-slot ring, one per (channel block, tap).
+// issue_slab(i, cb, lds_addr) starts load i (of NLS per wavefront) of channel block cb's slab;
+// issue_b(i, cb, j, lds_addr) load i (of NLB) of the weight panel of (cb, j).  The slab of
+// block cb+1 is requested in the read phase of the first panel of block cb, ahead of that
+// phase's weight prefetch, so every wait that covers a weight panel also covers the older slab.
+// Phases and barriers are those of run_pingpong.
+template <int NLS, int NLB, int SLAB_BYTES, int STAGE_BYTES, class CoreT, class IssueSlab, class IssueB>
+__device__ __forceinline__ void run_slab_pipeline(CoreT& core, unsigned char* lds, int ncb, int k, IssueSlab issue_slab,
+                                                  IssueB issue_b, int kg, int wm, int wn, int lane)
+{
+    static_assert(NLS + NLB < 64, "loads in flight must fit the vmcnt counter");
+    const unsigned lds0 = (unsigned)(size_t)(lds_byte*)lds;
+    const unsigned ring0 = lds0 + 2 * SLAB_BYTES;
+    unsigned char* ring = lds + 2 * SLAB_BYTES;
+    const int nsteps = ncb * k;
+    int pcb = 0, pj = 0;  // (channel block, tap) of the next weight panel to prefetch
+    auto advance = [&]() {
+        if (pj + 1 < k) ++pj;
+        else if (pcb + 1 < ncb) { pj = 0; ++pcb; }  // past the end: keep refetching the last panel
+    };
+#pragma unroll
+    for (int i = 0; i < NLS; ++i) issue_slab(i, 0, lds0);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+#pragma unroll
+        for (int i = 0; i < NLB; ++i) issue_b(i, pcb, pj, ring0 + s * STAGE_BYTES);
+        advance();
+    }
+    wait_vmcnt<NLB>();  // slab 0 and weight panel 0 have landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kg == 1) {  // phase 0 of the ping-pong schedule: nothing to do for group 1
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
+    int cb = 0, j = 0, slot = 0;
+    for (int st = 0; st < nsteps; ++st) {
+        const bool has_slab = (j == 0) && (cb + 1 < ncb);
+        int pslot = slot - 1;
+        if (pslot < 0) pslot += 3;
+        const unsigned dst = ring0 + pslot * STAGE_BYTES;
+        const unsigned sdst = lds0 + ((cb + 1) & 1) * SLAB_BYTES;
+        // ---- R(st): the slab of the next channel block (first tap only), weight panel st+2, fragments
+        if (has_slab) {
+#pragma unroll
+            for (int i = 0; i < NLS; ++i) issue_slab(i, cb + 1, sdst);
+        }
+#pragma unroll
+        for (int i = 0; i < NLB; ++i) issue_b(i, pcb, pj, dst);
+        advance();
+        core.read_panel(lds + (cb & 1) * SLAB_BYTES, ring + slot * STAGE_BYTES, kg, wm, wn, lane, j);
+        // issued after weight panel st+1 (which must have landed): this phase's loads only
+        if (has_slab) wait_vmcnt<NLS + NLB>();
+        else wait_vmcnt<NLB>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // ---- M(st)
+        __builtin_amdgcn_sched_barrier(0);
+        core.mfma_panel();
+        __builtin_amdgcn_sched_barrier(0);
+        if (kg == 0 || st + 1 < nsteps) {
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
+        if (++j == k) { j = 0; ++cb; }
+        slot = (slot + 1 == 3) ? 0 : slot + 1;
+    }
+    wait_vmcnt<0>();
+}
+
 // bf16 epilogue shared by the forward and data-gradient kernels: the accumulators (+ add[j] per
 // column block) go to LDS as a row-major tile and leave as 16-byte row segments, every thread
 // of the workgroup storing.  When the padded tile does not fit the panel ring (256x256) the
-// two wavefront rows go one after the other.  rowoff(m) = element row of output row m.
+// two wavefront rows go one after the other.  rowoff(r) = output row (in units of N elements) of
+// tile row r, negative for rows that must not be stored.
 template <int BM, int BN, int KG, int LDS_BYTES, class CoreT, class RowOff>
 __device__ __forceinline__ void store_tile_bf16(const CoreT& core, unsigned char* lds, const float (&add)[CoreT::TN],
-                                                bf16_t* __restrict__ out, int m0, int n0, int M, int N, int kg, int wm,
-                                                int wn, int lane, RowOff rowoff)
+                                                bf16_t* __restrict__ out, int n0, int N, int kg, int wm, int wn, int lane,
+                                                RowOff rowoff)
 {
     constexpr int PITCH = CoreT::OPITCH, CPRW = BN / 8, NTHR = 256 * KG;
     constexpr int PASSES = (BM * PITCH <= LDS_BYTES) ? 1 : 2;
@@ -411,9 +583,10 @@ __device__ __forceinline__ void store_tile_bf16(const CoreT& core, unsigned char
 #pragma unroll
         for (int c = threadIdx.x; c < ROWS * CPRW; c += NTHR) {
             const int row = c / CPRW, cc = c - row * CPRW;
-            const int m = m0 + h * ROWS + row, n = n0 + cc * 8;
-            if (m < M && n < N)
-                *reinterpret_cast<uint4*>(out + (size_t)rowoff(m) * N + n) =
+            const int n = n0 + cc * 8;
+            const long long ro = rowoff(h * ROWS + row);  // < 0: a row that is not stored
+            if (ro >= 0 && n < N)
+                *reinterpret_cast<uint4*>(out + (size_t)ro * N + n) =
                     *reinterpret_cast<const uint4*>(lds + row * PITCH + cc * 16);
         }
     }
@@ -492,7 +665,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_k(const bf16_t* __restrict_
     Core<BM, BN, BKT, KG, PA, PB> core;
     core.zero();
     const int nsteps = (K + BKT - 1) / BKT;  // FAST requires K % BKT == 0
-    run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
+    run_ring<STAGES, KG, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
         [&](int i, int st, unsigned dst) {
             if (FAST) {
@@ -513,8 +686,9 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_k(const bf16_t* __restrict_
         bv[j] = (bias && n < N) ? bias[n] : 0.f;
     }
     if (sizeof(TO) == 2 && N % 8 == 0) {
-        store_tile_bf16<BM, BN, KG, STAGES * STAGE>(core, lds, bv, reinterpret_cast<bf16_t*>(y), m0, n0, M, N, kg, wm, wn,
-                                                    lane, [&](int m) { return out_row(m, g.Tp, g.y_pitch, g.y_halo); });
+        store_tile_bf16<BM, BN, KG, STAGES * STAGE>(
+            core, lds, bv, reinterpret_cast<bf16_t*>(y), n0, N, kg, wm, wn, lane,
+            [&](int r) { return m0 + r < M ? out_row(m0 + r, g.Tp, g.y_pitch, g.y_halo) : -1LL; });
         return;
     }
     if (kg != 0) return;
@@ -529,6 +703,82 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_k(const bf16_t* __restrict_
             for (int j = 0; j < core.TN; ++j) {
                 const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
                 if (n < N) Elem<TO>::store(y, row + n, core.acc[i][j][r] + bv[j]);
+            }
+        }
+}
+
+// dynamic LDS of a slab kernel: two slabs + three weight panels, or the fp32 tile of the group reduction
+constexpr int slab_lds_bytes(int bm, int bn, int srows, int kg)
+{
+    const int ring = 2 * srows * 128 + 3 * bn * 128;
+    return (kg == 2 && bm * bn * 4 > ring) ? bm * bn * 4 : ring;
+}
+
+// Forward pass, stride 1, input kept with a zero halo (see FAST above), Cin % 64 == 0: tiles
+// run over the frames of the input *layout* (halo frames included; their outputs are dropped),
+// so that the frames a tile reads are one contiguous block -- the activation slab.
+template <int BM, int BN, int SROWS, int KG, typename TO>
+__global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
+                                                            const float* __restrict__ bias, TO* __restrict__ y,
+                                                            ConvGeom g)
+{
+    using PS = PanelK<SROWS, 64, 4 * KG>;
+    using PB = PanelK<BN, 64, 4 * KG>;
+    extern __shared__ __align__(1024) unsigned char lds[];
+    constexpr int LDS_BYTES = slab_lds_bytes(BM, BN, SROWS, KG);
+    const int F = (g.B - 1) * g.x_pitch + g.T;  // frames from the first real one to the last real one
+    const int N = g.Cout, K = g.k * g.Cin;
+    int tm, tn;
+    tile_of_block((F + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
+    const int f0 = g.x_halo + tm * BM, n0 = tn * BN;  // layout frame of tile row 0
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
+
+    PS ps;
+    PB pb;
+    ps.init(x);
+    pb.init(w);
+#pragma unroll
+    for (int i = 0; i < PS::NI; ++i) ps.set_fast(i, (long long)(f0 - g.p + PS::row_of(i)) * g.Cin);
+#pragma unroll
+    for (int i = 0; i < PB::NI; ++i) {
+        int n = n0 + PB::row_of(i);
+        if (n >= N) n = N - 1;
+        pb.set_fast(i, (long long)n * K);
+    }
+    Core<BM, BN, 64, KG, PS, PB> core;
+    core.zero();
+    run_slab_pipeline<PS::NI, PB::NI, PS::BYTES, PB::BYTES>(
+        core, lds, g.Cin / 64, g.k,
+        [&](int i, int cb, unsigned dst) { ps.issue_fast(i, x + cb * 64, dst); },
+        [&](int i, int cb, int j, unsigned dst) { pb.issue_fast(i, w + (j * g.Cin + cb * 64), dst); }, kg, wm, wn, lane);
+    core.reduce_groups(lds, kg, w4, lane);
+    float bv[core.TN];
+#pragma unroll
+    for (int j = 0; j < core.TN; ++j) {
+        const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+        bv[j] = (bias && n < N) ? bias[n] : 0.f;
+    }
+    // tile row r is layout frame f0 + r: utterance b, frame t; stored only if it is a real frame
+    auto rowoff = [&](int r) {
+        const int f = f0 + r, b = f / g.x_pitch, t = f - b * g.x_pitch - g.x_halo;
+        return (b < g.B && t >= 0 && t < g.T) ? (long long)b * g.y_pitch + g.y_halo + t : -1LL;
+    };
+    if (sizeof(TO) == 2 && N % 8 == 0) {
+        store_tile_bf16<BM, BN, KG, LDS_BYTES>(core, lds, bv, reinterpret_cast<bf16_t*>(y), n0, N, kg, wm, wn, lane, rowoff);
+        return;
+    }
+    if (kg != 0) return;
+#pragma unroll
+    for (int i = 0; i < core.TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const long long ro = rowoff(wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3));
+            if (ro < 0) continue;
+#pragma unroll
+            for (int j = 0; j < core.TN; ++j) {
+                const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+                if (n < N) Elem<TO>::store(y, (size_t)ro * N + n, core.acc[i][j][r] + bv[j]);
             }
         }
 }
@@ -575,7 +825,7 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_k(const bf16_t* __restric
     Core<BM, BN, BKT, KG, PA, PB> core;
     core.zero();
     const int nsteps = K / BKT;  // Cout is a multiple of BKT: a panel stays inside one tap
-    run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
+    run_ring<STAGES, KG, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
         [&](int i, int st, unsigned dst) {
             const int stc = (FAST && st >= nsteps) ? nsteps - 1 : st;
@@ -605,8 +855,9 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_k(const bf16_t* __restric
     float zero[core.TN];
 #pragma unroll
     for (int j = 0; j < core.TN; ++j) zero[j] = 0.f;
-    store_tile_bf16<BM, BN, KG, STAGES * STAGE>(core, lds, zero, dx, m0, n0, M, N, kg, wm, wn, lane,
-                                                [&](int m) { return out_row(m, g.T, g.x_pitch, g.x_halo); });
+    store_tile_bf16<BM, BN, KG, STAGES * STAGE>(
+        core, lds, zero, dx, n0, N, kg, wm, wn, lane,
+        [&](int r) { return m0 + r < M ? out_row(m0 + r, g.T, g.x_pitch, g.x_halo) : -1LL; });
 }
 
 // =============================== weight gradient ========================================
@@ -646,7 +897,7 @@ __global__ __launch_bounds__(256 * KG) void conv_wgrad_k(const bf16_t* __restric
     const int nsteps = FAST ? (frames + BKT - 1) / BKT : g.B * spb;
     Core<BM, BN, BKT, KG, PA, PB> core;
     core.zero();
-    run_pipeline<STAGES, PA::NI + PB::NI, STAGE, PA::BYTES>(
+    run_ring<STAGES, KG, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
         [&](int i, int st, unsigned dst) {
             if (FAST) {
@@ -734,6 +985,17 @@ bool common_ok(const ConvDesc& d)
 bool halo_ok_x(const ConvDesc& d) { return d.p == 0 || d.x_halo >= d.p; }
 bool halo_ok_y(const ConvDesc& d) { return d.p == 0 || d.y_halo >= d.p; }
 
+// Activation-slab kernels: stride 1, the slab tensor has C % 64 == 0 channels and a halo, at
+// least two taps, a slab of srows frames covers the tile's window, and the last tile's slab
+// stays inside the allocation (B * pitch + slack frames).
+bool slab_ok(const ConvDesc& d, int bm, int srows, int C, int frames, int pitch, int halo)
+{
+    if (d.s != 1 || d.k < 2 || C % 64 != 0 || halo < d.p || halo == 0 || bm + d.k - 1 > srows) return false;
+    const long long F = (long long)(d.B - 1) * pitch + frames;
+    const long long last_f0 = halo + (F - 1) / bm * bm;
+    return last_f0 - d.p + srows <= (long long)d.B * pitch + d.slack;
+}
+
 // tile -> (panel depth, ring depth): 3 x 48 KB for the tiles that fit, 4 x 32 KB for 256x256
 // and how many reduction groups of wavefronts (the 256x256 accumulators leave room for one)
 #define W2L_TILE_DISPATCH(CALL)                                             \
@@ -759,6 +1021,20 @@ int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* 
     const TileChoice tc = choose_tile(M, N);
     const bool fast = halo_ok_x(g) && ((long long)g.k * g.Cin) % 64 == 0;
     int rc = W2L_OK;
+    static const bool noslab = getenv("W2L_NOSLAB") != nullptr;
+    if (!noslab && fast && tc.bm == 192 && tc.bn == 192 && slab_ok(g, 192, 256, g.Cin, g.T, g.x_pitch, g.x_halo)) {
+        constexpr int bytes = slab_lds_bytes(192, 192, 256, 2);
+        const long long F = (long long)(g.B - 1) * g.x_pitch + g.T;
+        const unsigned grid = (unsigned)(((F + 191) / 192) * ((N + 191) / 192));
+        if (ydt == W2L_BF16) {
+            rc = set_lds(conv_fwd_slab_k<192, 192, 256, 2, bf16_t>, bytes);
+            if (!rc) hipLaunchKernelGGL((conv_fwd_slab_k<192, 192, 256, 2, bf16_t>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g);
+        } else {
+            rc = set_lds(conv_fwd_slab_k<192, 192, 256, 2, float>, bytes);
+            if (!rc) hipLaunchKernelGGL((conv_fwd_slab_k<192, 192, 256, 2, float>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g);
+        }
+        return rc ? rc : launch_status();
+    }
 #define LAUNCH(KERN, BYTES, ...)                                                          \
     {                                                                                     \
         rc = set_lds(KERN, BYTES);                                                        \

@@ -18,7 +18,7 @@ namespace {
 // after the last one, so the convolution kernels can read every window as plain memory.
 // Tensors only read elementwise (pre-GLU outputs y_i, gradients dh_i) stay dense.
 constexpr int HALO = 8;
-constexpr int SLACK = 64;
+constexpr int SLACK = 320;
 
 // A helper stream (default priority) on which the weight gradients run: wgrad of layer i needs
 // only dy_i and h_{i-1}, nothing downstream needs it before the step ends, and neither wgrad
