@@ -39,6 +39,7 @@
 // panel advance is a scalar add on the base pointer, and a load costs three instructions.
 #include "common.h"
 #include <cstdlib>
+#include <cstdio>
 #ifndef W2L_SPREAD_EXPR
 #define W2L_SPREAD_EXPR (CoreT::GROUPS / NL)
 #endif
@@ -860,6 +861,50 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_k(const bf16_t* __restric
         [&](int r) { return m0 + r < M ? out_row(m0 + r, g.T, g.x_pitch, g.x_halo) : -1LL; });
 }
 
+// Data gradient with the dy window kept as an activation slab (dy has a zero halo, Cout % 64
+// == 0): same schedule as conv_fwd_slab_k; the weight panel of (channel block, tap j') is the
+// 64 x BN block w[co0 .. co0+63][k-1-j'][n0 .. n0+BN-1], read through the LDS transpose read.
+template <int BM, int BN, int SROWS, int KG>
+__global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
+                                                              bf16_t* __restrict__ dx, ConvGeom g)
+{
+    using PS = PanelK<SROWS, 64, 4 * KG>;
+    using PB = PanelMN<BN, 64, 4 * KG>;
+    extern __shared__ __align__(1024) unsigned char lds[];
+    constexpr int LDS_BYTES = slab_lds_bytes(BM, BN, SROWS, KG);
+    const int F = (g.B - 1) * g.y_pitch + g.Tp;
+    const int N = g.Cin;
+    int tm, tn;
+    tile_of_block((F + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
+    const int f0 = g.y_halo + tm * BM, n0 = tn * BN;  // dy layout frame of tile row 0
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
+
+    PS ps;
+    PB pb;
+    ps.init(dy);
+    pb.init_fast(w, g.k * g.Cin, N - n0);
+#pragma unroll
+    for (int i = 0; i < PS::NI; ++i) ps.set_fast(i, (long long)(f0 - g.p + PS::row_of(i)) * g.Cout);
+    Core<BM, BN, 64, KG, PS, PB> core;
+    core.zero();
+    run_slab_pipeline<PS::NI, PB::NI, PS::BYTES, PB::BYTES>(
+        core, lds, g.Cout / 64, g.k,
+        [&](int i, int cb, unsigned dst) { ps.issue_fast(i, dy + cb * 64, dst); },
+        [&](int i, int cb, int j, unsigned dst) {
+            pb.issue_fast(i, w + ((long long)cb * 64 * g.k + (g.k - 1 - j)) * g.Cin + n0, dst);
+        },
+        kg, wm, wn, lane);
+    core.reduce_groups(lds, kg, w4, lane);
+    float zero[core.TN];
+#pragma unroll
+    for (int j = 0; j < core.TN; ++j) zero[j] = 0.f;
+    store_tile_bf16<BM, BN, KG, LDS_BYTES>(core, lds, zero, dx, n0, N, kg, wm, wn, lane, [&](int r) {
+        const int f = f0 + r, b = f / g.y_pitch, t = f - b * g.y_pitch - g.y_halo;
+        return (b < g.B && t >= 0 && t < g.T) ? (long long)b * g.x_pitch + g.x_halo + t : -1LL;
+    });
+}
+
 // =============================== weight gradient ========================================
 // dw[co, (j,ci)] = sum_{b,t'} dy[b,t',co] * x[b, s t' - p + j, ci].
 // CHECKED: the reduction walks utterance by utterance in BKT-frame panels (the last panel of
@@ -957,6 +1002,7 @@ int set_lds(K kern, int bytes)
 struct TileChoice { int bm, bn; };
 TileChoice choose_tile(long long M, long long N)
 {
+    if (const char* e = getenv("W2L_TILE")) { TileChoice t; if (sscanf(e, "%d,%d", &t.bm, &t.bn) == 2) return t; }  // DEV ONLY
     const TileChoice cand[] = {{256, 256}, {192, 192}, {256, 128}, {128, 256}, {128, 128}};
     double best = -1;
     TileChoice pick = cand[0];
@@ -1069,6 +1115,15 @@ int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, 
     const TileChoice tc = choose_tile(M, N);
     const bool fast = halo_ok_y(g);
     int rc = W2L_OK;
+    static const bool noslab = getenv("W2L_NOSLAB") != nullptr;
+    if (!noslab && fast && tc.bm == 256 && tc.bn == 128 && slab_ok(g, 256, 320, g.Cout, g.Tp, g.y_pitch, g.y_halo)) {
+        constexpr int bytes = slab_lds_bytes(256, 128, 320, 2);
+        const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
+        const unsigned grid = (unsigned)(((F + 255) / 256) * ((N + 127) / 128));
+        rc = set_lds(conv_dgrad_slab_k<256, 128, 320, 2>, bytes);
+        if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<256, 128, 320, 2>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g);
+        return rc ? rc : launch_status();
+    }
 #define CALL(BM_, BN_, BK_, ST_, KG_)                                                                     \
     {                                                                                                     \
         constexpr int bytes = ST_ * (BM_ + BN_) * BK_ * 2;                                                \
