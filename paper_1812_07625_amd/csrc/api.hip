@@ -87,7 +87,7 @@ namespace {
 // The C ABI takes dense tensors; the MFMA kernels run fastest on tensors with a zero halo
 // around every utterance.  Given workspace, the entry points first copy the window-read
 // operand(s) into that layout (one bandwidth-bound pass, a few percent of the GEMM).
-constexpr int ABI_HALO = 8, ABI_SLACK = 320;
+constexpr int ABI_HALO = LAYOUT_HALO, ABI_SLACK = LAYOUT_SLACK, ABI_SLACK_ZERO = LAYOUT_SLACK_ZERO;
 size_t haloed_bytes(int B, int frames, int C) { return round_up(((size_t)B * (frames + 2 * ABI_HALO) + ABI_SLACK) * C * 2, 256); }
 bool stage_fwd(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cin % 64 == 0 && Cout >= 16 && s >= 1; }
 bool stage_dgrad(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && s == 1 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cout % 64 == 0 && Cin % 8 == 0 && Cin >= 64; }
@@ -115,7 +115,7 @@ extern "C" int w2l_conv1d_fwd(const void* x, const void* w, const float* bias, v
     hipStream_t st = (hipStream_t)stream;
     ConvDesc d = dense_desc(B, T, Cin, Cout, k, stride);
     if (workspace && need) {
-        rc = pad_layout_bf16(x, workspace, B, T, Cin, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK, st);
+        rc = pad_layout_bf16(x, workspace, B, T, Cin, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
         if (rc) return rc;
         d.x_pitch = T + 2 * ABI_HALO;
         d.x_halo = ABI_HALO;
@@ -146,7 +146,7 @@ extern "C" int w2l_conv1d_bwd_data(const void* dy, const void* w, void* dx, int 
     hipStream_t st = (hipStream_t)stream;
     ConvDesc d = dense_desc(B, T, Cin, Cout, k, stride);
     if (workspace && need) {
-        rc = pad_layout_bf16(dy, workspace, B, d.Tp, Cout, d.Tp + 2 * ABI_HALO, ABI_HALO, ABI_SLACK, st);
+        rc = pad_layout_bf16(dy, workspace, B, d.Tp, Cout, d.Tp + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
         if (rc) return rc;
         d.y_pitch = d.Tp + 2 * ABI_HALO;
         d.y_halo = ABI_HALO;
@@ -183,9 +183,9 @@ extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, f
     if (dy_dtype == W2L_BF16 && stage_wgrad(Cin, Cout, k, stride, dtype)) {
         unsigned char* xp = ws + conv_wgrad_scratch_bytes(Cin, Cout, k);
         unsigned char* dyp = xp + haloed_bytes(B, T, Cin);
-        rc = pad_layout_bf16(x, xp, B, T, Cin, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK, st);
+        rc = pad_layout_bf16(x, xp, B, T, Cin, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
         if (rc) return rc;
-        rc = pad_layout_bf16(dy, dyp, B, T, Cout, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK, st);
+        rc = pad_layout_bf16(dy, dyp, B, T, Cout, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
         if (rc) return rc;
         d.x_pitch = d.y_pitch = T + 2 * ABI_HALO;
         d.x_halo = d.y_halo = ABI_HALO;

@@ -31,6 +31,15 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
     return (bf16_t)(((u & 0x7fffffffu) > 0x7f800000u) ? ((u >> 16) | 0x40u) : r);  // a select, not a branch
 }
 
+__device__ __forceinline__ float sigmoidf_(float u) { return 1.f / (1.f + __expf(-u)); }
+
+// Time layout of the activations the library keeps itself (train step workspace, staged
+// operands of the convolution entry points): LAYOUT_HALO zero frames on both sides of every
+// utterance, then LAYOUT_SLACK allocated frames after the last utterance, of which the first
+// LAYOUT_SLACK_ZERO are kept zero (kernels whose reduction runs through the frames over-read
+// into them); the rest is only ever read for outputs that are dropped.
+constexpr int LAYOUT_HALO = 8, LAYOUT_SLACK = 320, LAYOUT_SLACK_ZERO = 64;
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float load(const float* p, size_t i) { return p[i]; }
@@ -91,6 +100,12 @@ bool conv_fwd_mfma_ok(const ConvDesc& d);
 int conv_fwd_mfma(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int ydt, hipStream_t st);
 bool conv_dgrad_mfma_ok(const ConvDesc& d);
 int conv_dgrad_mfma(const ConvDesc& d, const void* dy, const void* w, void* dx, hipStream_t st);
+// data gradient of a layer fused with the GLU backward of the layer below it: instead of dx (=
+// dh of the layer below) it writes dy of the layer below, dy = GLU'(yprev) * dh, into a haloed
+// tensor with the same time layout as this layer's dy (halo frames are written as zeros).
+// yprev: dense [B*T, 2*Cin] pre-GLU activations of the layer below.
+bool conv_dgrad_glu_ok(const ConvDesc& d);
+int conv_dgrad_glu(const ConvDesc& d, const void* dy, const void* w, const void* yprev, void* dyprev, hipStream_t st);
 bool conv_wgrad_mfma_ok(const ConvDesc& d);
 int conv_wgrad_mfma(const ConvDesc& d, const void* x, const void* dy, float* dw, int accumulate, hipStream_t st);
 

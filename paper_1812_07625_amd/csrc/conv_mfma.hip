@@ -864,9 +864,13 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_k(const bf16_t* __restric
 // Data gradient with the dy window kept as an activation slab (dy has a zero halo, Cout % 64
 // == 0): same schedule as conv_fwd_slab_k; the weight panel of (channel block, tap j') is the
 // 64 x BN block w[co0 .. co0+63][k-1-j'][n0 .. n0+BN-1], read through the LDS transpose read.
-template <int BM, int BN, int SROWS, int KG>
+// GLUB: the tile is not stored as dx but pushed through the GLU backward of the layer below
+// (whose pre-GLU activations yprev are dense [B*T, 2N]): dx_out then has 2N channels and the
+// time layout of dy (tile row r -> its frame f0 + r); frames that are not real get zeros.
+template <int BM, int BN, int SROWS, int KG, bool GLUB>
 __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
-                                                              bf16_t* __restrict__ dx, ConvGeom g)
+                                                              bf16_t* __restrict__ dx, const bf16_t* __restrict__ yprev,
+                                                              ConvGeom g)
 {
     using PS = PanelK<SROWS, 64, 4 * KG>;
     using PB = PanelMN<BN, 64, 4 * KG>;
@@ -899,10 +903,65 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
     float zero[core.TN];
 #pragma unroll
     for (int j = 0; j < core.TN; ++j) zero[j] = 0.f;
-    store_tile_bf16<BM, BN, KG, LDS_BYTES>(core, lds, zero, dx, n0, N, kg, wm, wn, lane, [&](int r) {
-        const int f = f0 + r, b = f / g.y_pitch, t = f - b * g.y_pitch - g.y_halo;
-        return (b < g.B && t >= 0 && t < g.T) ? (long long)b * g.x_pitch + g.x_halo + t : -1LL;
-    });
+    if (!GLUB) {
+        store_tile_bf16<BM, BN, KG, LDS_BYTES>(core, lds, zero, dx, n0, N, kg, wm, wn, lane, [&](int r) {
+            const int f = f0 + r, b = f / g.y_pitch, t = f - b * g.y_pitch - g.y_halo;
+            return (b < g.B && t >= 0 && t < g.T) ? (long long)b * g.x_pitch + g.x_halo + t : -1LL;
+        });
+        return;
+    }
+    // dh tile (rounded to bf16, as the unfused path stores it) -> LDS -> GLU backward, 8 channels per thread
+    constexpr int PITCH = core.OPITCH, CPRW = BN / 8, NTHR = 256 * KG;
+    static_assert(BM * PITCH <= LDS_BYTES && (BM * CPRW) % NTHR == 0, "dh tile staging");
+    __syncthreads();
+    if (kg == 0) core.stage_bf16(lds, zero, 0, wm, wn, lane);
+    __syncthreads();
+    const long long alloc_frames = (long long)g.B * g.y_pitch + g.slack;
+#pragma unroll 2
+    for (int c = threadIdx.x; c < BM * CPRW; c += NTHR) {
+        const int row = c / CPRW, cc = c - row * CPRW;
+        const int n = n0 + cc * 8;
+        const int f = f0 + row, b = f / g.y_pitch, t = f - b * g.y_pitch - g.y_halo;
+        if (n >= N || f >= alloc_frames) continue;
+        uint4 oa = make_uint4(0, 0, 0, 0), og = oa;
+        if (b < g.B && t >= 0 && t < g.T) {
+            const bf16_t* yr = yprev + ((size_t)b * g.T + t) * 2 * N + n;
+            const uint4 ua = *reinterpret_cast<const uint4*>(yr), ug = *reinterpret_cast<const uint4*>(yr + N);
+            const uint4 ud = *reinterpret_cast<const uint4*>(lds + row * PITCH + cc * 16);
+            const unsigned* pa = &ua.x; const unsigned* pg = &ug.x; const unsigned* pd = &ud.x;
+            unsigned* qa = &oa.x; unsigned* qg = &og.x;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                unsigned ra = 0, rg = 0;
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const float a = bf16_to_f32((bf16_t)(pa[q] >> (16 * hh)));
+                    const float gg = bf16_to_f32((bf16_t)(pg[q] >> (16 * hh)));
+                    const float d = bf16_to_f32((bf16_t)(pd[q] >> (16 * hh)));
+                    const float sg = sigmoidf_(gg);
+                    ra |= (unsigned)f32_to_bf16(d * sg) << (16 * hh);
+                    rg |= (unsigned)f32_to_bf16(d * a * sg * (1.f - sg)) << (16 * hh);
+                }
+                qa[q] = ra;
+                qg[q] = rg;
+            }
+        }
+        bf16_t* o = dx + (size_t)f * 2 * N + n;
+        *reinterpret_cast<uint4*>(o) = oa;
+        *reinterpret_cast<uint4*>(o + N) = og;
+    }
+}
+
+// zero rows [r0, r1) and [r2, r3) of a [rows, C] bf16 tensor (C % 8 == 0)
+__global__ __launch_bounds__(256) void zero_rows_k(bf16_t* __restrict__ p, long long r0, long long r1, long long r2,
+                                                   long long r3, int C)
+{
+    const int cv = C / 8;
+    const long long na = (r1 - r0) * cv, nb = (r3 - r2) * cv;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < na + nb; i += (long long)gridDim.x * blockDim.x) {
+        const long long e = i < na ? r0 * cv + i : r2 * cv + (i - na);
+        reinterpret_cast<uint4*>(p)[e] = make_uint4(0, 0, 0, 0);
+    }
 }
 
 // =============================== weight gradient ========================================
@@ -1120,8 +1179,8 @@ int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, 
         constexpr int bytes = slab_lds_bytes(256, 128, 320, 2);
         const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
         const unsigned grid = (unsigned)(((F + 255) / 256) * ((N + 127) / 128));
-        rc = set_lds(conv_dgrad_slab_k<256, 128, 320, 2>, bytes);
-        if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<256, 128, 320, 2>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g);
+        rc = set_lds(conv_dgrad_slab_k<256, 128, 320, 2, false>, bytes);
+        if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<256, 128, 320, 2, false>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, g);
         return rc ? rc : launch_status();
     }
 #define CALL(BM_, BN_, BK_, ST_, KG_)                                                                     \
@@ -1134,6 +1193,32 @@ int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, 
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
+    return rc ? rc : launch_status();
+}
+
+bool conv_dgrad_glu_ok(const ConvDesc& d)
+{
+    // the slab kernel's tile, dy haloed, and dy of the layer below in the same time layout
+    return conv_dgrad_mfma_ok(d) && halo_ok_y(d) && d.Cin % 8 == 0 && d.x_pitch == d.y_pitch && d.x_halo == d.y_halo &&
+           d.T == d.Tp && d.slack >= LAYOUT_SLACK_ZERO && slab_ok(d, 256, 320, d.Cout, d.Tp, d.y_pitch, d.y_halo);
+}
+
+int conv_dgrad_glu(const ConvDesc& g, const void* dy, const void* w, const void* yprev, void* dyprev, hipStream_t st)
+{
+    if (!conv_dgrad_glu_ok(g)) return W2L_ERR_SHAPE;
+    constexpr int BM = 256, BN = 128;
+    constexpr int bytes = slab_lds_bytes(BM, BN, 320, 2);
+    const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
+    const long long tiles_m = (F + BM - 1) / BM;
+    // frames the tiles do not cover: the leading halo, and from the end of the last tile to the end of the zeroed slack
+    const long long t_end = g.y_halo + tiles_m * BM, z_end = (long long)g.B * g.y_pitch + LAYOUT_SLACK_ZERO;
+    hipLaunchKernelGGL(zero_rows_k, dim3(64), dim3(256), 0, st, (bf16_t*)dyprev, 0LL, (long long)g.y_halo, t_end,
+                       t_end > z_end ? t_end : z_end, 2 * g.Cin);
+    int rc = launch_status();
+    if (rc) return rc;
+    const unsigned grid = (unsigned)(tiles_m * ((g.Cin + BN - 1) / BN));
+    rc = set_lds(conv_dgrad_slab_k<BM, BN, 320, 2, true>, bytes);
+    if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<BM, BN, 320, 2, true>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dyprev, (const bf16_t*)yprev, g);
     return rc ? rc : launch_status();
 }
 

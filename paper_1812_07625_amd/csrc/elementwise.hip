@@ -6,7 +6,6 @@
 namespace w2l {
 namespace {
 
-__device__ __forceinline__ float sigmoidf_(float u) { return 1.f / (1.f + __expf(-u)); }
 
 // ---- GLU ---------------------------------------------------------------------------
 // Vector path: 8 channels per thread (16-byte bf16 loads, 2x16-byte fp32 loads).

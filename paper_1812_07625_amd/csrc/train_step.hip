@@ -17,8 +17,9 @@ namespace {
 // dgrad/wgrad) are kept with HALO zero frames around every utterance and SLACK zero frames
 // after the last one, so the convolution kernels can read every window as plain memory.
 // Tensors only read elementwise (pre-GLU outputs y_i, gradients dh_i) stay dense.
-constexpr int HALO = 8;
-constexpr int SLACK = 320;
+constexpr int HALO = LAYOUT_HALO;
+constexpr int SLACK = LAYOUT_SLACK;            // allocated after the last utterance
+constexpr int SLACK_ZERO = LAYOUT_SLACK_ZERO;  // of which kept zero
 
 // A helper stream (default priority) on which the weight gradients run: wgrad of layer i needs
 // only dy_i and h_{i-1}, nothing downstream needs it before the step ends, and neither wgrad
@@ -55,7 +56,7 @@ struct Plan {
     int n = 0, C = 0, Tlast = 0, tot_stride = 1;
     std::vector<int> Tin, Tout, outch;
     std::vector<size_t> pre, post;  // workspace offsets of conv output (dense) and GLU output (haloed) per layer
-    size_t dlogits = 0, crit_len = 0, gdy[2] = {0, 0}, gdh = 0, ctc = 0, conv = 0, total = 0;
+    size_t dlogits = 0, crit_len = 0, gdy[3] = {0, 0, 0}, gdh = 0, ctc = 0, conv = 0, total = 0;
     size_t ctc_bytes = 0, conv_bytes = 0;
     int status = W2L_OK;
 };
@@ -104,8 +105,7 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
     p.C = L[n - 1].cout;
     p.dlogits = off; off += round_up((size_t)B * p.Tlast * p.C * 4, 256);
     p.crit_len = off; off += round_up((size_t)B * 4, 256);
-    p.gdy[0] = off; off += round_up(dymax, 256);
-    p.gdy[1] = off; off += round_up(dymax, 256);
+    for (int q = 0; q < 3; ++q) { p.gdy[q] = off; off += round_up(dymax, 256); }
     p.gdh = off; off += round_up(dhmax, 256);
     p.ctc_bytes = w2l_ctc_workspace_bytes(B, p.Tlast, p.C, Lmax);
     p.ctc = off; off += round_up(p.ctc_bytes, 256);
@@ -172,7 +172,7 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
         if (rc) return rc;
         if (l.glu) {
             rc = glu_fwd_layout(ws + p.pre[i], ws + p.post[i], B, p.Tout[i], l.cout, dtype, p.Tout[i] + 2 * HALO, HALO,
-                                SLACK, st);
+                                SLACK_ZERO, st);
             if (rc) return rc;
         }
         h = ws + p.post[i];
@@ -195,32 +195,44 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
 
     // ---- backward.  dh = gradient wrt layer i's output (dense); dy = gradient wrt its conv
     // output: the haloed result of the GLU backward, or dh itself for a layer without GLU.
-    // Main stream: GLU bwd -> dgrad chain.  Side stream: wgrad (+dbias) of every layer, each
-    // started as soon as its dy exists.  dy buffers alternate so that layer i-1's GLU bwd does
-    // not overwrite what wgrad_i still reads; layer i-2's waits for wgrad_i.
+    // Main stream: the dgrad chain.  Where the shapes allow, the data gradient of layer i applies
+    // the GLU backward of layer i-1 in its epilogue and writes dy_{i-1} directly; otherwise dh
+    // goes to memory and a GLU-backward kernel follows.  Side stream: wgrad (+dbias) of every
+    // layer, each started as soon as its dy exists.  dy buffers rotate over three slots, so the
+    // writer of dy_i only has to wait for the weight gradient of layer i+3.
     SideStream* side = side_stream(n);
     hipStream_t wst = side ? side->stream : st;
     auto hip_ok = [&](hipError_t e) { if (e != hipSuccess) { note_hip_error(e); return false; } return true; };
+    auto wait_wgrad = [&](int layer) {  // main stream waits until that layer's weight gradient has read its dy
+        if (!side || layer >= n) return true;
+        return hip_ok(hipStreamWaitEvent(st, side->done[layer], 0));
+    };
     void* gdh = ws + p.gdh;
     const void* dh = dz;
     int dh_dt = W2L_F32;
+    bool dy_ready = false;  // dy of the current layer was already written by the layer above
     for (int i = n - 1; i >= 0; --i) {
         const w2l_layer& l = layers[i];
         ConvDesc d = desc(i);
         const void* dy = dh;
         int dy_dt = dh_dt;
         if (l.glu) {
-            void* gdy = ws + p.gdy[i & 1];
-            if (side && i + 2 < n && !hip_ok(hipStreamWaitEvent(st, side->done[i + 2], 0))) return W2L_ERR_LAUNCH;
-            rc = glu_bwd_layout(ws + p.pre[i], dh, gdy, B, p.Tout[i], l.cout, dtype, p.Tout[i] + 2 * HALO, HALO, SLACK, st);
-            if (rc) return rc;
+            void* gdy = ws + p.gdy[i % 3];
+            if (!dy_ready) {
+                if (!wait_wgrad(i + 3)) return W2L_ERR_LAUNCH;
+                rc = glu_bwd_layout(ws + p.pre[i], dh, gdy, B, p.Tout[i], l.cout, dtype, p.Tout[i] + 2 * HALO, HALO,
+                                    SLACK_ZERO, st);
+                if (rc) return rc;
+            }
             dy = gdy;
             dy_dt = dtype;
             d.y_pitch = p.Tout[i] + 2 * HALO;
             d.y_halo = HALO;
+            d.slack = SLACK;
         } else {
             d.slack = 0;  // dy is dense here: nothing may be read past its end
         }
+        dy_ready = false;
         if (side) {
             if (!hip_ok(hipEventRecord(side->ready[i], st)) || !hip_ok(hipStreamWaitEvent(wst, side->ready[i], 0)))
                 return W2L_ERR_LAUNCH;
@@ -230,6 +242,13 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
         if (rc) return rc;
         if (side && !hip_ok(hipEventRecord(side->done[i], wst))) return W2L_ERR_LAUNCH;
         if (i > 0) {
+            if (layers[i - 1].glu && dtype == W2L_BF16 && dy_dt == W2L_BF16 && conv_dgrad_glu_ok(d)) {
+                if (!wait_wgrad(i + 2)) return W2L_ERR_LAUNCH;  // last reader of the slot dy_{i-1} goes into
+                rc = conv_dgrad_glu(d, dy, weights[i], ws + p.pre[i - 1], ws + p.gdy[(i - 1) % 3], st);
+                if (rc) return rc;
+                dy_ready = true;
+                continue;
+            }
             ConvDesc dd = d;   // dx = dh_{i-1} is written dense
             dd.x_pitch = p.Tin[i];
             dd.x_halo = 0;
