@@ -10,12 +10,13 @@
 //   dgrad  m=(b,t)   n=ci      r=(j',co)  A = dy window (r-contiguous)  B = w (n-contiguous), j'=k-1-j
 //   wgrad  m=co      n=(j,ci)  r=(b,t')   A = dy (m-contiguous)         B = x window (n-contiguous)
 //
-// One workgroup computes a BM x BN tile with KG groups of 4 wavefronts (2x2); a wavefront owns a
-// (BM/2)x(BN/2) sub-tile of 32x32 MFMA blocks held in accumulation registers.  With KG = 2 the
-// two groups split the reduction (alternate 16-element sub-steps of every panel) and their
-// accumulators are summed through LDS at the end: every SIMD then hosts two wavefronts, so one
-// can issue matrix instructions while the other issues loads or waits, and the register budget
-// per wavefront (256) still holds a 96x96 or 128x64 sub-tile.
+// One workgroup computes a BM x BN tile with one or two groups of 4 wavefronts (2x2).  Two
+// groups put two wavefronts on every SIMD, which then work in opposite phases (one multiplies
+// while the other moves data, see run_pingpong); each wavefront may then use 256 registers, i.e.
+// hold a 96x96 or 128x64 block of accumulators.  The groups either split the reduction (KG = 2:
+// alternate 16-element sub-steps of every panel, accumulators summed through LDS at the end;
+// tiles up to 192x192 / 256x128) or the tile's columns (GN = 2: group g owns columns
+// [g BN/2, (g+1) BN/2), tile 256x256).
 //
 // Data movement.  Operand panels of BKT reduction elements go global -> LDS directly
 // (global_load_lds_dwordx4: no staging registers, no LDS store instructions) into a ring
@@ -207,9 +208,11 @@ struct PanelMN {
 
 // ---- the MFMA core: KG groups of 2x2 wavefronts ----------------------------------------
 // Group kg multiplies the sub-steps ks = kg, kg + KG, ... of every panel.
-template <int BM, int BN, int BKT, int KG, class PA, class PB>
+template <int BM, int BN, int BKT, int KG, int GN, class PA, class PB>
 struct Core {
-    static constexpr int TM = BM / 2 / 32, TN = BN / 2 / 32;  // 32x32 blocks per wavefront
+    static_assert(KG * GN <= 2, "at most two groups of wavefronts");
+    static constexpr int WTN = BN / (2 * GN);              // columns per wavefront (wn = 0 .. 2 GN - 1)
+    static constexpr int TM = BM / 2 / 32, TN = WTN / 32;  // 32x32 blocks per wavefront
     f32x16 acc[TM][TN];
     __device__ __forceinline__ void zero()
     {
@@ -236,7 +239,7 @@ struct Core {
 #pragma unroll
         for (int i = 0; i < TM; ++i) fa[set][i] = PA::frag(la, wm * (BM / 2) + i * 32 + arow, ks, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[set][j] = PB::frag(lb, wn * (BN / 2) + j * 32, ks, lane);
+        for (int j = 0; j < TN; ++j) fb[set][j] = PB::frag(lb, wn * WTN + j * 32, ks, lane);
     }
     template <class Hook>
     __device__ __forceinline__ void mfmas(int u, Hook hook)
@@ -297,7 +300,7 @@ struct Core {
             for (int r = 0; r < 16; ++r) {
                 const int m = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) f(m, wn * (BN / 2) + j * 32 + (lane & 31), acc[i][j][r]);
+                for (int j = 0; j < TN; ++j) f(m, wn * WTN + j * 32 + (lane & 31), acc[i][j][r]);
             }
     }
     // bf16 output tile staged in LDS as [rows][BN] (rows padded by 16 bytes so that the two row
@@ -314,7 +317,7 @@ struct Core {
                 const int m = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) - row_base;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    const int n = wn * (BN / 2) + j * 32 + (lane & 31);
+                    const int n = wn * WTN + j * 32 + (lane & 31);
                     *reinterpret_cast<bf16_t*>(buf + m * OPITCH + n * 2) = f32_to_bf16(acc[i][j][r] + add[j]);
                 }
             }
@@ -323,7 +326,6 @@ struct Core {
     // free of panel traffic).  Lane-contiguous 16-byte accesses; the sum order is fixed.
     __device__ __forceinline__ void reduce_groups(unsigned char* buf, int kg, int w4, int lane)
     {
-        static_assert(KG <= 2, "two reduction groups at most");
         if (KG == 1) return;
         typedef __attribute__((ext_vector_type(4))) float f32x4;
         f32x4* q = reinterpret_cast<f32x4*>(buf) + (size_t)w4 * TM * TN * 4 * 64 + lane;
@@ -429,35 +431,38 @@ __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, in
 // every barrier.  Panel st is read in phases 2st and 2st+1; its ring slot is written again by
 // loads issued in phase 2st+2 or later, and panel st+1 has landed (every wavefront waited for
 // its own share at the end of a read phase no later than phase 2st+1) before phase 2st+2.
-template <int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
-__device__ __forceinline__ void run_pingpong(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int kg, int wm,
-                                             int wn, int lane)
+// grp = the group's phase offset (0 or 1); kg = which sub-steps of a panel the wavefront
+// multiplies.  With a ring of STAGES slots the loads of panel st+STAGES-1 start in R(st).
+template <int STAGES, int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
+__device__ __forceinline__ void run_pingpong(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int grp, int kg,
+                                             int wm, int wn, int lane)
 {
-    static_assert(NL < 64, "loads in flight must fit the vmcnt counter");
+    static_assert(STAGES == 3 || STAGES == 4, "ring depth");
+    static_assert((STAGES - 2) * NL < 64, "loads in flight must fit the vmcnt counter");
     const unsigned lds0 = (unsigned)(size_t)(lds_byte*)lds;
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
+    for (int s = 0; s < STAGES - 1; ++s) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) issue(i, s, lds0 + s * STAGE_BYTES);
     }
-    wait_vmcnt<NL>();  // panel 0 has landed
+    wait_vmcnt<(STAGES - 2) * NL>();  // panel 0 has landed
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kg == 1) {  // phase 0: nothing to do for group 1
+    if (grp == 1) {  // phase 0: nothing to do for group 1
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     }
     int slot = 0;
     for (int st = 0; st < nsteps; ++st) {
-        int pslot = slot - 1;  // the slot panel st-1 occupied = the slot of panel st+2
-        if (pslot < 0) pslot += 3;
+        int pslot = slot - 1;  // the slot panel st-1 occupied = the slot of panel st+STAGES-1
+        if (pslot < 0) pslot += STAGES;
         const unsigned dst = lds0 + pslot * STAGE_BYTES;
         const unsigned char* cur = lds + slot * STAGE_BYTES;
         // ---- R(st)
 #pragma unroll
-        for (int i = 0; i < NL; ++i) issue(i, st + 2, dst);
+        for (int i = 0; i < NL; ++i) issue(i, st + STAGES - 1, dst);
         core.read_panel(cur, cur + A_BYTES, kg, wm, wn, lane);
-        wait_vmcnt<NL>();                                   // this wavefront's share of panel st+1 has landed
+        wait_vmcnt<(STAGES - 2) * NL>();                    // this wavefront's share of panel st+1 has landed
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // and its reads of panel st are done
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -465,22 +470,21 @@ __device__ __forceinline__ void run_pingpong(CoreT& core, unsigned char* lds, in
         __builtin_amdgcn_sched_barrier(0);
         core.mfma_panel();
         __builtin_amdgcn_sched_barrier(0);
-        if (kg == 0 || st + 1 < nsteps) {  // group 1's last multiply phase is the last phase
+        if (grp == 0 || st + 1 < nsteps) {  // group 1's last multiply phase is the last phase
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
         }
-        slot = (slot + 1 == 3) ? 0 : slot + 1;
+        slot = (slot + 1 == STAGES) ? 0 : slot + 1;
     }
     wait_vmcnt<0>();  // the trailing panels must land before LDS is reused or released
 }
 
-template <int STAGES, int KG, int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
-__device__ __forceinline__ void run_ring(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int kg, int wm, int wn,
-                                         int lane)
+template <int STAGES, int GROUPS, int NL, int STAGE_BYTES, int A_BYTES, class CoreT, class Issue>
+__device__ __forceinline__ void run_ring(CoreT& core, unsigned char* lds, int nsteps, Issue issue, int grp, int kg, int wm,
+                                         int wn, int lane)
 {
-    if constexpr (KG == 2) {
-        static_assert(STAGES == 3, "the ping-pong schedule uses a three-slot ring");
-        run_pingpong<NL, STAGE_BYTES, A_BYTES>(core, lds, nsteps, issue, kg, wm, wn, lane);
+    if constexpr (GROUPS == 2) {
+        run_pingpong<STAGES, NL, STAGE_BYTES, A_BYTES>(core, lds, nsteps, issue, grp, kg, wm, wn, lane);
     } else {
         run_pipeline<STAGES, NL, STAGE_BYTES, A_BYTES>(core, lds, nsteps, issue, kg, wm, wn, lane);
     }
@@ -566,12 +570,12 @@ __device__ __forceinline__ void run_slab_pipeline(CoreT& core, unsigned char* ld
 // of the workgroup storing.  When the padded tile does not fit the panel ring (256x256) the
 // two wavefront rows go one after the other.  rowoff(r) = output row (in units of N elements) of
 // tile row r, negative for rows that must not be stored.
-template <int BM, int BN, int KG, int LDS_BYTES, class CoreT, class RowOff>
+template <int BM, int BN, int NTHR, int LDS_BYTES, class CoreT, class RowOff>
 __device__ __forceinline__ void store_tile_bf16(const CoreT& core, unsigned char* lds, const float (&add)[CoreT::TN],
                                                 bf16_t* __restrict__ out, int n0, int N, int kg, int wm, int wn, int lane,
                                                 RowOff rowoff)
 {
-    constexpr int PITCH = CoreT::OPITCH, CPRW = BN / 8, NTHR = 256 * KG;
+    constexpr int PITCH = CoreT::OPITCH, CPRW = BN / 8;
     constexpr int PASSES = (BM * PITCH <= LDS_BYTES) ? 1 : 2;
     constexpr int ROWS = BM / PASSES;
     static_assert(ROWS * PITCH <= LDS_BYTES, "output tile staging must fit the panel ring");
@@ -615,12 +619,12 @@ __device__ __forceinline__ long long out_row(int m, int frames, int pitch, int h
 }
 
 // =============================== forward ================================================
-template <int BM, int BN, int BKT, int STAGES, int KG, bool FAST, typename TO>
-__global__ __launch_bounds__(256 * KG) void conv_fwd_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
+template <int BM, int BN, int BKT, int STAGES, int KG, int GN, bool FAST, typename TO>
+__global__ __launch_bounds__(256 * KG * GN) void conv_fwd_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
                                                  const float* __restrict__ bias, TO* __restrict__ y, ConvGeom g)
 {
-    using PA = PanelK<BM, BKT, 4 * KG>;
-    using PB = PanelK<BN, BKT, 4 * KG>;
+    using PA = PanelK<BM, BKT, 4 * KG * GN>;
+    using PB = PanelK<BN, BKT, 4 * KG * GN>;
     extern __shared__ __align__(1024) unsigned char lds[];
     constexpr int STAGE = PA::BYTES + PB::BYTES;
     static_assert(KG == 1 || BM * BN * 4 <= STAGES * STAGE, "the group reduction reuses the panel ring");
@@ -629,7 +633,8 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_k(const bf16_t* __restrict_
     tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
+    const int grp = wave >> 2, w4 = wave & 3, wm = w4 >> 1;
+    const int kg = (KG == 2) ? grp : 0, wn = (GN == 2 ? 2 * grp : 0) + (w4 & 1);
 
     PA pa;
     PB pb;
@@ -663,10 +668,10 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_k(const bf16_t* __restrict_
             pb.hi[i] = (n < N) ? K : 0;
         }
     }
-    Core<BM, BN, BKT, KG, PA, PB> core;
+    Core<BM, BN, BKT, KG, GN, PA, PB> core;
     core.zero();
     const int nsteps = (K + BKT - 1) / BKT;  // FAST requires K % BKT == 0
-    run_ring<STAGES, KG, PA::NI + PB::NI, STAGE, PA::BYTES>(
+    run_ring<STAGES, KG * GN, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
         [&](int i, int st, unsigned dst) {
             if (FAST) {
@@ -678,16 +683,16 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_k(const bf16_t* __restrict_
                 else pb.issue(i - PA::NI, st * BKT, dst + PA::BYTES);
             }
         },
-        kg, wm, wn, lane);
+        grp, kg, wm, wn, lane);
     core.reduce_groups(lds, kg, w4, lane);
     float bv[core.TN];
 #pragma unroll
     for (int j = 0; j < core.TN; ++j) {
-        const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+        const int n = n0 + wn * core.WTN + j * 32 + (lane & 31);
         bv[j] = (bias && n < N) ? bias[n] : 0.f;
     }
     if (sizeof(TO) == 2 && N % 8 == 0) {
-        store_tile_bf16<BM, BN, KG, STAGES * STAGE>(
+        store_tile_bf16<BM, BN, 256 * KG * GN, STAGES * STAGE>(
             core, lds, bv, reinterpret_cast<bf16_t*>(y), n0, N, kg, wm, wn, lane,
             [&](int r) { return m0 + r < M ? out_row(m0 + r, g.Tp, g.y_pitch, g.y_halo) : -1LL; });
         return;
@@ -702,7 +707,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_k(const bf16_t* __restrict_
             const size_t row = (size_t)out_row(m, g.Tp, g.y_pitch, g.y_halo) * N;
 #pragma unroll
             for (int j = 0; j < core.TN; ++j) {
-                const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+                const int n = n0 + wn * core.WTN + j * 32 + (lane & 31);
                 if (n < N) Elem<TO>::store(y, row + n, core.acc[i][j][r] + bv[j]);
             }
         }
@@ -747,7 +752,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
         if (n >= N) n = N - 1;
         pb.set_fast(i, (long long)n * K);
     }
-    Core<BM, BN, 64, KG, PS, PB> core;
+    Core<BM, BN, 64, KG, 1, PS, PB> core;
     core.zero();
     run_slab_pipeline<PS::NI, PB::NI, PS::BYTES, PB::BYTES>(
         core, lds, g.Cin / 64, g.k,
@@ -757,7 +762,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
     float bv[core.TN];
 #pragma unroll
     for (int j = 0; j < core.TN; ++j) {
-        const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+        const int n = n0 + wn * core.WTN + j * 32 + (lane & 31);
         bv[j] = (bias && n < N) ? bias[n] : 0.f;
     }
     // tile row r is layout frame f0 + r: utterance b, frame t; stored only if it is a real frame
@@ -766,7 +771,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
         return (b < g.B && t >= 0 && t < g.T) ? (long long)b * g.y_pitch + g.y_halo + t : -1LL;
     };
     if (sizeof(TO) == 2 && N % 8 == 0) {
-        store_tile_bf16<BM, BN, KG, LDS_BYTES>(core, lds, bv, reinterpret_cast<bf16_t*>(y), n0, N, kg, wm, wn, lane, rowoff);
+        store_tile_bf16<BM, BN, 256 * KG, LDS_BYTES>(core, lds, bv, reinterpret_cast<bf16_t*>(y), n0, N, kg, wm, wn, lane, rowoff);
         return;
     }
     if (kg != 0) return;
@@ -778,7 +783,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
             if (ro < 0) continue;
 #pragma unroll
             for (int j = 0; j < core.TN; ++j) {
-                const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+                const int n = n0 + wn * core.WTN + j * 32 + (lane & 31);
                 if (n < N) Elem<TO>::store(y, (size_t)ro * N + n, core.acc[i][j][r] + bv[j]);
             }
         }
@@ -786,12 +791,12 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
 
 // =============================== data gradient (stride 1) =============================
 // dx[b,t,ci] = sum_{j',co} dy[b, t-p+j', co] * w[co, k-1-j', ci]
-template <int BM, int BN, int BKT, int STAGES, int KG, bool FAST>
-__global__ __launch_bounds__(256 * KG) void conv_dgrad_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
+template <int BM, int BN, int BKT, int STAGES, int KG, int GN, bool FAST>
+__global__ __launch_bounds__(256 * KG * GN) void conv_dgrad_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
                                                    bf16_t* __restrict__ dx, ConvGeom g)
 {
-    using PA = PanelK<BM, BKT, 4 * KG>;
-    using PB = PanelMN<BN, BKT, 4 * KG>;
+    using PA = PanelK<BM, BKT, 4 * KG * GN>;
+    using PB = PanelMN<BN, BKT, 4 * KG * GN>;
     extern __shared__ __align__(1024) unsigned char lds[];
     constexpr int STAGE = PA::BYTES + PB::BYTES;
     static_assert(KG == 1 || BM * BN * 4 <= STAGES * STAGE, "the group reduction reuses the panel ring");
@@ -800,7 +805,8 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_k(const bf16_t* __restric
     tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
+    const int grp = wave >> 2, w4 = wave & 3, wm = w4 >> 1;
+    const int kg = (KG == 2) ? grp : 0, wn = (GN == 2 ? 2 * grp : 0) + (w4 & 1);
 
     PA pa;
     PB pb;
@@ -823,10 +829,10 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_k(const bf16_t* __restric
             pa.hi[i] = (m < M) ? (last < g.k ? last : g.k) * g.Cout : 0;
         }
     }
-    Core<BM, BN, BKT, KG, PA, PB> core;
+    Core<BM, BN, BKT, KG, GN, PA, PB> core;
     core.zero();
     const int nsteps = K / BKT;  // Cout is a multiple of BKT: a panel stays inside one tap
-    run_ring<STAGES, KG, PA::NI + PB::NI, STAGE, PA::BYTES>(
+    run_ring<STAGES, KG * GN, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
         [&](int i, int st, unsigned dst) {
             const int stc = (FAST && st >= nsteps) ? nsteps - 1 : st;
@@ -851,12 +857,12 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_k(const bf16_t* __restric
                 },
                 dst + PA::BYTES);
         },
-        kg, wm, wn, lane);
+        grp, kg, wm, wn, lane);
     core.reduce_groups(lds, kg, w4, lane);
     float zero[core.TN];
 #pragma unroll
     for (int j = 0; j < core.TN; ++j) zero[j] = 0.f;
-    store_tile_bf16<BM, BN, KG, STAGES * STAGE>(
+    store_tile_bf16<BM, BN, 256 * KG * GN, STAGES * STAGE>(
         core, lds, zero, dx, n0, N, kg, wm, wn, lane,
         [&](int r) { return m0 + r < M ? out_row(m0 + r, g.T, g.x_pitch, g.x_halo) : -1LL; });
 }
@@ -890,7 +896,7 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
     pb.init_fast(w, g.k * g.Cin, N - n0);
 #pragma unroll
     for (int i = 0; i < PS::NI; ++i) ps.set_fast(i, (long long)(f0 - g.p + PS::row_of(i)) * g.Cout);
-    Core<BM, BN, 64, KG, PS, PB> core;
+    Core<BM, BN, 64, KG, 1, PS, PB> core;
     core.zero();
     run_slab_pipeline<PS::NI, PB::NI, PS::BYTES, PB::BYTES>(
         core, lds, g.Cout / 64, g.k,
@@ -904,7 +910,7 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
 #pragma unroll
     for (int j = 0; j < core.TN; ++j) zero[j] = 0.f;
     if (!GLUB) {
-        store_tile_bf16<BM, BN, KG, LDS_BYTES>(core, lds, zero, dx, n0, N, kg, wm, wn, lane, [&](int r) {
+        store_tile_bf16<BM, BN, 256 * KG, LDS_BYTES>(core, lds, zero, dx, n0, N, kg, wm, wn, lane, [&](int r) {
             const int f = f0 + r, b = f / g.y_pitch, t = f - b * g.y_pitch - g.y_halo;
             return (b < g.B && t >= 0 && t < g.T) ? (long long)b * g.x_pitch + g.x_halo + t : -1LL;
         });
@@ -971,12 +977,12 @@ __global__ __launch_bounds__(256) void zero_rows_k(bf16_t* __restrict__ p, long 
 // reduction runs straight through the frames of all utterances including the halo frames
 // between them -- dy is zero there, so they add nothing -- which makes every panel a dense
 // block of BKT consecutive frames of both tensors.
-template <int BM, int BN, int BKT, int STAGES, int KG, bool FAST>
-__global__ __launch_bounds__(256 * KG) void conv_wgrad_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
+template <int BM, int BN, int BKT, int STAGES, int KG, int GN, bool FAST>
+__global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
                                                    float* __restrict__ dw, ConvGeom g, int accumulate)
 {
-    using PA = PanelMN<BM, BKT, 4 * KG>;
-    using PB = PanelMN<BN, BKT, 4 * KG>;
+    using PA = PanelMN<BM, BKT, 4 * KG * GN>;
+    using PB = PanelMN<BN, BKT, 4 * KG * GN>;
     extern __shared__ __align__(1024) unsigned char lds[];
     constexpr int STAGE = PA::BYTES + PB::BYTES;
     static_assert(KG == 1 || BM * BN * 4 <= STAGES * STAGE, "the group reduction reuses the panel ring");
@@ -985,7 +991,8 @@ __global__ __launch_bounds__(256 * KG) void conv_wgrad_k(const bf16_t* __restric
     tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
+    const int grp = wave >> 2, w4 = wave & 3, wm = w4 >> 1;
+    const int kg = (KG == 2) ? grp : 0, wn = (GN == 2 ? 2 * grp : 0) + (w4 & 1);
 
     PA pa;
     PB pb;
@@ -999,9 +1006,9 @@ __global__ __launch_bounds__(256 * KG) void conv_wgrad_k(const bf16_t* __restric
     const int spb = (g.Tp + BKT - 1) / BKT;  // CHECKED: panels per utterance
     const int frames = (g.B - 1) * g.y_pitch + g.Tp;  // FAST: first real frame of utterance 0 .. last real frame
     const int nsteps = FAST ? (frames + BKT - 1) / BKT : g.B * spb;
-    Core<BM, BN, BKT, KG, PA, PB> core;
+    Core<BM, BN, BKT, KG, GN, PA, PB> core;
     core.zero();
-    run_ring<STAGES, KG, PA::NI + PB::NI, STAGE, PA::BYTES>(
+    run_ring<STAGES, KG * GN, PA::NI + PB::NI, STAGE, PA::BYTES>(
         core, lds, nsteps,
         [&](int i, int st, unsigned dst) {
             if (FAST) {
@@ -1037,7 +1044,7 @@ __global__ __launch_bounds__(256 * KG) void conv_wgrad_k(const bf16_t* __restric
                 },
                 dst + PA::BYTES);
         },
-        kg, wm, wn, lane);
+        grp, kg, wm, wn, lane);
     core.reduce_groups(lds, kg, w4, lane);
     if (kg != 0) return;
     core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
@@ -1102,13 +1109,13 @@ bool slab_ok(const ConvDesc& d, int bm, int srows, int C, int frames, int pitch,
 }
 
 // tile -> (panel depth, ring depth): 3 x 48 KB for the tiles that fit, 4 x 32 KB for 256x256
-// and how many reduction groups of wavefronts (the 256x256 accumulators leave room for one)
-#define W2L_TILE_DISPATCH(CALL)                                             \
-    if (tc.bm == 256 && tc.bn == 256) { CALL(256, 256, 32, 4, 1); }         \
-    else if (tc.bm == 192 && tc.bn == 192) { CALL(192, 192, 64, 3, 2); }    \
-    else if (tc.bm == 256 && tc.bn == 128) { CALL(256, 128, 64, 3, 2); }    \
-    else if (tc.bm == 128 && tc.bn == 256) { CALL(128, 256, 64, 3, 2); }    \
-    else { CALL(128, 128, 64, 3, 2); }
+// and the groups of wavefronts: two reduction groups, or for 256x256 two column groups
+#define W2L_TILE_DISPATCH(CALL)                                                \
+    if (tc.bm == 256 && tc.bn == 256) { CALL(256, 256, 32, 4, 1, 2); }         \
+    else if (tc.bm == 192 && tc.bn == 192) { CALL(192, 192, 64, 3, 2, 1); }    \
+    else if (tc.bm == 256 && tc.bn == 128) { CALL(256, 128, 64, 3, 2, 1); }    \
+    else if (tc.bm == 128 && tc.bn == 256) { CALL(128, 256, 64, 3, 2, 1); }    \
+    else { CALL(128, 128, 64, 3, 2, 1); }
 
 }  // namespace
 
@@ -1145,17 +1152,17 @@ int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* 
         rc = set_lds(KERN, BYTES);                                                        \
         if (!rc) hipLaunchKernelGGL(KERN, dim3(grid), dim3(nthreads), BYTES, st, __VA_ARGS__);  \
     }
-#define CALL(BM_, BN_, BK_, ST_, KG_)                                                                         \
+#define CALL(BM_, BN_, BK_, ST_, KG_, GN_)                                                                         \
     {                                                                                                         \
         constexpr int bytes = ST_ * (BM_ + BN_) * BK_ * 2;                                                    \
-        const unsigned nthreads = 256 * KG_;                                                                  \
+        const unsigned nthreads = 256 * KG_ * GN_;                                                                  \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                      \
         if (ydt == W2L_BF16) {                                                                                \
-            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, true, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g) \
-            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, false, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g)     \
+            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, GN_, true, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g) \
+            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, GN_, false, bf16_t>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g)     \
         } else {                                                                                              \
-            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, true, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)   \
-            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, false, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)       \
+            if (fast) LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, GN_, true, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)   \
+            else LAUNCH((conv_fwd_k<BM_, BN_, BK_, ST_, KG_, GN_, false, float>), bytes, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g)       \
         }                                                                                                     \
     }
     W2L_TILE_DISPATCH(CALL)
@@ -1183,13 +1190,13 @@ int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, 
         if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<256, 128, 320, 2, false>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, g);
         return rc ? rc : launch_status();
     }
-#define CALL(BM_, BN_, BK_, ST_, KG_)                                                                     \
+#define CALL(BM_, BN_, BK_, ST_, KG_, GN_)                                                                     \
     {                                                                                                     \
         constexpr int bytes = ST_ * (BM_ + BN_) * BK_ * 2;                                                \
-        const unsigned nthreads = 256 * KG_;                                                              \
+        const unsigned nthreads = 256 * KG_ * GN_;                                                              \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                  \
-        if (fast) LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, KG_, true>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g) \
-        else LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, KG_, false>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g)     \
+        if (fast) LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, true>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g) \
+        else LAUNCH((conv_dgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, false>), bytes, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, g)     \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
@@ -1235,13 +1242,13 @@ int conv_wgrad_mfma(const ConvDesc& g, const void* x, const void* dy, float* dw,
     const bool fast = g.s == 1 && g.x_pitch == g.y_pitch && g.x_halo == g.y_halo && g.x_halo >= g.p && g.slack >= 64 &&
                       (g.B == 1 || g.x_halo > 0 || g.p == 0);
     int rc = W2L_OK;
-#define CALL(BM_, BN_, BK_, ST_, KG_)                                                                     \
+#define CALL(BM_, BN_, BK_, ST_, KG_, GN_)                                                                     \
     {                                                                                                     \
         constexpr int bytes = ST_ * (BM_ + BN_) * BK_ * 2;                                                \
-        const unsigned nthreads = 256 * KG_;                                                              \
+        const unsigned nthreads = 256 * KG_ * GN_;                                                              \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                  \
-        if (fast) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, true>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate) \
-        else LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate)     \
+        if (fast) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, true>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate) \
+        else LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate)     \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
