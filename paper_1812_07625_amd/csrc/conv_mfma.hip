@@ -536,7 +536,11 @@ __device__ __forceinline__ void run_slab_pipeline(CoreT& core, unsigned char* ld
         if (pslot < 0) pslot += 3;
         const unsigned dst = ring0 + pslot * STAGE_BYTES;
         const unsigned sdst = lds0 + ((cb + 1) & 1) * SLAB_BYTES;
-        // ---- R(st): the slab of the next channel block (first tap only), weight panel st+2, fragments
+        // ---- R(st): fragments first (the loads queue up behind each other in the memory pipeline
+        // and would hold the reads back), then the slab of the next channel block (first tap only)
+        // and weight panel st+2
+        core.read_panel(lds + (cb & 1) * SLAB_BYTES, ring + slot * STAGE_BYTES, kg, wm, wn, lane, j);
+        __builtin_amdgcn_sched_barrier(0);
         if (has_slab) {
 #pragma unroll
             for (int i = 0; i < NLS; ++i) issue_slab(i, cb + 1, sdst);
@@ -544,7 +548,6 @@ __device__ __forceinline__ void run_slab_pipeline(CoreT& core, unsigned char* ld
 #pragma unroll
         for (int i = 0; i < NLB; ++i) issue_b(i, pcb, pj, dst);
         advance();
-        core.read_panel(lds + (cb & 1) * SLAB_BYTES, ring + slot * STAGE_BYTES, kg, wm, wn, lane, j);
         // issued after weight panel st+1 (which must have landed): this phase's loads only
         if (has_slab) wait_vmcnt<NLS + NLB>();
         else wait_vmcnt<NLB>();
