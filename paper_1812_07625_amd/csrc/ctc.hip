@@ -37,16 +37,19 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 constexpr float NEG = -1.0e30f;      // log zero: absorbs every finite addend, never turns into NaN
 constexpr float NEG_TEST = -1.0e29f;  // anything below is "log zero"
 
-// log2( 2^a + 2^b [+ 2^c] ); operands may be NEG
+// log2( 2^a + 2^b [+ 2^c] ); operands may be NEG.  The largest term contributes exactly 1, so
+// only the others cost an exp2.
 __device__ __forceinline__ float lse3_log2(float a, float b, float c)
 {
-    const float m = fmaxf(a, fmaxf(b, c));
-    return m + fast_log2(fast_exp2(a - m) + fast_exp2(b - m) + fast_exp2(c - m));
+    const float m = __builtin_fmaxf(__builtin_fmaxf(a, b), c);
+    const float lo = __builtin_fminf(__builtin_fminf(a, b), c);
+    const float md = __builtin_amdgcn_fmed3f(a, b, c);
+    return m + fast_log2(1.f + fast_exp2(md - m) + fast_exp2(lo - m));
 }
 __device__ __forceinline__ float lse2_log2(float a, float b)
 {
     const float m = fmaxf(a, b);
-    return m + fast_log2(fast_exp2(a - m) + fast_exp2(b - m));
+    return m + fast_log2(1.f + fast_exp2(fminf(a, b) - m));
 }
 __device__ __forceinline__ float wave_max_f(float v)
 {
@@ -54,21 +57,35 @@ __device__ __forceinline__ float wave_max_f(float v)
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
     return v;
 }
+// value of the lane to the left (lane - 1); lane 0 gets `edge`
+__device__ __forceinline__ float from_left_lane(float v, float edge)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(edge), __float_as_int(v), 0x138 /* wave_shr:1 */,
+                                                      0xf, 0xf, false));
+}
 
 constexpr int SCORE_AHEAD = 16;  // frames of scores held in registers ahead of the recursion;
-                                 // also the renormalisation period
+                                 // also the period of the hand-over between wavefronts and of the renormalisation
+constexpr int HALO_LANES = SCORE_AHEAD;     // lanes of a wavefront that mirror the wavefront on its left
+constexpr int OWN_LANES = 64 - HALO_LANES;  // lanes whose states a wavefront owns (and stores)
 
 // One workgroup per (utterance, direction).  The extended sequence is cut into pairs
-// (blank 2i, label 2i+1); a thread owns PPT consecutive pairs and keeps their alpha values in
-// registers, so per frame it needs exactly one value from outside: the label state of the
-// pair to its left, which comes from the neighbouring lane (or, across a wavefront boundary,
-// through a two-slot LDS mailbox and the one barrier of the step).  The scores lp[t, blank]
-// and lp[t, label] are fetched SCORE_AHEAD frames early into a register ring, off the
-// dependency chain.  beta is the same recursion on the reversed sequence and reversed time
-// (state index q counts from the end), stored in its own q order.  The step body is
-// straight-line code with a fixed number of memory operations (threads past the end of the
-// target write to a spare pair, steps past the last frame to a spare row), so the score
-// prefetches and lattice stores stay in flight across steps.
+// (blank 2i, label 2i+1); a lane holds PPT consecutive pairs in registers, so per frame it needs
+// exactly one value from outside: the label state of the pair to its left, which a DPP
+// whole-wavefront shift delivers from the neighbouring lane.  No value crosses a wavefront
+// boundary inside a block of SCORE_AHEAD frames: the first HALO_LANES lanes of every wavefront
+// recompute the pairs owned by the last lanes of the wavefront on its left.  Their leftmost input
+// is missing, so they go stale from the left at one pair per frame -- after SCORE_AHEAD frames
+// the staleness has not yet reached the lanes the wavefront owns -- and once per block they are
+// refreshed through LDS, at the one barrier of the block, where the states are also
+// renormalised.  The dependency chain of a frame is therefore one lane shift and one
+// log-sum-exp.  States to the right of the target's last pair are computed too (nothing reads
+// them; a state depends only on states to its left); states left of pair 0 stay at log zero.
+// The scores lp[t, blank] and lp[t, label] are fetched SCORE_AHEAD frames early into a register
+// ring.  beta is the same recursion on the reversed sequence and reversed time (state index q
+// counts from the end), stored in its own q order.  The step body is straight-line code with a
+// fixed number of memory operations (lanes that own no real pair write to a spare pair, steps
+// past the last frame to a spare row).
 // Stored per frame: the relative states (fp32) and the offset that applies to them (fp64).
 template <int PPT>
 __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp, const int* __restrict__ targets,
@@ -77,9 +94,8 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                                                     float* __restrict__ alpha, float* __restrict__ beta,
                                                     double* __restrict__ aoff, double* __restrict__ boff, CtcDims d)
 {
-    __shared__ float mailbox[2][16];
-    __shared__ float wmax[16];
-    __shared__ float fin[2];
+    __shared__ float xbuf[2][16][HALO_LANES][2 * PPT];  // [block parity][wavefront][lane - OWN_LANES][state]
+    __shared__ float wmax[2][16];
     __shared__ int bad_len, bad;
     const int dir = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
@@ -87,8 +103,6 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     if (tid == 0) {
         bad_len = (T < 0 || T > d.Tp || L < 0 || L > d.Lmax) ? 1 : 0;
         bad = 0;
-        fin[0] = NEG;
-        fin[1] = NEG;
     }
     __syncthreads();
     if (bad_len) {
@@ -113,20 +127,26 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         return;
     }
     // pair i (in this direction's order) = states q = 2i (blank), 2i+1 (label i, absent for i = L)
-    int cls[PPT];      // class of the label state
-    bool has_l[PPT];   // label state exists
-    bool skip[PPT];    // label state may be entered from the label of the pair to the left
-    bool live[PPT];    // pair exists
-    int slot[PPT];     // lattice position of the pair (the spare pair for threads past the end)
+    const int gi = wave * OWN_LANES + lane - HALO_LANES;  // this lane's group of PPT pairs; < 0: left of the sequence
+    const bool owner = lane >= HALO_LANES;               // not a mirror of the wavefront on the left
+    int cls[PPT];     // class of the label state
+    bool skip[PPT];   // label state may be entered from the label of the pair to the left
+    int slot[PPT];    // lattice position of the pair (the spare pair for lanes that own no real pair)
+    bool cnt_b[PPT], cnt_l[PPT];  // states that count towards the renormalisation maximum: real and owned
+    float ab[PPT], al[PPT];
 #pragma unroll
     for (int j = 0; j < PPT; ++j) {
-        const int i = tid * PPT + j;
-        live[j] = i <= L;
-        has_l[j] = i < L;
+        const int i = gi * PPT + j;
+        const bool real = gi >= 0 && i <= L, has_l = gi >= 0 && i < L;
         const int li = dir ? L - 1 - i : i;          // label index in the target
-        cls[j] = has_l[j] ? lab[li] : d.blank;
-        skip[j] = has_l[j] && i >= 1 && lab[dir ? li + 1 : li - 1] != cls[j];
-        slot[j] = 2 * (live[j] ? i : d.Lmax + 1);
+        cls[j] = has_l ? lab[li] : d.blank;
+        skip[j] = has_l && i >= 1 && lab[dir ? li + 1 : li - 1] != cls[j];
+        slot[j] = 2 * ((real && owner) ? i : d.Lmax + 1);
+        cnt_b[j] = real && owner;
+        cnt_l[j] = has_l && owner;
+        // the state "before frame 0": all mass in front of pair 0, so that frame 0 comes out of the recursion itself
+        ab[j] = (gi >= 0 && i == 0) ? 0.f : NEG;
+        al[j] = NEG;
     }
     const float* lpb = lp + (size_t)b * d.Tp * d.C;
     float* lat = (dir ? beta : alpha) + (size_t)b * (d.Tp + 1) * d.Sp;
@@ -142,12 +162,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
         for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
     }
-    float ab[PPT], al[PPT], fin_b[PPT], fin_l[PPT];
-#pragma unroll
-    for (int j = 0; j < PPT; ++j) { ab[j] = NEG; al[j] = NEG; fin_b[j] = NEG; fin_l[j] = NEG; }
-    float left = NEG;   // label state of the pair to the left of this thread's first pair, previous frame
     double offset = 0;  // true log2 value = relative value + offset
-    double fin_off = 0;
     const int nwaves = NT >> 6;
     const int tblocks = (T + SCORE_AHEAD - 1) / SCORE_AHEAD;
 
@@ -155,10 +170,10 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
         for (int k = 0; k < SCORE_AHEAD; ++k) {
             const int step = tb * SCORE_AHEAD + k;
-            const float s_b = sb[k] * log2e;
+            const float s_b = sb[k];
             float s_l[PPT];
 #pragma unroll
-            for (int j = 0; j < PPT; ++j) s_l[j] = sl[j][k] * log2e;
+            for (int j = 0; j < PPT; ++j) s_l[j] = sl[j][k];
             {   // refill this ring slot for step + SCORE_AHEAD
                 const int nf = step + SCORE_AHEAD;
                 const int f = frame(nf < T ? nf : T - 1);
@@ -167,50 +182,48 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                 for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
             }
             const int row = step < T ? frame(step) : d.Tp;
-            float carry = left;  // label value (previous frame) of the pair to the left of pair j
+            // label value (previous frame) of the pair to the left of this lane's first pair
+            float carry = from_left_lane(al[PPT - 1], NEG);
 #pragma unroll
             for (int j = 0; j < PPT; ++j) {
                 const float ob = ab[j], ol = al[j];
-                const bool first = (tid * PPT + j) == 0;
-                float nb = lse2_log2(ob, carry) + s_b;
-                float nl = lse3_log2(ol, ob, skip[j] ? carry : NEG) + s_l[j];
-                nb = (step == 0) ? (first ? s_b : NEG) : nb;
-                nl = (step == 0) ? (first ? s_l[j] : NEG) : nl;
-                nb = live[j] ? nb : NEG;
-                nl = has_l[j] ? nl : NEG;
+                const float nb = fmaf(s_b, log2e, lse2_log2(ob, carry));
+                const float nl = fmaf(s_l[j], log2e, lse3_log2(ol, ob, skip[j] ? carry : NEG));
                 carry = ol;
                 ab[j] = nb;
                 al[j] = nl;
-                fin_b[j] = (step == T - 1) ? nb : fin_b[j];
-                fin_l[j] = (step == T - 1) ? nl : fin_l[j];
                 *reinterpret_cast<float2*>(lat + (size_t)row * d.Sp + slot[j]) = make_float2(nb, nl);
             }
-            if (tid == 0) offs[row] = offset;
-            fin_off = (step == T - 1) ? offset : fin_off;
-            // hand this thread's last label value to the thread on its right
-            const float send = al[PPT - 1];
-            float recv = __shfl_up(send, 1, 64);
-            if (nwaves > 1) {
-                if (lane == 63) mailbox[step & 1][wave] = send;
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                asm volatile("" ::: "memory");
-                const float mb = mailbox[step & 1][wave > 0 ? wave - 1 : 0];
-                recv = (lane == 0) ? mb : recv;
-            }
-            left = (tid == 0) ? NEG : recv;
         }
-        // renormalise: move the workgroup's largest state into the offset
+        if (tid < SCORE_AHEAD) {  // the offset of the block's frames (it changes only at block boundaries)
+            const int step = tb * SCORE_AHEAD + tid;
+            offs[step < T ? frame(step) : d.Tp] = offset;
+        }
+        // ---- block boundary: refresh the mirror lanes from the left neighbour, renormalise
+        const int par = tb & 1;
         float m = NEG;
 #pragma unroll
-        for (int j = 0; j < PPT; ++j) m = fmaxf(m, fmaxf(ab[j], al[j]));
+        for (int j = 0; j < PPT; ++j) m = fmaxf(m, fmaxf(cnt_b[j] ? ab[j] : NEG, cnt_l[j] ? al[j] : NEG));
         m = wave_max_f(m);
         if (nwaves > 1) {
-            if (lane == 0) wmax[wave] = m;
+            if (lane == 0) wmax[par][wave] = m;
+            if (lane >= OWN_LANES) {
+#pragma unroll
+                for (int j = 0; j < PPT; ++j) {
+                    xbuf[par][wave][lane - OWN_LANES][2 * j] = ab[j];
+                    xbuf[par][wave][lane - OWN_LANES][2 * j + 1] = al[j];
+                }
+            }
             __syncthreads();
-            m = wmax[0];
-            for (int w2 = 1; w2 < nwaves; ++w2) m = fmaxf(m, wmax[w2]);
-            __syncthreads();
+            if (wave > 0 && !owner) {
+#pragma unroll
+                for (int j = 0; j < PPT; ++j) {
+                    ab[j] = xbuf[par][wave - 1][lane][2 * j];
+                    al[j] = xbuf[par][wave - 1][lane][2 * j + 1];
+                }
+            }
+            m = wmax[par][0];
+            for (int w2 = 1; w2 < nwaves; ++w2) m = fmaxf(m, wmax[par][w2]);
         }
         if (m > NEG_TEST) {  // uniform over the workgroup
 #pragma unroll
@@ -218,21 +231,19 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                 ab[j] = ab[j] > NEG_TEST ? ab[j] - m : NEG;
                 al[j] = al[j] > NEG_TEST ? al[j] - m : NEG;
             }
-            left = left > NEG_TEST ? left - m : NEG;
             offset += (double)m;
         }
     }
-    // log P = lse( alpha_{T-1}(S-1), alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1
+    // log P = lse( alpha_{T-1}(S-1), alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1, read back
+    // from the stored lattice row of the last frame (written by this workgroup)
     if (dir == 0) {
-#pragma unroll
-        for (int j = 0; j < PPT; ++j) {
-            const int i = tid * PPT + j;
-            if (i == L) fin[0] = fin_b[j];
-            if (i == L - 1) fin[1] = fin_l[j];
-        }
         __syncthreads();
         if (tid == 0) {
-            const float rel = lse2_log2(fin[0], fin[1]);
+            const float* last = lat + (size_t)(T - 1) * d.Sp;
+            const float fb = __builtin_nontemporal_load(last + 2 * L);
+            const float fl = L > 0 ? __builtin_nontemporal_load(last + 2 * L - 1) : NEG;
+            const double fin_off = __builtin_nontemporal_load(offs + (T - 1));
+            const float rel = lse2_log2(fb, fl);
             const bool none = rel < NEG_TEST;
             const double lp2 = none ? -INFINITY : (double)rel + fin_off;
             logp2_out[b] = lp2;
@@ -420,11 +431,11 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
         hipError_t e = hipFuncSetAttribute((const void*)ctc_grad, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
         if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }
     }
-    // one thread per (blank,label) pair of the extended target; more pairs per thread only
-    // when a workgroup of 1024 cannot cover Lmax+1 pairs
+    // one lane per (blank,label) pair of the extended target, OWN_LANES of them per wavefront;
+    // more pairs per lane only when 16 wavefronts cannot cover Lmax+1 pairs
     const int pairs = Lmax + 1;
-    const int ppt = pairs <= 1024 ? 1 : (pairs <= 2048 ? 2 : 4);
-    int nt = ((pairs + ppt - 1) / ppt + 63) / 64 * 64;
+    const int ppt = pairs <= 16 * OWN_LANES ? 1 : (pairs <= 32 * OWN_LANES ? 2 : 4);
+    const int nt = 64 * (((pairs + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);  // OWN_LANES pair groups per wavefront
     if (nt > 1024) return W2L_ERR_SHAPE;
     const dim3 g1(2, B), b1(nt);
     if (ppt == 1) hipLaunchKernelGGL(ctc_lattice<1>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, aoff, boff, d);
