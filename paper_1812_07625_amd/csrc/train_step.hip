@@ -56,7 +56,7 @@ struct Plan {
     int n = 0, C = 0, Tlast = 0, tot_stride = 1;
     std::vector<int> Tin, Tout, outch;
     std::vector<size_t> pre, post;  // workspace offsets of conv output (dense) and GLU output (haloed) per layer
-    size_t dlogits = 0, crit_len = 0, gdy[3] = {0, 0, 0}, gdh = 0, ctc = 0, conv = 0, total = 0;
+    size_t dlogits = 0, crit_len = 0, gdy[3] = {0, 0, 0}, gdh = 0, ctc = 0, conv = 0, dbias = 0, total = 0;
     size_t ctc_bytes = 0, conv_bytes = 0;
     int status = W2L_OK;
 };
@@ -110,6 +110,9 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
     p.ctc_bytes = w2l_ctc_workspace_bytes(B, p.Tlast, p.C, Lmax);
     p.ctc = off; off += round_up(p.ctc_bytes, 256);
     p.conv = off; off += round_up(p.conv_bytes, 256);
+    int cmax = 0;
+    for (int i = 0; i < n; ++i) cmax = L[i].cout > cmax ? L[i].cout : cmax;
+    p.dbias = off; off += round_up((size_t)DBIAS_CHUNKS * cmax * 4, 256);
     p.total = off;
     return p;
 }
@@ -238,9 +241,17 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
                 return W2L_ERR_LAUNCH;
         }
         const void* xin = (i == 0) ? x : (const void*)(ws + p.post[i - 1]);
-        rc = conv_wgrad(d, xin, dy, dweights[i], dbiases[i], dtype, dy_dt, 0, ws + p.conv, wst);
+        // weight gradient on the side stream; the (small, bandwidth-bound) bias gradient stays on
+        // the main stream, which has the shorter chain
+        rc = conv_wgrad(d, xin, dy, dweights[i], side ? nullptr : dbiases[i], dtype, dy_dt, 0, ws + p.conv, wst);
         if (rc) return rc;
         if (side && !hip_ok(hipEventRecord(side->done[i], wst))) return W2L_ERR_LAUNCH;
+        if (side && dbiases[i]) {
+            // halo frames hold zeros, so summing every frame of the allocation is the same sum
+            rc = dbias_reduce(dy, dbiases[i], (long long)d.B * d.y_pitch, d.Cout, dy_dt, 0,
+                              reinterpret_cast<float*>(ws + p.dbias), st);
+            if (rc) return rc;
+        }
         if (i > 0) {
             if (layers[i - 1].glu && dtype == W2L_BF16 && dy_dt == W2L_BF16 && conv_dgrad_glu_ok(d)) {
                 if (!wait_wgrad(i + 2)) return W2L_ERR_LAUNCH;  // last reader of the slot dy_{i-1} goes into
