@@ -28,9 +28,11 @@ PEAK_HBM = 8.0e12         # B/s
 DOMINANT_KERNEL_HBM_BYTES = {"conv1d_bwd_data": 341265323, "conv1d_fwd": 249.5e6, "conv1d_bwd_weight": 204.6e6}
 
 
-def event_time_ms(fn, iters, warmup=2):
+def event_time_ms(fn, iters, warmup=None):
     """Average milliseconds per call, HIP events on torch's current stream (the launch stream)."""
     import torch
+    if warmup is None:
+        warmup = max(2, iters // 10)  # short bursts run at a different clock than sustained work
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -49,7 +51,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kernel-iters", type=int, default=20)
+    ap.add_argument("--kernel-iters", type=int, default=200)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "

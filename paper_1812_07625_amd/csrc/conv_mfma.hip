@@ -39,11 +39,6 @@
 // window is then plain in-bounds memory, the per-lane byte offsets are loop invariants, the
 // panel advance is a scalar add on the base pointer, and a load costs three instructions.
 #include "common.h"
-#include <cstdlib>
-#include <cstdio>
-#ifndef W2L_SPREAD_EXPR
-#define W2L_SPREAD_EXPR (CoreT::GROUPS / NL)
-#endif
 
 namespace w2l {
 namespace {
@@ -378,7 +373,7 @@ __device__ __forceinline__ void run_pipeline(CoreT& core, unsigned char* lds, in
     static_assert((STAGES - 2) * NL < 64, "loads in flight must fit the vmcnt counter");
     // one load after every SPREAD-th MFMA: a burst of loads would fill the memory pipeline's
     // queue and stall the wavefront (and the MFMAs behind the load in program order) at issue
-    constexpr int SPREAD = W2L_SPREAD_EXPR;
+    constexpr int SPREAD = CoreT::GROUPS / NL;
     static_assert((NL - 1) * SPREAD < CoreT::GROUPS, "the prefetch loads must all be issued within the panel");
     // loads of the newest panel issued before the hand-over point
     constexpr int E = (CoreT::EARLY + SPREAD - 1) / SPREAD < NL ? (CoreT::EARLY + SPREAD - 1) / SPREAD : NL;
@@ -1071,7 +1066,6 @@ int set_lds(K kern, int bytes)
 struct TileChoice { int bm, bn; };
 TileChoice choose_tile(long long M, long long N)
 {
-    if (const char* e = getenv("W2L_TILE")) { TileChoice t; if (sscanf(e, "%d,%d", &t.bm, &t.bn) == 2) return t; }  // DEV ONLY
     const TileChoice cand[] = {{256, 256}, {192, 192}, {256, 128}, {128, 256}, {128, 128}};
     double best = -1;
     TileChoice pick = cand[0];
@@ -1136,8 +1130,7 @@ int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* 
     const TileChoice tc = choose_tile(M, N);
     const bool fast = halo_ok_x(g) && ((long long)g.k * g.Cin) % 64 == 0;
     int rc = W2L_OK;
-    static const bool noslab = getenv("W2L_NOSLAB") != nullptr;
-    if (!noslab && fast && tc.bm == 192 && tc.bn == 192 && slab_ok(g, 192, 256, g.Cin, g.T, g.x_pitch, g.x_halo)) {
+    if (fast && tc.bm == 192 && tc.bn == 192 && slab_ok(g, 192, 256, g.Cin, g.T, g.x_pitch, g.x_halo)) {
         constexpr int bytes = slab_lds_bytes(192, 192, 256, 2);
         const long long F = (long long)(g.B - 1) * g.x_pitch + g.T;
         const unsigned grid = (unsigned)(((F + 191) / 192) * ((N + 191) / 192));
@@ -1184,8 +1177,7 @@ int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, 
     const TileChoice tc = choose_tile(M, N);
     const bool fast = halo_ok_y(g);
     int rc = W2L_OK;
-    static const bool noslab = getenv("W2L_NOSLAB") != nullptr;
-    if (!noslab && fast && tc.bm == 256 && tc.bn == 128 && slab_ok(g, 256, 320, g.Cout, g.Tp, g.y_pitch, g.y_halo)) {
+    if (fast && tc.bm == 256 && tc.bn == 128 && slab_ok(g, 256, 320, g.Cout, g.Tp, g.y_pitch, g.y_halo)) {
         constexpr int bytes = slab_lds_bytes(256, 128, 320, 2);
         const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
         const unsigned grid = (unsigned)(((F + 255) / 256) * ((N + 127) / 128));
