@@ -100,6 +100,10 @@ bool conv_fwd_mfma_ok(const ConvDesc& d);
 int conv_fwd_mfma(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int ydt, hipStream_t st);
 bool conv_dgrad_mfma_ok(const ConvDesc& d);
 int conv_dgrad_mfma(const ConvDesc& d, const void* dy, const void* w, void* dx, hipStream_t st);
+// forward pass fused with the layer's GLU: writes y (dense, pre-GLU, bf16) and h = GLU(y) into a
+// haloed tensor with the time layout of x (halo frames and the zeroed slack written as zeros)
+bool conv_fwd_glu_ok(const ConvDesc& d);
+int conv_fwd_glu(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, void* h, hipStream_t st);
 // data gradient of a layer fused with the GLU backward of the layer below it: instead of dx (=
 // dh of the layer below) it writes dy of the layer below, dy = GLU'(yprev) * dh, into a haloed
 // tensor with the same time layout as this layer's dy (halo frames are written as zeros).

@@ -721,22 +721,30 @@ constexpr int slab_lds_bytes(int bm, int bn, int srows, int kg)
 // Forward pass, stride 1, input kept with a zero halo (see FAST above), Cin % 64 == 0: tiles
 // run over the frames of the input *layout* (halo frames included; their outputs are dropped),
 // so that the frames a tile reads are one contiguous block -- the activation slab.
-template <int BM, int BN, int SROWS, int KG, typename TO>
+// GLUF: the layer's GLU is applied in the epilogue.  The tile then takes its first BN/2 columns
+// from the value half of the output channels and the other BN/2 from the matching gate channels
+// (column c of the tile <-> channel chan(c)), so that both operands of every GLU output sit in
+// the same staged tile; besides y it writes h = a * sigmoid(g) ([frames][Cout/2], the time layout
+// of x, zeros in halo frames and in the zeroed part of the slack).
+template <int BM, int BN, int SROWS, int KG, typename TO, bool GLUF>
 __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
                                                             const float* __restrict__ bias, TO* __restrict__ y,
-                                                            ConvGeom g)
+                                                            bf16_t* __restrict__ h, ConvGeom g)
 {
     using PS = PanelK<SROWS, 64, 4 * KG>;
     using PB = PanelK<BN, 64, 4 * KG>;
     extern __shared__ __align__(1024) unsigned char lds[];
     constexpr int LDS_BYTES = slab_lds_bytes(BM, BN, SROWS, KG);
     const int F = (g.B - 1) * g.x_pitch + g.T;  // frames from the first real one to the last real one
-    const int N = g.Cout, K = g.k * g.Cin;
+    const int N = g.Cout, K = g.k * g.Cin, H = g.Cout / 2;
+    const int tiles_m = (F + BM - 1) / BM;
     int tm, tn;
-    tile_of_block((F + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
+    tile_of_block(tiles_m, (N + BN - 1) / BN, tm, tn);
     const int f0 = g.x_halo + tm * BM, n0 = tn * BN;  // layout frame of tile row 0
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
+    // output channel of tile column c (GLUF requires H % (BN/2) == 0, so no tile is ragged)
+    auto chan = [&](int c) { return GLUF ? (c < BN / 2 ? tn * (BN / 2) + c : H + tn * (BN / 2) + c - BN / 2) : n0 + c; };
 
     PS ps;
     PB pb;
@@ -746,7 +754,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
     for (int i = 0; i < PS::NI; ++i) ps.set_fast(i, (long long)(f0 - g.p + PS::row_of(i)) * g.Cin);
 #pragma unroll
     for (int i = 0; i < PB::NI; ++i) {
-        int n = n0 + PB::row_of(i);
+        int n = chan(PB::row_of(i));
         if (n >= N) n = N - 1;
         pb.set_fast(i, (long long)n * K);
     }
@@ -760,7 +768,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
     float bv[core.TN];
 #pragma unroll
     for (int j = 0; j < core.TN; ++j) {
-        const int n = n0 + wn * core.WTN + j * 32 + (lane & 31);
+        const int n = chan(wn * core.WTN + j * 32 + (lane & 31));
         bv[j] = (bias && n < N) ? bias[n] : 0.f;
     }
     // tile row r is layout frame f0 + r: utterance b, frame t; stored only if it is a real frame
@@ -768,6 +776,55 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
         const int f = f0 + r, b = f / g.x_pitch, t = f - b * g.x_pitch - g.x_halo;
         return (b < g.B && t >= 0 && t < g.T) ? (long long)b * g.y_pitch + g.y_halo + t : -1LL;
     };
+    if constexpr (GLUF) {
+        static_assert(sizeof(TO) == 2, "the fused GLU writes bf16");
+        constexpr int PITCH = core.OPITCH, CPH = BN / 16, NTHR = 256 * KG;  // CPH: 16-byte chunks per half row
+        static_assert(BM * PITCH <= LDS_BYTES, "output tile staging");
+        bf16_t* yo = reinterpret_cast<bf16_t*>(y);
+        __syncthreads();
+        if (kg == 0) core.stage_bf16(lds, bv, 0, wm, wn, lane);
+        __syncthreads();
+        const long long zero_end = (long long)g.B * g.x_pitch + LAYOUT_SLACK_ZERO;  // h is zero up to here outside real frames
+        const int ch0 = tn * (BN / 2);
+#pragma unroll 2
+        for (int c = threadIdx.x; c < BM * CPH; c += NTHR) {
+            const int row = c / CPH, cc = c - row * CPH;
+            const int f = f0 + row;
+            const long long ro = rowoff(row);
+            uint4 oh = make_uint4(0, 0, 0, 0);
+            if (ro >= 0) {
+                const uint4 ua = *reinterpret_cast<const uint4*>(lds + row * PITCH + cc * 16);
+                const uint4 ug = *reinterpret_cast<const uint4*>(lds + row * PITCH + (BN / 2) * 2 + cc * 16);
+                *reinterpret_cast<uint4*>(yo + (size_t)ro * N + ch0 + cc * 8) = ua;
+                *reinterpret_cast<uint4*>(yo + (size_t)ro * N + H + ch0 + cc * 8) = ug;
+                const unsigned* pa = &ua.x; const unsigned* pg = &ug.x;
+                unsigned* qh = &oh.x;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    unsigned r2 = 0;
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        const float a = bf16_to_f32((bf16_t)(pa[q] >> (16 * hh)));
+                        const float gg = bf16_to_f32((bf16_t)(pg[q] >> (16 * hh)));
+                        r2 |= (unsigned)f32_to_bf16(a * sigmoidf_(gg)) << (16 * hh);
+                    }
+                    qh[q] = r2;
+                }
+            }
+            if (f < zero_end || ro >= 0) *reinterpret_cast<uint4*>(h + (size_t)f * H + ch0 + cc * 8) = oh;
+        }
+        // frames no tile covers: the leading halo (first row of tiles) and from the end of the last
+        // tile to the end of the zeroed slack (last row of tiles)
+        const long long t_end = (long long)g.x_halo + (long long)tiles_m * BM;
+        const long long lead = (tm == 0) ? g.x_halo : 0, trail = (tm == tiles_m - 1 && t_end < zero_end) ? zero_end - t_end : 0;
+        for (long long c = threadIdx.x; c < (lead + trail) * CPH; c += NTHR) {
+            const long long r = c / CPH;
+            const int cc = (int)(c - r * CPH);
+            const long long f = r < lead ? r : t_end + (r - lead);
+            *reinterpret_cast<uint4*>(h + (size_t)f * H + ch0 + cc * 8) = make_uint4(0, 0, 0, 0);
+        }
+        return;
+    }
     if (sizeof(TO) == 2 && N % 8 == 0) {
         store_tile_bf16<BM, BN, 256 * KG, LDS_BYTES>(core, lds, bv, reinterpret_cast<bf16_t*>(y), n0, N, kg, wm, wn, lane, rowoff);
         return;
@@ -1135,11 +1192,11 @@ int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* 
         const long long F = (long long)(g.B - 1) * g.x_pitch + g.T;
         const unsigned grid = (unsigned)(((F + 191) / 192) * ((N + 191) / 192));
         if (ydt == W2L_BF16) {
-            rc = set_lds(conv_fwd_slab_k<192, 192, 256, 2, bf16_t>, bytes);
-            if (!rc) hipLaunchKernelGGL((conv_fwd_slab_k<192, 192, 256, 2, bf16_t>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, g);
+            rc = set_lds(conv_fwd_slab_k<192, 192, 256, 2, bf16_t, false>, bytes);
+            if (!rc) hipLaunchKernelGGL((conv_fwd_slab_k<192, 192, 256, 2, bf16_t, false>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, (bf16_t*)nullptr, g);
         } else {
-            rc = set_lds(conv_fwd_slab_k<192, 192, 256, 2, float>, bytes);
-            if (!rc) hipLaunchKernelGGL((conv_fwd_slab_k<192, 192, 256, 2, float>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, g);
+            rc = set_lds(conv_fwd_slab_k<192, 192, 256, 2, float, false>, bytes);
+            if (!rc) hipLaunchKernelGGL((conv_fwd_slab_k<192, 192, 256, 2, float, false>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, (float*)y, (bf16_t*)nullptr, g);
         }
         return rc ? rc : launch_status();
     }
@@ -1163,6 +1220,26 @@ int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* 
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
+    return rc ? rc : launch_status();
+}
+
+bool conv_fwd_glu_ok(const ConvDesc& d)
+{
+    // the 192x192 slab kernel with the two GLU halves interleaved per tile; h in the time layout of x
+    const long long M = (long long)d.B * d.Tp;
+    const TileChoice tc = choose_tile(M, d.Cout);
+    return conv_fwd_mfma_ok(d) && halo_ok_x(d) && tc.bm == 192 && tc.bn == 192 && d.Cout % 2 == 0 && (d.Cout / 2) % 96 == 0 &&
+           d.T == d.Tp && d.slack >= LAYOUT_SLACK_ZERO && slab_ok(d, 192, 256, d.Cin, d.T, d.x_pitch, d.x_halo);
+}
+
+int conv_fwd_glu(const ConvDesc& g, const void* x, const void* w, const float* bias, void* y, void* h, hipStream_t st)
+{
+    if (!conv_fwd_glu_ok(g)) return W2L_ERR_SHAPE;
+    constexpr int bytes = slab_lds_bytes(192, 192, 256, 2);
+    const long long F = (long long)(g.B - 1) * g.x_pitch + g.T;
+    const unsigned grid = (unsigned)(((F + 191) / 192) * (g.Cout / 192));
+    int rc = set_lds(conv_fwd_slab_k<192, 192, 256, 2, bf16_t, true>, bytes);
+    if (!rc) hipLaunchKernelGGL((conv_fwd_slab_k<192, 192, 256, 2, bf16_t, true>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, (bf16_t*)h, g);
     return rc ? rc : launch_status();
 }
 

@@ -171,7 +171,14 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
     for (int i = 0; i < n; ++i) {
         const w2l_layer& l = layers[i];
         const int ydt = (i == n - 1) ? W2L_F32 : dtype;
-        rc = conv_fwd(desc(i), h, weights[i], biases[i], ws + p.pre[i], dtype, ydt, st);
+        const ConvDesc fd = desc(i);
+        if (l.glu && dtype == W2L_BF16 && ydt == W2L_BF16 && conv_fwd_glu_ok(fd)) {
+            rc = conv_fwd_glu(fd, h, weights[i], biases[i], ws + p.pre[i], ws + p.post[i], st);  // GLU in the epilogue
+            if (rc) return rc;
+            h = ws + p.post[i];
+            continue;
+        }
+        rc = conv_fwd(fd, h, weights[i], biases[i], ws + p.pre[i], dtype, ydt, st);
         if (rc) return rc;
         if (l.glu) {
             rc = glu_fwd_layout(ws + p.pre[i], ws + p.post[i], B, p.Tout[i], l.cout, dtype, p.Tout[i] + 2 * HALO, HALO,
