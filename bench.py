@@ -23,9 +23,8 @@ PEAK_HBM = 8.0e12         # B/s
 # HBM bytes per launch of the dominant kernel, from two `rocprofv3 --pmc` runs
 # (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, scaled by the same counters' reading for a
 # device copy of known size).  The runs and the factor are recorded in
-# profiles/conv_kernels_config4_body_hbm_traffic.txt (332.0 MB fetched + 9.2 MB written by
-# conv_dgrad_k<256,128,64,3,true>, the kernel behind conv1d_bwd_data at the body-layer shape).
-DOMINANT_KERNEL_HBM_BYTES = {"conv1d_bwd_data": 341265323, "conv1d_fwd": 249.5e6, "conv1d_bwd_weight": 204.6e6}
+# profiles/conv_kernels_config4_body_hbm_traffic.txt.
+DOMINANT_KERNEL_HBM_BYTES = {"conv1d_bwd_data": 237504645, "conv1d_fwd": 236.5e6, "conv1d_bwd_weight": 202.5e6}
 
 
 def event_time_ms(fn, iters, warmup=None):

@@ -597,14 +597,16 @@ __device__ __forceinline__ void store_tile_bf16(const CoreT& core, unsigned char
 
 // Workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own
 // L2); give each XCD a contiguous run of tiles, ordered with the shorter grid dimension
-// fastest, so that the tiles sharing an L2 cover a compact block of operand panels.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn)
+// fastest, so that the tiles sharing an L2 cover a compact block of operand panels -- or, with
+// m_fastest, with the row tiles fastest, so that an XCD sees few column tiles and the weight
+// slices it streams stay resident in its L2.
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn, bool m_fastest = false)
 {
     const int nb = tiles_m * tiles_n;
     const int per = (nb + 7) / 8;
     int id = (blockIdx.x % 8) * per + blockIdx.x / 8;
     if (nb % 8 != 0) id = blockIdx.x;  // keep it a bijection when the count does not split evenly
-    if (tiles_n <= tiles_m) { tm = id / tiles_n; tn = id % tiles_n; }
+    if (tiles_n <= tiles_m && !m_fastest) { tm = id / tiles_n; tn = id % tiles_n; }
     else { tn = id / tiles_m; tm = id % tiles_m; }
 }
 
@@ -940,7 +942,7 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
     const int F = (g.B - 1) * g.y_pitch + g.Tp;
     const int N = g.Cin;
     int tm, tn;
-    tile_of_block((F + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
+    tile_of_block((F + BM - 1) / BM, (N + BN - 1) / BN, tm, tn, true);
     const int f0 = g.y_halo + tm * BM, n0 = tn * BN;  // dy layout frame of tile row 0
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
