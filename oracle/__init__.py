@@ -185,6 +185,19 @@ def logsoftmax_bwd(lp, dlp):
     return dz
 
 
+# ----------------------------------------------------------------------------- optimiser
+def sgd_momentum(w, v, g, lr, momentum, weight_decay=0.0):
+    """One SGD-with-momentum update (Sec. 4.1; heavy-ball form): returns (w', v') with
+    v' = momentum * v + (g + weight_decay * w),  w' = w - lr * v'.  Inputs are not modified."""
+    w2 = np.array(w, dtype=np.float64, copy=True).ravel()
+    v2 = np.array(v, dtype=np.float64, copy=True).ravel()
+    g2, pg = _d(np.asarray(g).ravel())
+    assert w2.size == v2.size == g2.size
+    _load().orc_sgd_momentum(w2.ctypes.data_as(C.POINTER(C.c_double)), v2.ctypes.data_as(C.POINTER(C.c_double)), pg,
+                             C.c_longlong(w2.size), C.c_double(lr), C.c_double(momentum), C.c_double(weight_decay))
+    return w2.reshape(np.shape(w)), v2.reshape(np.shape(v))
+
+
 # ----------------------------------------------------------------------------- CTC
 def ctc(lp, targets, in_len, tgt_len, blank=0, want_lattice=False):
     """Per-utterance CTC loss and d(sum_b loss_b)/d lp (= -G), from log-probabilities.

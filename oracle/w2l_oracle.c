@@ -235,6 +235,23 @@ void orc_logsoftmax_bwd(const double *lp, const double *dlp, double *dz, long lo
 }
 
 /* ---------------------------------------------------------------------------
+ * SGD with momentum (Sec. 4.1: every model in the paper's experiments is trained with
+ * it; the update rule itself is not written out there).  Classical (heavy-ball) form,
+ * with optional L2 weight decay folded into the gradient:
+ *   v' = mu * v + (g + wd * w)
+ *   w' = w - lr * v'
+ * Elementwise over n values; w and v are updated in place. */
+void orc_sgd_momentum(double *w, double *v, const double *g, long long n, double lr, double mu, double wd)
+{
+#pragma omp parallel for schedule(static)
+    for (long long i = 0; i < n; ++i) {
+        const double vn = mu * v[i] + (g[i] + wd * w[i]);
+        v[i] = vn;
+        w[i] = w[i] - lr * vn;
+    }
+}
+
+/* ---------------------------------------------------------------------------
  * CTC criterion (Sec. 2.3, citing Graves et al. 2006), in log space.
  * For one utterance with T valid frames and target l_1..l_L, the extended
  * sequence l' = (blank, l_1, blank, ..., l_L, blank) has S = 2L+1 states and

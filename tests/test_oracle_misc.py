@@ -184,3 +184,40 @@ def test_workload_recipes():
     assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.0 + 2 ** -6 and r[3] == 1.0
     assert abs(r[4] - v[4]) <= abs(v[4]) * 2 ** -8
     np.testing.assert_array_equal(W.bits_to_f32(W.bf16_bits(r)), r)
+
+
+def test_sgd_momentum_pins():
+    """Pins of the SGD-with-momentum oracle (paper Sec. 4.1 names the optimiser; the update is the
+    classical heavy-ball form): closed forms that a dropped term or a wrong sign would break."""
+    rng = np.random.default_rng(7)
+    w0 = rng.standard_normal(257)
+    g = rng.standard_normal(257)
+    v0 = np.zeros(257)
+    # momentum 0, no decay: plain gradient descent
+    w1, v1 = oracle.sgd_momentum(w0, v0, g, 0.1, 0.0)
+    np.testing.assert_allclose(w1, w0 - 0.1 * g, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(v1, g, rtol=0, atol=0)
+    # constant gradient, n steps: v_n = g (1 - mu^n) / (1 - mu),  w_n = w_0 - lr * sum_i v_i
+    mu, lr, n = 0.9, 0.05, 25
+    w, v = w0.copy(), v0.copy()
+    for _ in range(n):
+        w, v = oracle.sgd_momentum(w, v, g, lr, mu)
+    vn = g * (1 - mu ** n) / (1 - mu)
+    sum_v = g * (n - mu * (1 - mu ** n) / (1 - mu)) / (1 - mu)
+    np.testing.assert_allclose(v, vn, rtol=1e-12)
+    np.testing.assert_allclose(w, w0 - lr * sum_v, rtol=1e-12, atol=1e-12)
+    # quadratic bowl f = a w^2 / 2 (g = a w): the iterates follow the 2x2 linear recurrence
+    #   [w'; v'] = [[1 - lr a, -lr mu], [a, mu]] [w; v];  its powers give the iterate in closed form
+    a_, lr, mu = 2.0, 0.1, 0.5
+    M = np.array([[1 - lr * a_, -lr * mu], [a_, mu]])
+    w, v = np.array([1.5]), np.array([0.25])
+    for _ in range(7):
+        w, v = oracle.sgd_momentum(w, v, a_ * w, lr, mu)
+    ref = np.linalg.matrix_power(M, 7) @ np.array([1.5, 0.25])
+    np.testing.assert_allclose([w[0], v[0]], ref, rtol=1e-12)
+    # weight decay is the gradient of wd |w|^2 / 2 added to g; inputs are not modified
+    w2, v2 = oracle.sgd_momentum(w0, v0, g, 0.1, 0.9, weight_decay=0.01)
+    w3, v3 = oracle.sgd_momentum(w0, v0, g + 0.01 * w0, 0.1, 0.9)
+    np.testing.assert_allclose(w2, w3, rtol=1e-15)
+    np.testing.assert_allclose(v2, v3, rtol=1e-15)
+    assert np.all(v0 == 0)
