@@ -156,6 +156,17 @@ def main():
     cells = int(np.sum(c2["in_len"].astype(np.int64) * (2 * c2["tgt_len"].astype(np.int64) + 1)))
     ctc_bytes = 2 * 32 * 750 * 29 * 4 + 2 * 4 * cells
 
+    # optimiser step over all parameters of the model as one flat fp32 buffer (not part of `value`:
+    # the metric is forward + backward)
+    npar = W.num_params(layers)
+    ow = torch.zeros(npar, dtype=torch.float32, device="cuda:0")
+    ov = torch.zeros_like(ow)
+    og = torch.full_like(ow, 1e-3)
+    olp = torch.empty(npar, dtype=torch.bfloat16, device="cuda:0")
+    t_sgd = event_time_ms(lambda: P.w2l_sgd_momentum_step(ow, ov, og, olp, 0.01, 0.9), 20, 3)
+    sgd_bytes = npar * 22.0
+    del ow, ov, og, olp
+
     out = {
         "metric": "training frames/sec (fwd+bwd) for 105M conv-GLU CTC model",
         "value": frames / dt,
@@ -204,6 +215,8 @@ def main():
                                      "frac_hbm_peak": ctc_bytes / (t_ctc * 1e-3) / PEAK_HBM,
                                      "serial_steps": int(c2["in_len"].max()),
                                      "us_per_serial_step": t_ctc * 1e3 / int(c2["in_len"].max())},
+            "sgd_momentum_step(all %d params)" % npar: {"ms": t_sgd, "GBps": sgd_bytes / (t_sgd * 1e-3) / 1e9,
+                                                         "frac_hbm_peak": sgd_bytes / (t_sgd * 1e-3) / PEAK_HBM},
         },
     }
 

@@ -119,6 +119,19 @@ int w2l_logsoftmax_fwd(const void *z, float *lp, long long rows, int C, int z_dt
 int w2l_logsoftmax_bwd(const float *lp, const float *dlp, float *dz, long long rows, int C,
                        void *stream);
 
+/* ---- SGD with momentum (Sec. 4.1: the optimiser of every run in the paper) ---------
+ * The paper names the optimiser and does not write the update out; this is the classical
+ * heavy-ball form with optional L2 weight decay, elementwise over n values:
+ *   v[i] = momentum * v[i] + (grad[i] + weight_decay * w[i])
+ *   w[i] = w[i] - lr * v[i]
+ *   w_lowp[i] = bf16(w[i])              (only if w_lowp != NULL)
+ * w: fp32 master weights, v: fp32 velocity (both updated in place), grad: fp32 (the dw / dbias
+ * buffers of w2l_train_step), w_lowp: optional bf16 copy of the updated weights (the tensor the
+ * next w2l_train_step reads), round-to-nearest-even.  All device pointers, n >= 0, 16-byte
+ * aligned.  Arithmetic is fp32.  Returns W2L_ERR_NULL / _SHAPE / _ALIGN like the other calls. */
+int w2l_sgd_momentum_step(float *w, float *v, const float *grad, void *w_lowp, long long n, float lr,
+                          float momentum, float weight_decay, void *stream);
+
 /* ---- CTC criterion (Sec. 2.3, after Graves et al. 2006) ---------------------------
  * For utterance b with T_b = in_len[b] valid frames and target l (L_b = tgt_len[b]
  * labels), over the extended sequence l' = (blank, l_1, blank, ..., l_L, blank):

@@ -20,7 +20,8 @@ __all__ = [
     "w2l_conv1d_fwd", "w2l_conv1d_bwd_data", "w2l_conv1d_bwd_weight", "w2l_conv1d_fwd_workspace_bytes",
     "w2l_conv1d_bwd_data_workspace_bytes", "w2l_conv1d_bwd_weight_workspace_bytes", "w2l_glu_fwd", "w2l_glu_bwd",
     "w2l_logsoftmax_fwd", "w2l_logsoftmax_bwd", "w2l_ctc_workspace_bytes", "w2l_ctc_fwd_bwd",
-    "w2l_ctc_check_targets_host", "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_probe_mfma", "raw",
+    "w2l_ctc_check_targets_host", "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_sgd_momentum_step",
+    "w2l_probe_mfma", "raw",
     "workspace",
 ]
 
@@ -64,6 +65,7 @@ def _load():
         "w2l_ctc_fwd_bwd": (i, [vp, i, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]),
         "w2l_ctc_check_targets_host": (i, [vp, vp, vp, i, i, i, i, i]),
         "w2l_probe_mfma": (i, [vp, i, i, vp]),
+        "w2l_sgd_momentum_step": (i, [vp, vp, vp, vp, ll, f, f, f, vp]),
         "w2l_train_step_workspace_bytes": (sz, [C.POINTER(w2l_layer), i, i, i, i, i]),
         "w2l_train_step": (i, [C.POINTER(w2l_layer), i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                C.POINTER(vp), vp, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]),
@@ -194,6 +196,13 @@ def w2l_logsoftmax_bwd(lp, dlp, dz, stream=None):
     _check(raw.w2l_logsoftmax_bwd(_p(lp), _p(dlp), _p(dz), lp.numel() // Cc, Cc, _stream(stream)),
            "w2l_logsoftmax_bwd")
     return dz
+
+
+def w2l_sgd_momentum_step(w, v, grad, w_lowp, lr, momentum, weight_decay=0.0, stream=None):
+    _check(raw.w2l_sgd_momentum_step(_p(w), _p(v), _p(grad), _p(w_lowp) if w_lowp is not None else None,
+                                     w.numel(), float(lr), float(momentum), float(weight_decay), _stream(stream)),
+           "w2l_sgd_momentum_step")
+    return w
 
 
 def w2l_ctc_workspace_bytes(B, Tp, Cc, Lmax) -> int:

@@ -131,6 +131,34 @@ def test_logsoftmax(P, rows, Cc):
     lpb = P.w2l_logsoftmax_fwd(to_dev(zb, "bf16"), empty((rows, Cc)))
     assert np.linalg.norm(to_host(lpb) - oracle.logsoftmax_fwd(zb)) <= 1e-5 * max(np.linalg.norm(lp_o), 1.0)
 
+@pytest.mark.parametrize("n,steps,wd", [(1 << 20, 3, 0.0), (4099, 5, 1e-3), (3, 2, 0.0), (26_000_001, 1, 0.0)])
+def test_sgd_momentum(P, n, steps, wd):
+    """fp32 update vs the fp64 oracle (tolerance: a few fp32 roundings per step, 1e-6 relative to
+    the tensor norm); the bf16 copy must be the round-to-nearest-even of the kernel's own fp32
+    weights, bit for bit.  Sizes: several blocks, a ragged tail (n % 4 != 0), fewer values than
+    one vector, and one weight tensor of the 105M model (k=11, 768 -> 1536 plus one) at full size."""
+    rng = np.random.default_rng(n)
+    w0 = rng.standard_normal(n).astype(np.float32)
+    v0 = (rng.standard_normal(n) * 0.1).astype(np.float32)
+    lr, mu = 0.05, 0.9
+    w, v = to_dev(w0), to_dev(v0)
+    lowp = empty((n,), "bf16")
+    wo, vo = w0.astype(np.float64), v0.astype(np.float64)
+    for s_ in range(steps):
+        g = rng.standard_normal(n).astype(np.float32)
+        P.w2l_sgd_momentum_step(w, v, to_dev(g), lowp, lr, mu, wd)
+        wo, vo = oracle.sgd_momentum(wo, vo, g, lr, mu, wd)
+    torch.cuda.synchronize()
+    wg = w.cpu().numpy()
+    assert rel_l2(wg, wo) <= 1e-6 and rel_l2(v.cpu().numpy(), vo) <= 1e-6
+    np.testing.assert_array_equal(to_host(lowp), W.round_to_bf16(wg).astype(np.float64))
+    # without the low-precision copy
+    w2, v2 = to_dev(w0), to_dev(v0)
+    g = rng.standard_normal(n).astype(np.float32)
+    P.w2l_sgd_momentum_step(w2, v2, to_dev(g), None, lr, mu, wd)
+    w2o, _ = oracle.sgd_momentum(w0.astype(np.float64), v0.astype(np.float64), g, lr, mu, wd)
+    assert rel_l2(w2.cpu().numpy(), w2o) <= 1e-6
+
 
 def _run_ctc(P, inp, is_logits, targets, in_len, tgt_len, blank=0, scale=1.0):
     B, Tp, Cc = inp.shape
