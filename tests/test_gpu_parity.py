@@ -296,6 +296,18 @@ def test_train_step_10m_model_reduced_batch(P):
     cfg = W.config3(B=4)
     check_train_step(run_train_step(P, cfg), oracle_train_step(cfg), "bf16")
 
+def test_train_step_wide_layer_fused_epilogues(P):
+    """A model whose second layer has the benchmark's output shape (B*T' = 6000 frames, 1536
+    channels) but a short reduction, so that the fp64 oracle stays affordable: the train step then
+    takes the kernels the 105M model takes -- forward convolution with the GLU in its epilogue
+    (layer 1), data gradient with the GLU backward of the layer below in its epilogue (layer 2
+    writes dy of layer 1), activation slabs, 256x256 weight-gradient tiles -- and every gradient is
+    compared with the oracle."""
+    layers = [dict(k=3, stride=1, cin=16, cout=128, glu=1), dict(k=3, stride=1, cin=64, cout=1536, glu=1),
+              dict(k=5, stride=1, cin=768, cout=128, glu=1), dict(k=1, stride=1, cin=64, cout=29, glu=0)]
+    cfg = W.small_model(33, 8, 700, 750, 16, layers, True, 20, 60)
+    check_train_step(run_train_step(P, cfg), oracle_train_step(cfg), "bf16")
+
 
 def test_train_step_is_deterministic(P):
     cfg = W.config0(seed=3)
