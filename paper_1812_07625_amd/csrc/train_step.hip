@@ -211,7 +211,6 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
     // layer, each started as soon as its dy exists.  dy buffers rotate over three slots, so the
     // writer of dy_i only has to wait for the weight gradient of layer i+3.
     SideStream* side = side_stream(n);
-    hipStream_t wst = side ? side->stream : st;
     auto hip_ok = [&](hipError_t e) { if (e != hipSuccess) { note_hip_error(e); return false; } return true; };
     auto wait_wgrad = [&](int layer) {  // main stream waits until that layer's weight gradient has read its dy
         if (!side || layer >= n) return true;
@@ -243,7 +242,11 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
             d.slack = 0;  // dy is dense here: nothing may be read past its end
         }
         dy_ready = false;
-        if (side) {
+        // layer 0 has no data gradient: its weight gradient takes the main stream, next to the
+        // helper stream's last launch, instead of queueing behind it
+        const bool on_side = side && i > 0;
+        hipStream_t wst = on_side ? side->stream : st;
+        if (on_side) {
             if (!hip_ok(hipEventRecord(side->ready[i], st)) || !hip_ok(hipStreamWaitEvent(wst, side->ready[i], 0)))
                 return W2L_ERR_LAUNCH;
         }
@@ -252,7 +255,7 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
         // the main stream, which has the shorter chain
         rc = conv_wgrad(d, xin, dy, dweights[i], side ? nullptr : dbiases[i], dtype, dy_dt, 0, ws + p.conv, wst);
         if (rc) return rc;
-        if (side && !hip_ok(hipEventRecord(side->done[i], wst))) return W2L_ERR_LAUNCH;
+        if (on_side && !hip_ok(hipEventRecord(side->done[i], wst))) return W2L_ERR_LAUNCH;
         if (side && dbiases[i]) {
             // halo frames hold zeros, so summing every frame of the allocation is the same sum
             rc = dbias_reduce(dy, dbiases[i], (long long)d.B * d.y_pitch, d.Cout, dy_dt, 0,
@@ -277,6 +280,6 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
         }
     }
     // join: the side stream is in order, so its last event covers every weight gradient
-    if (side && !hip_ok(hipStreamWaitEvent(st, side->done[0], 0))) return W2L_ERR_LAUNCH;
+    if (side && n > 1 && !hip_ok(hipStreamWaitEvent(st, side->done[1], 0))) return W2L_ERR_LAUNCH;
     return W2L_OK;
 }
