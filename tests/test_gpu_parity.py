@@ -358,6 +358,10 @@ def test_conv_full_size_sampled(P, shape):
     idx = np.unique(np.concatenate([idx, np.array(corners)]))
     ref = oracle.conv1d_fwd_at(x, w, bias, idx, s)
     assert rel_l2(y[idx], ref) <= TOL["bf16"]
+    if name == "config4-body":
+        # the same kernel family with fp32 output (how a last layer writes logits): no output rounding
+        y32 = to_host(P.w2l_conv1d_fwd(xd, wd, bd, empty((B, Tp, Cout)), s, wf)).reshape(-1)
+        assert rel_l2(y32[idx], ref) <= 2e-5  # fp32 accumulation over k*Cin = 8448 products
 
     if s == 1:
         wb = P.workspace(P.w2l_conv1d_bwd_data_workspace_bytes(B, T, Cin, Cout, k, s, P.W2L_BF16))
