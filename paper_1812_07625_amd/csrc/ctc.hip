@@ -165,6 +165,12 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     double offset = 0;  // true log2 value = relative value + offset
     const int nwaves = NT >> 6;
     const int tblocks = (T + SCORE_AHEAD - 1) / SCORE_AHEAD;
+    // running pointers instead of per-step index arithmetic: the score row fetched next (clamped
+    // at the last frame) and the lattice row written next
+    const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)d.Sp : d.Sp;
+    const float* sptr = lpb + (size_t)frame(SCORE_AHEAD - 1 < T ? SCORE_AHEAD - 1 : T - 1) * d.C;
+    float* rptr = lat + (size_t)frame(0) * d.Sp;
+    float* const spare = lat + (size_t)d.Tp * d.Sp;
 
     for (int tb = 0; tb < tblocks; ++tb) {
 #pragma unroll
@@ -174,14 +180,14 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
             float s_l[PPT];
 #pragma unroll
             for (int j = 0; j < PPT; ++j) s_l[j] = sl[j][k];
-            {   // refill this ring slot for step + SCORE_AHEAD
-                const int nf = step + SCORE_AHEAD;
-                const int f = frame(nf < T ? nf : T - 1);
-                sb[k] = lpb[(size_t)f * d.C + d.blank];
+            {   // refill this ring slot for step + SCORE_AHEAD (past the end: the last frame again)
+                sptr += (step + SCORE_AHEAD < T) ? sstep : 0;
+                sb[k] = sptr[d.blank];
 #pragma unroll
-                for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
+                for (int j = 0; j < PPT; ++j) sl[j][k] = sptr[cls[j]];
             }
-            const int row = step < T ? frame(step) : d.Tp;
+            float* const row = step < T ? rptr : spare;
+            rptr += rstep;
             // label value (previous frame) of the pair to the left of this lane's first pair
             float carry = from_left_lane(al[PPT - 1], NEG);
 #pragma unroll
@@ -192,7 +198,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                 carry = ol;
                 ab[j] = nb;
                 al[j] = nl;
-                *reinterpret_cast<float2*>(lat + (size_t)row * d.Sp + slot[j]) = make_float2(nb, nl);
+                *reinterpret_cast<float2*>(row + slot[j]) = make_float2(nb, nl);
             }
         }
         if (tid < SCORE_AHEAD) {  // the offset of the block's frames (it changes only at block boundaries)
