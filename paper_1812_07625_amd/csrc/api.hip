@@ -54,9 +54,11 @@ int conv_fwd(const ConvDesc& d, const void* x, const void* w, const float* bias,
     return conv_fwd_generic(d, x, w, bias, y, dt, ydt, st);
 }
 
-int conv_dgrad(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st)
+int conv_dgrad(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st,
+               void* scratch, size_t scratch_bytes)
 {
-    if (dt == W2L_BF16 && dydt == W2L_BF16 && conv_dgrad_mfma_ok(d)) return conv_dgrad_mfma(d, dy, w, dx, st);
+    if (dt == W2L_BF16 && dydt == W2L_BF16 && conv_dgrad_mfma_ok(d))
+        return conv_dgrad_mfma(d, dy, w, dx, scratch, scratch_bytes, st);
     return conv_dgrad_generic(d, dy, w, dx, dt, dydt, st);
 }
 
@@ -125,10 +127,23 @@ extern "C" int w2l_conv1d_fwd(const void* x, const void* w, const float* bias, v
     return conv_fwd(d, x, w, bias, y, dtype, y_dtype, st);
 }
 
+namespace {
+// geometry of the data gradient once dy has been staged into the haloed layout
+ConvDesc staged_dgrad_desc(int B, int T, int Cin, int Cout, int k, int stride)
+{
+    ConvDesc d = dense_desc(B, T, Cin, Cout, k, stride);
+    d.y_pitch = d.Tp + 2 * ABI_HALO;
+    d.y_halo = ABI_HALO;
+    d.slack = ABI_SLACK;
+    return d;
+}
+}  // namespace
+
 extern "C" size_t w2l_conv1d_bwd_data_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype)
 {
     if (check_conv_shape(B, T, Cin, Cout, k, stride)) return 0;
-    return stage_dgrad(Cin, Cout, k, stride, dtype) ? haloed_bytes(B, out_len(T, stride), Cout) : 0;
+    if (!stage_dgrad(Cin, Cout, k, stride, dtype)) return 0;
+    return haloed_bytes(B, out_len(T, stride), Cout) + conv_dgrad_scratch_bytes(staged_dgrad_desc(B, T, Cin, Cout, k, stride));
 }
 
 extern "C" int w2l_conv1d_bwd_data(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout,
@@ -148,10 +163,10 @@ extern "C" int w2l_conv1d_bwd_data(const void* dy, const void* w, void* dx, int 
     if (workspace && need) {
         rc = pad_layout_bf16(dy, workspace, B, d.Tp, Cout, d.Tp + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
         if (rc) return rc;
-        d.y_pitch = d.Tp + 2 * ABI_HALO;
-        d.y_halo = ABI_HALO;
-        d.slack = ABI_SLACK;
+        d = staged_dgrad_desc(B, T, Cin, Cout, k, stride);
         dy = workspace;
+        const size_t used = haloed_bytes(B, d.Tp, Cout);
+        return conv_dgrad(d, dy, w, dx, dtype, dy_dtype, st, static_cast<unsigned char*>(workspace) + used, need - used);
     }
     return conv_dgrad(d, dy, w, dx, dtype, dy_dtype, st);
 }

@@ -74,7 +74,11 @@ inline ConvDesc dense_desc(int B, int T, int Cin, int Cout, int k, int s)
 // dispatchers (api.hip): MFMA kernels where the shape allows, shape-agnostic kernels otherwise
 int conv_fwd(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int dt, int ydt,
              hipStream_t st);
-int conv_dgrad(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st);
+// scratch (optional): conv_dgrad_scratch_bytes(d) bytes of device memory; given it, shapes that would
+// leave CUs idle split their reduction over two workgroups per tile
+int conv_dgrad(const ConvDesc& d, const void* dy, const void* w, void* dx, int dt, int dydt, hipStream_t st,
+               void* scratch = nullptr, size_t scratch_bytes = 0);
+size_t conv_dgrad_scratch_bytes(const ConvDesc& d);
 // scratch: conv_wgrad_scratch_bytes() bytes of device memory
 size_t conv_wgrad_scratch_bytes(int Cin, int Cout, int k);
 int conv_wgrad(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int dt, int dydt,
@@ -99,7 +103,8 @@ int dbias_reduce(const void* dy, float* dbias, long long rows, int Cout, int dyd
 bool conv_fwd_mfma_ok(const ConvDesc& d);
 int conv_fwd_mfma(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int ydt, hipStream_t st);
 bool conv_dgrad_mfma_ok(const ConvDesc& d);
-int conv_dgrad_mfma(const ConvDesc& d, const void* dy, const void* w, void* dx, hipStream_t st);
+int conv_dgrad_mfma(const ConvDesc& d, const void* dy, const void* w, void* dx, void* scratch, size_t scratch_bytes,
+                    hipStream_t st);
 // forward pass fused with the layer's GLU: writes y (dense, pre-GLU, bf16) and h = GLU(y) into a
 // haloed tensor with the time layout of x (halo frames and the zeroed slack written as zeros)
 bool conv_fwd_glu_ok(const ConvDesc& d);

@@ -142,8 +142,15 @@ struct PanelMN {
     static constexpr int CPR = COLS / 8;
     static constexpr int NI = BYTES / 1024 / NW;
     static_assert(BYTES % (1024 * NW) == 0, "panel must split into 1 KB blocks over the wavefronts");
-    static_assert(CPR % 8 == 0, "swizzle flips chunk-index bits 2 and 3");
+    static_assert(CPR % 8 == 0, "the swizzle permutes chunks within aligned groups of 8 (or 16)");
     const bf16_t* base;
+    // Chunk swizzle: the transpose read touches 4 consecutive reduction rows at once.  Rows that
+    // are a multiple of 256 bytes apart start on the same bank, so all four need different chunk
+    // groups (flip bits 2-3 with the row's low bits; needs CPR % 16 == 0); with 384-byte rows
+    // (192 columns) only rows two apart collide, and flipping bit 2 with bit 1 of the row keeps
+    // the permutation inside groups of 8 chunks.  swz(r + 4) == swz(r): the two reads of a
+    // fragment share it.
+    static __device__ __forceinline__ int swz(int row) { return CPR % 16 == 0 ? (row & 3) << 2 : ((row >> 1) & 1) << 2; }
     unsigned voff[NI];  // FAST mode only
 
     __device__ __forceinline__ void init(const bf16_t* b) { base = b; }
@@ -156,7 +163,7 @@ struct PanelMN {
         for (int i = 0; i < NI; ++i) {
             const int q = chunk_of(i);
             const int row = q / CPR, slot = q - row * CPR;
-            int c8 = (slot ^ ((row & 3) << 2)) * 8;
+            int c8 = (slot ^ swz(row)) * 8;
             if (c8 >= ncols) c8 = 0;
             voff[i] = (unsigned)(((long long)row * row_pitch + c8) * 2);
         }
@@ -175,7 +182,7 @@ struct PanelMN {
         const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_stage + (threadIdx.x >> 6) * 1024);
         const int q = chunk_of(i);
         const int row = q / CPR, slot = q - row * CPR;
-        const int c8 = (slot ^ ((row & 3) << 2)) * 8;
+        const int c8 = (slot ^ swz(row)) * 8;
         long long off;
         int lo, hi;
         f(row, off, lo, hi);
@@ -190,7 +197,7 @@ struct PanelMN {
         const int q = lane >> 4, i = lane & 15;
         const int col = col0 + 16 * (q & 1) + 4 * (i & 3);
         const int r = ks * 16 + 8 * (q >> 1) + (i >> 2);
-        const int slot = (col >> 3) ^ ((r & 3) << 2);           // (r+4)&3 == r&3: both reads share it
+        const int slot = (col >> 3) ^ swz(r);
         const unsigned char* p = lds + r * RS + slot * 16 + (col & 7) * 2;
         const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
         const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * RS));
@@ -930,10 +937,13 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_dgrad_k(const bf16_t* __re
 // GLUB: the tile is not stored as dx but pushed through the GLU backward of the layer below
 // (whose pre-GLU activations yprev are dense [B*T, 2N]): dx_out then has 2N channels and the
 // time layout of dy (tile row r -> its frame f0 + r); frames that are not real get zeros.
+// part != nullptr (grid.y = 2): the reduction over channel blocks is split in two between the
+// workgroups (blockIdx.y) of a tile, which then store their fp32 sums to part[blockIdx.y]
+// ([tile rows][N]) for dgrad_combine_k -- twice the workgroups when one per tile leaves CUs idle.
 template <int BM, int BN, int SROWS, int KG, bool GLUB>
 __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
                                                               bf16_t* __restrict__ dx, const bf16_t* __restrict__ yprev,
-                                                              ConvGeom g)
+                                                              float* __restrict__ part, ConvGeom g)
 {
     using PS = PanelK<SROWS, 64, 4 * KG>;
     using PB = PanelMN<BN, 64, 4 * KG>;
@@ -955,14 +965,23 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
     for (int i = 0; i < PS::NI; ++i) ps.set_fast(i, (long long)(f0 - g.p + PS::row_of(i)) * g.Cout);
     Core<BM, BN, 64, KG, 1, PS, PB> core;
     core.zero();
+    const int nparts = gridDim.y, ncb = g.Cout / 64 / nparts, cb0 = blockIdx.y * ncb;  // this workgroup's channel blocks
     run_slab_pipeline<PS::NI, PB::NI, PS::BYTES, PB::BYTES>(
-        core, lds, g.Cout / 64, g.k,
-        [&](int i, int cb, unsigned dst) { ps.issue_fast(i, dy + cb * 64, dst); },
+        core, lds, ncb, g.k,
+        [&](int i, int cb, unsigned dst) { ps.issue_fast(i, dy + (cb0 + cb) * 64, dst); },
         [&](int i, int cb, int j, unsigned dst) {
-            pb.issue_fast(i, w + ((long long)cb * 64 * g.k + (g.k - 1 - j)) * g.Cin + n0, dst);
+            pb.issue_fast(i, w + ((long long)(cb0 + cb) * 64 * g.k + (g.k - 1 - j)) * g.Cin + n0, dst);
         },
         kg, wm, wn, lane);
     core.reduce_groups(lds, kg, w4, lane);
+    if (!GLUB && part) {
+        if (kg != 0) return;
+        float* po = part + (size_t)blockIdx.y * ((size_t)gridDim.x / ((N + BN - 1) / BN) * BM) * N;  // [tiles_m * BM][N]
+        core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
+            if (n0 + nn < N) po[(size_t)(tm * BM + mm) * N + n0 + nn] = v;
+        });
+        return;
+    }
     float zero[core.TN];
 #pragma unroll
     for (int j = 0; j < core.TN; ++j) zero[j] = 0.f;
@@ -1012,6 +1031,31 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
         bf16_t* o = dx + (size_t)f * 2 * N + n;
         *reinterpret_cast<uint4*>(o) = oa;
         *reinterpret_cast<uint4*>(o + N) = og;
+    }
+}
+
+// dx = bf16(part[0] + part[1]) for the real frames; part: [2][rows][N] fp32 over the layout frames
+// starting at frame y_halo (tile row r = layout frame y_halo + r), N % 8 == 0
+__global__ __launch_bounds__(256) void dgrad_combine_k(const float* __restrict__ part, bf16_t* __restrict__ dx, long long rows,
+                                                       ConvGeom g)
+{
+    const int N = g.Cin, nv = N / 8;
+    const long long total = rows * nv;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const long long r = i / nv;
+        const int c = (int)(i - r * nv) * 8;
+        const long long f = g.y_halo + r;
+        const int b = (int)(f / g.y_pitch), t = (int)(f - (long long)b * g.y_pitch) - g.y_halo;
+        if (b >= g.B || t < 0 || t >= g.T) continue;
+        const float4* p0 = reinterpret_cast<const float4*>(part + r * N + c);
+        const float4* p1 = reinterpret_cast<const float4*>(part + (rows + r) * N + c);
+        const float4 a0 = p0[0], a1 = p0[1], b0 = p1[0], b1 = p1[1];
+        uint4 o;
+        o.x = (unsigned)f32_to_bf16(a0.x + b0.x) | ((unsigned)f32_to_bf16(a0.y + b0.y) << 16);
+        o.y = (unsigned)f32_to_bf16(a0.z + b0.z) | ((unsigned)f32_to_bf16(a0.w + b0.w) << 16);
+        o.z = (unsigned)f32_to_bf16(a1.x + b1.x) | ((unsigned)f32_to_bf16(a1.y + b1.y) << 16);
+        o.w = (unsigned)f32_to_bf16(a1.z + b1.z) | ((unsigned)f32_to_bf16(a1.w + b1.w) << 16);
+        *reinterpret_cast<uint4*>(dx + ((size_t)b * g.x_pitch + g.x_halo + t) * N + c) = o;
     }
 }
 
@@ -1250,18 +1294,53 @@ bool conv_dgrad_mfma_ok(const ConvDesc& d)
     return d.s == 1 && common_ok(d) && d.Cout % 64 == 0 && d.Cin >= 64 && (long long)d.B * d.T >= 128;
 }
 
-int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, hipStream_t st)
+// Split-reduction data gradient: 192x192 tiles, two workgroups per tile, fp32 partial sums in
+// scratch, then one combining pass.  Taken when one workgroup per tile would leave more than a
+// third of the CUs idle and two per tile fit the chip in one round.
+bool dgrad_split_ok(const ConvDesc& g)
+{
+    if (!conv_dgrad_mfma_ok(g) || !halo_ok_y(g) || g.Cin % 8 != 0 || (g.Cout / 64) % 2 != 0 || g.Cout < 256) return false;
+    if (!slab_ok(g, 192, 256, g.Cout, g.Tp, g.y_pitch, g.y_halo)) return false;
+    const long long M = (long long)g.B * g.T, N = g.Cin, F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
+    const TileChoice tc = choose_tile(M, N);
+    const long long t1 = ((M + tc.bm - 1) / tc.bm) * ((N + tc.bn - 1) / tc.bn);
+    const long long t2 = ((F + 191) / 192) * ((N + 191) / 192);
+    return t1 <= 170 && 2 * t2 <= 256 && 2 * t2 > t1;
+}
+size_t conv_dgrad_scratch_bytes(const ConvDesc& g)
+{
+    if (!dgrad_split_ok(g)) return 0;
+    const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
+    return round_up((size_t)2 * ((F + 191) / 192 * 192) * g.Cin * 4, 256);
+}
+
+int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, void* scratch, size_t scratch_bytes,
+                    hipStream_t st)
 {
     const long long M = (long long)g.B * g.T, N = g.Cin;
     const TileChoice tc = choose_tile(M, N);
     const bool fast = halo_ok_y(g);
     int rc = W2L_OK;
+    if (scratch && dgrad_split_ok(g) && scratch_bytes >= conv_dgrad_scratch_bytes(g)) {
+        constexpr int bytes = slab_lds_bytes(192, 192, 256, 2);
+        const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
+        const long long tiles_m = (F + 191) / 192, rows = tiles_m * 192;
+        const dim3 grid((unsigned)(tiles_m * ((N + 191) / 192)), 2);
+        rc = set_lds(conv_dgrad_slab_k<192, 192, 256, 2, false>, bytes);
+        if (rc) return rc;
+        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, false>), grid, dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, (float*)scratch, g);
+        rc = launch_status();
+        if (rc) return rc;
+        const long long work = rows * (N / 8);
+        hipLaunchKernelGGL(dgrad_combine_k, dim3((unsigned)((work + 255) / 256 < 4096 ? (work + 255) / 256 : 4096)), dim3(256), 0, st, (const float*)scratch, (bf16_t*)dx, rows, g);
+        return launch_status();
+    }
     if (fast && tc.bm == 256 && tc.bn == 128 && slab_ok(g, 256, 320, g.Cout, g.Tp, g.y_pitch, g.y_halo)) {
         constexpr int bytes = slab_lds_bytes(256, 128, 320, 2);
         const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
         const unsigned grid = (unsigned)(((F + 255) / 256) * ((N + 127) / 128));
         rc = set_lds(conv_dgrad_slab_k<256, 128, 320, 2, false>, bytes);
-        if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<256, 128, 320, 2, false>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, g);
+        if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<256, 128, 320, 2, false>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, (float*)nullptr, g);
         return rc ? rc : launch_status();
     }
 #define CALL(BM_, BN_, BK_, ST_, KG_, GN_)                                                                     \
@@ -1299,7 +1378,7 @@ int conv_dgrad_glu(const ConvDesc& g, const void* dy, const void* w, const void*
     if (rc) return rc;
     const unsigned grid = (unsigned)(tiles_m * ((g.Cin + BN - 1) / BN));
     rc = set_lds(conv_dgrad_slab_k<BM, BN, 320, 2, true>, bytes);
-    if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<BM, BN, 320, 2, true>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dyprev, (const bf16_t*)yprev, g);
+    if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<BM, BN, 320, 2, true>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dyprev, (const bf16_t*)yprev, (float*)nullptr, g);
     return rc ? rc : launch_status();
 }
 
