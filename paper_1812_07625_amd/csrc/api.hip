@@ -198,9 +198,7 @@ extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, f
     if (dy_dtype == W2L_BF16 && stage_wgrad(Cin, Cout, k, stride, dtype)) {
         unsigned char* xp = ws + conv_wgrad_scratch_bytes(Cin, Cout, k);
         unsigned char* dyp = xp + haloed_bytes(B, T, Cin);
-        rc = pad_layout_bf16(x, xp, B, T, Cin, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
-        if (rc) return rc;
-        rc = pad_layout_bf16(dy, dyp, B, T, Cout, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
+        rc = pad_layout2_bf16(x, xp, Cin, dy, dyp, Cout, B, T, T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
         if (rc) return rc;
         d.x_pitch = d.y_pitch = T + 2 * ABI_HALO;
         d.x_halo = d.y_halo = ABI_HALO;

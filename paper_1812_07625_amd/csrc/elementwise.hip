@@ -149,6 +149,29 @@ __global__ __launch_bounds__(256) void pad_layout_k(const bf16_t* __restrict__ s
     }
 }
 
+// two tensors with the same time layout in one launch (the weight gradient stages x and dy)
+__global__ __launch_bounds__(256) void pad_layout2_k(const bf16_t* __restrict__ src0, bf16_t* __restrict__ dst0, int C0,
+                                                     const bf16_t* __restrict__ src1, bf16_t* __restrict__ dst1, int C1,
+                                                     long long out_rows, RowMap map)
+{
+    const int cv0 = C0 / 8, cv1 = C1 / 8;
+    const long long n0 = out_rows * cv0, total = n0 + out_rows * cv1;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const bool second = i >= n0;
+        const long long e = second ? i - n0 : i;
+        const int cv = second ? cv1 : cv0, C = second ? C1 : C0;
+        const bf16_t* src = second ? src1 : src0;
+        bf16_t* dst = second ? dst1 : dst0;
+        const long long f = e / cv;
+        const int c = (int)(e - f * cv) * 8;
+        const long long r = map.src(f);
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r >= 0) v = *reinterpret_cast<const uint4*>(src + r * C + c);
+        *reinterpret_cast<uint4*>(dst + f * C + c) = v;
+    }
+}
+
 inline unsigned grid_for(long long items)
 {
     long long b = (items + 255) / 256;
@@ -258,6 +281,17 @@ int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch,
     const RowMap map{Tp, pitch, halo, (long long)B * pitch};
     hipLaunchKernelGGL(pad_layout_k, dim3(grid_for(out_rows * (C / 8))), dim3(256), 0, st, (const bf16_t*)src,
                        (bf16_t*)dst, out_rows, C, map);
+    return launch_status();
+}
+
+int pad_layout2_bf16(const void* src0, void* dst0, int C0, const void* src1, void* dst1, int C1, int B, int Tp, int pitch,
+                     int halo, int slack, hipStream_t st)
+{
+    if (C0 % 8 || C1 % 8) return W2L_ERR_SHAPE;
+    const long long out_rows = (long long)B * pitch + slack;
+    const RowMap map{Tp, pitch, halo, (long long)B * pitch};
+    hipLaunchKernelGGL(pad_layout2_k, dim3(grid_for(out_rows * ((C0 + C1) / 8))), dim3(256), 0, st, (const bf16_t*)src0,
+                       (bf16_t*)dst0, C0, (const bf16_t*)src1, (bf16_t*)dst1, C1, out_rows, map);
     return launch_status();
 }
 }  // namespace w2l
