@@ -24,7 +24,9 @@ PEAK_HBM = 8.0e12         # B/s
 # (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, scaled by the same counters' reading for a
 # device copy of known size).  The runs and the factor are recorded in
 # profiles/conv_kernels_config4_body_hbm_traffic.txt.
-DOMINANT_KERNEL_HBM_BYTES = {"conv1d_bwd_data": 237504645, "conv1d_fwd": 236.5e6, "conv1d_bwd_weight": 202.5e6}
+# For conv1d_bwd_data the figure is the split-reduction tile kernel alone; its combining pass
+# moves another 47 MB per call.
+DOMINANT_KERNEL_HBM_BYTES = {"conv1d_bwd_data": 166989279, "conv1d_fwd": 236551629, "conv1d_bwd_weight": 202474160}
 
 
 def event_time_ms(fn, iters, warmup=None):
