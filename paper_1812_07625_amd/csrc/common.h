@@ -114,7 +114,11 @@ int conv_fwd_glu(const ConvDesc& d, const void* x, const void* w, const float* b
 // tensor with the same time layout as this layer's dy (halo frames are written as zeros).
 // yprev: dense [B*T, 2*Cin] pre-GLU activations of the layer below.
 bool conv_dgrad_glu_ok(const ConvDesc& d);
-int conv_dgrad_glu(const ConvDesc& d, const void* dy, const void* w, const void* yprev, void* dyprev, hipStream_t st);
+// scratch (optional): conv_dgrad_scratch_bytes(d) bytes; given it, shapes dgrad_split_ok(d) accepts take
+// the split-reduction tiles and the GLU backward moves into their combining pass
+int conv_dgrad_glu(const ConvDesc& d, const void* dy, const void* w, const void* yprev, void* dyprev, void* scratch,
+                   size_t scratch_bytes, hipStream_t st);
+bool dgrad_split_ok(const ConvDesc& d);
 bool conv_wgrad_mfma_ok(const ConvDesc& d);
 int conv_wgrad_mfma(const ConvDesc& d, const void* x, const void* dy, float* dw, int accumulate, hipStream_t st);
 

@@ -1059,6 +1059,54 @@ __global__ __launch_bounds__(256) void dgrad_combine_k(const float* __restrict__
     }
 }
 
+// Combining pass of the split data gradient fused with the GLU backward of the layer below:
+// dh = bf16(part[0] + part[1]) (rounded as the unfused path stores it), then
+// dyprev[f] = (dh * sigmoid(g), dh * a * sigmoid(g) * (1 - sigmoid(g))) for the real frames and zeros for
+// every other frame of the first `frames` layout frames.  yprev: dense [B*T, 2N]; dyprev: [frames.., 2N].
+__global__ __launch_bounds__(256) void dgrad_combine_glu_k(const float* __restrict__ part, const bf16_t* __restrict__ yprev,
+                                                           bf16_t* __restrict__ dyprev, long long rows, long long frames,
+                                                           ConvGeom g)
+{
+    const int N = g.Cin, nv = N / 8;
+    const long long total = frames * nv;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const long long f = i / nv;
+        const int c = (int)(i - f * nv) * 8;
+        const int b = (int)(f / g.y_pitch), t = (int)(f - (long long)b * g.y_pitch) - g.y_halo;
+        uint4 oa = make_uint4(0, 0, 0, 0), og = oa;
+        if (b < g.B && t >= 0 && t < g.T) {
+            const long long r = f - g.y_halo;
+            const float4* p0 = reinterpret_cast<const float4*>(part + r * N + c);
+            const float4* p1 = reinterpret_cast<const float4*>(part + (rows + r) * N + c);
+            const float4 a0 = p0[0], a1 = p0[1], b0 = p1[0], b1 = p1[1];
+            const float dh[8] = {a0.x + b0.x, a0.y + b0.y, a0.z + b0.z, a0.w + b0.w,
+                                 a1.x + b1.x, a1.y + b1.y, a1.z + b1.z, a1.w + b1.w};
+            const bf16_t* yr = yprev + ((size_t)b * g.T + t) * 2 * N + c;
+            const uint4 ua = *reinterpret_cast<const uint4*>(yr), ug = *reinterpret_cast<const uint4*>(yr + N);
+            const unsigned* pa = &ua.x; const unsigned* pg = &ug.x;
+            unsigned* qa = &oa.x; unsigned* qg = &og.x;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                unsigned ra = 0, rg = 0;
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const float a = bf16_to_f32((bf16_t)(pa[q] >> (16 * hh)));
+                    const float gg = bf16_to_f32((bf16_t)(pg[q] >> (16 * hh)));
+                    const float d = bf16_to_f32(f32_to_bf16(dh[2 * q + hh]));
+                    const float sg = sigmoidf_(gg);
+                    ra |= (unsigned)f32_to_bf16(d * sg) << (16 * hh);
+                    rg |= (unsigned)f32_to_bf16(d * a * sg * (1.f - sg)) << (16 * hh);
+                }
+                qa[q] = ra;
+                qg[q] = rg;
+            }
+        }
+        bf16_t* o = dyprev + (size_t)f * 2 * N + c;
+        *reinterpret_cast<uint4*>(o) = oa;
+        *reinterpret_cast<uint4*>(o + N) = og;
+    }
+}
+
 // zero rows [r0, r1) and [r2, r3) of a [rows, C] bf16 tensor (C % 8 == 0)
 __global__ __launch_bounds__(256) void zero_rows_k(bf16_t* __restrict__ p, long long r0, long long r1, long long r2,
                                                    long long r3, int C)
@@ -1363,9 +1411,25 @@ bool conv_dgrad_glu_ok(const ConvDesc& d)
            d.T == d.Tp && d.slack >= LAYOUT_SLACK_ZERO && slab_ok(d, 256, 320, d.Cout, d.Tp, d.y_pitch, d.y_halo);
 }
 
-int conv_dgrad_glu(const ConvDesc& g, const void* dy, const void* w, const void* yprev, void* dyprev, hipStream_t st)
+int conv_dgrad_glu(const ConvDesc& g, const void* dy, const void* w, const void* yprev, void* dyprev, void* scratch,
+                   size_t scratch_bytes, hipStream_t st)
 {
     if (!conv_dgrad_glu_ok(g)) return W2L_ERR_SHAPE;
+    if (scratch && dgrad_split_ok(g) && scratch_bytes >= conv_dgrad_scratch_bytes(g)) {
+        // two workgroups per 192x192 tile, then the combining pass applies the GLU backward
+        constexpr int bytes = slab_lds_bytes(192, 192, 256, 2);
+        const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp, N = g.Cin;
+        const long long tiles_m = (F + 191) / 192, rows = tiles_m * 192;
+        const dim3 grid((unsigned)(tiles_m * ((N + 191) / 192)), 2);
+        int rc = set_lds(conv_dgrad_slab_k<192, 192, 256, 2, false>, bytes);
+        if (rc) return rc;
+        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, false>), grid, dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)nullptr, (const bf16_t*)nullptr, (float*)scratch, g);
+        rc = launch_status();
+        if (rc) return rc;
+        const long long frames = (long long)g.B * g.y_pitch + LAYOUT_SLACK_ZERO, work = frames * (N / 8);
+        hipLaunchKernelGGL(dgrad_combine_glu_k, dim3((unsigned)((work + 255) / 256 < 8192 ? (work + 255) / 256 : 8192)), dim3(256), 0, st, (const float*)scratch, (const bf16_t*)yprev, (bf16_t*)dyprev, rows, frames, g);
+        return launch_status();
+    }
     constexpr int BM = 256, BN = 128;
     constexpr int bytes = slab_lds_bytes(BM, BN, 320, 2);
     const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;

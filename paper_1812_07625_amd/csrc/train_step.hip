@@ -56,8 +56,8 @@ struct Plan {
     int n = 0, C = 0, Tlast = 0, tot_stride = 1;
     std::vector<int> Tin, Tout, outch;
     std::vector<size_t> pre, post;  // workspace offsets of conv output (dense) and GLU output (haloed) per layer
-    size_t dlogits = 0, crit_len = 0, gdy[3] = {0, 0, 0}, gdh = 0, ctc = 0, conv = 0, dbias = 0, total = 0;
-    size_t ctc_bytes = 0, conv_bytes = 0;
+    size_t dlogits = 0, crit_len = 0, gdy[3] = {0, 0, 0}, gdh = 0, ctc = 0, conv = 0, dbias = 0, dgs = 0, total = 0;
+    size_t ctc_bytes = 0, conv_bytes = 0, dgs_bytes = 0;
     int status = W2L_OK;
 };
 
@@ -99,6 +99,12 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
         dhmax = g2 > dhmax ? g2 : dhmax;
         const size_t cw = w2l_conv1d_bwd_weight_workspace_bytes(B, t, l.cin, l.cout, l.k, l.stride, dtype);
         p.conv_bytes = cw > p.conv_bytes ? cw : p.conv_bytes;
+        if (i > 0 && L[i - 1].glu) {
+            // fp32 partial sums of a split-reduction data gradient: two copies of dh over the haloed frames, whole tiles
+            const size_t rows = ((size_t)B * (to + 2 * HALO) + 191) / 192 * 192;
+            const size_t sb = 2 * rows * l.cin * 4;
+            p.dgs_bytes = sb > p.dgs_bytes ? sb : p.dgs_bytes;
+        }
         t = to;
     }
     p.Tlast = t;
@@ -113,6 +119,7 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
     int cmax = 0;
     for (int i = 0; i < n; ++i) cmax = L[i].cout > cmax ? L[i].cout : cmax;
     p.dbias = off; off += round_up((size_t)DBIAS_CHUNKS * cmax * 4, 256);
+    p.dgs = off; off += round_up(p.dgs_bytes, 256);
     p.total = off;
     return p;
 }
@@ -265,7 +272,7 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
         if (i > 0) {
             if (layers[i - 1].glu && dtype == W2L_BF16 && dy_dt == W2L_BF16 && conv_dgrad_glu_ok(d)) {
                 if (!wait_wgrad(i + 2)) return W2L_ERR_LAUNCH;  // last reader of the slot dy_{i-1} goes into
-                rc = conv_dgrad_glu(d, dy, weights[i], ws + p.pre[i - 1], ws + p.gdy[(i - 1) % 3], st);
+                rc = conv_dgrad_glu(d, dy, weights[i], ws + p.pre[i - 1], ws + p.gdy[(i - 1) % 3], ws + p.dgs, p.dgs_bytes, st);
                 if (rc) return rc;
                 dy_ready = true;
                 continue;

@@ -300,11 +300,12 @@ def test_train_step_wide_layer_fused_epilogues(P):
     """A model whose second layer has the benchmark's output shape (B*T' = 6000 frames, 1536
     channels) but a short reduction, so that the fp64 oracle stays affordable: the train step then
     takes the kernels the 105M model takes -- forward convolution with the GLU in its epilogue
-    (layer 1), data gradient with the GLU backward of the layer below in its epilogue (layer 2
-    writes dy of layer 1), activation slabs, 256x256 weight-gradient tiles -- and every gradient is
-    compared with the oracle."""
+    (layer 1), data gradient with its reduction split over two workgroups per tile and the GLU
+    backward of the layer below in the combining pass (layer 2 writes dy of layer 1), data gradient
+    with the GLU backward in its own epilogue (layer 1 writes dy of layer 0), activation slabs,
+    256x256 weight-gradient tiles -- and every gradient is compared with the oracle."""
     layers = [dict(k=3, stride=1, cin=16, cout=128, glu=1), dict(k=3, stride=1, cin=64, cout=1536, glu=1),
-              dict(k=5, stride=1, cin=768, cout=128, glu=1), dict(k=1, stride=1, cin=64, cout=29, glu=0)]
+              dict(k=5, stride=1, cin=768, cout=256, glu=1), dict(k=1, stride=1, cin=128, cout=29, glu=0)]
     cfg = W.small_model(33, 8, 700, 750, 16, layers, True, 20, 60)
     check_train_step(run_train_step(P, cfg), oracle_train_step(cfg), "bf16")
 
