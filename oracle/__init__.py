@@ -242,6 +242,36 @@ def ctc_from_logits(z, targets, in_len, tgt_len, blank=0, grad_scale=1.0):
     return loss, lp, dz
 
 
+# ----------------------------------------------------------------------------- ASG
+def asg(em, trans, targets, in_len, tgt_len, grad_scale=1.0, want_terms=False):
+    """ASG criterion (Sec. 2.3 names it; definition: see ``orc_asg``): loss[b] = FCC_b - FAL_b from
+    unnormalised emissions em[B,Tp,C] and transitions trans[C,C] (trans[i,j]: class j followed by
+    class i).  Returns (loss[B], d em [B,Tp,C], d trans [C,C]) with both gradients of
+    grad_scale * sum_b loss_b, and with ``want_terms`` also (FCC[B], FAL[B])."""
+    B, Tp, Cc = em.shape
+    targets = np.asarray(targets, dtype=np.int32).reshape(B, -1)
+    Lmax = targets.shape[1]
+    if Lmax == 0:
+        targets = np.zeros((B, 1), dtype=np.int32)
+        Lmax = 1
+    em, pe = _d(em)
+    trans, ptr = _d(trans)
+    assert trans.shape == (Cc, Cc)
+    targets, pt = _i(targets)
+    in_len, pil = _i(in_len)
+    tgt_len, ptl = _i(tgt_len)
+    dp = lambda a: a.ctypes.data_as(C.POINTER(C.c_double))
+    loss, ge, gt, fcc, fal = np.empty(B), np.empty((B, Tp, Cc)), np.empty((Cc, Cc)), np.empty(B), np.empty(B)
+    rc = _load().orc_asg(pe, ptr, pt, pil, ptl, dp(loss), dp(ge), dp(gt), dp(fcc), dp(fal), B, Tp, Cc, Lmax)
+    if rc != 0:
+        raise ValueError("invalid ASG target or length")
+    ge *= grad_scale
+    gt *= grad_scale
+    if want_terms:
+        return loss, ge, gt, fcc, fal
+    return loss, ge, gt
+
+
 # ----------------------------------------------------------------------------- train step
 def train_step(layers, weights, biases, x, in_len, targets, tgt_len, grad_scale=1.0, blank=0,
                keep_activations=False):

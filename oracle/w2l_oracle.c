@@ -15,8 +15,10 @@
  * x[b][t][c].  All arithmetic is double; nothing is rounded to a narrower type.
  *
  * Parity pins (tests/test_oracle_*.py): brute-force alignment enumeration,
- * closed forms, finite differences, adjoint identities, invariants.  No function
- * in this file is "parity unpinned".
+ * closed forms, finite differences, adjoint identities, invariants.  orc_asg is
+ * "parity unpinned" with respect to the paper (which only cites that criterion's
+ * source; its definition here is a stated reading, pinned to itself by brute force);
+ * no other function in this file is.
  */
 #include <math.h>
 #include <stddef.h>
@@ -359,6 +361,158 @@ int orc_ctc(const double *lp, const int *targets, const int *in_len, const int *
         free(alpha);
         free(beta);
     }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * ASG criterion (AutoSegCriterion; Sec. 2.3 lists it beside CTC and cites Collobert
+ * et al. 2016 for it -- the paper itself prints no formula, so the definition below is
+ * a stated reading of the cited criterion and is "parity unpinned" with respect to the
+ * paper's own text; the tests pin it to this definition by brute-force enumeration,
+ * closed forms and finite differences).
+ *
+ * No blank, no per-frame normalisation.  Inputs per utterance: emissions f[t][c]
+ * (unnormalised scores, T valid frames, C classes), a learned transition matrix
+ * g[i][j] = score of class j at frame t-1 being followed by class i at frame t, and a
+ * target y_0..y_{L-1}.  The score of a frame labelling pi_0..pi_{T-1} is
+ *   sc(pi) = sum_{t=0}^{T-1} f[t][pi_t] + sum_{t=1}^{T-1} g[pi_t][pi_{t-1}]
+ *   FCC = log sum over all C^T labellings of exp(sc(pi))            ("fully connected")
+ *   FAL = log sum over the monotone alignments s_0 = 0, s_{T-1} = L-1,
+ *         s_t - s_{t-1} in {0,1}, pi_t = y_{s_t}, of exp(sc(pi))    ("forced alignment")
+ *   loss = FCC - FAL   (>= 0: every alignment is one of the labellings)
+ * Both by the log-space forward/backward recursions:
+ *   A_0[i] = f[0][i];  A_t[i] = f[t][i] + lse_j( A_{t-1}[j] + g[i][j] );  FCC = lse_i A_{T-1}[i]
+ *   a_0[0] = f[0][y_0]; a_t[s] = f[t][y_s] + lse( a_{t-1}[s] + g[y_s][y_s], a_{t-1}[s-1] + g[y_s][y_{s-1}] )
+ *   FAL = a_{T-1}[L-1]
+ * Gradients are differences of posteriors (occupancies of nodes and of edges):
+ *   dloss/df[t][c]  = P_fcc(pi_t = c) - P_fal(pi_t = c)
+ *   dloss/dg[i][j]  = sum_{t>=1} P_fcc(pi_t = i, pi_{t-1} = j) - the same under FAL
+ * grad_trans is the sum over the batch (added in the order b = 0..B-1).  Frames
+ * t >= T get gradient 0.  No valid alignment (T < L, or L = 0 with T > 0): loss +inf,
+ * zero gradients.  T = 0 and L = 0: loss 0.
+ * fcc_out / fal_out (nullable): the two terms per utterance.
+ * Returns 0, or -1 for a label outside [0,C) or a length outside its range.
+ * ------------------------------------------------------------------------- */
+static double lse_n(const double *v, int n)
+{
+    double m = -INFINITY;
+    for (int i = 0; i < n; ++i) if (v[i] > m) m = v[i];
+    if (m == -INFINITY) return -INFINITY;
+    double sum = 0.0;
+    for (int i = 0; i < n; ++i) sum += exp(v[i] - m);
+    return m + log(sum);
+}
+
+int orc_asg(const double *em, const double *trans, const int *targets, const int *in_len, const int *tgt_len,
+            double *loss, double *grad_em, double *grad_trans, double *fcc_out, double *fal_out,
+            int B, int Tp, int C, int Lmax)
+{
+    for (int b = 0; b < B; ++b) {
+        if (in_len[b] < 0 || in_len[b] > Tp || tgt_len[b] < 0 || tgt_len[b] > Lmax) return -1;
+        for (int i = 0; i < tgt_len[b]; ++i) {
+            const int l = targets[(size_t)b * Lmax + i];
+            if (l < 0 || l >= C) return -1;
+        }
+    }
+    double *gt_b = (double *)calloc((size_t)B * C * C, sizeof(double)); /* per-utterance d loss_b / d g */
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int T = in_len[b], L = tgt_len[b];
+        const double *f = em + IDX3(b, 0, 0, Tp, C);
+        const int *y = targets + (size_t)b * Lmax;
+        double *ge = grad_em ? grad_em + IDX3(b, 0, 0, Tp, C) : NULL;
+        double *gt = gt_b + (size_t)b * C * C;
+        if (ge) for (size_t i = 0; i < (size_t)Tp * C; ++i) ge[i] = 0.0;
+        if (T == 0) {
+            const double fal0 = (L == 0) ? 0.0 : -INFINITY;
+            if (fcc_out) fcc_out[b] = 0.0;
+            if (fal_out) fal_out[b] = fal0;
+            loss[b] = 0.0 - fal0;
+            continue;
+        }
+        double *tmp = (double *)malloc(sizeof(double) * (size_t)C);
+        /* fully connected lattice */
+        double *A = (double *)malloc(sizeof(double) * (size_t)T * C);
+        double *Bt = (double *)malloc(sizeof(double) * (size_t)T * C);
+        for (int i = 0; i < C; ++i) A[i] = f[i];
+        for (int t = 1; t < T; ++t)
+            for (int i = 0; i < C; ++i) {
+                for (int j = 0; j < C; ++j) tmp[j] = A[(size_t)(t - 1) * C + j] + trans[(size_t)i * C + j];
+                A[(size_t)t * C + i] = f[(size_t)t * C + i] + lse_n(tmp, C);
+            }
+        const double fcc = lse_n(A + (size_t)(T - 1) * C, C);
+        for (int j = 0; j < C; ++j) Bt[(size_t)(T - 1) * C + j] = 0.0;
+        for (int t = T - 2; t >= 0; --t)
+            for (int j = 0; j < C; ++j) {
+                for (int i = 0; i < C; ++i)
+                    tmp[i] = trans[(size_t)i * C + j] + f[(size_t)(t + 1) * C + i] + Bt[(size_t)(t + 1) * C + i];
+                Bt[(size_t)t * C + j] = lse_n(tmp, C);
+            }
+        /* forced alignment lattice */
+        double fal = -INFINITY;
+        double *a = NULL, *bb = NULL;
+        const int feasible = (L >= 1 && L <= T);
+        if (feasible) {
+            a = (double *)malloc(sizeof(double) * (size_t)T * L);
+            bb = (double *)malloc(sizeof(double) * (size_t)T * L);
+            for (int s = 0; s < L; ++s) a[s] = -INFINITY;
+            a[0] = f[y[0]];
+            for (int t = 1; t < T; ++t)
+                for (int s = 0; s < L; ++s) {
+                    double v = a[(size_t)(t - 1) * L + s] + trans[(size_t)y[s] * C + y[s]];
+                    if (s >= 1) v = lse2(v, a[(size_t)(t - 1) * L + s - 1] + trans[(size_t)y[s] * C + y[s - 1]]);
+                    a[(size_t)t * L + s] = (v == -INFINITY) ? -INFINITY : v + f[(size_t)t * C + y[s]];
+                }
+            fal = a[(size_t)(T - 1) * L + L - 1];
+            for (int s = 0; s < L; ++s) bb[(size_t)(T - 1) * L + s] = -INFINITY;
+            bb[(size_t)(T - 1) * L + L - 1] = 0.0;
+            for (int t = T - 2; t >= 0; --t)
+                for (int s = 0; s < L; ++s) {
+                    double v = trans[(size_t)y[s] * C + y[s]] + f[(size_t)(t + 1) * C + y[s]] + bb[(size_t)(t + 1) * L + s];
+                    if (s + 1 < L)
+                        v = lse2(v, trans[(size_t)y[s + 1] * C + y[s]] + f[(size_t)(t + 1) * C + y[s + 1]] +
+                                        bb[(size_t)(t + 1) * L + s + 1]);
+                    bb[(size_t)t * L + s] = v;
+                }
+        }
+        if (fcc_out) fcc_out[b] = fcc;
+        if (fal_out) fal_out[b] = fal;
+        loss[b] = fcc - fal;
+        if (feasible && fal != -INFINITY) {
+            /* + fully connected occupancies */
+            for (int t = 0; t < T; ++t)
+                for (int i = 0; i < C; ++i) {
+                    if (ge) ge[(size_t)t * C + i] += exp(A[(size_t)t * C + i] + Bt[(size_t)t * C + i] - fcc);
+                    if (t >= 1)
+                        for (int j = 0; j < C; ++j)
+                            gt[(size_t)i * C + j] += exp(A[(size_t)(t - 1) * C + j] + trans[(size_t)i * C + j] +
+                                                         f[(size_t)t * C + i] + Bt[(size_t)t * C + i] - fcc);
+                }
+            /* - forced alignment occupancies */
+            for (int t = 0; t < T; ++t)
+                for (int s = 0; s < L; ++s) {
+                    const double av = a[(size_t)t * L + s], bv = bb[(size_t)t * L + s];
+                    if (av != -INFINITY && bv != -INFINITY && ge) ge[(size_t)t * C + y[s]] -= exp(av + bv - fal);
+                    if (t >= 1 && bv != -INFINITY) {
+                        const double tail = f[(size_t)t * C + y[s]] + bv - fal;
+                        const double stay = a[(size_t)(t - 1) * L + s];
+                        if (stay != -INFINITY)
+                            gt[(size_t)y[s] * C + y[s]] -= exp(stay + trans[(size_t)y[s] * C + y[s]] + tail);
+                        if (s >= 1 && a[(size_t)(t - 1) * L + s - 1] != -INFINITY)
+                            gt[(size_t)y[s] * C + y[s - 1]] -=
+                                exp(a[(size_t)(t - 1) * L + s - 1] + trans[(size_t)y[s] * C + y[s - 1]] + tail);
+                    }
+                }
+        }
+        free(tmp); free(A); free(Bt); free(a); free(bb);
+    }
+    if (grad_trans) {
+        for (size_t i = 0; i < (size_t)C * C; ++i) grad_trans[i] = 0.0;
+        for (int b = 0; b < B; ++b)
+            for (size_t i = 0; i < (size_t)C * C; ++i) grad_trans[i] += gt_b[(size_t)b * C * C + i];
+    }
+    free(gt_b);
     return 0;
 }
 
