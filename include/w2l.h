@@ -161,6 +161,44 @@ int w2l_ctc_fwd_bwd(const float *input, int is_logits, const int *targets, const
 int w2l_ctc_check_targets_host(const int *targets, const int *in_len, const int *tgt_len,
                                int B, int Tp, int C, int Lmax, int blank);
 
+/* ---- ASG criterion (Sec. 2.3: the original wav2letter AutoSegCriterion, the criterion with
+ * learned parameters; the paper cites Collobert et al. 2016 for it and prints no formula --
+ * the definition below is this library's reading of that criterion) --------------------
+ * No blank and no per-frame normalisation.  For utterance b with T_b = in_len[b] frames,
+ * target y_0..y_{L-1} (L = tgt_len[b]), emissions f = emissions[b] and transitions g:
+ *   score(pi) = sum_{t<T_b} f[t][pi_t] + sum_{1<=t<T_b} g[pi_t][pi_{t-1}]
+ *   FCC  = log sum over all C^T_b frame labellings pi of exp(score(pi))
+ *   FAL  = log sum over the alignments pi_t = y_{s_t}, s_0 = 0, s_{T_b-1} = L-1,
+ *          s_t - s_{t-1} in {0,1}, of exp(score(pi))
+ *   loss[b] = FCC - FAL            (natural log; >= 0)
+ * in:  emissions [B,Tp,C] fp32 (unnormalised scores); trans [C,C] fp32, trans[i*C+j] = g[i][j]
+ *      = score of class j at one frame being followed by class i at the next;
+ *      targets [B,Lmax] int32 (labels in [0,C); equal neighbours are allowed),
+ *      in_len [B] int32 (0..Tp), tgt_len [B] int32 (0..Lmax).
+ * out: loss [B] fp32;
+ *      grad_emissions [B,Tp,C] fp32 = grad_scale * d(sum_b loss_b)/d emissions
+ *        = grad_scale * (P_fcc(pi_t = c) - P_fal(pi_t = c)); rows t >= in_len[b] are 0;
+ *      grad_trans [C,C] fp32 (nullable: not wanted) = grad_scale * d(sum_b loss_b)/d trans
+ *        = grad_scale * sum_b sum_t (P_fcc(pi_t = i, pi_{t-1} = j) - the same under FAL),
+ *        summed over the batch in a fixed order (overwritten, not accumulated).
+ * An utterance with no alignment (L > T_b, or L = 0 with T_b > 0) gets loss +inf and
+ * contributes zero gradients; T_b = 0 and L = 0 gives loss 0.  A label outside [0,C) or a
+ * length outside its range cannot be reported by an asynchronous call: that utterance gets
+ * loss NaN and zero gradients (w2l_asg_check_targets_host() validates host copies).
+ * All device pointers; emissions, targets, grad_emissions 16-byte aligned; workspace of
+ * w2l_asg_workspace_bytes() bytes, 256-byte aligned, owned by the caller.
+ * Limits: C <= 64, Lmax <= 3000.  Errors: W2L_ERR_NULL / _SHAPE / _ALIGN / _WORKSPACE / _LAUNCH. */
+size_t w2l_asg_workspace_bytes(int B, int Tp, int C, int Lmax);
+int w2l_asg_fwd_bwd(const float *emissions, const float *trans, const int *targets,
+                    const int *in_len, const int *tgt_len, float *loss,
+                    float *grad_emissions, float *grad_trans,
+                    int B, int Tp, int C, int Lmax, float grad_scale,
+                    void *workspace, size_t ws_bytes, void *stream);
+/* HOST pointers.  Returns W2L_ERR_TARGET for a label outside [0,C), in_len outside [0,Tp]
+ * or tgt_len outside [0,Lmax]. */
+int w2l_asg_check_targets_host(const int *targets, const int *in_len, const int *tgt_len,
+                               int B, int Tp, int C, int Lmax);
+
 /* ---- one training step: network forward, criterion, backward (Sec. 2.3, Sec. 4.1) --
  * layers[0..n_layers): layer i maps [B,T_i,cin_i] to [B,ceil(T_i/stride_i),cout_i or
  * cout_i/2]; cin_0 is the feature dimension, cin_{i+1} must equal layer i's output

@@ -20,7 +20,8 @@ __all__ = [
     "w2l_conv1d_fwd", "w2l_conv1d_bwd_data", "w2l_conv1d_bwd_weight", "w2l_conv1d_fwd_workspace_bytes",
     "w2l_conv1d_bwd_data_workspace_bytes", "w2l_conv1d_bwd_weight_workspace_bytes", "w2l_glu_fwd", "w2l_glu_bwd",
     "w2l_logsoftmax_fwd", "w2l_logsoftmax_bwd", "w2l_ctc_workspace_bytes", "w2l_ctc_fwd_bwd",
-    "w2l_ctc_check_targets_host", "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_sgd_momentum_step",
+    "w2l_ctc_check_targets_host", "w2l_asg_workspace_bytes", "w2l_asg_fwd_bwd", "w2l_asg_check_targets_host",
+    "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_sgd_momentum_step",
     "w2l_probe_mfma", "raw",
     "workspace",
 ]
@@ -64,6 +65,9 @@ def _load():
         "w2l_ctc_workspace_bytes": (sz, [i] * 4),
         "w2l_ctc_fwd_bwd": (i, [vp, i, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]),
         "w2l_ctc_check_targets_host": (i, [vp, vp, vp, i, i, i, i, i]),
+        "w2l_asg_workspace_bytes": (sz, [i] * 4),
+        "w2l_asg_fwd_bwd": (i, [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, f, vp, sz, vp]),
+        "w2l_asg_check_targets_host": (i, [vp, vp, vp, i, i, i, i]),
         "w2l_probe_mfma": (i, [vp, i, i, vp]),
         "w2l_sgd_momentum_step": (i, [vp, vp, vp, vp, ll, f, f, f, vp]),
         "w2l_train_step_workspace_bytes": (sz, [C.POINTER(w2l_layer), i, i, i, i, i]),
@@ -228,6 +232,32 @@ def w2l_ctc_check_targets_host(targets, in_len, tgt_len, Tp, Cc, blank=0) -> int
     tl = np.ascontiguousarray(tgt_len, dtype=np.int32)
     return raw.w2l_ctc_check_targets_host(t.ctypes.data, il.ctypes.data, tl.ctypes.data, t.shape[0], Tp, Cc,
                                           t.shape[1], blank)
+
+
+def w2l_asg_workspace_bytes(B, Tp, Cc, Lmax) -> int:
+    return raw.w2l_asg_workspace_bytes(B, Tp, Cc, Lmax)
+
+
+def w2l_asg_fwd_bwd(emissions, trans, targets, in_len, tgt_len, loss, grad_emissions, grad_trans=None,
+                    grad_scale=1.0, workspace=None, stream=None):
+    B, Tp, Cc = emissions.shape
+    Lmax = targets.shape[1]
+    wp, wn = _ws(workspace)
+    _check(raw.w2l_asg_fwd_bwd(_p(emissions), _p(trans), _p(targets), _p(in_len), _p(tgt_len), _p(loss),
+                               _p(grad_emissions), _p(grad_trans) if grad_trans is not None else None,
+                               B, Tp, Cc, Lmax, float(grad_scale), wp, wn, _stream(stream)),
+           "w2l_asg_fwd_bwd")
+    return loss, grad_emissions, grad_trans
+
+
+def w2l_asg_check_targets_host(targets, in_len, tgt_len, Tp, Cc) -> int:
+    """numpy int32 host arrays; returns the status instead of raising."""
+    import numpy as np
+    t = np.ascontiguousarray(targets, dtype=np.int32)
+    il = np.ascontiguousarray(in_len, dtype=np.int32)
+    tl = np.ascontiguousarray(tgt_len, dtype=np.int32)
+    return raw.w2l_asg_check_targets_host(t.ctypes.data, il.ctypes.data, tl.ctypes.data, t.shape[0], Tp, Cc,
+                                          t.shape[1])
 
 
 def w2l_probe_mfma(out, blocks, iters, stream=None):

@@ -1,0 +1,653 @@
+// ASG criterion on the GPU (AutoSegCriterion: paper Sec. 2.3 lists it beside CTC as the
+// original wav2letter criterion with learned parameters, and cites its source; the paper
+// prints no formula).  Definition used here: unnormalised emissions f[t][c], a learned
+// transition matrix g[i][j] (class j at frame t-1 followed by class i at frame t), no blank;
+//   loss = FCC - FAL,
+//   FCC = log-sum of exp(score) over all C^T frame labellings          (fully connected lattice)
+//   FAL = the same over the monotone alignments of the target            (forced alignment lattice)
+//   score(pi) = sum_t f[t][pi_t] + sum_{t>=1} g[pi_t][pi_{t-1}]
+// and the gradients are differences of node / edge occupancies of the two lattices.
+//
+// Kernels, all deterministic (no floating-point atomics):
+//   1. asg_lattice: one workgroup per (utterance, lattice, direction).  Forward and backward run
+//      concurrently (backward = the same recursion on reversed time with the transposed
+//      transitions, and for FAL the reversed target), so the serial chain is T_b steps.  Base-2
+//      log domain (hardware exp2/log2), fp32 states relative to a double-precision offset that
+//      absorbs the largest state every 16 frames, "log zero" a large negative finite number.
+//      FAL: one lane per target position, the value of the position to the left by a DPP
+//      wavefront shift; wavefronts overlap by 16 mirrored positions so that nothing crosses a
+//      wavefront boundary inside a block of 16 frames.  FCC: one wavefront, lane = class; a step
+//      reads all C states of the previous frame through lane broadcasts and does a full
+//      log-sum-exp, so any range of transition scores is handled.
+//   2. asg_grad_em: per frame, node occupancies of both lattices, each normalised per frame;
+//      FAL positions are summed per class in a fixed order ((class, position) sort).
+//   3. asg_trans_partial: per (utterance, 64 frames), edge occupancies summed over the frames:
+//      FCC per class pair, FAL per target position (stay / advance).
+//   4. asg_trans_fal_table: per utterance, FAL edge sums scattered into a C x C table in position order.
+//   5. asg_trans_reduce: sum over utterances and frame chunks in a fixed order.
+#include "common.h"
+
+namespace w2l {
+namespace {
+
+constexpr double LOG2E = 1.4426950408889634074;
+constexpr double LN2 = 0.69314718055994530942;
+constexpr float NEG = -1.0e30f;       // log zero: absorbs every finite addend, never turns into NaN
+constexpr float NEG_TEST = -1.0e29f;  // anything below is "log zero"
+constexpr int AHEAD = 16;             // frames of scores held in registers ahead of the recursion; period of the
+                                      // hand-over between wavefronts and of the renormalisation
+constexpr int HALO_LANES = AHEAD;     // lanes of a wavefront that mirror the wavefront on its left
+constexpr int OWN_LANES = 64 - HALO_LANES;
+constexpr int CP = 64;                // pitch of an FCC lattice row; the class limit
+constexpr int GRAD_ROWS = 16;         // frames per asg_grad_em workgroup (4 per wavefront)
+constexpr int CHUNK = 64;             // frames per asg_trans_partial workgroup
+
+struct AsgDims {
+    int B, Tp, C, Lmax;
+    int Sp;   // FAL lattice row pitch = Lmax + 4 (the last four are spare slots); Tp + 1 rows per utterance
+    int nch;  // frame chunks per utterance
+};
+
+// workspace pointers
+struct AsgWs {
+    float *fal[2], *fcc[2];          // lattices per direction: [B][Tp+1][Sp] and [B][Tp+1][CP]
+    double *faloff[2], *fccoff[2];   // [B][Tp+1] offsets of the rows
+    double* terms;                   // [B][2]: FCC, FAL in base-2 units
+    int* status;                     // [B]: 0 live, 1 no alignment, 2 invalid
+    float *izf, *iza;                // [B][Tp] inverse per-frame normalisers of the node occupancies
+    float *partF, *partA, *tabA;     // [B][nch][C*C], [B][nch][2][Lmax], [B][C*C]
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float lse2_log2(float a, float b)
+{
+    const float m = fmaxf(a, b);
+    return m + fast_log2(1.f + fast_exp2(fminf(a, b) - m));
+}
+__device__ __forceinline__ float wave_max_f(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum_f(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+// value of the lane to the left (lane - 1); lane 0 gets `edge`
+__device__ __forceinline__ float from_left_lane(float v, float edge)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(edge), __float_as_int(v), 0x138 /* wave_shr:1 */,
+                                                      0xf, 0xf, false));
+}
+
+// ---- forced alignment lattice, one direction.  Position i (in this direction's order) is held
+// by lane group gi = i / PPT; a_t[i] = f[t][y_i] + lse( a_{t-1}[i] + g_stay[i], a_{t-1}[i-1] + g_adv[i] ).
+// Frame 0 comes out of the recursion itself: "before frame 0" all mass sits on a virtual
+// position -1 that can only advance (into position 0, at no cost).  Mirror lanes, score ring,
+// spare slots and renormalisation as described at the top of the file.
+template <int PPT>
+__device__ __forceinline__ void fal_lattice(const float* __restrict__ em, const float* __restrict__ trans,
+                                            const int* __restrict__ lab, int T, int L, int dir,
+                                            float* __restrict__ lat, double* __restrict__ offs, double* term_out,
+                                            const AsgDims& d, float (*xbuf)[16][HALO_LANES][4], float (*wmax)[16])
+{
+    const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
+    const int gi = wave * OWN_LANES + lane - HALO_LANES;
+    const bool owner = lane >= HALO_LANES;
+    const float log2e = (float)LOG2E;
+    int cls[PPT], slot[PPT];
+    bool cnt[PPT];
+    float gs[PPT], ga[PPT], a[PPT];
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) {
+        const int i = gi * PPT + j;
+        const bool real = i >= 0 && i < L;
+        const int li = dir ? L - 1 - i : i;
+        cls[j] = real ? lab[li] : 0;
+        gs[j] = real ? trans[(size_t)cls[j] * d.C + cls[j]] * log2e : NEG;
+        ga[j] = NEG;
+        if (real && i >= 1) {
+            const int prev = lab[dir ? li + 1 : li - 1];  // the position entered from, in this direction
+            ga[j] = (dir ? trans[(size_t)prev * d.C + cls[j]] : trans[(size_t)cls[j] * d.C + prev]) * log2e;
+        } else if (i == 0) {
+            ga[j] = 0.f;
+        }
+        slot[j] = (real && owner) ? i : d.Lmax + j;
+        cnt[j] = real && owner;
+        a[j] = (i == -1) ? 0.f : NEG;
+    }
+    auto frame = [&](int step) { return dir ? T - 1 - step : step; };
+    float sl[PPT][AHEAD];
+#pragma unroll
+    for (int k = 0; k < AHEAD; ++k) {
+        const int f = frame(k < T ? k : T - 1);
+#pragma unroll
+        for (int j = 0; j < PPT; ++j) sl[j][k] = em[(size_t)f * d.C + cls[j]];
+    }
+    double offset = 0;  // true log2 value = relative value + offset
+    const int nwaves = NT >> 6;
+    const int tblocks = (T + AHEAD - 1) / AHEAD;
+    const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)d.Sp : d.Sp;
+    const float* sptr = em + (size_t)frame(AHEAD - 1 < T ? AHEAD - 1 : T - 1) * d.C;
+    float* rptr = lat + (size_t)frame(0) * d.Sp;
+    float* const spare = lat + (size_t)d.Tp * d.Sp;
+
+    for (int tb = 0; tb < tblocks; ++tb) {
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) {
+            const int step = tb * AHEAD + k;
+            float s[PPT];
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) s[j] = sl[j][k];
+            sptr += (step + AHEAD < T) ? sstep : 0;  // refill this ring slot (past the end: the last frame again)
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) sl[j][k] = sptr[cls[j]];
+            float* const row = step < T ? rptr : spare;
+            rptr += rstep;
+            float carry = from_left_lane(a[PPT - 1], NEG);
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) {
+                const float o = a[j];
+                const float n = fmaf(s[j], log2e, lse2_log2(o + gs[j], carry + ga[j]));
+                carry = o;
+                a[j] = n;
+                row[slot[j]] = n;
+            }
+        }
+        if (tid < AHEAD) {
+            const int step = tb * AHEAD + tid;
+            offs[step < T ? frame(step) : d.Tp] = offset;
+        }
+        // ---- block boundary: refresh the mirror lanes from the left neighbour, renormalise
+        const int par = tb & 1;
+        float m = NEG;
+#pragma unroll
+        for (int j = 0; j < PPT; ++j) m = fmaxf(m, cnt[j] ? a[j] : NEG);
+        m = wave_max_f(m);
+        if (nwaves > 1) {
+            if (lane == 0) wmax[par][wave] = m;
+            if (lane >= OWN_LANES) {
+#pragma unroll
+                for (int j = 0; j < PPT; ++j) xbuf[par][wave][lane - OWN_LANES][j] = a[j];
+            }
+            __syncthreads();
+            if (wave > 0 && !owner) {
+#pragma unroll
+                for (int j = 0; j < PPT; ++j) a[j] = xbuf[par][wave - 1][lane][j];
+            }
+            m = wmax[par][0];
+            for (int w2 = 1; w2 < nwaves; ++w2) m = fmaxf(m, wmax[par][w2]);
+        }
+        if (m > NEG_TEST) {  // uniform over the workgroup
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) a[j] = a[j] > NEG_TEST ? a[j] - m : NEG;
+            offset += (double)m;
+        }
+    }
+    if (dir == 0) {  // FAL = a_{T-1}[L-1], read back from the stored row of the last frame
+        __syncthreads();
+        if (tid == 0) {
+            const float v = L >= 1 ? __builtin_nontemporal_load(lat + (size_t)(T - 1) * d.Sp + (L - 1)) : NEG;
+            const double off = __builtin_nontemporal_load(offs + (T - 1));
+            *term_out = v < NEG_TEST ? -INFINITY : (double)v + off;
+        }
+    }
+}
+
+// ---- fully connected lattice, one direction, one wavefront: lane i holds class i.
+//   A_0[i] = f[0][i];  A_t[i] = f[t][i] + lse_j( A_{t-1}[j] + G[i][j] ),  G = g (forward) or g^T (backward)
+template <int CMAX>
+__device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const float* __restrict__ trans, int T, int dir,
+                                            float* __restrict__ lat, double* __restrict__ offs, double* term_out,
+                                            const AsgDims& d)
+{
+    const int lane = threadIdx.x & 63;
+    const bool real = lane < d.C;
+    const float log2e = (float)LOG2E;
+    float G[CMAX];
+#pragma unroll
+    for (int j = 0; j < CMAX; ++j)
+        G[j] = (real && j < d.C) ? (dir ? trans[(size_t)j * d.C + lane] : trans[(size_t)lane * d.C + j]) * log2e : NEG;
+    auto frame = [&](int step) { return dir ? T - 1 - step : step; };
+    const int cl = real ? lane : 0;
+    float sc[AHEAD];
+#pragma unroll
+    for (int k = 0; k < AHEAD; ++k) sc[k] = em[(size_t)frame(k < T ? k : T - 1) * d.C + cl];
+    double offset = 0;
+    const int tblocks = (T + AHEAD - 1) / AHEAD;
+    const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)CP : CP;
+    const float* sptr = em + (size_t)frame(AHEAD - 1 < T ? AHEAD - 1 : T - 1) * d.C;
+    float* rptr = lat + (size_t)frame(0) * CP;
+    float* const spare = lat + (size_t)d.Tp * CP;
+    float a = NEG;
+    for (int tb = 0; tb < tblocks; ++tb) {
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) {
+            const int step = tb * AHEAD + k;
+            const float s = real ? sc[k] * log2e : NEG;
+            sptr += (step + AHEAD < T) ? sstep : 0;
+            sc[k] = sptr[cl];
+            float* const row = step < T ? rptr : spare;
+            rptr += rstep;
+            // CMAX = 64 recomputes the terms in the second pass instead of keeping 64 more registers
+            float v[CMAX <= 32 ? CMAX : 1];
+            float m = NEG;
+#pragma unroll
+            for (int j = 0; j < CMAX; ++j) {
+                const float x = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), j)) + G[j];
+                if (CMAX <= 32) v[j] = x;
+                m = fmaxf(m, x);
+            }
+            float sum = 0.f;
+#pragma unroll
+            for (int j = 0; j < CMAX; ++j) {
+                const float x = CMAX <= 32 ? v[j] : __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), j)) + G[j];
+                sum += fast_exp2(x - m);
+            }
+            const float n = step == 0 ? s : s + (m + fast_log2(sum));
+            if (dir == 0 && step == T - 1) {  // FCC = lse_i A_{T-1}[i]
+                const float x = real ? n : NEG;
+                const float mx = wave_max_f(x);
+                const float sx = wave_sum_f(fast_exp2(x - mx));
+                if (lane == 0) *term_out = (double)(mx + fast_log2(sx)) + offset;
+            }
+            a = n;
+            row[lane] = real ? n : NEG;
+        }
+        if (lane < AHEAD) {
+            const int step = tb * AHEAD + lane;
+            offs[step < T ? frame(step) : d.Tp] = offset;
+        }
+        const float m = wave_max_f(real ? a : NEG);
+        if (m > NEG_TEST) {
+            a = a > NEG_TEST ? a - m : NEG;
+            offset += (double)m;
+        }
+    }
+}
+
+// grid (4, B): x = 0/1 FAL forward/backward, 2/3 FCC forward/backward
+template <int PPT, int CMAX, int MAXT>
+__global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em, const float* __restrict__ trans,
+                                                    const int* __restrict__ targets, const int* __restrict__ in_len,
+                                                    const int* __restrict__ tgt_len, AsgWs w, AsgDims d)
+{
+    __shared__ float xbuf[2][16][HALO_LANES][4];
+    __shared__ float wmax[2][16];
+    __shared__ int bad;
+    const int kind = blockIdx.x >> 1, dir = blockIdx.x & 1, b = blockIdx.y;
+    const int tid = threadIdx.x, NT = blockDim.x;
+    const int T = in_len[b], L = tgt_len[b];
+    const bool bad_len = T < 0 || T > d.Tp || L < 0 || L > d.Lmax;  // uniform
+    if (tid == 0) bad = 0;
+    __syncthreads();
+    const int* lab = targets + (size_t)b * d.Lmax;
+    if (!bad_len)
+        for (int i = tid; i < L; i += NT) {
+            const int l = lab[i];
+            if (l < 0 || l >= d.C) bad = 1;
+        }
+    __syncthreads();
+    if (bad_len || bad) {
+        if (blockIdx.x == 0 && tid == 0) w.status[b] = 2;
+        return;
+    }
+    if (T == 0 || L == 0 || L > T) {  // nothing to run: no alignment, or no frames and no labels (loss 0)
+        if (blockIdx.x == 0 && tid == 0) {
+            w.status[b] = (T == 0 && L == 0) ? 0 : 1;
+            w.terms[2 * b] = 0.0;
+            w.terms[2 * b + 1] = (T == 0 && L == 0) ? 0.0 : -INFINITY;
+        }
+        return;
+    }
+    if (blockIdx.x == 0 && tid == 0) w.status[b] = 0;
+    const float* emb = em + (size_t)b * d.Tp * d.C;
+    if (kind == 0) {
+        fal_lattice<PPT>(emb, trans, lab, T, L, dir, w.fal[dir] + (size_t)b * (d.Tp + 1) * d.Sp,
+                         w.faloff[dir] + (size_t)b * (d.Tp + 1), w.terms + 2 * b + 1, d, xbuf, wmax);
+    } else {
+        if (tid >= 64) return;
+        fcc_lattice<CMAX>(emb, trans, T, dir, w.fcc[dir] + (size_t)b * (d.Tp + 1) * CP,
+                          w.fccoff[dir] + (size_t)b * (d.Tp + 1), w.terms + 2 * b, d);
+    }
+}
+
+// Node occupancies and the loss.  One workgroup per (16 frames, utterance), one wavefront per frame.
+//   grad_em[t][c] = grad_scale * ( P_fcc(pi_t = c) - P_fal(pi_t = c) )
+__global__ __launch_bounds__(256) void asg_grad_em(const float* __restrict__ em, const int* __restrict__ targets,
+                                                   const int* __restrict__ in_len, const int* __restrict__ tgt_len,
+                                                   float* __restrict__ loss, float* __restrict__ grad, AsgWs w, AsgDims d,
+                                                   float grad_scale)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int b = blockIdx.y, t0 = blockIdx.x * GRAD_ROWS;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float* gb = grad + (size_t)b * d.Tp * d.C;
+    const int status = w.status[b];
+    const int T = in_len[b];
+    const double fcc2 = w.terms[2 * b], fal2 = w.terms[2 * b + 1];
+    if (blockIdx.x == 0 && tid == 0)
+        loss[b] = status == 2 ? NAN : (status == 1 ? INFINITY : (float)((fcc2 - fal2) * LN2));
+    if (status != 0 || T <= 0) {
+        for (int e = tid; e < GRAD_ROWS * d.C; e += 256) {
+            const int t = t0 + e / d.C;
+            if (t < d.Tp) gb[(size_t)t0 * d.C + e] = 0.f;
+        }
+        return;
+    }
+    const int L = tgt_len[b];
+    int* lab = reinterpret_cast<int*>(smem_raw);  // [Lmax]
+    int* order = lab + d.Lmax;                    // [Lmax] positions sorted by (class, position)
+    int* cstart = order + d.Lmax;                 // [C+1]
+    float* ebuf = reinterpret_cast<float*>(cstart + d.C + 1) + (size_t)wave * d.Sp;  // [4][Sp]
+    for (int i = tid; i < L; i += 256) lab[i] = targets[(size_t)b * d.Lmax + i];
+    for (int c = tid; c <= d.C; c += 256) cstart[c] = 0;
+    __syncthreads();
+    for (int i = tid; i < L; i += 256) atomicAdd(&cstart[lab[i] + 1], 1);  // integer: order-independent
+    __syncthreads();
+    if (tid == 0)
+        for (int c = 0; c < d.C; ++c) cstart[c + 1] += cstart[c];
+    __syncthreads();
+    for (int i = tid; i < L; i += 256) {
+        const int c = lab[i];
+        int r = cstart[c];
+        for (int j = 0; j < i; ++j) r += (lab[j] == c);
+        order[r] = i;
+    }
+    __syncthreads();
+
+    const float log2e = (float)LOG2E;
+    const size_t rowb = (size_t)b * (d.Tp + 1);
+    for (int rr = wave; rr < GRAD_ROWS; rr += 4) {
+        const int t = t0 + rr;
+        if (t >= d.Tp) break;
+        float* grow = gb + (size_t)t * d.C;
+        if (t >= T) {
+            for (int c = lane; c < d.C; c += 64) grow[c] = 0.f;
+            continue;
+        }
+        const float* erow = em + ((size_t)b * d.Tp + t) * d.C;
+        // fully connected: lane = class
+        const float shiftF = (float)(w.fccoff[0][rowb + t] + w.fccoff[1][rowb + t] - fcc2);
+        float pf = 0.f;
+        if (lane < d.C) {
+            const float av = w.fcc[0][(rowb + t) * CP + lane], bv = w.fcc[1][(rowb + t) * CP + lane];
+            if (av > NEG_TEST && bv > NEG_TEST) pf = fast_exp2((av + bv) + (shiftF - erow[lane] * log2e));
+        }
+        const float zf = wave_sum_f(pf);
+        // forced alignment: lanes stride over the positions (backward rows are stored in reversed order)
+        const float shiftA = (float)(w.faloff[0][rowb + t] + w.faloff[1][rowb + t] - fal2);
+        const float* ar = w.fal[0] + (rowb + t) * d.Sp;
+        const float* br = w.fal[1] + (rowb + t) * d.Sp;
+        float za = 0.f;
+        for (int s = lane; s < L; s += 64) {
+            const float av = ar[s], bv = br[L - 1 - s];
+            float e = 0.f;
+            if (av > NEG_TEST && bv > NEG_TEST) e = fast_exp2((av + bv) + (shiftA - erow[lab[s]] * log2e));
+            ebuf[s] = e;
+            za += e;
+        }
+        za = wave_sum_f(za);
+        const float izf = zf > 0.f ? 1.f / zf : 0.f, iza = za > 0.f ? 1.f / za : 0.f;
+        if (lane == 0) {
+            w.izf[(size_t)b * d.Tp + t] = izf;
+            w.iza[(size_t)b * d.Tp + t] = iza;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane < d.C) {
+            float g = 0.f;
+            for (int q = cstart[lane]; q < cstart[lane + 1]; ++q) g += ebuf[order[q]];
+            grow[lane] = grad_scale * (pf * izf - g * iza);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Edge occupancies summed over a chunk of frames.  Workgroup (chunk, utterance).
+//   FCC: partF[i*C+j] = sum_t P_fcc(pi_t = i, pi_{t-1} = j)
+//   FAL: partA[0][s]  = sum_t P_fal(position s at t-1 and at t),  partA[1][s] = sum_t P_fal(s-1 at t-1, s at t)
+// An edge's weight is exp2( fwd_{t-1}[source] + g + bwd_t[destination] - total ), normalised by the
+// node normaliser of frame t (the edge occupancies of a frame sum to the same 1).
+__global__ __launch_bounds__(256) void asg_trans_partial(const float* __restrict__ trans, const int* __restrict__ targets,
+                                                         const int* __restrict__ in_len, const int* __restrict__ tgt_len,
+                                                         AsgWs w, AsgDims d)
+{
+    __shared__ float sA[CHUNK + 1][CP];  // forward rows t0-1 .. t0+CHUNK-1
+    __shared__ float sB[CHUNK][CP];      // backward rows t0 .. t0+CHUNK-1
+    __shared__ float wF[CHUNK], wA[CHUNK];
+    const int ch = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int C2 = d.C * d.C;
+    float* pF = w.partF + ((size_t)b * d.nch + ch) * C2;
+    float* pA = w.partA + ((size_t)b * d.nch + ch) * 2 * d.Lmax;
+    const int T = in_len[b], L = tgt_len[b];
+    const int t0 = ch * CHUNK;
+    const int tlo = t0 < 1 ? 1 : t0, thi = t0 + CHUNK < T ? t0 + CHUNK : T;  // frames [tlo, thi)
+    if (w.status[b] != 0 || tlo >= thi) {
+        for (int p = tid; p < C2; p += 256) pF[p] = 0.f;
+        for (int s = tid; s < 2 * d.Lmax; s += 256) pA[s] = 0.f;
+        return;
+    }
+    const size_t rowb = (size_t)b * (d.Tp + 1);
+    const double fcc2 = w.terms[2 * b], fal2 = w.terms[2 * b + 1];
+    for (int e = tid; e < (CHUNK + 1) * CP; e += 256) {
+        const int r = e / CP, c = e - r * CP, t = t0 - 1 + r;
+        sA[r][c] = (t >= 0 && t < T && c < d.C) ? w.fcc[0][(rowb + t) * CP + c] : NEG;
+    }
+    for (int e = tid; e < CHUNK * CP; e += 256) {
+        const int r = e / CP, c = e - r * CP, t = t0 + r;
+        sB[r][c] = (t < T && c < d.C) ? w.fcc[1][(rowb + t) * CP + c] : NEG;
+    }
+    if (tid < CHUNK) {
+        const int t = t0 + tid;
+        float f = NEG, a = NEG;
+        if (t >= tlo && t < thi) {
+            const float izf = w.izf[(size_t)b * d.Tp + t], iza = w.iza[(size_t)b * d.Tp + t];
+            if (izf > 0.f) f = (float)(w.fccoff[0][rowb + t - 1] + w.fccoff[1][rowb + t] - fcc2) + fast_log2(izf);
+            if (iza > 0.f) a = (float)(w.faloff[0][rowb + t - 1] + w.faloff[1][rowb + t] - fal2) + fast_log2(iza);
+        }
+        wF[tid] = f;
+        wA[tid] = a;
+    }
+    __syncthreads();
+    const float log2e = (float)LOG2E;
+    for (int p = tid; p < C2; p += 256) {
+        const int i = p / d.C, j = p - i * d.C;
+        const float g2 = trans[p] * log2e;
+        float acc = 0.f;
+        for (int r = tlo - t0; r < thi - t0; ++r) acc += fast_exp2((sA[r][j] + sB[r][i]) + (g2 + wF[r]));
+        pF[p] = acc;
+    }
+    const int* lab = targets + (size_t)b * d.Lmax;
+    for (int s = tid; s < d.Lmax; s += 256) {
+        float stay = 0.f, adv = 0.f;
+        if (s < L) {
+            const int c = lab[s];
+            const float gs = trans[(size_t)c * d.C + c] * log2e;
+            const float ga = s >= 1 ? trans[(size_t)c * d.C + lab[s - 1]] * log2e : NEG;
+            for (int t = tlo; t < thi; ++t) {
+                const float* ar = w.fal[0] + (rowb + t - 1) * d.Sp;
+                const float bv = w.fal[1][(rowb + t) * d.Sp + (L - 1 - s)] + wA[t - t0];
+                stay += fast_exp2((ar[s] + bv) + gs);
+                if (s >= 1) adv += fast_exp2((ar[s - 1] + bv) + ga);
+            }
+        }
+        pA[s] = stay;
+        pA[d.Lmax + s] = adv;
+    }
+}
+
+// Per utterance: FAL edge sums (added over the chunks in order) scattered into a C x C table;
+// entry (i, j) adds its positions in increasing order.
+__global__ __launch_bounds__(256) void asg_trans_fal_table(const int* __restrict__ targets, const int* __restrict__ tgt_len,
+                                                           AsgWs w, AsgDims d)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int b = blockIdx.x, tid = threadIdx.x, C2 = d.C * d.C;
+    float* tab = w.tabA + (size_t)b * C2;
+    if (w.status[b] != 0) {
+        for (int p = tid; p < C2; p += 256) tab[p] = 0.f;
+        return;
+    }
+    const int L = tgt_len[b];
+    int* lab = reinterpret_cast<int*>(smem_raw);           // [Lmax]
+    float* stay = reinterpret_cast<float*>(lab + d.Lmax);  // [Lmax]
+    float* adv = stay + d.Lmax;                            // [Lmax]
+    for (int s = tid; s < L; s += 256) {
+        lab[s] = targets[(size_t)b * d.Lmax + s];
+        float x = 0.f, y = 0.f;
+        for (int ch = 0; ch < d.nch; ++ch) {
+            const float* pA = w.partA + ((size_t)b * d.nch + ch) * 2 * d.Lmax;
+            x += pA[s];
+            y += pA[d.Lmax + s];
+        }
+        stay[s] = x;
+        adv[s] = y;
+    }
+    __syncthreads();
+    for (int p = tid; p < C2; p += 256) {
+        const int i = p / d.C, j = p - i * d.C;
+        float acc = 0.f;
+        for (int s = 0; s < L; ++s) {
+            if (lab[s] != i) continue;
+            if (i == j) acc += stay[s];
+            if (s >= 1 && lab[s - 1] == j) acc += adv[s];
+        }
+        tab[p] = acc;
+    }
+}
+
+//   grad_trans[p] = grad_scale * ( sum_{b, chunk} partF - sum_b tabA ), added in that fixed order
+__global__ __launch_bounds__(256) void asg_trans_reduce(float* __restrict__ grad_trans, AsgWs w, AsgDims d, float grad_scale)
+{
+    const int p = blockIdx.x * 256 + threadIdx.x, C2 = d.C * d.C;
+    if (p >= C2) return;
+    float f = 0.f, a = 0.f;
+    for (int q = 0; q < d.B * d.nch; ++q) f += w.partF[(size_t)q * C2 + p];
+    for (int b = 0; b < d.B; ++b) a += w.tabA[(size_t)b * C2 + p];
+    grad_trans[p] = grad_scale * (f - a);
+}
+
+struct WsLayout { size_t fal[2], fcc[2], faloff[2], fccoff[2], terms, status, izf, iza, partF, partA, tabA, total; };
+WsLayout ws_layout(int B, int Tp, int C, int Lmax)
+{
+    WsLayout w;
+    size_t off = 0;
+    const size_t rows = (size_t)B * (Tp + 1);
+    const int nch = (Tp + CHUNK - 1) / CHUNK;
+    for (int q = 0; q < 2; ++q) { w.fal[q] = off; off += round_up(rows * ((size_t)Lmax + 4) * 4, 256); }
+    for (int q = 0; q < 2; ++q) { w.fcc[q] = off; off += round_up(rows * CP * 4, 256); }
+    for (int q = 0; q < 2; ++q) { w.faloff[q] = off; off += round_up(rows * 8, 256); }
+    for (int q = 0; q < 2; ++q) { w.fccoff[q] = off; off += round_up(rows * 8, 256); }
+    w.terms = off; off += round_up((size_t)B * 16, 256);
+    w.status = off; off += round_up((size_t)B * 4, 256);
+    w.izf = off; off += round_up((size_t)B * Tp * 4, 256);
+    w.iza = off; off += round_up((size_t)B * Tp * 4, 256);
+    w.partF = off; off += round_up((size_t)B * nch * C * C * 4, 256);
+    w.partA = off; off += round_up((size_t)B * nch * 2 * Lmax * 4, 256);
+    w.tabA = off; off += round_up((size_t)B * C * C * 4, 256);
+    w.total = off;
+    return w;
+}
+
+template <int PPT>
+void launch_lattice(int cmax, dim3 grid, dim3 block, hipStream_t st, const float* em, const float* trans, const int* targets,
+                    const int* in_len, const int* tgt_len, const AsgWs& w, const AsgDims& d)
+{
+    // the register budget follows the workgroup size: up to four wavefronts get a whole SIMD each
+    if (block.x <= 256) {
+        if (cmax <= 32) hipLaunchKernelGGL((asg_lattice<PPT, 32, 256>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d);
+        else hipLaunchKernelGGL((asg_lattice<PPT, 64, 256>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d);
+    } else {
+        if (cmax <= 32) hipLaunchKernelGGL((asg_lattice<PPT, 32, 1024>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d);
+        else hipLaunchKernelGGL((asg_lattice<PPT, 64, 1024>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d);
+    }
+}
+
+}  // namespace
+}  // namespace w2l
+
+using namespace w2l;
+
+extern "C" size_t w2l_asg_workspace_bytes(int B, int Tp, int C, int Lmax)
+{
+    if (B <= 0 || Tp <= 0 || C <= 0 || C > CP || Lmax <= 0) return 0;
+    return ws_layout(B, Tp, C, Lmax).total;
+}
+
+extern "C" int w2l_asg_check_targets_host(const int* targets, const int* in_len, const int* tgt_len, int B, int Tp,
+                                          int C, int Lmax)
+{
+    if (!targets || !in_len || !tgt_len) return W2L_ERR_NULL;
+    if (B <= 0 || Tp <= 0 || C <= 0 || Lmax <= 0) return W2L_ERR_SHAPE;
+    for (int b = 0; b < B; ++b) {
+        if (in_len[b] < 0 || in_len[b] > Tp || tgt_len[b] < 0 || tgt_len[b] > Lmax) return W2L_ERR_TARGET;
+        for (int i = 0; i < tgt_len[b]; ++i) {
+            const int l = targets[(size_t)b * Lmax + i];
+            if (l < 0 || l >= C) return W2L_ERR_TARGET;
+        }
+    }
+    return W2L_OK;
+}
+
+extern "C" int w2l_asg_fwd_bwd(const float* emissions, const float* trans, const int* targets, const int* in_len,
+                               const int* tgt_len, float* loss, float* grad_emissions, float* grad_trans, int B, int Tp,
+                               int C, int Lmax, float grad_scale, void* workspace, size_t ws_bytes, void* stream)
+{
+    if (!emissions || !trans || !targets || !in_len || !tgt_len || !loss || !grad_emissions) return W2L_ERR_NULL;
+    if (B <= 0 || Tp <= 0 || C <= 0 || C > CP || Lmax <= 0 || Lmax > 3000 || B > 65535) return W2L_ERR_SHAPE;
+    if (!aligned16(emissions) || !aligned16(targets) || !aligned16(grad_emissions)) return W2L_ERR_ALIGN;
+    const WsLayout l = ws_layout(B, Tp, C, Lmax);
+    if (!workspace || ws_bytes < l.total || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return W2L_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    AsgDims d{B, Tp, C, Lmax, Lmax + 4, (Tp + CHUNK - 1) / CHUNK};
+    AsgWs w;
+    for (int q = 0; q < 2; ++q) {
+        w.fal[q] = reinterpret_cast<float*>(ws + l.fal[q]);
+        w.fcc[q] = reinterpret_cast<float*>(ws + l.fcc[q]);
+        w.faloff[q] = reinterpret_cast<double*>(ws + l.faloff[q]);
+        w.fccoff[q] = reinterpret_cast<double*>(ws + l.fccoff[q]);
+    }
+    w.terms = reinterpret_cast<double*>(ws + l.terms);
+    w.status = reinterpret_cast<int*>(ws + l.status);
+    w.izf = reinterpret_cast<float*>(ws + l.izf);
+    w.iza = reinterpret_cast<float*>(ws + l.iza);
+    w.partF = reinterpret_cast<float*>(ws + l.partF);
+    w.partA = reinterpret_cast<float*>(ws + l.partA);
+    w.tabA = reinterpret_cast<float*>(ws + l.tabA);
+
+    const size_t lds_em = (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (Lmax + 4);
+    const size_t lds_tab = (size_t)4 * 3 * Lmax;
+    if (lds_em > 160 * 1024) return W2L_ERR_SHAPE;
+    if (lds_em > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)asg_grad_em, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_em);
+        if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }
+    }
+    // one lane per target position, OWN_LANES of them per wavefront; more positions per lane only
+    // when 16 wavefronts cannot cover Lmax
+    const int ppt = Lmax <= 16 * OWN_LANES ? 1 : (Lmax <= 32 * OWN_LANES ? 2 : 4);
+    const int nt = 64 * (((Lmax + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);
+    if (nt > 1024) return W2L_ERR_SHAPE;
+    const dim3 g1(4, B), b1(nt);
+    if (ppt == 1) launch_lattice<1>(C, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (ppt == 2) launch_lattice<2>(C, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else launch_lattice<4>(C, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    int rc = launch_status();
+    if (rc) return rc;
+    hipLaunchKernelGGL(asg_grad_em, dim3((Tp + GRAD_ROWS - 1) / GRAD_ROWS, B), dim3(256), lds_em, st, emissions, targets,
+                       in_len, tgt_len, loss, grad_emissions, w, d, grad_scale);
+    rc = launch_status();
+    if (rc || !grad_trans) return rc;
+    hipLaunchKernelGGL(asg_trans_partial, dim3(d.nch, B), dim3(256), 0, st, trans, targets, in_len, tgt_len, w, d);
+    rc = launch_status();
+    if (rc) return rc;
+    hipLaunchKernelGGL(asg_trans_fal_table, dim3(B), dim3(256), lds_tab, st, targets, tgt_len, w, d);
+    rc = launch_status();
+    if (rc) return rc;
+    hipLaunchKernelGGL(asg_trans_reduce, dim3((C * C + 255) / 256), dim3(256), 0, st, grad_trans, w, d, grad_scale);
+    return launch_status();
+}

@@ -1,7 +1,7 @@
 """Seeded synthetic inputs for the five benchmark/parity configurations.
 
 This module only draws random numbers and lays them out; it holds none of the
-method's arithmetic (no convolution, GLU, softmax or CTC) and is the one piece
+method's arithmetic (no convolution, GLU, softmax, CTC or ASG) and is the one piece
 shared by the oracle-side and the GPU-side callers.  Everything is numpy on the
 host.  Shapes follow the paper's workload (Sec. 4.1: log-mel feature frames at
 10 ms, grapheme targets, length-sorted -- hence narrow -- utterance lengths, an
@@ -156,6 +156,31 @@ def config2(seed=2, B=32, T=750, Cc=NUM_CLASSES, in_lo=600, in_hi=750, l_lo=50, 
         targets[b, :tgt_len[b]] = lab
     return dict(logits=logits, in_len=in_len, targets=targets, tgt_len=tgt_len, B=B, T=T, C=Cc,
                 blank=BLANK)
+
+
+def asg_batch(seed=12, B=32, T=750, Cc=NUM_CLASSES - 1, in_lo=600, in_hi=750, l_lo=50, l_hi=200, em_std=np.sqrt(2.0),
+              trans_std=0.5, allow_repeats=False):
+    """ASG criterion alone, fp32, in the shape of config 2 without the blank class: emissions ~
+    N(0, em_std^2); transitions ~ N(0, trans_std^2); input lengths U[in_lo,in_hi]; target lengths
+    U[l_lo,l_hi] clipped to the input length; labels U[0,C-1], redrawn where equal to the label
+    before them unless ``allow_repeats`` (the criterion's own preprocessing replaces letter repeats
+    by repetition symbols, so neighbours differ).  Draw order: input lengths, emissions,
+    transitions, target lengths, targets."""
+    rng = np.random.default_rng(seed)
+    in_len = rng.integers(in_lo, in_hi + 1, size=B).astype(np.int32)
+    em = (rng.standard_normal(size=(B, T, Cc)) * em_std).astype(np.float32)
+    trans = (rng.standard_normal(size=(Cc, Cc)) * trans_std).astype(np.float32)
+    tgt_len = np.minimum(rng.integers(l_lo, l_hi + 1, size=B), np.maximum(in_len, 1)).astype(np.int32)
+    Lmax = int(max(1, tgt_len.max()))
+    targets = np.zeros((B, Lmax), dtype=np.int32)
+    for b in range(B):
+        lab = rng.integers(0, Cc, size=tgt_len[b])
+        if not allow_repeats and Cc > 1:
+            for i in range(1, len(lab)):
+                while lab[i] == lab[i - 1]:
+                    lab[i] = rng.integers(0, Cc)
+        targets[b, :tgt_len[b]] = lab
+    return dict(emissions=em, trans=trans, in_len=in_len, targets=targets, tgt_len=tgt_len, B=B, T=T, C=Cc)
 
 
 def config3(seed=3, B=16):
