@@ -158,6 +158,15 @@ def main():
     cells = int(np.sum(c2["in_len"].astype(np.int64) * (2 * c2["tgt_len"].astype(np.int64) + 1)))
     ctc_bytes = 2 * 32 * 750 * 29 * 4 + 2 * 4 * cells
 
+    # ASG alone at the same criterion shape without the blank class (B=32, T=750, C=28)
+    a2 = W.asg_batch()
+    ae, at, atg, ai, al = (to_dev(a2[k]) for k in ("emissions", "trans", "targets", "in_len", "tgt_len"))
+    aws = P.workspace(P.w2l_asg_workspace_bytes(a2["B"], a2["T"], a2["C"], a2["targets"].shape[1]))
+    aloss, age, agt = empty((a2["B"],)), empty(a2["emissions"].shape), empty(a2["trans"].shape)
+    t_asg = event_time_ms(lambda: P.w2l_asg_fwd_bwd(ae, at, atg, ai, al, aloss, age, agt, 1.0, aws), args.kernel_iters)
+    a_cells = int(np.sum(a2["in_len"].astype(np.int64) * (a2["tgt_len"].astype(np.int64) + a2["C"])))
+    asg_bytes = 2 * a2["emissions"].size * 4 + 2 * 2 * 4 * a_cells   # emissions in, gradient out; lattices written and read once
+
     # optimiser step over all parameters of the model as one flat fp32 buffer (not part of `value`:
     # the metric is forward + backward)
     npar = W.num_params(layers)
@@ -217,6 +226,10 @@ def main():
                                      "frac_hbm_peak": ctc_bytes / (t_ctc * 1e-3) / PEAK_HBM,
                                      "serial_steps": int(c2["in_len"].max()),
                                      "us_per_serial_step": t_ctc * 1e3 / int(c2["in_len"].max())},
+            "asg_fwd_bwd(B=32,T=750,C=28)": {"ms": t_asg, "GBps": asg_bytes / (t_asg * 1e-3) / 1e9,
+                                             "frac_hbm_peak": asg_bytes / (t_asg * 1e-3) / PEAK_HBM,
+                                             "serial_steps": int(a2["in_len"].max()),
+                                             "us_per_serial_step": t_asg * 1e3 / int(a2["in_len"].max())},
             "sgd_momentum_step(all %d params)" % npar: {"ms": t_sgd, "GBps": sgd_bytes / (t_sgd * 1e-3) / 1e9,
                                                          "frac_hbm_peak": sgd_bytes / (t_sgd * 1e-3) / PEAK_HBM},
         },

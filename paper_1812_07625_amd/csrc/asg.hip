@@ -21,10 +21,11 @@
 //      log-sum-exp, so any range of transition scores is handled.
 //   2. asg_grad_em: per frame, node occupancies of both lattices, each normalised per frame;
 //      FAL positions are summed per class in a fixed order ((class, position) sort).
-//   3. asg_trans_partial: per (utterance, 64 frames), edge occupancies summed over the frames:
+//   3. asg_trans_partial: per (utterance, 32 frames), edge occupancies summed over the frames:
 //      FCC per class pair, FAL per target position (stay / advance).
-//   4. asg_trans_fal_table: per utterance, FAL edge sums scattered into a C x C table in position order.
-//   5. asg_trans_reduce: sum over utterances and frame chunks in a fixed order.
+//   4. asg_trans_utt: per utterance, FCC edge sums minus FAL edge sums as a C x C table (the FAL
+//      sums are scattered with 64-bit fixed-point integer atomics, which are order-independent).
+//   5. asg_trans_reduce: sum over utterances in a fixed order.
 #include "common.h"
 
 namespace w2l {
@@ -40,7 +41,7 @@ constexpr int HALO_LANES = AHEAD;     // lanes of a wavefront that mirror the wa
 constexpr int OWN_LANES = 64 - HALO_LANES;
 constexpr int CP = 64;                // pitch of an FCC lattice row; the class limit
 constexpr int GRAD_ROWS = 16;         // frames per asg_grad_em workgroup (4 per wavefront)
-constexpr int CHUNK = 64;             // frames per asg_trans_partial workgroup
+constexpr int CHUNK = 32;             // frames per asg_trans_partial workgroup
 
 struct AsgDims {
     int B, Tp, C, Lmax;
@@ -55,7 +56,7 @@ struct AsgWs {
     double* terms;                   // [B][2]: FCC, FAL in base-2 units
     int* status;                     // [B]: 0 live, 1 no alignment, 2 invalid
     float *izf, *iza;                // [B][Tp] inverse per-frame normalisers of the node occupancies
-    float *partF, *partA, *tabA;     // [B][nch][C*C], [B][nch][2][Lmax], [B][C*C]
+    float *partF, *partA, *tabD;     // [B][nch][C*C], [B][nch][2][Lmax], [B][C*C] (per-utterance d loss / d g)
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -82,6 +83,36 @@ __device__ __forceinline__ float from_left_lane(float v, float edge)
 {
     return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(edge), __float_as_int(v), 0x138 /* wave_shr:1 */,
                                                       0xf, 0xf, false));
+}
+
+// Wavefront reductions on the DPP path (no LDS traffic, no wait counters): four row shifts
+// leave each row's result in its lane 15, two row broadcasts carry it to lane 63, one lane
+// read hands it to every lane.  Lanes a step does not reach keep `old` (the identity).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f(float old, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_max_bcast(float v)
+{
+    v = fmaxf(v, dpp_f<0x111, 0xf>(v, v));  // row_shr:1
+    v = fmaxf(v, dpp_f<0x112, 0xf>(v, v));  // row_shr:2
+    v = fmaxf(v, dpp_f<0x114, 0xf>(v, v));  // row_shr:4
+    v = fmaxf(v, dpp_f<0x118, 0xf>(v, v));  // row_shr:8
+    v = fmaxf(v, dpp_f<0x142, 0xa>(v, v));  // row_bcast:15 into rows 1 and 3
+    v = fmaxf(v, dpp_f<0x143, 0xc>(v, v));  // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_min_bcast(float v) { return -wave_max_bcast(-v); }
+__device__ __forceinline__ float wave_sum_bcast(float v)
+{
+    v += dpp_f<0x111, 0xf>(0.f, v);
+    v += dpp_f<0x112, 0xf>(0.f, v);
+    v += dpp_f<0x114, 0xf>(0.f, v);
+    v += dpp_f<0x118, 0xf>(0.f, v);
+    v += dpp_f<0x142, 0xa>(0.f, v);
+    v += dpp_f<0x143, 0xc>(0.f, v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // ---- forced alignment lattice, one direction.  Position i (in this direction's order) is held
@@ -198,31 +229,116 @@ __device__ __forceinline__ void fal_lattice(const float* __restrict__ em, const 
     }
 }
 
-// ---- fully connected lattice, one direction, one wavefront: lane i holds class i.
+// ---- fully connected lattice, one direction, one wavefront.
 //   A_0[i] = f[0][i];  A_t[i] = f[t][i] + lse_j( A_{t-1}[j] + G[i][j] ),  G = g (forward) or g^T (backward)
+// Up to 32 classes: two lanes per class (lane = 2 * class + half), each taking half of the source
+// classes j, combined with one DPP lane swap; up to 64 classes: one lane per class.  A step
+// publishes the states through a small LDS array and reads the sources back as broadcast 16-byte
+// reads (one wavefront: LDS operations execute in order, no barrier needed).
+// Two recursions write the same rows (base-2 log of the state relative to the row's offset):
+//  * linear, when the transition scores span at most LINEAR_RANGE bits: the states are kept as
+//    plain numbers, a step is the matrix-vector product  n[i] = 2^(f'[i]) * sum_j E[i][j] a[j]  with
+//    E = 2^(G - max G) <= 1 and f' = f[t] - max_i f[t][i]; every second step the result is scaled
+//    by the power of two that brings the largest input state to [0.5, 1) -- exact, and tracked in
+//    the offset.  Under that bound a step changes the largest state by a factor between
+//    2^-(LINEAR_RANGE+1) and 2^7, so between two scalings the largest state stays above 2^-62:
+//    what is flushed to zero is below 2^-64 of the largest state and could regain at most
+//    2^LINEAR_RANGE of that in later frames;
+//  * log domain otherwise: a full log-sum-exp per state and step (one exp2 per source class), which
+//    takes any range of scores.
+constexpr float LINEAR_RANGE = 30.f;  // bits, about 21 nats
+
+__device__ __forceinline__ float swap_pair(float v)  // value of lane ^ 1
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1 /* quad_perm:[1,0,3,2] */, 0xf, 0xf, false));
+}
+
 template <int CMAX>
 __device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const float* __restrict__ trans, int T, int dir,
                                             float* __restrict__ lat, double* __restrict__ offs, double* term_out,
-                                            const AsgDims& d)
+                                            const AsgDims& d, float* abuf)
 {
+    constexpr int LPC = CMAX <= 32 ? 2 : 1;  // lanes per class
+    constexpr int NSRC = CMAX / LPC;         // source classes per lane
     const int lane = threadIdx.x & 63;
-    const bool real = lane < d.C;
+    const int ci = lane / LPC, half = lane % LPC;
+    const bool real = ci < d.C;
+    const bool writer = real && half == 0;
     const float log2e = (float)LOG2E;
-    float G[CMAX];
+    float G[NSRC];
+    float gmax = NEG, gmin = -NEG;
 #pragma unroll
-    for (int j = 0; j < CMAX; ++j)
-        G[j] = (real && j < d.C) ? (dir ? trans[(size_t)j * d.C + lane] : trans[(size_t)lane * d.C + j]) * log2e : NEG;
+    for (int jj = 0; jj < NSRC; ++jj) {
+        const int j = half * NSRC + jj;
+        const bool on = real && j < d.C;
+        G[jj] = on ? (dir ? trans[(size_t)j * d.C + ci] : trans[(size_t)ci * d.C + j]) * log2e : NEG;
+        gmax = on ? fmaxf(gmax, G[jj]) : gmax;
+        gmin = on ? fminf(gmin, G[jj]) : gmin;
+    }
+    gmax = wave_max_bcast(gmax);
+    gmin = wave_min_bcast(gmin);
+    const bool linear = gmax - gmin <= LINEAR_RANGE;  // uniform (false also for NaN or infinite scores)
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
-    const int cl = real ? lane : 0;
+    const int cl = real ? ci : 0;
     float sc[AHEAD];
 #pragma unroll
     for (int k = 0; k < AHEAD; ++k) sc[k] = em[(size_t)frame(k < T ? k : T - 1) * d.C + cl];
-    double offset = 0;
+    double offset = 0;  // true log2 value = stored value + offset
     const int tblocks = (T + AHEAD - 1) / AHEAD;
     const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)CP : CP;
     const float* sptr = em + (size_t)frame(AHEAD - 1 < T ? AHEAD - 1 : T - 1) * d.C;
     float* rptr = lat + (size_t)frame(0) * CP;
     float* const spare = lat + (size_t)d.Tp * CP;
+    const float4* src = reinterpret_cast<const float4*>(abuf + half * NSRC);
+    float v[NSRC];
+    auto gather = [&](float a) {  // publish this lane's state, read this lane's source states
+        abuf[ci] = a;
+        __builtin_amdgcn_wave_barrier();  // compiler-level ordering only: the store stays ahead of the reads
+#pragma unroll
+        for (int q = 0; q < NSRC / 4; ++q) {
+            const float4 x = src[q];
+            v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
+        }
+        __builtin_amdgcn_wave_barrier();  // ... and the reads ahead of the next store
+    };
+
+    if (linear) {
+#pragma unroll
+        for (int jj = 0; jj < NSRC; ++jj) G[jj] = (real && half * NSRC + jj < d.C) ? fast_exp2(G[jj] - gmax) : 0.f;  // E
+        float a = 0.f;
+        for (int tb = 0; tb < tblocks; ++tb) {
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) {
+                const int step = tb * AHEAD + k;
+                const float s2 = real ? sc[k] * log2e : NEG;
+                sptr += (step + AHEAD < T) ? sstep : 0;
+                sc[k] = sptr[cl];
+                float* const row = step < T ? rptr : spare;
+                rptr += rstep;
+                gather(a);
+                const float mx = wave_max_bcast(s2);
+                const float e = fast_exp2(s2 - mx);
+                // every second step: the exponent of the largest input state (0 for an all-zero input)
+                const int ex = (k & 1) ? 0 : __builtin_amdgcn_frexp_expf(wave_max_bcast(a));
+                float acc[4] = {0.f, 0.f, 0.f, 0.f};  // four chains: a dependent fma would wait for the one before it
+#pragma unroll
+                for (int jj = 0; jj < NSRC; ++jj) acc[jj & 3] = fmaf(v[jj], G[jj], acc[jj & 3]);
+                float raw = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+                if (LPC == 2) raw += swap_pair(raw);
+                const float n = step == 0 ? e : ((k & 1) ? e * raw : __builtin_amdgcn_ldexpf(e * raw, -ex));
+                offset += (double)mx + (step == 0 ? 0.0 : (double)gmax + (double)ex);
+                if (dir == 0 && step == T - 1) {  // FCC = log2 sum_i 2^(A_{T-1}[i])
+                    const float sx = wave_sum_bcast(writer ? n : 0.f);
+                    if (lane == 0) *term_out = (double)fast_log2(sx) + offset;
+                }
+                a = n;
+                if (half == 0) row[ci] = fmaxf(fast_log2(n), NEG);
+                if (lane == 0) offs[step < T ? frame(step) : d.Tp] = offset;
+            }
+        }
+        return;
+    }
+
     float a = NEG;
     for (int tb = 0; tb < tblocks; ++tb) {
 #pragma unroll
@@ -233,36 +349,36 @@ __device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const 
             sc[k] = sptr[cl];
             float* const row = step < T ? rptr : spare;
             rptr += rstep;
-            // CMAX = 64 recomputes the terms in the second pass instead of keeping 64 more registers
-            float v[CMAX <= 32 ? CMAX : 1];
-            float m = NEG;
+            gather(a);
+            // four interleaved chains for the maximum and for the sum
+            float m4[4] = {NEG, NEG, NEG, NEG};
 #pragma unroll
-            for (int j = 0; j < CMAX; ++j) {
-                const float x = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), j)) + G[j];
-                if (CMAX <= 32) v[j] = x;
-                m = fmaxf(m, x);
+            for (int jj = 0; jj < NSRC; ++jj) {
+                v[jj] += G[jj];
+                m4[jj & 3] = fmaxf(m4[jj & 3], v[jj]);
             }
-            float sum = 0.f;
+            float m = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+            if (LPC == 2) m = fmaxf(m, swap_pair(m));
+            float s4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < CMAX; ++j) {
-                const float x = CMAX <= 32 ? v[j] : __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), j)) + G[j];
-                sum += fast_exp2(x - m);
-            }
+            for (int jj = 0; jj < NSRC; ++jj) s4[jj & 3] += fast_exp2(v[jj] - m);
+            float sum = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+            if (LPC == 2) sum += swap_pair(sum);
             const float n = step == 0 ? s : s + (m + fast_log2(sum));
             if (dir == 0 && step == T - 1) {  // FCC = lse_i A_{T-1}[i]
                 const float x = real ? n : NEG;
-                const float mx = wave_max_f(x);
-                const float sx = wave_sum_f(fast_exp2(x - mx));
+                const float mx = wave_max_bcast(x);
+                const float sx = wave_sum_bcast(writer ? fast_exp2(x - mx) : 0.f);
                 if (lane == 0) *term_out = (double)(mx + fast_log2(sx)) + offset;
             }
-            a = n;
-            row[lane] = real ? n : NEG;
+            a = real ? n : NEG;
+            if (half == 0) row[ci] = a;
         }
         if (lane < AHEAD) {
             const int step = tb * AHEAD + lane;
             offs[step < T ? frame(step) : d.Tp] = offset;
         }
-        const float m = wave_max_f(real ? a : NEG);
+        const float m = wave_max_bcast(a);
         if (m > NEG_TEST) {
             a = a > NEG_TEST ? a - m : NEG;
             offset += (double)m;
@@ -278,6 +394,7 @@ __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em
 {
     __shared__ float xbuf[2][16][HALO_LANES][4];
     __shared__ float wmax[2][16];
+    __shared__ __align__(16) float abuf[64];
     __shared__ int bad;
     const int kind = blockIdx.x >> 1, dir = blockIdx.x & 1, b = blockIdx.y;
     const int tid = threadIdx.x, NT = blockDim.x;
@@ -305,6 +422,9 @@ __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em
         return;
     }
     if (blockIdx.x == 0 && tid == 0) w.status[b] = 0;
+#ifdef ASG_SKIP_KIND
+    if (kind == ASG_SKIP_KIND) return;
+#endif
     const float* emb = em + (size_t)b * d.Tp * d.C;
     if (kind == 0) {
         fal_lattice<PPT>(emb, trans, lab, T, L, dir, w.fal[dir] + (size_t)b * (d.Tp + 1) * d.Sp,
@@ -312,7 +432,7 @@ __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em
     } else {
         if (tid >= 64) return;
         fcc_lattice<CMAX>(emb, trans, T, dir, w.fcc[dir] + (size_t)b * (d.Tp + 1) * CP,
-                          w.fccoff[dir] + (size_t)b * (d.Tp + 1), w.terms + 2 * b, d);
+                          w.fccoff[dir] + (size_t)b * (d.Tp + 1), w.terms + 2 * b, d, abuf);
     }
 }
 
@@ -468,11 +588,24 @@ __global__ __launch_bounds__(256) void asg_trans_partial(const float* __restrict
             const int c = lab[s];
             const float gs = trans[(size_t)c * d.C + c] * log2e;
             const float ga = s >= 1 ? trans[(size_t)c * d.C + lab[s - 1]] * log2e : NEG;
-            for (int t = tlo; t < thi; ++t) {
-                const float* ar = w.fal[0] + (rowb + t - 1) * d.Sp;
-                const float bv = w.fal[1][(rowb + t) * d.Sp + (L - 1 - s)] + wA[t - t0];
-                stay += fast_exp2((ar[s] + bv) + gs);
-                if (s >= 1) adv += fast_exp2((ar[s - 1] + bv) + ga);
+            const float* a0 = w.fal[0] + rowb * d.Sp + s;                // forward row t-1 is read at a0[(t-1) * Sp]
+            const float* b0 = w.fal[1] + rowb * d.Sp + (L - 1 - s);      // backward rows are stored in reversed order
+            for (int t = tlo; t < thi; t += 8) {   // loads of eight frames in flight together
+                float x0[8], x1[8], y[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int tt = t + u < thi ? t + u : thi - 1;
+                    x0[u] = a0[(size_t)(tt - 1) * d.Sp];
+                    x1[u] = s >= 1 ? a0[(size_t)(tt - 1) * d.Sp - 1] : NEG;
+                    y[u] = b0[(size_t)tt * d.Sp];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (t + u >= thi) break;
+                    const float bv = y[u] + wA[t + u - t0];
+                    stay += fast_exp2((x0[u] + bv) + gs);
+                    adv += fast_exp2((x1[u] + bv) + ga);
+                }
             }
         }
         pA[s] = stay;
@@ -480,58 +613,61 @@ __global__ __launch_bounds__(256) void asg_trans_partial(const float* __restrict
     }
 }
 
-// Per utterance: FAL edge sums (added over the chunks in order) scattered into a C x C table;
-// entry (i, j) adds its positions in increasing order.
-__global__ __launch_bounds__(256) void asg_trans_fal_table(const int* __restrict__ targets, const int* __restrict__ tgt_len,
-                                                           AsgWs w, AsgDims d)
+// Per utterance: d loss_b / d g as a C x C table.  FAL edge sums (added over the chunks in
+// order) are scattered into the table as 64-bit fixed-point numbers with integer atomics -- integer
+// addition does not depend on the order, so the result is reproducible -- and subtracted from
+// the FCC edge sums (added over the chunks in order).
+constexpr double FIXED_ONE = 4294967296.0;  // 2^32: occupancies up to 2^31 frames, resolved to 2.3e-10
+__global__ __launch_bounds__(256) void asg_trans_utt(const int* __restrict__ targets, const int* __restrict__ tgt_len,
+                                                     AsgWs w, AsgDims d)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int b = blockIdx.x, tid = threadIdx.x, C2 = d.C * d.C;
-    float* tab = w.tabA + (size_t)b * C2;
+    float* tab = w.tabD + (size_t)b * C2;
     if (w.status[b] != 0) {
         for (int p = tid; p < C2; p += 256) tab[p] = 0.f;
         return;
     }
     const int L = tgt_len[b];
-    int* lab = reinterpret_cast<int*>(smem_raw);           // [Lmax]
-    float* stay = reinterpret_cast<float*>(lab + d.Lmax);  // [Lmax]
-    float* adv = stay + d.Lmax;                            // [Lmax]
+    unsigned long long* fal = reinterpret_cast<unsigned long long*>(smem_raw);  // [C*C]
+    for (int p = tid; p < C2; p += 256) fal[p] = 0ull;
+    __syncthreads();
+    const int* lab = targets + (size_t)b * d.Lmax;
+    const float* pA = w.partA + (size_t)b * d.nch * 2 * d.Lmax;
     for (int s = tid; s < L; s += 256) {
-        lab[s] = targets[(size_t)b * d.Lmax + s];
-        float x = 0.f, y = 0.f;
+        float stay = 0.f, adv = 0.f;
+#pragma unroll 8
         for (int ch = 0; ch < d.nch; ++ch) {
-            const float* pA = w.partA + ((size_t)b * d.nch + ch) * 2 * d.Lmax;
-            x += pA[s];
-            y += pA[d.Lmax + s];
+            stay += pA[(size_t)ch * 2 * d.Lmax + s];
+            adv += pA[(size_t)ch * 2 * d.Lmax + d.Lmax + s];
         }
-        stay[s] = x;
-        adv[s] = y;
+        const int c = lab[s];
+        atomicAdd(&fal[c * d.C + c], (unsigned long long)(long long)__double2ll_rn((double)stay * FIXED_ONE));
+        if (s >= 1)
+            atomicAdd(&fal[c * d.C + lab[s - 1]], (unsigned long long)(long long)__double2ll_rn((double)adv * FIXED_ONE));
     }
     __syncthreads();
+    const float* pF = w.partF + (size_t)b * d.nch * C2;
     for (int p = tid; p < C2; p += 256) {
-        const int i = p / d.C, j = p - i * d.C;
-        float acc = 0.f;
-        for (int s = 0; s < L; ++s) {
-            if (lab[s] != i) continue;
-            if (i == j) acc += stay[s];
-            if (s >= 1 && lab[s - 1] == j) acc += adv[s];
-        }
-        tab[p] = acc;
+        float f = 0.f;
+#pragma unroll 8
+        for (int ch = 0; ch < d.nch; ++ch) f += pF[(size_t)ch * C2 + p];
+        tab[p] = f - (float)((double)(long long)fal[p] * (1.0 / FIXED_ONE));
     }
 }
 
-//   grad_trans[p] = grad_scale * ( sum_{b, chunk} partF - sum_b tabA ), added in that fixed order
-__global__ __launch_bounds__(256) void asg_trans_reduce(float* __restrict__ grad_trans, AsgWs w, AsgDims d, float grad_scale)
+//   grad_trans[p] = grad_scale * sum_b tabD[b][p], added in the order b = 0, 1, ...
+__global__ __launch_bounds__(64) void asg_trans_reduce(float* __restrict__ grad_trans, AsgWs w, AsgDims d, float grad_scale)
 {
-    const int p = blockIdx.x * 256 + threadIdx.x, C2 = d.C * d.C;
+    const int p = blockIdx.x * 64 + threadIdx.x, C2 = d.C * d.C;
     if (p >= C2) return;
-    float f = 0.f, a = 0.f;
-    for (int q = 0; q < d.B * d.nch; ++q) f += w.partF[(size_t)q * C2 + p];
-    for (int b = 0; b < d.B; ++b) a += w.tabA[(size_t)b * C2 + p];
-    grad_trans[p] = grad_scale * (f - a);
+    float acc = 0.f;
+#pragma unroll 8
+    for (int b = 0; b < d.B; ++b) acc += w.tabD[(size_t)b * C2 + p];
+    grad_trans[p] = grad_scale * acc;
 }
 
-struct WsLayout { size_t fal[2], fcc[2], faloff[2], fccoff[2], terms, status, izf, iza, partF, partA, tabA, total; };
+struct WsLayout { size_t fal[2], fcc[2], faloff[2], fccoff[2], terms, status, izf, iza, partF, partA, tabD, total; };
 WsLayout ws_layout(int B, int Tp, int C, int Lmax)
 {
     WsLayout w;
@@ -548,7 +684,7 @@ WsLayout ws_layout(int B, int Tp, int C, int Lmax)
     w.iza = off; off += round_up((size_t)B * Tp * 4, 256);
     w.partF = off; off += round_up((size_t)B * nch * C * C * 4, 256);
     w.partA = off; off += round_up((size_t)B * nch * 2 * Lmax * 4, 256);
-    w.tabA = off; off += round_up((size_t)B * C * C * 4, 256);
+    w.tabD = off; off += round_up((size_t)B * C * C * 4, 256);
     w.total = off;
     return w;
 }
@@ -618,10 +754,10 @@ extern "C" int w2l_asg_fwd_bwd(const float* emissions, const float* trans, const
     w.iza = reinterpret_cast<float*>(ws + l.iza);
     w.partF = reinterpret_cast<float*>(ws + l.partF);
     w.partA = reinterpret_cast<float*>(ws + l.partA);
-    w.tabA = reinterpret_cast<float*>(ws + l.tabA);
+    w.tabD = reinterpret_cast<float*>(ws + l.tabD);
 
     const size_t lds_em = (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (Lmax + 4);
-    const size_t lds_tab = (size_t)4 * 3 * Lmax;
+    const size_t lds_tab = (size_t)8 * C * C;
     if (lds_em > 160 * 1024) return W2L_ERR_SHAPE;
     if (lds_em > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)asg_grad_em, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_em);
@@ -645,9 +781,9 @@ extern "C" int w2l_asg_fwd_bwd(const float* emissions, const float* trans, const
     hipLaunchKernelGGL(asg_trans_partial, dim3(d.nch, B), dim3(256), 0, st, trans, targets, in_len, tgt_len, w, d);
     rc = launch_status();
     if (rc) return rc;
-    hipLaunchKernelGGL(asg_trans_fal_table, dim3(B), dim3(256), lds_tab, st, targets, tgt_len, w, d);
+    hipLaunchKernelGGL(asg_trans_utt, dim3(B), dim3(256), lds_tab, st, targets, tgt_len, w, d);
     rc = launch_status();
     if (rc) return rc;
-    hipLaunchKernelGGL(asg_trans_reduce, dim3((C * C + 255) / 256), dim3(256), 0, st, grad_trans, w, d, grad_scale);
+    hipLaunchKernelGGL(asg_trans_reduce, dim3((C * C + 63) / 64), dim3(64), 0, st, grad_trans, w, d, grad_scale);
     return launch_status();
 }
