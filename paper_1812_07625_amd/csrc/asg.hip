@@ -253,6 +253,147 @@ __device__ __forceinline__ float swap_pair(float v)  // value of lane ^ 1
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1 /* quad_perm:[1,0,3,2] */, 0xf, 0xf, false));
 }
 
+// acc (+)= e * (x of the lane R places around this lane's row of 16): one DPP instruction per source.
+// The _FIRST form sits behind two wait states: the first DPP read of a register that a vector
+// instruction has just written.
+#define W2L_DPP_TAIL(R) " row_ror:" #R " row_mask:0xf bank_mask:0xf bound_ctrl:1"
+#define W2L_FMAC_ROR(acc, x, e, R) asm volatile("v_fmac_f32_dpp %0, %1, %2" W2L_DPP_TAIL(R) : "+v"(acc) : "v"(x), "v"(e))
+#define W2L_MUL_ROR(acc, x, e, R) asm volatile("v_mul_f32_dpp %0, %1, %2" W2L_DPP_TAIL(R) : "=v"(acc) : "v"(x), "v"(e))
+#define W2L_MUL_ROR_FIRST(acc, x, e, R) \
+    asm volatile("s_nop 1\n\tv_mul_f32_dpp %0, %1, %2" W2L_DPP_TAIL(R) : "=v"(acc) : "v"(x), "v"(e))
+template <int R>
+__device__ __forceinline__ int ror_i(int x)
+{
+    return R == 0 ? x : __builtin_amdgcn_update_dpp(0, x, 0x120 + (R == 0 ? 1 : R), 0xf, 0xf, true);
+}
+// largest value over lanes 0..31 of non-negative floats (their bit patterns order like unsigned
+// integers), valid in lane 31: four row shifts and one row broadcast, each a single DPP instruction
+__device__ __forceinline__ unsigned max_bits_lane31(unsigned u)
+{
+    asm volatile("s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf"
+                 : "+v"(u));
+    return u;
+}
+
+// Linear recursion for up to 32 classes without LDS: class = lane & 31, so a row of 16 lanes
+// holds 16 classes and both halves of the wavefront hold every class.  A lane reaches the 16
+// states of a row with DPP row rotations; lanes 0..31 sum over the source classes of their own
+// row, lanes 32..63 -- after one row swap (v_permlane16_swap) -- over those of the other row, and
+// one half swap (v_permlane32_swap) adds the two.  Which lane a rotation or a swap delivers is not
+// assumed: the same operations are applied to the lane numbers first and the transition factors
+// are laid out to match.  All 64 lanes end a step with the new state of their class.
+__device__ __forceinline__ void fcc_linear_rows(const float* __restrict__ em, const float* __restrict__ trans, int T, int dir,
+                                                float* __restrict__ lat, double* __restrict__ offs, double* term_out,
+                                                const AsgDims& d, float gmax)
+{
+    const int lane = threadIdx.x & 63, ci = lane & 31;
+    const bool real = ci < d.C, upper = lane >= 32;
+    const float log2e = (float)LOG2E;
+    // The row swap returns two registers.  Applied to the lane numbers it tells which of the two a
+    // lane has to take: lanes 0..31 the one that still holds their own number, lanes 32..63 the one
+    // that holds a lane of the other row.  (The half swap needs no such choice: the sum of its two
+    // results is the sum of both halves in every lane.)
+    const auto sw16 = __builtin_amdgcn_permlane16_swap((unsigned)lane, (unsigned)lane, false, false);
+    const bool take0 = upper ? ((sw16[0] ^ (unsigned)lane) & 16u) != 0 : sw16[0] == (unsigned)lane;
+    const int xid = (int)((take0 ? sw16[0] : sw16[1]) & 31u);  // class whose state this lane feeds into the rotations
+    float E[16];  // factors by rotation
+    auto factor = [&](int src) {
+        if (!real || src >= d.C) return 0.f;
+        return fast_exp2((dir ? trans[(size_t)src * d.C + ci] : trans[(size_t)ci * d.C + src]) * log2e - gmax);
+    };
+#define W2L_E(R) E[R] = factor(ror_i<R>(xid));
+    W2L_E(0) W2L_E(1) W2L_E(2) W2L_E(3) W2L_E(4) W2L_E(5) W2L_E(6) W2L_E(7)
+    W2L_E(8) W2L_E(9) W2L_E(10) W2L_E(11) W2L_E(12) W2L_E(13) W2L_E(14) W2L_E(15)
+#undef W2L_E
+    auto frame = [&](int step) { return dir ? T - 1 - step : step; };
+    const int cl = real ? ci : 0;
+    float sc[AHEAD];
+#pragma unroll
+    for (int k = 0; k < AHEAD; ++k) sc[k] = em[(size_t)frame(k < T ? k : T - 1) * d.C + cl];
+    double offset = 0;
+    const int tblocks = (T + AHEAD - 1) / AHEAD;
+    const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)CP : CP;
+    const float* sptr = em + (size_t)frame(AHEAD - 1 < T ? AHEAD - 1 : T - 1) * d.C;
+    float* rptr = lat + (size_t)frame(0) * CP + ci;
+    float* const spare = lat + (size_t)d.Tp * CP + ci;
+    const double gmax_d = (double)gmax;
+    float a = 0.f;
+    for (int tb = 0; tb < tblocks; ++tb) {
+        // the block's 16 frames of scores at once: per-frame maximum (16 interleaved DPP reductions)
+        // and normalised emission factors; then the ring is refilled for the next block
+        float s2[AHEAD], mx[AHEAD];
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) mx[k] = s2[k] = real ? sc[k] * log2e : NEG;
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x111, 0xf>(mx[k], mx[k]));
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x112, 0xf>(mx[k], mx[k]));
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x114, 0xf>(mx[k], mx[k]));
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x118, 0xf>(mx[k], mx[k]));
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x142, 0xa>(mx[k], mx[k]));
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) {
+            mx[k] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx[k]), 31));  // lanes 0..31 hold every class
+            s2[k] = fast_exp2(s2[k] - mx[k]);  // e
+            const int step = tb * AHEAD + k;
+            sptr += (step + AHEAD < T) ? sstep : 0;
+            sc[k] = sptr[cl];
+        }
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) {
+            const int step = tb * AHEAD + k;
+            float* const row = step < T ? rptr : spare;
+            rptr += rstep;
+            // every second step: the exponent of the largest input state (0 for an all-zero input); the
+            // scaling is folded into the emission factor, off the chain of the states
+            int ex = 0;
+            if (!(k & 1))
+                ex = __builtin_amdgcn_frexp_expf(
+                    __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)max_bits_lane31(__float_as_uint(a)), 31)));
+            const float e = (k & 1) ? s2[k] : __builtin_amdgcn_ldexpf(s2[k], -ex);
+            const auto o16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(a), false, false);
+            const float x = __uint_as_float(take0 ? o16[0] : o16[1]);
+            float acc[4];  // four chains: a dependent fma would wait for the one before it
+            acc[0] = x * E[0];
+            W2L_MUL_ROR_FIRST(acc[1], x, E[1], 1);
+            W2L_MUL_ROR(acc[2], x, E[2], 2);
+            W2L_MUL_ROR(acc[3], x, E[3], 3);
+            W2L_FMAC_ROR(acc[0], x, E[4], 4);
+            W2L_FMAC_ROR(acc[1], x, E[5], 5);
+            W2L_FMAC_ROR(acc[2], x, E[6], 6);
+            W2L_FMAC_ROR(acc[3], x, E[7], 7);
+            W2L_FMAC_ROR(acc[0], x, E[8], 8);
+            W2L_FMAC_ROR(acc[1], x, E[9], 9);
+            W2L_FMAC_ROR(acc[2], x, E[10], 10);
+            W2L_FMAC_ROR(acc[3], x, E[11], 11);
+            W2L_FMAC_ROR(acc[0], x, E[12], 12);
+            W2L_FMAC_ROR(acc[1], x, E[13], 13);
+            W2L_FMAC_ROR(acc[2], x, E[14], 14);
+            W2L_FMAC_ROR(acc[3], x, E[15], 15);
+            const float part = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+            const auto o32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(part), __float_as_uint(part), false, false);
+            const float raw = __uint_as_float(o32[0]) + __uint_as_float(o32[1]);  // lower half + upper half, in every lane
+            const float n = step == 0 ? s2[k] : e * raw;
+            offset += (double)mx[k] + (step == 0 ? 0.0 : gmax_d + (double)ex);
+            if (dir == 0 && step == T - 1) {  // FCC = log2 sum_i 2^(A_{T-1}[i])
+                const float sx = wave_sum_bcast(real && !upper ? n : 0.f);
+                if (lane == 0) *term_out = (double)fast_log2(sx) + offset;
+            }
+            a = n;
+            // both halves store the same values to the same places: no lane masking in the loop
+            *row = fmaxf(fast_log2(n), NEG);
+            offs[step < T ? frame(step) : d.Tp] = offset;
+        }
+    }
+}
+
 template <int CMAX>
 __device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const float* __restrict__ trans, int T, int dir,
                                             float* __restrict__ lat, double* __restrict__ offs, double* term_out,
@@ -278,6 +419,10 @@ __device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const 
     gmax = wave_max_bcast(gmax);
     gmin = wave_min_bcast(gmin);
     const bool linear = gmax - gmin <= LINEAR_RANGE;  // uniform (false also for NaN or infinite scores)
+    if (CMAX <= 32 && linear) {
+        fcc_linear_rows(em, trans, T, dir, lat, offs, term_out, d, gmax);
+        return;
+    }
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
     const int cl = real ? ci : 0;
     float sc[AHEAD];
@@ -307,17 +452,38 @@ __device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const 
         for (int jj = 0; jj < NSRC; ++jj) G[jj] = (real && half * NSRC + jj < d.C) ? fast_exp2(G[jj] - gmax) : 0.f;  // E
         float a = 0.f;
         for (int tb = 0; tb < tblocks; ++tb) {
+            // the block's 16 frames of scores at once: per-frame maximum (16 interleaved DPP
+            // reductions) and normalised emission factors; then the ring is refilled for the next block
+            float s2[AHEAD], mx[AHEAD];
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) mx[k] = s2[k] = real ? sc[k] * log2e : NEG;
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x111, 0xf>(mx[k], mx[k]));
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x112, 0xf>(mx[k], mx[k]));
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x114, 0xf>(mx[k], mx[k]));
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x118, 0xf>(mx[k], mx[k]));
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x142, 0xa>(mx[k], mx[k]));
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x143, 0xc>(mx[k], mx[k]));
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) {
+                mx[k] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx[k]), 63));
+                s2[k] = fast_exp2(s2[k] - mx[k]);  // e
+                const int step = tb * AHEAD + k;
+                sptr += (step + AHEAD < T) ? sstep : 0;
+                sc[k] = sptr[cl];
+            }
 #pragma unroll
             for (int k = 0; k < AHEAD; ++k) {
                 const int step = tb * AHEAD + k;
-                const float s2 = real ? sc[k] * log2e : NEG;
-                sptr += (step + AHEAD < T) ? sstep : 0;
-                sc[k] = sptr[cl];
                 float* const row = step < T ? rptr : spare;
                 rptr += rstep;
                 gather(a);
-                const float mx = wave_max_bcast(s2);
-                const float e = fast_exp2(s2 - mx);
+                const float e = s2[k];
                 // every second step: the exponent of the largest input state (0 for an all-zero input)
                 const int ex = (k & 1) ? 0 : __builtin_amdgcn_frexp_expf(wave_max_bcast(a));
                 float acc[4] = {0.f, 0.f, 0.f, 0.f};  // four chains: a dependent fma would wait for the one before it
@@ -326,7 +492,7 @@ __device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const 
                 float raw = (acc[0] + acc[1]) + (acc[2] + acc[3]);
                 if (LPC == 2) raw += swap_pair(raw);
                 const float n = step == 0 ? e : ((k & 1) ? e * raw : __builtin_amdgcn_ldexpf(e * raw, -ex));
-                offset += (double)mx + (step == 0 ? 0.0 : (double)gmax + (double)ex);
+                offset += (double)mx[k] + (step == 0 ? 0.0 : (double)gmax + (double)ex);
                 if (dir == 0 && step == T - 1) {  // FCC = log2 sum_i 2^(A_{T-1}[i])
                     const float sx = wave_sum_bcast(writer ? n : 0.f);
                     if (lane == 0) *term_out = (double)fast_log2(sx) + offset;
