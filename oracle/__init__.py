@@ -1,4 +1,4 @@
-"""fp64 CPU oracle for the conv-GLU + CTC training path -- TEST INFRASTRUCTURE ONLY.
+"""fp64 CPU oracle for the conv-GLU + CTC training path (and the ASG criterion) -- TEST INFRASTRUCTURE ONLY.
 
 Thin ctypes marshalling around ``w2l_oracle.c`` (plain C loops, double precision)
 plus :func:`train_step`, which strings those definitions together in the order of
