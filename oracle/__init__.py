@@ -272,6 +272,66 @@ def asg(em, trans, targets, in_len, tgt_len, grad_scale=1.0, want_terms=False):
     return loss, ge, gt
 
 
+# ----------------------------------------------------------------------------- log-mel features
+def logmel_num_frames(n_samples: int, win: int, hop: int) -> int:
+    """Frames that lie wholly inside the signal: 1 + floor((n - win) / hop), or 0 if n < win."""
+    return 0 if n_samples < win else 1 + (n_samples - win) // hop
+
+
+def mel_of_hz(f):
+    """The mel scale m = 2595 log10(1 + f / 700)."""
+    return 2595.0 * np.log10(1.0 + np.asarray(f, dtype=np.float64) / 700.0)
+
+
+def hz_of_mel(m):
+    return 700.0 * (10.0 ** (np.asarray(m, dtype=np.float64) / 2595.0) - 1.0)
+
+
+def mel_filterbank(n_mels, nfft, sample_rate, fmin, fmax):
+    """[n_mels, nfft/2+1] triangular filters, peak 1: n_mels + 2 points equally spaced on the mel
+    scale between fmin and fmax; filter f rises linearly (in Hz) from point f to point f+1 and falls
+    to point f+2, evaluated at the DFT bin frequencies k * sample_rate / nfft."""
+    pts = hz_of_mel(np.linspace(mel_of_hz(fmin), mel_of_hz(fmax), n_mels + 2))
+    freqs = np.arange(nfft // 2 + 1, dtype=np.float64) * sample_rate / nfft
+    fb = np.zeros((n_mels, nfft // 2 + 1))
+    for f in range(n_mels):
+        lo, ce, hi = pts[f], pts[f + 1], pts[f + 2]
+        up = (freqs - lo) / (ce - lo)
+        down = (hi - freqs) / (hi - ce)
+        fb[f] = np.maximum(0.0, np.minimum(up, down))
+    return fb
+
+
+def logmel(wav, wav_len, n_mels=40, sample_rate=16000, win=400, hop=160, nfft=512, fmin=0.0, fmax=None,
+           floor=1e-10, Tmax=None):
+    """Log-mel filterbank features (Sec. 2.2 lists them among the feature types, Sec. 4.1 uses 40 of
+    them per frame; the paper gives no constant or formula -- the steps below are a stated reading):
+    frames of ``win`` samples every ``hop`` samples, only frames wholly inside the signal;
+    Hamming window 0.54 - 0.46 cos(2 pi n / (win - 1)); zero-padded DFT of size nfft; power
+    spectrum |X_k|^2, k = 0..nfft/2; triangular mel filterbank; natural log of max(energy, floor).
+    wav: [B, Nmax]; wav_len: [B].  Returns (feat [B, Tmax, n_mels] with zeros beyond each
+    utterance's frames, feat_len [B])."""
+    wav = np.asarray(wav, dtype=np.float64)
+    B = wav.shape[0]
+    fmax = sample_rate / 2.0 if fmax is None else fmax
+    nfr = [logmel_num_frames(int(n), win, hop) for n in wav_len]
+    if Tmax is None:
+        Tmax = max(nfr + [0])
+    fb = mel_filterbank(n_mels, nfft, sample_rate, fmin, fmax)
+    window = 0.54 - 0.46 * np.cos(2.0 * np.pi * np.arange(win) / (win - 1))
+    feat = np.zeros((B, Tmax, n_mels))
+    out_len = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        T = min(nfr[b], Tmax)
+        out_len[b] = T
+        for t in range(T):
+            seg = wav[b, t * hop:t * hop + win] * window
+            spec = np.fft.rfft(seg, n=nfft)
+            power = spec.real ** 2 + spec.imag ** 2
+            feat[b, t] = np.log(np.maximum(fb @ power, floor))
+    return feat, out_len
+
+
 # ----------------------------------------------------------------------------- train step
 def train_step(layers, weights, biases, x, in_len, targets, tgt_len, grad_scale=1.0, blank=0,
                keep_activations=False):
