@@ -199,6 +199,32 @@ int w2l_asg_fwd_bwd(const float *emissions, const float *trans, const int *targe
 int w2l_asg_check_targets_host(const int *targets, const int *in_len, const int *tgt_len,
                                int B, int Tp, int C, int Lmax);
 
+/* ---- log-mel filterbank features (Sec. 2.2: log-mels are among the feature types computed on
+ * the fly before every network evaluation; Sec. 4.1: 40 per frame feed the networks.  The paper
+ * fixes no constant or formula -- this is the library's reading) -----------------------------
+ * For utterance b with n = wav_len[b] samples (clamped to [0, Nmax]):
+ *   frames   t = 0 .. T_b-1, T_b = 1 + floor((n - win) / hop) (0 if n < win): only frames wholly
+ *            inside the signal; frame t covers samples t*hop .. t*hop + win - 1
+ *   window   0.54 - 0.46 cos(2 pi i / (win - 1))          (Hamming)
+ *   spectrum P[k] = | sum_i x[i] window[i] exp(-2 pi sqrt(-1) i k / nfft) |^2, k = 0 .. nfft/2
+ *   mel      n_mels + 2 points equally spaced in m = 2595 log10(1 + f/700) between fmin and fmax;
+ *            band j rises linearly in Hz from point j to point j+1 (weight 1) and falls to point
+ *            j+2, evaluated at the bin frequencies k * sample_rate / nfft
+ *   feature  log( max( sum_k weight_j[k] P[k], floor ) )   (natural log)
+ * No pre-emphasis, dither or normalisation.
+ * in:  wav [B,Nmax] fp32, wav_len [B] int32.
+ * out: feat [B,Tmax,n_mels] (dtype: W2L_F32 or W2L_BF16), rows t >= min(T_b, Tmax) are 0 -- the
+ *      layout and padding w2l_train_step expects of x; feat_len [B] int32 = min(T_b, Tmax), the
+ *      in_len of that call.
+ * All device pointers, no workspace; arithmetic fp32 (mel points in double).
+ * Limits: nfft a power of two in [128, 1024], 2 <= win <= nfft, hop >= 1, n_mels <= 256,
+ * 0 <= fmin < fmax <= sample_rate/2, floor > 0.  Errors: W2L_ERR_NULL / _SHAPE / _DTYPE / _LAUNCH.
+ * w2l_logmel_num_frames: the frame count above, on the host. */
+int w2l_logmel_num_frames(int n_samples, int win, int hop);
+int w2l_logmel_fwd(const float *wav, const int *wav_len, void *feat, int *feat_len,
+                   int B, int Nmax, int Tmax, int n_mels, int sample_rate, int win, int hop,
+                   int nfft, float fmin, float fmax, float floor, int dtype, void *stream);
+
 /* ---- one training step: network forward, criterion, backward (Sec. 2.3, Sec. 4.1) --
  * layers[0..n_layers): layer i maps [B,T_i,cin_i] to [B,ceil(T_i/stride_i),cout_i or
  * cout_i/2]; cin_0 is the feature dimension, cin_{i+1} must equal layer i's output

@@ -21,6 +21,7 @@ __all__ = [
     "w2l_conv1d_bwd_data_workspace_bytes", "w2l_conv1d_bwd_weight_workspace_bytes", "w2l_glu_fwd", "w2l_glu_bwd",
     "w2l_logsoftmax_fwd", "w2l_logsoftmax_bwd", "w2l_ctc_workspace_bytes", "w2l_ctc_fwd_bwd",
     "w2l_ctc_check_targets_host", "w2l_asg_workspace_bytes", "w2l_asg_fwd_bwd", "w2l_asg_check_targets_host",
+    "w2l_logmel_num_frames", "w2l_logmel_fwd",
     "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_sgd_momentum_step",
     "w2l_probe_mfma", "raw",
     "workspace",
@@ -65,6 +66,8 @@ def _load():
         "w2l_ctc_workspace_bytes": (sz, [i] * 4),
         "w2l_ctc_fwd_bwd": (i, [vp, i, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]),
         "w2l_ctc_check_targets_host": (i, [vp, vp, vp, i, i, i, i, i]),
+        "w2l_logmel_num_frames": (i, [i, i, i]),
+        "w2l_logmel_fwd": (i, [vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, f, f, i, vp]),
         "w2l_asg_workspace_bytes": (sz, [i] * 4),
         "w2l_asg_fwd_bwd": (i, [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, f, vp, sz, vp]),
         "w2l_asg_check_targets_host": (i, [vp, vp, vp, i, i, i, i]),
@@ -232,6 +235,21 @@ def w2l_ctc_check_targets_host(targets, in_len, tgt_len, Tp, Cc, blank=0) -> int
     tl = np.ascontiguousarray(tgt_len, dtype=np.int32)
     return raw.w2l_ctc_check_targets_host(t.ctypes.data, il.ctypes.data, tl.ctypes.data, t.shape[0], Tp, Cc,
                                           t.shape[1], blank)
+
+
+def w2l_logmel_num_frames(n_samples, win=400, hop=160) -> int:
+    return raw.w2l_logmel_num_frames(int(n_samples), win, hop)
+
+
+def w2l_logmel_fwd(wav, wav_len, feat, feat_len, sample_rate=16000, win=400, hop=160, nfft=512, fmin=0.0,
+                   fmax=None, floor=1e-10, stream=None):
+    B, Nmax = wav.shape
+    _, Tmax, n_mels = feat.shape
+    fmax = sample_rate / 2.0 if fmax is None else fmax
+    _check(raw.w2l_logmel_fwd(_p(wav), _p(wav_len), _p(feat), _p(feat_len), B, Nmax, Tmax, n_mels, sample_rate, win, hop,
+                              nfft, float(fmin), float(fmax), float(floor), _dt(feat), _stream(stream)),
+           "w2l_logmel_fwd")
+    return feat, feat_len
 
 
 def w2l_asg_workspace_bytes(B, Tp, Cc, Lmax) -> int:

@@ -1,7 +1,7 @@
 """Seeded synthetic inputs for the five benchmark/parity configurations.
 
 This module only draws random numbers and lays them out; it holds none of the
-method's arithmetic (no convolution, GLU, softmax, CTC or ASG) and is the one piece
+method's arithmetic (no convolution, GLU, softmax, CTC, ASG or feature computation) and is the one piece
 shared by the oracle-side and the GPU-side callers.  Everything is numpy on the
 host.  Shapes follow the paper's workload (Sec. 4.1: log-mel feature frames at
 10 ms, grapheme targets, length-sorted -- hence narrow -- utterance lengths, an
@@ -181,6 +181,33 @@ def asg_batch(seed=12, B=32, T=750, Cc=NUM_CLASSES - 1, in_lo=600, in_hi=750, l_
                     lab[i] = rng.integers(0, Cc)
         targets[b, :tgt_len[b]] = lab
     return dict(emissions=em, trans=trans, in_len=in_len, targets=targets, tgt_len=tgt_len, B=B, T=T, C=Cc)
+
+
+def waveforms(seed=13, B=8, n_lo=160000, n_hi=240240, sample_rate=16000):
+    """Speech-shaped synthetic audio for the feature kernel (no recording is used): per utterance a
+    harmonic source -- fundamental wandering between 90 and 250 Hz, 12 harmonics with a 1/h roll-off
+    and random phases -- under a slow amplitude envelope with pauses, plus white noise 30 dB below
+    the peak; fp32 samples in about [-1, 1], zeros beyond each utterance's length U[n_lo, n_hi]
+    (n_hi = 240240 samples = 1500 frames of 25 ms every 10 ms).  Draw order: lengths, then per
+    utterance: pitch track, phases, envelope, noise."""
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(n_lo, n_hi + 1, size=B).astype(np.int32)
+    Nmax = int(lens.max())
+    wav = np.zeros((B, Nmax), dtype=np.float32)
+    t = np.arange(Nmax) / sample_rate
+    for b in range(B):
+        knots = rng.uniform(90.0, 250.0, size=Nmax // 8000 + 2)
+        f0 = np.interp(np.arange(Nmax) / 8000.0, np.arange(len(knots)), knots)
+        phase = 2 * np.pi * np.cumsum(f0) / sample_rate
+        ph0 = rng.uniform(0, 2 * np.pi, size=12)
+        sig = sum(np.sin(h * phase + ph0[h - 1]) / h for h in range(1, 13))
+        env_knots = np.clip(rng.uniform(-0.3, 1.0, size=Nmax // 4000 + 2), 0.0, 1.0)
+        env = np.interp(np.arange(Nmax) / 4000.0, np.arange(len(env_knots)), env_knots)
+        x = 0.5 * env * sig / np.max(np.abs(sig)) + 0.5 * 10 ** (-30 / 20) * rng.standard_normal(Nmax)
+        x[lens[b]:] = 0.0
+        wav[b] = x.astype(np.float32)
+    del t
+    return dict(wav=wav, wav_len=lens, B=B, sample_rate=sample_rate)
 
 
 def config3(seed=3, B=16):
