@@ -167,6 +167,15 @@ def main():
     a_cells = int(np.sum(a2["in_len"].astype(np.int64) * (a2["tgt_len"].astype(np.int64) + a2["C"])))
     asg_bytes = 2 * a2["emissions"].size * 4 + 2 * 2 * 4 * a_cells   # emissions in, gradient out; lattices written and read once
 
+    # log-mel features for a batch of the model's shape: B=8 waveforms of up to 240240 samples -> 1500 frames x 80 bands (bf16)
+    wv = W.waveforms()
+    wd, wl = to_dev(wv["wav"]), to_dev(wv["wav_len"])
+    lfeat = empty((wv["B"], 1500, 80), "bf16")
+    llen = torch.zeros(wv["B"], dtype=torch.int32, device="cuda:0")
+    t_mel = event_time_ms(lambda: P.w2l_logmel_fwd(wd, wl, lfeat, llen), args.kernel_iters)
+    mel_bytes = int(wv["wav_len"].sum()) * 4 + wv["B"] * 1500 * 80 * 2   # samples read once, features written once
+    mel_frames = int(sum(max(0, 1 + (int(n) - 400) // 160) for n in wv["wav_len"]))
+
     # optimiser step over all parameters of the model as one flat fp32 buffer (not part of `value`:
     # the metric is forward + backward)
     npar = W.num_params(layers)
@@ -230,6 +239,9 @@ def main():
                                              "frac_hbm_peak": asg_bytes / (t_asg * 1e-3) / PEAK_HBM,
                                              "serial_steps": int(a2["in_len"].max()),
                                              "us_per_serial_step": t_asg * 1e3 / int(a2["in_len"].max())},
+            "logmel_fwd(B=8,1500x80)": {"ms": t_mel, "GBps": mel_bytes / (t_mel * 1e-3) / 1e9,
+                                        "frac_hbm_peak": mel_bytes / (t_mel * 1e-3) / PEAK_HBM,
+                                        "frames": mel_frames, "Mframes_per_s": mel_frames / (t_mel * 1e-3) / 1e6},
             "sgd_momentum_step(all %d params)" % npar: {"ms": t_sgd, "GBps": sgd_bytes / (t_sgd * 1e-3) / 1e9,
                                                          "frac_hbm_peak": sgd_bytes / (t_sgd * 1e-3) / PEAK_HBM},
         },

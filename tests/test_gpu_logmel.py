@@ -98,3 +98,46 @@ def test_logmel_is_deterministic(P):
     a = run_logmel(P, cfg["wav"], cfg["wav_len"], 200, 80)
     b = run_logmel(P, cfg["wav"], cfg["wav_len"], 200, 80)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_features_feed_the_train_step(P):
+    """Waveforms -> log-mel -> network forward, CTC, backward -> SGD with momentum, all through the
+    C ABI with no host round trip in between (feat / feat_len are handed to w2l_train_step as x /
+    in_len as they are), against the same chain of oracle functions.  fp32 model; the tolerance is
+    1e-3 because the feature error (above) goes through the whole network."""
+    from test_gpu_parity import rel_l2 as _rel
+    cfg = W.waveforms(seed=21, B=3, n_lo=20000, n_hi=32000)
+    layers = [dict(k=5, stride=2, cin=40, cout=64, glu=1), dict(k=3, stride=1, cin=32, cout=48, glu=1),
+              dict(k=1, stride=1, cin=24, cout=W.NUM_CLASSES, glu=0)]
+    model = W.small_model(22, 3, 10, 10, 40, layers, False, 4, 12)     # only its weights, biases and targets are used
+    Tmax = max(oracle.logmel_num_frames(int(n), 400, 160) for n in cfg["wav_len"])
+    # ---- GPU chain
+    wd, ld = to_dev(cfg["wav"]), to_dev(cfg["wav_len"])
+    feat = empty((3, Tmax, 40))
+    flen = torch.zeros(3, dtype=torch.int32, device="cuda:0")
+    P.w2l_logmel_fwd(wd, ld, feat, flen)
+    wts = [to_dev(w) for w in model["weights"]]
+    bss = [to_dev(b) for b in model["biases"]]
+    dws = [empty(w.shape) for w in model["weights"]]
+    dbs = [empty(b.shape) for b in model["biases"]]
+    tg, tl = to_dev(model["targets"]), to_dev(model["tgt_len"])
+    Lmax = model["targets"].shape[1]
+    ws = P.workspace(P.w2l_train_step_workspace_bytes(layers, 3, Tmax, Lmax, P.W2L_F32))
+    loss = empty((3,))
+    P.w2l_train_step(layers, wts, bss, dws, dbs, feat, flen, tg, tl, loss, None, 0, 1.0, ws)
+    vel = [torch.zeros_like(w) for w in wts]
+    for w, v, g in zip(wts, vel, dws):
+        P.w2l_sgd_momentum_step(w, v, g, None, 0.01, 0.9)
+    torch.cuda.synchronize()
+    # ---- oracle chain
+    f_o, l_o = oracle.logmel(cfg["wav"].astype(np.float64), cfg["wav_len"], n_mels=40)
+    assert np.array_equal(flen.cpu().numpy(), l_o)
+    ref = oracle.train_step(layers, [w.astype(np.float64) for w in model["weights"]],
+                            [b.astype(np.float64) for b in model["biases"]], f_o, l_o, model["targets"],
+                            model["tgt_len"])
+    assert np.all(np.abs(to_host(loss) - ref["loss"]) <= 1e-3 * np.abs(ref["loss"]))
+    for i, (g, r) in enumerate(zip(dws, ref["dw"])):
+        assert _rel(to_host(g), r) <= 1e-3, i
+    for w, w0, r in zip(wts, model["weights"], ref["dw"]):
+        w_o, _ = oracle.sgd_momentum(w0.astype(np.float64), np.zeros_like(r), r, 0.01, 0.9)
+        assert _rel(to_host(w), w_o) <= 1e-5
