@@ -250,6 +250,22 @@ int w2l_train_step(const w2l_layer *layers, int n_layers,
                    int B, int T, int Lmax, int blank, int dtype, float grad_scale,
                    void *workspace, size_t ws_bytes, void *stream);
 
+/* The same step with the ASG criterion (Sec. 2.3) in place of log-softmax + CTC: the network
+ * output [B,T_last,C] is handed to w2l_asg_fwd_bwd as emissions (C <= 64, no blank).
+ * trans: [C,C] fp32 transition scores (device); dtrans: [C,C] fp32 (device, nullable = not
+ * wanted), overwritten with the gradient of grad_scale * sum_b loss[b].  Everything else as in
+ * w2l_train_step; workspace from w2l_train_step_asg_workspace_bytes (0 if the shape is not
+ * supported). */
+size_t w2l_train_step_asg_workspace_bytes(const w2l_layer *layers, int n_layers, int B, int T,
+                                          int Lmax, int dtype);
+int w2l_train_step_asg(const w2l_layer *layers, int n_layers,
+                       const void *const *weights, const float *const *biases,
+                       float *const *dweights, float *const *dbiases,
+                       const void *x, const int *in_len, const int *targets, const int *tgt_len,
+                       const float *trans, float *dtrans, float *loss, float *logits,
+                       int B, int T, int Lmax, int dtype, float grad_scale,
+                       void *workspace, size_t ws_bytes, void *stream);
+
 /* ---- measurement aid (not part of the training path) -----------------------------------
  * Launches `blocks` workgroups of 4 wavefronts, each wavefront issuing 8*iters independent
  * v_mfma_f32_32x32x16_bf16 (32768 FLOP each) and nothing else; out: [blocks*256] fp32 sink.

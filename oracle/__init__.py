@@ -334,8 +334,10 @@ def logmel(wav, wav_len, n_mels=40, sample_rate=16000, win=400, hop=160, nfft=51
 
 # ----------------------------------------------------------------------------- train step
 def train_step(layers, weights, biases, x, in_len, targets, tgt_len, grad_scale=1.0, blank=0,
-               keep_activations=False):
-    """Forward + backward of the conv-GLU network with the CTC criterion.
+               keep_activations=False, trans=None):
+    """Forward + backward of the conv-GLU network with the CTC criterion, or -- if a transition
+    matrix ``trans`` is given -- with the ASG criterion on the network output as emissions (then
+    the result also holds dtrans, and lp is None).
 
     ``layers`` is a list of dicts {k, stride, cin, cout, glu}.  ``in_len`` counts
     valid input frames per utterance (frames beyond it are expected to be zero in
@@ -354,7 +356,12 @@ def train_step(layers, weights, biases, x, in_len, targets, tgt_len, grad_scale=
         tot_stride *= L["stride"]
     logits = h
     crit_len = np.array([out_len(int(n), tot_stride) for n in in_len], dtype=np.int32)
-    loss, lp, dz = ctc_from_logits(logits, targets, crit_len, tgt_len, blank, grad_scale)
+    dtrans = None
+    if trans is None:
+        loss, lp, dz = ctc_from_logits(logits, targets, crit_len, tgt_len, blank, grad_scale)
+    else:
+        loss, dz, dtrans = asg(logits, trans, targets, crit_len, tgt_len, grad_scale)
+        lp = None
     dws, dbs = [None] * len(layers), [None] * len(layers)
     dh = dz
     for i in range(len(layers) - 1, -1, -1):
@@ -363,7 +370,7 @@ def train_step(layers, weights, biases, x, in_len, targets, tgt_len, grad_scale=
         dws[i], dbs[i] = conv1d_bwd_weight(saved_in[i], dy, L["k"], L["stride"])
         if i > 0:
             dh = conv1d_bwd_data(dy, weights[i], saved_in[i].shape[1], L["stride"])
-    out = dict(loss=loss, logits=logits, lp=lp, dlogits=dz, dw=dws, db=dbs, crit_len=crit_len)
+    out = dict(loss=loss, logits=logits, lp=lp, dlogits=dz, dw=dws, db=dbs, crit_len=crit_len, dtrans=dtrans)
     if keep_activations:
         out["inputs"] = saved_in
         out["pre"] = saved_pre

@@ -22,7 +22,8 @@ __all__ = [
     "w2l_logsoftmax_fwd", "w2l_logsoftmax_bwd", "w2l_ctc_workspace_bytes", "w2l_ctc_fwd_bwd",
     "w2l_ctc_check_targets_host", "w2l_asg_workspace_bytes", "w2l_asg_fwd_bwd", "w2l_asg_check_targets_host",
     "w2l_logmel_num_frames", "w2l_logmel_fwd",
-    "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_sgd_momentum_step",
+    "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_train_step_asg_workspace_bytes", "w2l_train_step_asg",
+    "w2l_sgd_momentum_step",
     "w2l_probe_mfma", "raw",
     "workspace",
 ]
@@ -76,6 +77,9 @@ def _load():
         "w2l_train_step_workspace_bytes": (sz, [C.POINTER(w2l_layer), i, i, i, i, i]),
         "w2l_train_step": (i, [C.POINTER(w2l_layer), i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                C.POINTER(vp), vp, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]),
+        "w2l_train_step_asg_workspace_bytes": (sz, [C.POINTER(w2l_layer), i, i, i, i, i]),
+        "w2l_train_step_asg": (i, [C.POINTER(w2l_layer), i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                   C.POINTER(vp), vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, f, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -307,4 +311,23 @@ def w2l_train_step(layers, weights, biases, dweights, dbiases, x, in_len, target
                               _p(in_len), _p(targets), _p(tgt_len), _p(loss), _p(logits), B, T,
                               targets.shape[1], blank, _dt(x), float(grad_scale), wp, wn, _stream(stream)),
            "w2l_train_step")
+    return loss
+
+
+def w2l_train_step_asg_workspace_bytes(layers, B, T, Lmax, dtype) -> int:
+    arr = _layer_array(layers)
+    return raw.w2l_train_step_asg_workspace_bytes(arr, len(layers), B, T, Lmax, dtype)
+
+
+def w2l_train_step_asg(layers, weights, biases, dweights, dbiases, x, in_len, targets, tgt_len, trans, dtrans, loss,
+                       logits=None, grad_scale=1.0, workspace=None, stream=None):
+    n = len(layers)
+    arr = _layer_array(layers)
+    tab = lambda ts: (C.c_void_p * n)(*[_p(t) for t in ts])
+    B, T, _ = x.shape
+    wp, wn = _ws(workspace)
+    _check(raw.w2l_train_step_asg(arr, n, tab(weights), tab(biases), tab(dweights), tab(dbiases), _p(x),
+                                  _p(in_len), _p(targets), _p(tgt_len), _p(trans), _p(dtrans), _p(loss), _p(logits),
+                                  B, T, targets.shape[1], _dt(x), float(grad_scale), wp, wn, _stream(stream)),
+           "w2l_train_step_asg")
     return loss

@@ -52,6 +52,8 @@ SideStream* side_stream(int n_layers)
     return s.ok ? &s : nullptr;
 }
 
+enum { CRIT_CTC = 0, CRIT_ASG = 1 };
+
 struct Plan {
     int n = 0, C = 0, Tlast = 0, tot_stride = 1;
     std::vector<int> Tin, Tout, outch;
@@ -63,7 +65,7 @@ struct Plan {
 
 size_t haloed_bytes(int B, int frames, int ch, size_t es) { return ((size_t)B * (frames + 2 * HALO) + SLACK) * ch * es; }
 
-Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
+Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype, int criterion)
 {
     Plan p;
     p.n = n;
@@ -113,7 +115,8 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype)
     p.crit_len = off; off += round_up((size_t)B * 4, 256);
     for (int q = 0; q < 3; ++q) { p.gdy[q] = off; off += round_up(dymax, 256); }
     p.gdh = off; off += round_up(dhmax, 256);
-    p.ctc_bytes = w2l_ctc_workspace_bytes(B, p.Tlast, p.C, Lmax);
+    p.ctc_bytes = criterion == CRIT_ASG ? w2l_asg_workspace_bytes(B, p.Tlast, p.C, Lmax) : w2l_ctc_workspace_bytes(B, p.Tlast, p.C, Lmax);
+    if (p.ctc_bytes == 0) { p.status = W2L_ERR_SHAPE; return p; }  // more classes or labels than the criterion takes
     p.ctc = off; off += round_up(p.ctc_bytes, 256);
     p.conv = off; off += round_up(p.conv_bytes, 256);
     int cmax = 0;
@@ -141,21 +144,30 @@ using namespace w2l;
 extern "C" size_t w2l_train_step_workspace_bytes(const w2l_layer* layers, int n_layers, int B, int T, int Lmax,
                                                  int dtype)
 {
-    Plan p = make_plan(layers, n_layers, B, T, Lmax, dtype);
+    Plan p = make_plan(layers, n_layers, B, T, Lmax, dtype, CRIT_CTC);
     return p.status == W2L_OK ? p.total : 0;
 }
 
-extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void* const* weights,
-                              const float* const* biases, float* const* dweights, float* const* dbiases,
-                              const void* x, const int* in_len, const int* targets, const int* tgt_len,
-                              float* loss, float* logits, int B, int T, int Lmax, int blank, int dtype,
-                              float grad_scale, void* workspace, size_t ws_bytes, void* stream)
+extern "C" size_t w2l_train_step_asg_workspace_bytes(const w2l_layer* layers, int n_layers, int B, int T, int Lmax,
+                                                     int dtype)
+{
+    Plan p = make_plan(layers, n_layers, B, T, Lmax, dtype, CRIT_ASG);
+    return p.status == W2L_OK ? p.total : 0;
+}
+
+// network forward, criterion (CTC on the log-softmax of the output, or ASG on the output itself), backward
+static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers, const void* const* weights,
+                           const float* const* biases, float* const* dweights, float* const* dbiases, const void* x,
+                           const int* in_len, const int* targets, const int* tgt_len, const float* trans, float* dtrans,
+                           float* loss, float* logits, int B, int T, int Lmax, int blank, int dtype, float grad_scale,
+                           void* workspace, size_t ws_bytes, void* stream)
 {
     if (!layers || !weights || !biases || !dweights || !dbiases || !x || !in_len || !targets || !tgt_len || !loss)
         return W2L_ERR_NULL;
-    Plan p = make_plan(layers, n_layers, B, T, Lmax, dtype);
+    if (criterion == CRIT_ASG && !trans) return W2L_ERR_NULL;
+    Plan p = make_plan(layers, n_layers, B, T, Lmax, dtype, criterion);
     if (p.status) return p.status;
-    if (blank < 0 || blank >= p.C) return W2L_ERR_SHAPE;
+    if (criterion == CRIT_CTC && (blank < 0 || blank >= p.C)) return W2L_ERR_SHAPE;
     for (int i = 0; i < n_layers; ++i)
         if (!weights[i] || !dweights[i]) return W2L_ERR_NULL;
     if (!workspace || ws_bytes < p.total || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return W2L_ERR_WORKSPACE;
@@ -206,8 +218,12 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
     rc = launch_status();
     if (rc) return rc;
     float* dz = reinterpret_cast<float*>(ws + p.dlogits);
-    rc = w2l_ctc_fwd_bwd(z, 1, targets, clen, tgt_len, loss, dz, B, p.Tlast, p.C, Lmax, blank, grad_scale,
-                         ws + p.ctc, p.ctc_bytes, stream);
+    if (criterion == CRIT_ASG)
+        rc = w2l_asg_fwd_bwd(z, trans, targets, clen, tgt_len, loss, dz, dtrans, B, p.Tlast, p.C, Lmax, grad_scale,
+                             ws + p.ctc, p.ctc_bytes, stream);
+    else
+        rc = w2l_ctc_fwd_bwd(z, 1, targets, clen, tgt_len, loss, dz, B, p.Tlast, p.C, Lmax, blank, grad_scale,
+                             ws + p.ctc, p.ctc_bytes, stream);
     if (rc) return rc;
 
     // ---- backward.  dh = gradient wrt layer i's output (dense); dy = gradient wrt its conv
@@ -289,4 +305,24 @@ extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void*
     // join: the side stream is in order, so its last event covers every weight gradient
     if (side && n > 1 && !hip_ok(hipStreamWaitEvent(st, side->done[1], 0))) return W2L_ERR_LAUNCH;
     return W2L_OK;
+}
+
+extern "C" int w2l_train_step(const w2l_layer* layers, int n_layers, const void* const* weights,
+                              const float* const* biases, float* const* dweights, float* const* dbiases,
+                              const void* x, const int* in_len, const int* targets, const int* tgt_len,
+                              float* loss, float* logits, int B, int T, int Lmax, int blank, int dtype,
+                              float grad_scale, void* workspace, size_t ws_bytes, void* stream)
+{
+    return train_step_impl(CRIT_CTC, layers, n_layers, weights, biases, dweights, dbiases, x, in_len, targets, tgt_len,
+                           nullptr, nullptr, loss, logits, B, T, Lmax, blank, dtype, grad_scale, workspace, ws_bytes, stream);
+}
+
+extern "C" int w2l_train_step_asg(const w2l_layer* layers, int n_layers, const void* const* weights,
+                                  const float* const* biases, float* const* dweights, float* const* dbiases,
+                                  const void* x, const int* in_len, const int* targets, const int* tgt_len,
+                                  const float* trans, float* dtrans, float* loss, float* logits, int B, int T, int Lmax,
+                                  int dtype, float grad_scale, void* workspace, size_t ws_bytes, void* stream)
+{
+    return train_step_impl(CRIT_ASG, layers, n_layers, weights, biases, dweights, dbiases, x, in_len, targets, tgt_len,
+                           trans, dtrans, loss, logits, B, T, Lmax, 0, dtype, grad_scale, workspace, ws_bytes, stream);
 }

@@ -140,3 +140,44 @@ def test_asg_is_deterministic(P):
     b = run_asg(P, cfg["emissions"], cfg["trans"], cfg["targets"], cfg["in_len"], cfg["tgt_len"])
     for u, v in zip(a, b):
         assert np.array_equal(u, v)
+
+
+def test_train_step_with_asg_criterion(P):
+    """w2l_train_step_asg: the network of the bf16 parity case with its output taken as ASG
+    emissions (28 classes) -- loss, every weight / bias gradient and the transition gradient
+    against the oracle's train step with the same criterion."""
+    from gpu_util import rel_l2
+    layers = [dict(k=7, stride=2, cin=40, cout=96, glu=1), dict(k=5, stride=1, cin=48, cout=128, glu=1),
+              dict(k=3, stride=1, cin=64, cout=80, glu=1), dict(k=1, stride=1, cin=40, cout=28, glu=0)]
+    cfg = W.small_model(31, 5, 90, 171, 40, layers, True, 4, 20)
+    rng = np.random.default_rng(32)
+    trans = (rng.standard_normal((28, 28)) * 0.5).astype(np.float32)
+    targets = (cfg["targets"] % 28).astype(np.int32)            # labels 0..27, no blank
+    B, T = cfg["B"], cfg["T"]
+    xd = to_dev(cfg["x"], "bf16")
+    wd = [to_dev(w, "bf16") for w in cfg["weights"]]
+    bd = [to_dev(b) for b in cfg["biases"]]
+    dwd = [empty(w.shape) for w in cfg["weights"]]
+    dbd = [empty(b.shape) for b in cfg["biases"]]
+    tg, il, tl, td = to_dev(targets), to_dev(cfg["in_len"]), to_dev(cfg["tgt_len"]), to_dev(trans)
+    dtd, loss = empty((28, 28)), empty((B,))
+    Lmax = targets.shape[1]
+    ws = P.workspace(P.w2l_train_step_asg_workspace_bytes(layers, B, T, Lmax, P.W2L_BF16))
+    Tl = oracle.out_len(T, 2)
+    logits = empty((B, Tl, 28))
+    P.w2l_train_step_asg(layers, wd, bd, dwd, dbd, xd, il, tg, tl, td, dtd, loss, logits, 0.5, ws)
+    torch.cuda.synchronize()
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    ref = oracle.train_step(layers, [f64(w) for w in cfg["weights"]], [f64(b) for b in cfg["biases"]], f64(cfg["x"]),
+                            cfg["in_len"], targets, cfg["tgt_len"], 0.5, trans=f64(trans))
+    tol = 2e-2                                                   # bf16 activations between the layers
+    assert rel_l2(to_host(logits), ref["logits"]) <= tol
+    assert np.all(np.abs(to_host(loss) - ref["loss"]) <= tol * np.abs(ref["loss"]))
+    for i, (a, b) in enumerate(zip(dwd, ref["dw"])):
+        assert rel_l2(to_host(a), b) <= tol, "dw of layer %d" % i
+    for i, (a, b) in enumerate(zip(dbd, ref["db"])):
+        assert rel_l2(to_host(a), b) <= tol, "db of layer %d" % i
+    assert rel_l2(to_host(dtd), ref["dtrans"]) <= tol
+    # a class count the criterion does not take is reported, not run
+    big = [dict(k=1, stride=1, cin=40, cout=80, glu=0)]
+    assert P.w2l_train_step_asg_workspace_bytes(big, 2, 50, 5, P.W2L_F32) == 0
