@@ -217,7 +217,7 @@ int w2l_asg_check_targets_host(const int *targets, const int *in_len, const int 
  *      layout and padding w2l_train_step expects of x; feat_len [B] int32 = min(T_b, Tmax), the
  *      in_len of that call.
  * All device pointers, no workspace; arithmetic fp32 (mel points in double).
- * Limits: nfft a power of two in [128, 1024], 2 <= win <= nfft, hop >= 1, n_mels <= 256,
+ * Limits: nfft a power of two in [128, 1024], 2 <= win <= nfft, hop >= 1, n_mels <= 255,
  * 0 <= fmin < fmax <= sample_rate/2, floor > 0.  Errors: W2L_ERR_NULL / _SHAPE / _DTYPE / _LAUNCH.
  * w2l_logmel_num_frames: the frame count above, on the host. */
 int w2l_logmel_num_frames(int n_samples, int win, int hop);
