@@ -236,7 +236,8 @@ __global__ __launch_bounds__(256) void wgrad_skinny_stage2(const float* __restri
     const long long i = blockIdx.x * 256LL + threadIdx.x;
     if (i >= total) return;
     float acc = 0.f;
-    for (int c = 0; c < chunks; ++c) acc += part[(size_t)c * total + i];
+#pragma unroll 8
+    for (int c = 0; c < chunks; ++c) acc += part[(size_t)c * total + i];  // independent loads, added in order
     dw[i] = accumulate ? dw[i] + acc : acc;
 }
 
