@@ -2,7 +2,13 @@
 
 Thin ctypes marshalling around ``w2l_oracle.c`` (plain C loops, double precision)
 plus :func:`train_step`, which strings those definitions together in the order of
-the paper's training loop (Sec. 2.3: network forward, criterion, backward).
+the paper's training loop (Sec. 2.3: network forward, criterion, backward), and
+:func:`logmel`, the log-mel feature recipe (Sec. 2.2) in numpy, fp64.
+
+Parity status: :func:`asg` and :func:`logmel` follow definitions the paper only names (it
+cites the criterion's source and fixes no feature constant), so both are "parity unpinned" with
+respect to the paper's text; each is pinned to its stated definition by brute force, closed
+forms and invariants in ``tests/test_oracle_asg.py`` / ``tests/test_oracle_logmel.py``.
 
 Only tests, the smoke check and the bench's ``cpu_baseline`` leg may import this
 package.  It shares nothing with the HIP library and never imports it.
