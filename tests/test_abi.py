@@ -93,3 +93,45 @@ def test_train_step_plan_checks():
     bad = [dict(l) for l in lay]
     bad[-1]["glu"] = 1
     assert P.w2l_train_step_workspace_bytes(bad, 8, 1500, 150, P.W2L_BF16) == 0
+
+
+def test_host_side_argument_checks_of_the_widened_rows():
+    """ASG, log-mel and the optimiser step reject bad arguments before any launch (no GPU needed)."""
+    import paper_1812_07625_amd as P
+    r = P.raw
+    NULL = None
+    fake = 0x1000
+    ws = 0x1100  # 256-byte aligned, never dereferenced
+    # ASG: B, Tp, C, Lmax
+    assert r.w2l_asg_fwd_bwd(fake, NULL, fake, fake, fake, fake, fake, fake, 2, 10, 5, 3, 1.0, ws, 1 << 30, NULL) == -1
+    assert r.w2l_asg_fwd_bwd(fake, fake, fake, fake, fake, fake, fake, NULL, 2, 10, 65, 3, 1.0, ws, 1 << 30, NULL) == -2  # C > 64
+    assert r.w2l_asg_fwd_bwd(fake, fake, fake, fake, fake, fake, fake, NULL, 2, 10, 5, 3001, 1.0, ws, 1 << 30, NULL) == -2
+    assert r.w2l_asg_fwd_bwd(fake + 4, fake, fake, fake, fake, fake, fake, NULL, 2, 10, 5, 3, 1.0, ws, 1 << 30, NULL) == -4
+    assert r.w2l_asg_fwd_bwd(fake, fake, fake, fake, fake, fake, fake, NULL, 2, 10, 5, 3, 1.0, NULL, 0, NULL) == -5
+    assert r.w2l_asg_fwd_bwd(fake, fake, fake, fake, fake, fake, fake, NULL, 2, 10, 5, 3, 1.0, ws, 64, NULL) == -5
+    assert r.w2l_asg_workspace_bytes(2, 10, 5, 3) > 4 * 2 * 11 * 7 * 4
+    assert r.w2l_asg_workspace_bytes(2, 10, 65, 3) == 0
+    t = np.array([[1, 2, 3], [4, 4, 0]], np.int32)
+    assert P.w2l_asg_check_targets_host(t, [10, 10], [3, 3], 10, 5) == 0      # label 0 and equal neighbours are fine
+    assert P.w2l_asg_check_targets_host(t, [10, 10], [3, 2], 10, 4) == -6     # label >= C
+    assert P.w2l_asg_check_targets_host(t, [10, 11], [3, 2], 10, 5) == -6
+    # log-mel: B, Nmax, Tmax, n_mels, sample_rate, win, hop, nfft, fmin, fmax, floor, dtype
+    ok = (2, 4000, 20, 40, 16000, 400, 160, 512, 0.0, 8000.0, 1e-10, 0)
+    assert r.w2l_logmel_fwd(NULL, fake, fake, fake, *ok, NULL) == -1
+    for pos, val in ((7, 500), (7, 2048), (5, 600), (3, 256), (9, 9000.0), (8, 8000.0), (10, 0.0), (6, 0)):
+        bad = list(ok)
+        bad[pos] = val
+        assert r.w2l_logmel_fwd(fake, fake, fake, fake, *bad, NULL) == -2, (pos, val)
+    bad = list(ok)
+    bad[11] = 5
+    assert r.w2l_logmel_fwd(fake, fake, fake, fake, *bad, NULL) == -3
+    assert r.w2l_logmel_num_frames(400, 400, 160) == 1 and r.w2l_logmel_num_frames(399, 400, 160) == 0
+    # optimiser step
+    assert r.w2l_sgd_momentum_step(fake, NULL, fake, NULL, 16, 0.1, 0.9, 0.0, NULL) == -1
+    assert r.w2l_sgd_momentum_step(fake, fake, fake, NULL, -1, 0.1, 0.9, 0.0, NULL) == -2
+    assert r.w2l_sgd_momentum_step(fake + 4, fake, fake, NULL, 16, 0.1, 0.9, 0.0, NULL) == -4
+    # train step with ASG: class count and missing transitions
+    lay = [dict(k=3, stride=1, cin=8, cout=16, glu=1), dict(k=1, stride=1, cin=8, cout=12, glu=0)]
+    assert P.w2l_train_step_asg_workspace_bytes(lay, 2, 20, 4, P.W2L_F32) > 0
+    lay[-1]["cout"] = 70
+    assert P.w2l_train_step_asg_workspace_bytes(lay, 2, 20, 4, P.W2L_F32) == 0
