@@ -15,29 +15,36 @@ struct alignas(16) f32x4 { float v[4]; };
 template <typename T> struct Vec8;
 template <> struct Vec8<bf16_t> {
     static __device__ __forceinline__ void load(const bf16_t* p, float* o) {
-        bf16x8 r = *reinterpret_cast<const bf16x8*>(p);
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const u4 r = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));  // streaming: each element is touched once
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = bf16_to_f32(r.v[i]);
+        for (int i = 0; i < 4; ++i) {
+            o[2 * i] = bf16_to_f32((bf16_t)(r[i] & 0xffffu));
+            o[2 * i + 1] = bf16_to_f32((bf16_t)(r[i] >> 16));
+        }
     }
     static __device__ __forceinline__ void store(bf16_t* p, const float* o) {
-        bf16x8 r;
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        u4 r;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) r.v[i] = f32_to_bf16(o[i]);
-        *reinterpret_cast<bf16x8*>(p) = r;
+        for (int i = 0; i < 4; ++i) r[i] = (unsigned)f32_to_bf16(o[2 * i]) | ((unsigned)f32_to_bf16(o[2 * i + 1]) << 16);
+        __builtin_nontemporal_store(r, reinterpret_cast<u4*>(p));
     }
 };
 template <> struct Vec8<float> {
     static __device__ __forceinline__ void load(const float* p, float* o) {
-        f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const f4 a = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p)), b = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p) + 1);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { o[i] = a.v[i]; o[4 + i] = b.v[i]; }
+        for (int i = 0; i < 4; ++i) { o[i] = a[i]; o[4 + i] = b[i]; }
     }
     static __device__ __forceinline__ void store(float* p, const float* o) {
-        f32x4 a, b;
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        f4 a, b;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { a.v[i] = o[i]; b.v[i] = o[4 + i]; }
-        *reinterpret_cast<f32x4*>(p) = a;
-        *reinterpret_cast<f32x4*>(p + 4) = b;
+        for (int i = 0; i < 4; ++i) { a[i] = o[i]; b[i] = o[4 + i]; }
+        __builtin_nontemporal_store(a, reinterpret_cast<f4*>(p));
+        __builtin_nontemporal_store(b, reinterpret_cast<f4*>(p) + 1);
     }
 };
 
@@ -350,20 +357,24 @@ __global__ __launch_bounds__(256) void sgd_momentum_k(float* __restrict__ w, flo
                                                       long long n, float lr, float mu, float wd)
 {
     const long long n4 = n / 4;
+    // every value is touched exactly once: streaming (non-temporal) loads and stores keep it out of the caches
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) {
-        float4 wv = reinterpret_cast<float4*>(w)[i], vv = reinterpret_cast<float4*>(v)[i];
-        const float4 gv = reinterpret_cast<const float4*>(g)[i];
+        f4 wv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(w) + i);
+        f4 vv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(v) + i);
+        const f4 gv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g) + i);
         vv.x = mu * vv.x + (gv.x + wd * wv.x); wv.x -= lr * vv.x;
         vv.y = mu * vv.y + (gv.y + wd * wv.y); wv.y -= lr * vv.y;
         vv.z = mu * vv.z + (gv.z + wd * wv.z); wv.z -= lr * vv.z;
         vv.w = mu * vv.w + (gv.w + wd * wv.w); wv.w -= lr * vv.w;
-        reinterpret_cast<float4*>(w)[i] = wv;
-        reinterpret_cast<float4*>(v)[i] = vv;
+        __builtin_nontemporal_store(wv, reinterpret_cast<f4*>(w) + i);
+        __builtin_nontemporal_store(vv, reinterpret_cast<f4*>(v) + i);
         if (lowp) {
-            uint2 o;
+            u2 o;
             o.x = (unsigned)w2l::f32_to_bf16(wv.x) | ((unsigned)w2l::f32_to_bf16(wv.y) << 16);
             o.y = (unsigned)w2l::f32_to_bf16(wv.z) | ((unsigned)w2l::f32_to_bf16(wv.w) << 16);
-            reinterpret_cast<uint2*>(lowp)[i] = o;
+            __builtin_nontemporal_store(o, reinterpret_cast<u2*>(lowp) + i);
         }
     }
     // tail (n % 4 values)
