@@ -261,24 +261,15 @@ __device__ __forceinline__ float swap_pair(float v)  // value of lane ^ 1
 #define W2L_MUL_ROR(acc, x, e, R) asm volatile("v_mul_f32_dpp %0, %1, %2" W2L_DPP_TAIL(R) : "=v"(acc) : "v"(x), "v"(e))
 #define W2L_MUL_ROR_FIRST(acc, x, e, R) \
     asm volatile("s_nop 1\n\tv_mul_f32_dpp %0, %1, %2" W2L_DPP_TAIL(R) : "=v"(acc) : "v"(x), "v"(e))
+// one link of the maximum over lanes 0..31 of non-negative floats (their bit patterns order like
+// unsigned integers; result in lane 31 after row_shr:1,2,4,8 and row_bcast:15).  Two other
+// instructions must separate it from the previous write of u.
+#define W2L_MAX_LINK(u, CTRL) asm volatile("v_max_u32_dpp %0, %0, %0 " CTRL " bank_mask:0xf" : "+v"(u))
 template <int R>
 __device__ __forceinline__ int ror_i(int x)
 {
     return R == 0 ? x : __builtin_amdgcn_update_dpp(0, x, 0x120 + (R == 0 ? 1 : R), 0xf, 0xf, true);
 }
-// largest value over lanes 0..31 of non-negative floats (their bit patterns order like unsigned
-// integers), valid in lane 31: four row shifts and one row broadcast, each a single DPP instruction
-__device__ __forceinline__ unsigned max_bits_lane31(unsigned u)
-{
-    asm volatile("s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
-                 "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
-                 "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
-                 "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
-                 "s_nop 1\n\tv_max_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf"
-                 : "+v"(u));
-    return u;
-}
-
 // Linear recursion for up to 32 classes without LDS: class = lane & 31, so a row of 16 lanes
 // holds 16 classes and both halves of the wavefront hold every class.  A lane reaches the 16
 // states of a row with DPP row rotations; lanes 0..31 sum over the source classes of their own
@@ -351,13 +342,11 @@ __device__ __forceinline__ void fcc_linear_rows(const float* __restrict__ em, co
             const int step = tb * AHEAD + k;
             float* const row = step < T ? rptr : spare;
             rptr += rstep;
-            // every second step: the exponent of the largest input state (0 for an all-zero input); the
-            // scaling is folded into the emission factor, off the chain of the states
-            int ex = 0;
-            if (!(k & 1))
-                ex = __builtin_amdgcn_frexp_expf(
-                    __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)max_bits_lane31(__float_as_uint(a)), 31)));
-            const float e = (k & 1) ? s2[k] : __builtin_amdgcn_ldexpf(s2[k], -ex);
+            // every second step: the exponent of the largest input state (0 for an all-zero input), folded
+            // into the emission factor.  The five links of that reduction are dependent DPP instructions;
+            // they are spread between the independent multiply-adds below, which cover their wait states.
+            const bool scale = !(k & 1);
+            unsigned mb = __float_as_uint(a);
             const auto o16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(a), false, false);
             const float x = __uint_as_float(take0 ? o16[0] : o16[1]);
             float acc[4];  // four chains: a dependent fma would wait for the one before it
@@ -365,18 +354,25 @@ __device__ __forceinline__ void fcc_linear_rows(const float* __restrict__ em, co
             W2L_MUL_ROR_FIRST(acc[1], x, E[1], 1);
             W2L_MUL_ROR(acc[2], x, E[2], 2);
             W2L_MUL_ROR(acc[3], x, E[3], 3);
+            if (scale) W2L_MAX_LINK(mb, "row_shr:1 row_mask:0xf");
             W2L_FMAC_ROR(acc[0], x, E[4], 4);
             W2L_FMAC_ROR(acc[1], x, E[5], 5);
             W2L_FMAC_ROR(acc[2], x, E[6], 6);
+            if (scale) W2L_MAX_LINK(mb, "row_shr:2 row_mask:0xf");
             W2L_FMAC_ROR(acc[3], x, E[7], 7);
             W2L_FMAC_ROR(acc[0], x, E[8], 8);
             W2L_FMAC_ROR(acc[1], x, E[9], 9);
+            if (scale) W2L_MAX_LINK(mb, "row_shr:4 row_mask:0xf");
             W2L_FMAC_ROR(acc[2], x, E[10], 10);
             W2L_FMAC_ROR(acc[3], x, E[11], 11);
             W2L_FMAC_ROR(acc[0], x, E[12], 12);
+            if (scale) W2L_MAX_LINK(mb, "row_shr:8 row_mask:0xf");
             W2L_FMAC_ROR(acc[1], x, E[13], 13);
             W2L_FMAC_ROR(acc[2], x, E[14], 14);
             W2L_FMAC_ROR(acc[3], x, E[15], 15);
+            if (scale) W2L_MAX_LINK(mb, "row_bcast:15 row_mask:0xa");
+            const int ex = scale ? __builtin_amdgcn_frexp_expf(__uint_as_float((unsigned)__builtin_amdgcn_readlane((int)mb, 31))) : 0;
+            const float e = scale ? __builtin_amdgcn_ldexpf(s2[k], -ex) : s2[k];
             const float part = (acc[0] + acc[1]) + (acc[2] + acc[3]);
             const auto o32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(part), __float_as_uint(part), false, false);
             const float raw = __uint_as_float(o32[0]) + __uint_as_float(o32[1]);  // lower half + upper half, in every lane
