@@ -11,14 +11,17 @@
 // Kernels, all deterministic (no floating-point atomics):
 //   1. asg_lattice: one workgroup per (utterance, lattice, direction).  Forward and backward run
 //      concurrently (backward = the same recursion on reversed time with the transposed
-//      transitions, and for FAL the reversed target), so the serial chain is T_b steps.  Base-2
-//      log domain (hardware exp2/log2), fp32 states relative to a double-precision offset that
-//      absorbs the largest state every 16 frames, "log zero" a large negative finite number.
-//      FAL: one lane per target position, the value of the position to the left by a DPP
-//      wavefront shift; wavefronts overlap by 16 mirrored positions so that nothing crosses a
-//      wavefront boundary inside a block of 16 frames.  FCC: one wavefront, lane = class; a step
-//      reads all C states of the previous frame through lane broadcasts and does a full
-//      log-sum-exp, so any range of transition scores is handled.
+//      transitions, and for FAL the reversed target), so the serial chain is T_b steps.  Rows are
+//      stored as base-2 logs, fp32, relative to a double-precision offset per frame; "log zero" is
+//      a large negative finite number.
+//      FAL: log domain (hardware exp2/log2), one lane per target position, the value of the
+//      position to the left by a DPP wavefront shift; wavefronts overlap by 16 mirrored positions
+//      so that nothing crosses a wavefront boundary inside a block of 16 frames, at whose end the
+//      largest state moves into the offset.
+//      FCC: one wavefront.  While the transition scores span at most LINEAR_RANGE bits the states
+//      are plain numbers and a step is a matrix-vector product with exact power-of-two rescaling
+//      (up to 32 classes: lane rotations and swaps only; up to 64: through a small LDS array);
+//      beyond that range a log-domain recursion with a full log-sum-exp per state takes over.
 //   2. asg_grad_em: per frame, node occupancies of both lattices, each normalised per frame;
 //      FAL positions are summed per class in a fixed order ((class, position) sort).
 //   3. asg_trans_partial: per (utterance, 32 frames), edge occupancies summed over the frames:
