@@ -5,18 +5,20 @@
 // Three kernels, all deterministic (no floating-point atomics):
 //   1. (logits only) per-frame log-softmax into the workspace;
 //   2. ctc_lattice: one workgroup per (utterance, direction).  alpha runs forward in
-//      time, beta is the same recursion on the reversed label sequence and reversed
-//      time, so the two run concurrently and the serial chain is T_b steps, not 2 T_b.
-//      Scores are kept in the base-2 log domain so that the log-sum-exp maps onto the
-//      hardware exp2/log2 instructions.  States are fp32 values *relative to a running
-//      offset*: every 16 frames the workgroup's largest state is subtracted from all of
-//      them and added to a double-precision offset, so the fp32 values stay small (their
-//      rounding error does not grow with t) while the magnitude lives in the offset.
-//      "Log zero" is a large negative finite number, which keeps the recursion free of
-//      branches and NaNs;
-//   3. ctc_grad: one wavefront per frame combines alpha_t and beta_t into the state
-//      posteriors, normalises them per frame, and sums them per class in a fixed
-//      order given by a (class, position) sort of the target.
+//      time, beta is the same recursion on the reversed label sequence and reversed time,
+//      so the two run concurrently and the serial chain is T_b steps, not 2 T_b.
+//      A state is kept as a pair (v, e): its value is v * 2^e with v a float and e a 32-bit
+//      integer -- the range of the log domain without a transcendental on the chain.  The
+//      sum of predecessors aligns their exponents with v_ldexp and adds; the frame's score
+//      enters as 2^(lp * log2 e) split into an integer exponent and a mantissa in [1, 2).
+//      All terms are non-negative, so a mantissa never shrinks and grows by at most 6x per
+//      frame: every 16 frames each lane moves the exponent of its own mantissas into e.
+//      A zero state has v = 0 and a large negative e, which keeps the step free of branches;
+//      the lattice rows hold the (v, e) pairs;
+//   3. ctc_grad: one wavefront per frame combines alpha_t and beta_t (mantissas
+//      multiplied, exponents added, log P taken off) into the state posteriors, normalises
+//      them per frame, and sums them per class in a fixed order given by a (class, position)
+//      sort of the target.
 #include "common.h"
 
 namespace w2l {
@@ -28,35 +30,12 @@ constexpr int GRAD_ROWS = 16;   // frames per ctc_grad workgroup (4 per wavefron
 
 struct CtcDims {
     int B, Tp, C, Lmax, blank;
-    int Sp;  // lattice row pitch = 2*Lmax+4: pairs of doubles, the last pair is a spare; Tp+1 rows per utterance
+    int Sp;  // lattice row pitch in states = 2*Lmax+4 (the last pair is a spare); a state is 8 bytes; Tp+1 rows per utterance
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
-constexpr float NEG = -1.0e30f;      // log zero: absorbs every finite addend, never turns into NaN
-constexpr float NEG_TEST = -1.0e29f;  // anything below is "log zero"
-
-// log2( 2^a + 2^b [+ 2^c] ); operands may be NEG.  The largest term contributes exactly 1, so
-// only the others cost an exp2.
-__device__ __forceinline__ float lse3_log2(float a, float b, float c)
-{
-    const float m = __builtin_fmaxf(__builtin_fmaxf(a, b), c);
-    const float lo = __builtin_fminf(__builtin_fminf(a, b), c);
-    const float md = __builtin_amdgcn_fmed3f(a, b, c);
-    return m + fast_log2(1.f + fast_exp2(md - m) + fast_exp2(lo - m));
-}
-__device__ __forceinline__ float lse2_log2(float a, float b)
-{
-    const float m = fmaxf(a, b);
-    return m + fast_log2(1.f + fast_exp2(fminf(a, b) - m));
-}
-__device__ __forceinline__ float wave_max_f(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
 // value of the lane to the left (lane - 1); lane 0 gets `edge`
 __device__ __forceinline__ float from_left_lane(float v, float edge)
 {
@@ -69,6 +48,16 @@ constexpr int SCORE_AHEAD = 16;  // frames of scores held in registers ahead of 
 constexpr int HALO_LANES = SCORE_AHEAD;     // lanes of a wavefront that mirror the wavefront on its left
 constexpr int OWN_LANES = 64 - HALO_LANES;  // lanes whose states a wavefront owns (and stores)
 
+constexpr int EZ = -(1 << 30);        // exponent of a zero state
+constexpr float MIN_LOG2 = -65536.f;  // scores below 2^-65536 are taken as that (keeps integer exponents far from overflow)
+
+__device__ __forceinline__ int from_left_lane_i(int v, int edge)
+{
+    return __builtin_amdgcn_update_dpp(edge, v, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
+}
+// v * 2^e for a (v, e) pair as a double-precision base-2 log; -inf for a zero state
+__device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (double)fast_log2(v) + (double)e : -INFINITY; }
+
 // One workgroup per (utterance, direction).  The extended sequence is cut into pairs
 // (blank 2i, label 2i+1); a lane holds PPT consecutive pairs in registers, so per frame it needs
 // exactly one value from outside: the label state of the pair to its left, which a DPP
@@ -77,25 +66,21 @@ constexpr int OWN_LANES = 64 - HALO_LANES;  // lanes whose states a wavefront ow
 // recompute the pairs owned by the last lanes of the wavefront on its left.  Their leftmost input
 // is missing, so they go stale from the left at one pair per frame -- after SCORE_AHEAD frames
 // the staleness has not yet reached the lanes the wavefront owns -- and once per block they are
-// refreshed through LDS, at the one barrier of the block, where the states are also
-// renormalised.  The dependency chain of a frame is therefore one lane shift and one
-// log-sum-exp.  States to the right of the target's last pair are computed too (nothing reads
-// them; a state depends only on states to its left); states left of pair 0 stay at log zero.
-// The scores lp[t, blank] and lp[t, label] are fetched SCORE_AHEAD frames early into a register
-// ring.  beta is the same recursion on the reversed sequence and reversed time (state index q
-// counts from the end), stored in its own q order.  The step body is straight-line code with a
-// fixed number of memory operations (lanes that own no real pair write to a spare pair, steps
-// past the last frame to a spare row).
-// Stored per frame: the relative states (fp32) and the offset that applies to them (fp64).
+// refreshed through LDS, at the one barrier of the block.  States to the right of the target's
+// last pair are computed too (nothing reads them; a state depends only on states to its left);
+// states left of pair 0 stay zero.  The scores lp[t, blank] and lp[t, label] are fetched
+// SCORE_AHEAD frames early into a register ring.  beta is the same recursion on the reversed
+// sequence and reversed time (state index q counts from the end), stored in its own q order.
+// The step body is straight-line code with a fixed number of memory operations (lanes that own
+// no real pair write to a spare pair, steps past the last frame to a spare row).
+// Stored per frame and state: the pair (v, e), e as the bits of the second float.
 template <int PPT>
 __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp, const int* __restrict__ targets,
                                                     const int* __restrict__ in_len, const int* __restrict__ tgt_len,
                                                     float* __restrict__ loss, double* __restrict__ logp2_out,
-                                                    float* __restrict__ alpha, float* __restrict__ beta,
-                                                    double* __restrict__ aoff, double* __restrict__ boff, CtcDims d)
+                                                    float2* __restrict__ alpha, float2* __restrict__ beta, CtcDims d)
 {
-    __shared__ float xbuf[2][16][HALO_LANES][2 * PPT];  // [block parity][wavefront][lane - OWN_LANES][state]
-    __shared__ float wmax[2][16];
+    __shared__ float xbuf[2][16][HALO_LANES][4 * PPT];  // [block parity][wavefront][lane - OWN_LANES][v, e of blank, label]
     __shared__ int bad_len, bad;
     const int dir = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
@@ -132,8 +117,8 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     int cls[PPT];     // class of the label state
     bool skip[PPT];   // label state may be entered from the label of the pair to the left
     int slot[PPT];    // lattice position of the pair (the spare pair for lanes that own no real pair)
-    bool cnt_b[PPT], cnt_l[PPT];  // states that count towards the renormalisation maximum: real and owned
-    float ab[PPT], al[PPT];
+    float vb[PPT], vl[PPT];
+    int eb[PPT], el[PPT];
 #pragma unroll
     for (int j = 0; j < PPT; ++j) {
         const int i = gi * PPT + j;
@@ -142,15 +127,15 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         cls[j] = has_l ? lab[li] : d.blank;
         skip[j] = has_l && i >= 1 && lab[dir ? li + 1 : li - 1] != cls[j];
         slot[j] = 2 * ((real && owner) ? i : d.Lmax + 1);
-        cnt_b[j] = real && owner;
-        cnt_l[j] = has_l && owner;
         // the state "before frame 0": all mass in front of pair 0, so that frame 0 comes out of the recursion itself
-        ab[j] = (gi >= 0 && i == 0) ? 0.f : NEG;
-        al[j] = NEG;
+        const bool start = gi >= 0 && i == 0;
+        vb[j] = start ? 1.f : 0.f;
+        eb[j] = start ? 0 : EZ;
+        vl[j] = 0.f;
+        el[j] = EZ;
     }
     const float* lpb = lp + (size_t)b * d.Tp * d.C;
-    float* lat = (dir ? beta : alpha) + (size_t)b * (d.Tp + 1) * d.Sp;
-    double* offs = (dir ? boff : aoff) + (size_t)b * (d.Tp + 1);
+    float2* lat = (dir ? beta : alpha) + (size_t)b * (d.Tp + 1) * d.Sp;
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
     const float log2e = (float)LOG2E;
 
@@ -162,98 +147,108 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
         for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
     }
-    double offset = 0;  // true log2 value = relative value + offset
     const int nwaves = NT >> 6;
     const int tblocks = (T + SCORE_AHEAD - 1) / SCORE_AHEAD;
     // running pointers instead of per-step index arithmetic: the score row fetched next (clamped
     // at the last frame) and the lattice row written next
     const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)d.Sp : d.Sp;
     const float* sptr = lpb + (size_t)frame(SCORE_AHEAD - 1 < T ? SCORE_AHEAD - 1 : T - 1) * d.C;
-    float* rptr = lat + (size_t)frame(0) * d.Sp;
-    float* const spare = lat + (size_t)d.Tp * d.Sp;
+    float2* rptr = lat + (size_t)frame(0) * d.Sp;
+    float2* const spare = lat + (size_t)d.Tp * d.Sp;
+    // 2^(lp log2 e) = pm * 2^pe with pm in [1, 2)
+    auto split = [&](float s, float& pm, int& pe) {
+        const float x = fmaxf(s * log2e, MIN_LOG2);
+        const float fl = floorf(x);
+        pe = (int)fl;
+        pm = fast_exp2(x - fl);
+    };
 
     for (int tb = 0; tb < tblocks; ++tb) {
 #pragma unroll
         for (int k = 0; k < SCORE_AHEAD; ++k) {
             const int step = tb * SCORE_AHEAD + k;
-            const float s_b = sb[k];
-            float s_l[PPT];
+            float pmb, pml[PPT];
+            int peb, pel[PPT];
+            split(sb[k], pmb, peb);
 #pragma unroll
-            for (int j = 0; j < PPT; ++j) s_l[j] = sl[j][k];
+            for (int j = 0; j < PPT; ++j) split(sl[j][k], pml[j], pel[j]);
             {   // refill this ring slot for step + SCORE_AHEAD (past the end: the last frame again)
                 sptr += (step + SCORE_AHEAD < T) ? sstep : 0;
                 sb[k] = sptr[d.blank];
 #pragma unroll
                 for (int j = 0; j < PPT; ++j) sl[j][k] = sptr[cls[j]];
             }
-            float* const row = step < T ? rptr : spare;
+            float2* const row = step < T ? rptr : spare;
             rptr += rstep;
-            // label value (previous frame) of the pair to the left of this lane's first pair
-            float carry = from_left_lane(al[PPT - 1], NEG);
+            // label state (previous frame) of the pair to the left of this lane's first pair
+            float cv = from_left_lane(vl[PPT - 1], 0.f);
+            int ce = from_left_lane_i(el[PPT - 1], EZ);
 #pragma unroll
             for (int j = 0; j < PPT; ++j) {
-                const float ob = ab[j], ol = al[j];
-                const float nb = fmaf(s_b, log2e, lse2_log2(ob, carry));
-                const float nl = fmaf(s_l[j], log2e, lse3_log2(ol, ob, skip[j] ? carry : NEG));
-                carry = ol;
-                ab[j] = nb;
-                al[j] = nl;
-                *reinterpret_cast<float2*>(row + slot[j]) = make_float2(nb, nl);
+                const float obv = vb[j], olv = vl[j];
+                const int obe = eb[j], ole = el[j];
+                // blank: from itself and from the label on its left
+                const int E1 = max(obe, ce);
+                const float s1 = __builtin_amdgcn_ldexpf(obv, obe - E1) + __builtin_amdgcn_ldexpf(cv, ce - E1);
+                // label: from itself, from its blank, and (different neighbouring labels) from the label on its left
+                const float cvs = skip[j] ? cv : 0.f;
+                const int cs = skip[j] ? ce : EZ;
+                const int E2 = max(max(ole, obe), cs);
+                const float s2 = (__builtin_amdgcn_ldexpf(olv, ole - E2) + __builtin_amdgcn_ldexpf(obv, obe - E2)) +
+                                 __builtin_amdgcn_ldexpf(cvs, cs - E2);
+                cv = olv;
+                ce = ole;
+                vb[j] = pmb * s1;
+                eb[j] = s1 > 0.f ? E1 + peb : EZ;
+                vl[j] = pml[j] * s2;
+                el[j] = s2 > 0.f ? E2 + pel[j] : EZ;
+                *reinterpret_cast<float4*>(row + slot[j]) = make_float4(vb[j], __int_as_float(eb[j]), vl[j], __int_as_float(el[j]));
             }
         }
-        if (tid < SCORE_AHEAD) {  // the offset of the block's frames (it changes only at block boundaries)
-            const int step = tb * SCORE_AHEAD + tid;
-            offs[step < T ? frame(step) : d.Tp] = offset;
-        }
-        // ---- block boundary: refresh the mirror lanes from the left neighbour, renormalise
-        const int par = tb & 1;
-        float m = NEG;
+        // ---- block boundary: every lane moves the exponents of its mantissas into e; the mirror
+        // lanes are refreshed from the left neighbour
 #pragma unroll
-        for (int j = 0; j < PPT; ++j) m = fmaxf(m, fmaxf(cnt_b[j] ? ab[j] : NEG, cnt_l[j] ? al[j] : NEG));
-        m = wave_max_f(m);
+        for (int j = 0; j < PPT; ++j) {
+            const int xb = __builtin_amdgcn_frexp_expf(vb[j]), xl = __builtin_amdgcn_frexp_expf(vl[j]);  // 0 for a zero state
+            vb[j] = __builtin_amdgcn_ldexpf(vb[j], -xb);
+            eb[j] += vb[j] > 0.f ? xb : 0;
+            vl[j] = __builtin_amdgcn_ldexpf(vl[j], -xl);
+            el[j] += vl[j] > 0.f ? xl : 0;
+        }
         if (nwaves > 1) {
-            if (lane == 0) wmax[par][wave] = m;
+            const int par = tb & 1;
             if (lane >= OWN_LANES) {
 #pragma unroll
                 for (int j = 0; j < PPT; ++j) {
-                    xbuf[par][wave][lane - OWN_LANES][2 * j] = ab[j];
-                    xbuf[par][wave][lane - OWN_LANES][2 * j + 1] = al[j];
+                    float* q = &xbuf[par][wave][lane - OWN_LANES][4 * j];
+                    q[0] = vb[j]; q[1] = __int_as_float(eb[j]); q[2] = vl[j]; q[3] = __int_as_float(el[j]);
                 }
             }
             __syncthreads();
             if (wave > 0 && !owner) {
 #pragma unroll
                 for (int j = 0; j < PPT; ++j) {
-                    ab[j] = xbuf[par][wave - 1][lane][2 * j];
-                    al[j] = xbuf[par][wave - 1][lane][2 * j + 1];
+                    const float* q = &xbuf[par][wave - 1][lane][4 * j];
+                    vb[j] = q[0]; eb[j] = __float_as_int(q[1]); vl[j] = q[2]; el[j] = __float_as_int(q[3]);
                 }
             }
-            m = wmax[par][0];
-            for (int w2 = 1; w2 < nwaves; ++w2) m = fmaxf(m, wmax[par][w2]);
-        }
-        if (m > NEG_TEST) {  // uniform over the workgroup
-#pragma unroll
-            for (int j = 0; j < PPT; ++j) {
-                ab[j] = ab[j] > NEG_TEST ? ab[j] - m : NEG;
-                al[j] = al[j] > NEG_TEST ? al[j] - m : NEG;
-            }
-            offset += (double)m;
         }
     }
-    // log P = lse( alpha_{T-1}(S-1), alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1, read back
+    // log P = log( alpha_{T-1}(S-1) + alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1, read back
     // from the stored lattice row of the last frame (written by this workgroup)
     if (dir == 0) {
         __syncthreads();
         if (tid == 0) {
-            const float* last = lat + (size_t)(T - 1) * d.Sp;
-            const float fb = __builtin_nontemporal_load(last + 2 * L);
-            const float fl = L > 0 ? __builtin_nontemporal_load(last + 2 * L - 1) : NEG;
-            const double fin_off = __builtin_nontemporal_load(offs + (T - 1));
-            const float rel = lse2_log2(fb, fl);
-            const bool none = rel < NEG_TEST;
-            const double lp2 = none ? -INFINITY : (double)rel + fin_off;
+            const float2* last = lat + (size_t)(T - 1) * d.Sp;
+            const float fbv = __builtin_nontemporal_load(&last[2 * L].x);
+            const int fbe = __float_as_int(__builtin_nontemporal_load(&last[2 * L].y));
+            const float flv = L > 0 ? __builtin_nontemporal_load(&last[2 * L - 1].x) : 0.f;
+            const int fle = L > 0 ? __float_as_int(__builtin_nontemporal_load(&last[2 * L - 1].y)) : EZ;
+            const int E = max(fbe, fle);
+            const float sum = __builtin_amdgcn_ldexpf(fbv, fbe - E) + __builtin_amdgcn_ldexpf(flv, fle - E);
+            const double lp2 = pair_log2(sum, E);
             logp2_out[b] = lp2;
-            loss[b] = none ? INFINITY : (float)(-lp2 * LN2);
+            loss[b] = sum > 0.f ? (float)(-lp2 * LN2) : INFINITY;
         }
     }
 }
@@ -270,10 +265,8 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
                                                 const int* __restrict__ tgt_len,
                                                 const float* __restrict__ loss,
                                                 const double* __restrict__ logp2_in,
-                                                const float* __restrict__ alpha,
-                                                const float* __restrict__ beta,
-                                                const double* __restrict__ aoff,
-                                                const double* __restrict__ boff, float* __restrict__ grad,
+                                                const float2* __restrict__ alpha,
+                                                const float2* __restrict__ beta, float* __restrict__ grad,
                                                 CtcDims d, int is_logits, float grad_scale)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -322,17 +315,21 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
             for (int c = lane; c < d.C; c += 64) grow[c] = 0.f;
             continue;
         }
-        const float* ar = alpha + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
-        const float* br = beta + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
+        const float2* ar = alpha + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
+        const float2* br = beta + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
         const float* lrow = lpb + (size_t)t * d.C;
-        // offsets of the two lattices at this frame minus log P: what every state's sum needs added
-        const float shift = (float)(aoff[(size_t)b * (d.Tp + 1) + t] + boff[(size_t)b * (d.Tp + 1) + t] - logp2);
+        // log P split into an integer (taken off the integer exponents exactly) and a fraction
+        const int iref = (int)floor(logp2);
+        const float shift = (float)((double)iref - logp2);
         float z = 0.f, zb = 0.f;
         for (int s = lane; s < S; s += 64) {
             const int c = (s & 1) ? lab[(s - 1) >> 1] : d.blank;
-            const float a = ar[s], bt = br[S - 1 - s];  // beta rows are stored in reversed state order
+            const float2 a = ar[s], bt = br[S - 1 - s];  // beta rows are stored in reversed state order
             float e = 0.f;
-            if (a > NEG_TEST && bt > NEG_TEST) e = fast_exp2((a + bt) + (shift - lrow[c] * (float)LOG2E));
+            // alpha and beta both carry the frame's own score: one of them is taken off again
+            if (a.x > 0.f && bt.x > 0.f)
+                e = fast_exp2((fast_log2(a.x * bt.x) + (float)(__float_as_int(a.y) + __float_as_int(bt.y) - iref)) +
+                              (shift - fmaxf(lrow[c] * (float)LOG2E, MIN_LOG2)));
             ebuf[s] = e;
             z += e;
             if (!(s & 1)) zb += e;
@@ -361,19 +358,16 @@ size_t grad_lds_bytes(int Lmax, int C)
     return (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (2 * Lmax + 4);
 }
 
-struct WsLayout { size_t lp, logp, alpha, beta, aoff, boff, total; };
+struct WsLayout { size_t lp, logp, alpha, beta, total; };
 WsLayout ws_layout(int B, int Tp, int C, int Lmax)
 {
     WsLayout w;
     size_t off = 0;
     w.lp = off; off += round_up((size_t)B * Tp * C * 4, 256);
     w.logp = off; off += round_up((size_t)B * 8, 256);
-    const size_t lat = round_up((size_t)B * (Tp + 1) * (2 * (size_t)Lmax + 4) * 4, 256);
+    const size_t lat = round_up((size_t)B * (Tp + 1) * (2 * (size_t)Lmax + 4) * 8, 256);
     w.alpha = off; off += lat;
     w.beta = off; off += lat;
-    const size_t offs = round_up((size_t)B * (Tp + 1) * 8, 256);
-    w.aoff = off; off += offs;
-    w.boff = off; off += offs;
     w.total = off;
     return w;
 }
@@ -425,10 +419,8 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
         lp = lpw;
     }
     double* logp = reinterpret_cast<double*>(ws + w.logp);
-    float* alpha = reinterpret_cast<float*>(ws + w.alpha);
-    float* beta = reinterpret_cast<float*>(ws + w.beta);
-    double* aoff = reinterpret_cast<double*>(ws + w.aoff);
-    double* boff = reinterpret_cast<double*>(ws + w.boff);
+    float2* alpha = reinterpret_cast<float2*>(ws + w.alpha);
+    float2* beta = reinterpret_cast<float2*>(ws + w.beta);
     CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 4};
 
     const size_t lds2 = grad_lds_bytes(Lmax, C);
@@ -444,12 +436,12 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     const int nt = 64 * (((pairs + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);  // OWN_LANES pair groups per wavefront
     if (nt > 1024) return W2L_ERR_SHAPE;
     const dim3 g1(2, B), b1(nt);
-    if (ppt == 1) hipLaunchKernelGGL(ctc_lattice<1>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, aoff, boff, d);
-    else if (ppt == 2) hipLaunchKernelGGL(ctc_lattice<2>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, aoff, boff, d);
-    else hipLaunchKernelGGL(ctc_lattice<4>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, aoff, boff, d);
+    if (ppt == 1) hipLaunchKernelGGL(ctc_lattice<1>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
+    else if (ppt == 2) hipLaunchKernelGGL(ctc_lattice<2>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
+    else hipLaunchKernelGGL(ctc_lattice<4>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
     int rc = launch_status();
     if (rc) return rc;
     hipLaunchKernelGGL(ctc_grad, dim3((Tp + GRAD_ROWS - 1) / GRAD_ROWS, B), dim3(256), lds2, st, lp, targets,
-                       in_len, tgt_len, loss, logp, alpha, beta, aoff, boff, grad, d, is_logits, grad_scale);
+                       in_len, tgt_len, loss, logp, alpha, beta, grad, d, is_logits, grad_scale);
     return launch_status();
 }
