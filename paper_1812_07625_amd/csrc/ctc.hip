@@ -74,7 +74,15 @@ __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (
 // The step body is straight-line code with a fixed number of memory operations (lanes that own
 // no real pair write to a spare pair, steps past the last frame to a spare row).
 // Stored per frame and state: the pair (v, e), e as the bits of the second float.
-template <int PPT>
+// TABLE (the class rows of a block of frames fit the budget below): the scores do not come
+// through per-lane loads at all.  The workgroup keeps the rows lp[t, 0..C-1] of the current
+// block of SCORE_AHEAD frames in LDS, already split into (mantissa, exponent), in two buffers:
+// the rows of the next block are loaded (coalesced) before the block's steps start and written
+// to the other buffer after them, so the recursion itself issues no vector loads -- only
+// LDS reads, one frame ahead -- and never waits on the memory counter that its own lattice
+// stores keep busy.
+constexpr int TABLE_LOADS = 8;  // at most this many row elements per thread and block of frames
+template <int PPT, bool TABLE>
 __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp, const int* __restrict__ targets,
                                                     const int* __restrict__ in_len, const int* __restrict__ tgt_len,
                                                     float* __restrict__ loss, double* __restrict__ logp2_out,
@@ -82,6 +90,8 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 {
     __shared__ float xbuf[2][16][HALO_LANES][4 * PPT];  // [block parity][wavefront][lane - OWN_LANES][v, e of blank, label]
     __shared__ int bad_len, bad;
+    extern __shared__ __align__(16) unsigned char dyn_smem[];
+    float2* const tbl = reinterpret_cast<float2*>(dyn_smem);  // TABLE: [2][SCORE_AHEAD][C] (pm, pe)
     const int dir = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int T = in_len[b], L = tgt_len[b];
@@ -139,20 +149,11 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
     const float log2e = (float)LOG2E;
 
-    float sb[SCORE_AHEAD], sl[PPT][SCORE_AHEAD];
-#pragma unroll
-    for (int k = 0; k < SCORE_AHEAD; ++k) {
-        const int f = frame(k < T ? k : T - 1);
-        sb[k] = lpb[(size_t)f * d.C + d.blank];
-#pragma unroll
-        for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
-    }
     const int nwaves = NT >> 6;
     const int tblocks = (T + SCORE_AHEAD - 1) / SCORE_AHEAD;
     // running pointers instead of per-step index arithmetic: the score row fetched next (clamped
     // at the last frame) and the lattice row written next
     const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)d.Sp : d.Sp;
-    const float* sptr = lpb + (size_t)frame(SCORE_AHEAD - 1 < T ? SCORE_AHEAD - 1 : T - 1) * d.C;
     float2* rptr = lat + (size_t)frame(0) * d.Sp;
     float2* const spare = lat + (size_t)d.Tp * d.Sp;
     // 2^(lp log2 e) = pm * 2^pe with pm in [1, 2)
@@ -162,51 +163,36 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         pe = (int)fl;
         pm = fast_exp2(x - fl);
     };
-
-    for (int tb = 0; tb < tblocks; ++tb) {
+    // one frame of the recursion for this lane's pairs, given the split scores
+    auto advance = [&](float2* row, float pmb, int peb, const float (&pml)[PPT], const int (&pel)[PPT]) {
+        // label state (previous frame) of the pair to the left of this lane's first pair
+        float cv = from_left_lane(vl[PPT - 1], 0.f);
+        int ce = from_left_lane_i(el[PPT - 1], EZ);
 #pragma unroll
-        for (int k = 0; k < SCORE_AHEAD; ++k) {
-            const int step = tb * SCORE_AHEAD + k;
-            float pmb, pml[PPT];
-            int peb, pel[PPT];
-            split(sb[k], pmb, peb);
-#pragma unroll
-            for (int j = 0; j < PPT; ++j) split(sl[j][k], pml[j], pel[j]);
-            {   // refill this ring slot for step + SCORE_AHEAD (past the end: the last frame again)
-                sptr += (step + SCORE_AHEAD < T) ? sstep : 0;
-                sb[k] = sptr[d.blank];
-#pragma unroll
-                for (int j = 0; j < PPT; ++j) sl[j][k] = sptr[cls[j]];
-            }
-            float2* const row = step < T ? rptr : spare;
-            rptr += rstep;
-            // label state (previous frame) of the pair to the left of this lane's first pair
-            float cv = from_left_lane(vl[PPT - 1], 0.f);
-            int ce = from_left_lane_i(el[PPT - 1], EZ);
-#pragma unroll
-            for (int j = 0; j < PPT; ++j) {
-                const float obv = vb[j], olv = vl[j];
-                const int obe = eb[j], ole = el[j];
-                // blank: from itself and from the label on its left
-                const int E1 = max(obe, ce);
-                const float s1 = __builtin_amdgcn_ldexpf(obv, obe - E1) + __builtin_amdgcn_ldexpf(cv, ce - E1);
-                // label: from itself, from its blank, and (different neighbouring labels) from the label on its left
-                const float cvs = skip[j] ? cv : 0.f;
-                const int cs = skip[j] ? ce : EZ;
-                const int E2 = max(max(ole, obe), cs);
-                const float s2 = (__builtin_amdgcn_ldexpf(olv, ole - E2) + __builtin_amdgcn_ldexpf(obv, obe - E2)) +
-                                 __builtin_amdgcn_ldexpf(cvs, cs - E2);
-                cv = olv;
-                ce = ole;
-                vb[j] = pmb * s1;
-                eb[j] = s1 > 0.f ? E1 + peb : EZ;
-                vl[j] = pml[j] * s2;
-                el[j] = s2 > 0.f ? E2 + pel[j] : EZ;
-                *reinterpret_cast<float4*>(row + slot[j]) = make_float4(vb[j], __int_as_float(eb[j]), vl[j], __int_as_float(el[j]));
-            }
+        for (int j = 0; j < PPT; ++j) {
+            const float obv = vb[j], olv = vl[j];
+            const int obe = eb[j], ole = el[j];
+            // blank: from itself and from the label on its left
+            const int E1 = max(obe, ce);
+            const float s1 = __builtin_amdgcn_ldexpf(obv, obe - E1) + __builtin_amdgcn_ldexpf(cv, ce - E1);
+            // label: from itself, from its blank, and (different neighbouring labels) from the label on its left
+            const float cvs = skip[j] ? cv : 0.f;
+            const int cs = skip[j] ? ce : EZ;
+            const int E2 = max(max(ole, obe), cs);
+            const float s2 = (__builtin_amdgcn_ldexpf(olv, ole - E2) + __builtin_amdgcn_ldexpf(obv, obe - E2)) +
+                             __builtin_amdgcn_ldexpf(cvs, cs - E2);
+            cv = olv;
+            ce = ole;
+            vb[j] = pmb * s1;
+            eb[j] = s1 > 0.f ? E1 + peb : EZ;
+            vl[j] = pml[j] * s2;
+            el[j] = s2 > 0.f ? E2 + pel[j] : EZ;
+            *reinterpret_cast<float4*>(row + slot[j]) = make_float4(vb[j], __int_as_float(eb[j]), vl[j], __int_as_float(el[j]));
         }
-        // ---- block boundary: every lane moves the exponents of its mantissas into e; the mirror
-        // lanes are refreshed from the left neighbour
+    };
+    // block boundary: every lane moves the exponents of its mantissas into e; the mirror lanes
+    // are refreshed from the left neighbour (one workgroup barrier)
+    auto boundary = [&](int tb, bool sync_always) {
 #pragma unroll
         for (int j = 0; j < PPT; ++j) {
             const int xb = __builtin_amdgcn_frexp_expf(vb[j]), xl = __builtin_amdgcn_frexp_expf(vl[j]);  // 0 for a zero state
@@ -215,23 +201,112 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
             vl[j] = __builtin_amdgcn_ldexpf(vl[j], -xl);
             el[j] += vl[j] > 0.f ? xl : 0;
         }
-        if (nwaves > 1) {
-            const int par = tb & 1;
-            if (lane >= OWN_LANES) {
+        const int par = tb & 1;
+        if (nwaves > 1 && lane >= OWN_LANES) {
 #pragma unroll
-                for (int j = 0; j < PPT; ++j) {
-                    float* q = &xbuf[par][wave][lane - OWN_LANES][4 * j];
-                    q[0] = vb[j]; q[1] = __int_as_float(eb[j]); q[2] = vl[j]; q[3] = __int_as_float(el[j]);
+            for (int j = 0; j < PPT; ++j) {
+                float* q = &xbuf[par][wave][lane - OWN_LANES][4 * j];
+                q[0] = vb[j]; q[1] = __int_as_float(eb[j]); q[2] = vl[j]; q[3] = __int_as_float(el[j]);
+            }
+        }
+        if (nwaves > 1 || sync_always) __syncthreads();
+        if (nwaves > 1 && wave > 0 && !owner) {
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) {
+                const float* q = &xbuf[par][wave - 1][lane][4 * j];
+                vb[j] = q[0]; eb[j] = __float_as_int(q[1]); vl[j] = q[2]; el[j] = __float_as_int(q[3]);
+            }
+        }
+    };
+
+    if (TABLE) {
+        // element e of a block's rows: step k = e / C of the block, class c = e % C
+        const int nel = SCORE_AHEAD * d.C;
+        float raw[TABLE_LOADS];
+        auto load_rows = [&](int tb) {
+#pragma unroll
+            for (int q = 0; q < TABLE_LOADS; ++q) {
+                const int e = min(tid + q * NT, nel - 1);  // every thread loads something valid: no lane masking around the loads
+                const int k = e / d.C, c = e - k * d.C, step = tb * SCORE_AHEAD + k;
+                raw[q] = lpb[(size_t)frame(step < T ? step : T - 1) * d.C + c];
+            }
+        };
+        auto write_rows = [&](int buf) {
+#pragma unroll
+            for (int q = 0; q < TABLE_LOADS; ++q) {
+                const int e = tid + q * NT;
+                if (e < nel) {
+                    float pm;
+                    int pe;
+                    split(raw[q], pm, pe);
+                    tbl[buf * nel + e] = make_float2(pm, __int_as_float(pe));
                 }
             }
-            __syncthreads();
-            if (wave > 0 && !owner) {
+        };
+        load_rows(0);
+        write_rows(0);
+        __syncthreads();
+        for (int tb = 0; tb < tblocks; ++tb) {
+            const float2* cur = tbl + (tb & 1) * nel;
+            load_rows(tb + 1);  // in flight while the block's steps run (past the last block: the last frame again)
+            float2 nb = cur[d.blank], nl[PPT];        // scores of the block's first frame
 #pragma unroll
-                for (int j = 0; j < PPT; ++j) {
-                    const float* q = &xbuf[par][wave - 1][lane][4 * j];
-                    vb[j] = q[0]; eb[j] = __float_as_int(q[1]); vl[j] = q[2]; el[j] = __float_as_int(q[3]);
+            for (int j = 0; j < PPT; ++j) nl[j] = cur[cls[j]];
+#pragma unroll
+            for (int k = 0; k < SCORE_AHEAD; ++k) {
+                const int step = tb * SCORE_AHEAD + k;
+                const float pmb = nb.x;
+                const int peb = __float_as_int(nb.y);
+                float pml[PPT];
+                int pel[PPT];
+#pragma unroll
+                for (int j = 0; j < PPT; ++j) { pml[j] = nl[j].x; pel[j] = __float_as_int(nl[j].y); }
+                if (k + 1 < SCORE_AHEAD) {  // the next frame's scores, one step ahead
+                    nb = cur[(k + 1) * d.C + d.blank];
+#pragma unroll
+                    for (int j = 0; j < PPT; ++j) nl[j] = cur[(k + 1) * d.C + cls[j]];
                 }
+                float2* const row = step < T ? rptr : spare;
+                rptr += rstep;
+                advance(row, pmb, peb, pml, pel);
             }
+            // the loaded rows are not touched before the steps are done (tied to a value the last step
+            // produced): their wait must not move ahead of the steps, where it would also wait for nothing
+#pragma unroll
+            for (int q = 0; q < TABLE_LOADS; ++q) asm volatile("" : "+v"(raw[q]), "+v"(vb[0]));
+            write_rows((tb + 1) & 1);
+            boundary(tb, true);
+        }
+    } else {
+        float sb[SCORE_AHEAD], sl[PPT][SCORE_AHEAD];
+#pragma unroll
+        for (int k = 0; k < SCORE_AHEAD; ++k) {
+            const int f = frame(k < T ? k : T - 1);
+            sb[k] = lpb[(size_t)f * d.C + d.blank];
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
+        }
+        const float* sptr = lpb + (size_t)frame(SCORE_AHEAD - 1 < T ? SCORE_AHEAD - 1 : T - 1) * d.C;
+        for (int tb = 0; tb < tblocks; ++tb) {
+#pragma unroll
+            for (int k = 0; k < SCORE_AHEAD; ++k) {
+                const int step = tb * SCORE_AHEAD + k;
+                float pmb, pml[PPT];
+                int peb, pel[PPT];
+                split(sb[k], pmb, peb);
+#pragma unroll
+                for (int j = 0; j < PPT; ++j) split(sl[j][k], pml[j], pel[j]);
+                {   // refill this ring slot for step + SCORE_AHEAD (past the end: the last frame again)
+                    sptr += (step + SCORE_AHEAD < T) ? sstep : 0;
+                    sb[k] = sptr[d.blank];
+#pragma unroll
+                    for (int j = 0; j < PPT; ++j) sl[j][k] = sptr[cls[j]];
+                }
+                float2* const row = step < T ? rptr : spare;
+                rptr += rstep;
+                advance(row, pmb, peb, pml, pel);
+            }
+            boundary(tb, false);
         }
     }
     // log P = log( alpha_{T-1}(S-1) + alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1, read back
@@ -436,9 +511,21 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     const int nt = 64 * (((pairs + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);  // OWN_LANES pair groups per wavefront
     if (nt > 1024) return W2L_ERR_SHAPE;
     const dim3 g1(2, B), b1(nt);
-    if (ppt == 1) hipLaunchKernelGGL(ctc_lattice<1>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
-    else if (ppt == 2) hipLaunchKernelGGL(ctc_lattice<2>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
-    else hipLaunchKernelGGL(ctc_lattice<4>, g1, b1, 0, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d);
+    // the score table path: a block's class rows must fit TABLE_LOADS elements per thread and 64 KB of LDS
+    const bool table = (long long)SCORE_AHEAD * C <= (long long)TABLE_LOADS * nt && (size_t)2 * SCORE_AHEAD * C * 8 <= 64 * 1024;
+    const size_t lds1 = table ? (size_t)2 * SCORE_AHEAD * C * 8 : 0;
+#define W2L_CTC_LAUNCH(P_, T_)                                                                                        \
+    {                                                                                                                 \
+        if (lds1 > 32 * 1024) {                                                                                       \
+            hipError_t e = hipFuncSetAttribute((const void*)ctc_lattice<P_, T_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1); \
+            if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }                                        \
+        }                                                                                                             \
+        hipLaunchKernelGGL((ctc_lattice<P_, T_>), g1, b1, lds1, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d); \
+    }
+    if (ppt == 1) { if (table) W2L_CTC_LAUNCH(1, true) else W2L_CTC_LAUNCH(1, false) }
+    else if (ppt == 2) { if (table) W2L_CTC_LAUNCH(2, true) else W2L_CTC_LAUNCH(2, false) }
+    else { if (table) W2L_CTC_LAUNCH(4, true) else W2L_CTC_LAUNCH(4, false) }
+#undef W2L_CTC_LAUNCH
     int rc = launch_status();
     if (rc) return rc;
     hipLaunchKernelGGL(ctc_grad, dim3((Tp + GRAD_ROWS - 1) / GRAD_ROWS, B), dim3(256), lds2, st, lp, targets,
