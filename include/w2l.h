@@ -137,7 +137,8 @@ int w2l_sgd_momentum_step(float *w, float *v, const float *grad, void *w_lowp, l
  * labels), over the extended sequence l' = (blank, l_1, blank, ..., l_L, blank):
  *   loss[b] = -log sum over all frame labellings that collapse to l of
  *             prod_{t<T_b} exp(lp[b,t,pi_t])            (natural log)
- * computed with the log-space alpha/beta recursions, and
+ * computed with the alpha/beta recursions (every state kept as fp32 value x 2^int32, a range
+ * no smaller than log-space fp32), and
  *   G[b,t,c] = posterior probability that frame t carries class c given l.
  * in:  input [B,Tp,C] fp32 -- log-probabilities (is_logits = 0) or unnormalised
  *      logits (is_logits = 1: a log-softmax is applied inside);
