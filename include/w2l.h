@@ -147,6 +147,7 @@ int w2l_sgd_momentum_step(float *w, float *v, const float *grad, void *w_lowp, l
  * out: loss [B] fp32;  grad [B,Tp,C] fp32 = grad_scale * d(sum_b loss_b)/d input, i.e.
  *      -grad_scale*G (is_logits = 0) or grad_scale*(softmax - G) (is_logits = 1);
  *      rows t >= in_len[b] are 0.
+ * A log-probability of -inf (or below -65536 ln 2) is probability zero.
  * An utterance with no valid alignment gets loss +inf and zero gradient.  A label
  * equal to blank or outside [0,C), or a length outside its range, cannot be
  * reported by an asynchronous call: that utterance gets loss NaN and zero

@@ -156,12 +156,13 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)d.Sp : d.Sp;
     float2* rptr = lat + (size_t)frame(0) * d.Sp;
     float2* const spare = lat + (size_t)d.Tp * d.Sp;
-    // 2^(lp log2 e) = pm * 2^pe with pm in [1, 2)
+    // 2^(lp log2 e) = pm * 2^pe with pm in [1, 2); a score below 2^MIN_LOG2 (-inf included) is probability zero
     auto split = [&](float s, float& pm, int& pe) {
-        const float x = fmaxf(s * log2e, MIN_LOG2);
+        const float xr = s * log2e;
+        const float x = fmaxf(xr, MIN_LOG2);
         const float fl = floorf(x);
         pe = (int)fl;
-        pm = fast_exp2(x - fl);
+        pm = xr >= MIN_LOG2 ? fast_exp2(x - fl) : 0.f;
     };
     // one frame of the recursion for this lane's pairs, given the split scores
     auto advance = [&](float2* row, float pmb, int peb, const float (&pml)[PPT], const int (&pel)[PPT]) {
@@ -401,10 +402,13 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
             const int c = (s & 1) ? lab[(s - 1) >> 1] : d.blank;
             const float2 a = ar[s], bt = br[S - 1 - s];  // beta rows are stored in reversed state order
             float e = 0.f;
-            // alpha and beta both carry the frame's own score: one of them is taken off again
-            if (a.x > 0.f && bt.x > 0.f)
-                e = fast_exp2((fast_log2(a.x * bt.x) + (float)(__float_as_int(a.y) + __float_as_int(bt.y) - iref)) +
-                              (shift - fmaxf(lrow[c] * (float)LOG2E, MIN_LOG2)));
+            // alpha and beta both carry the frame's own score: one of them is taken off again, split exactly
+            // as the lattice kernel split it (integer part off the integer exponents, so nothing large cancels in fp32)
+            if (a.x > 0.f && bt.x > 0.f) {
+                const float x = fmaxf(lrow[c] * (float)LOG2E, MIN_LOG2), fl = floorf(x);
+                e = fast_exp2((fast_log2(a.x * bt.x) + (float)(__float_as_int(a.y) + __float_as_int(bt.y) - iref - (int)fl)) +
+                              (shift - (x - fl)));
+            }
             ebuf[s] = e;
             z += e;
             if (!(s & 1)) zb += e;

@@ -215,6 +215,36 @@ def test_ctc_from_logprobs_scale_blank_and_edges(P):
     _check_ctc(loss, grad, loss_o, 0.25 * g_o)
 
 
+def test_ctc_large_alphabet_gathers_scores_per_lane(P):
+    # 600 classes: the class rows of a block of frames do not fit the workgroup's score table
+    cfg = W.config2(seed=21, B=3, T=80, in_lo=60, in_hi=80, l_lo=5, l_hi=20, Cc=600)
+    loss, grad = _run_ctc(P, cfg["logits"], 1, cfg["targets"], cfg["in_len"], cfg["tgt_len"], 0, 1.0)
+    loss_o, _, dz_o = oracle.ctc_from_logits(cfg["logits"].astype(np.float64), cfg["targets"], cfg["in_len"],
+                                             cfg["tgt_len"])
+    _check_ctc(loss, grad, loss_o, dz_o)
+
+
+def test_ctc_peaked_and_impossible_scores(P):
+    # log-probabilities far outside the range of a linear fp32 recursion (about -1300 per frame), and -inf entries
+    rng = np.random.default_rng(22)
+    B, Tp, Cc, Lmax = 5, 300, 12, 40
+    z = rng.standard_normal((B, Tp, Cc)) * 400.0
+    lp = oracle.logsoftmax_fwd(z)
+    tg = rng.integers(1, Cc, size=(B, Lmax)).astype(np.int32)
+    in_len = np.array([300, 280, 300, 300, 150], np.int32)
+    tgt_len = np.array([40, 25, 30, 10, 12], np.int32)
+    lp[1, 100, 1:] = -np.inf                     # frame 100 of b=1 must be blank
+    lp[2, :, tg[2, 0]] = -np.inf                 # first label of b=2 impossible: no alignment
+    lp[3, 7, :] = -np.inf                        # nothing possible at frame 7 of b=3: no alignment
+    lp[4, 10:20, 0] = -np.inf                    # no blank for ten frames of b=4
+    lp = lp.astype(np.float32)
+    loss, grad = _run_ctc(P, lp, 0, tg, in_len, tgt_len, 0, 1.0)
+    loss_o, g_o = oracle.ctc(lp.astype(np.float64), tg, in_len, tgt_len, 0)
+    assert np.isfinite(loss_o[[0, 1, 4]]).all() and np.isinf(loss_o[[2, 3]]).all()
+    assert loss_o[0] > 30000.0                   # log2 P far below fp32's smallest exponent
+    _check_ctc(loss, grad, loss_o, g_o)
+
+
 def test_ctc_bad_label_gives_nan_loss_and_zero_grad(P):
     cfg = W.config2(seed=5, B=3, T=40, in_lo=30, in_hi=40, l_lo=3, l_hi=6)
     tg = cfg["targets"].copy()
