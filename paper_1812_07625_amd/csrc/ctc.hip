@@ -30,31 +30,33 @@ constexpr int GRAD_ROWS = 16;   // frames per ctc_grad workgroup (4 per wavefron
 
 struct CtcDims {
     int B, Tp, C, Lmax, blank;
-    int Sp;  // lattice row pitch in states = 2*Lmax+4 (the last pair is a spare); a state is 8 bytes; Tp+1 rows per utterance
+    int Sp;    // lattice row pitch in states = 2*Lmax+4 (the last pair is a spare); a state is 8 bytes
+    int rows;  // lattice rows per utterance = Tp + 2*SCORE_AHEAD: frame t is row SCORE_AHEAD + t
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
-// value of the lane to the left (lane - 1); lane 0 gets `edge`
-__device__ __forceinline__ float from_left_lane(float v, float edge)
+// value of the lane to the left (lane - 1); lane 0 gets 0
+__device__ __forceinline__ int from_left_lane_i(int v)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(edge), __float_as_int(v), 0x138 /* wave_shr:1 */,
-                                                      0xf, 0xf, false));
+    return __builtin_amdgcn_update_dpp(0, v, 0x138 /* wave_shr:1 */, 0xf, 0xf, true);
 }
+__device__ __forceinline__ float from_left_lane(float v) { return __int_as_float(from_left_lane_i(__float_as_int(v))); }
 
-constexpr int SCORE_AHEAD = 16;  // frames of scores held in registers ahead of the recursion;
-                                 // also the period of the hand-over between wavefronts and of the renormalisation
+constexpr int SCORE_AHEAD = 16;  // frames per block: the period of the score staging, of the hand-over
+                                 // between wavefronts and of the renormalisation
 constexpr int HALO_LANES = SCORE_AHEAD;     // lanes of a wavefront that mirror the wavefront on its left
 constexpr int OWN_LANES = 64 - HALO_LANES;  // lanes whose states a wavefront owns (and stores)
 
-constexpr int EZ = -(1 << 30);        // exponent of a zero state
-constexpr float MIN_LOG2 = -65536.f;  // scores below 2^-65536 are taken as that (keeps integer exponents far from overflow)
+// A state's exponent is kept with a bias, so that 0 can stand for "zero state" (the value a lane
+// shift fills in at the edge) and compares below every real exponent.  Real exponents stay within
+// +-MAX_FRAMES * 65536 = +-2^29 of the bias; the exponent of a zero-valued state stays below 2^29.
+constexpr int EXP_BIAS = 1 << 30;
+constexpr int MAX_FRAMES = 8192;
+constexpr float MIN_LOG2 = -65535.f;               // scores are clamped to 2^+-65535; below: probability zero
+constexpr int PE_ZERO = -2147483647 - 1;           // exponent of a zero score: pulls any biased exponent below 0
 
-__device__ __forceinline__ int from_left_lane_i(int v, int edge)
-{
-    return __builtin_amdgcn_update_dpp(edge, v, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
-}
 // v * 2^e for a (v, e) pair as a double-precision base-2 log; -inf for a zero state
 __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (double)fast_log2(v) + (double)e : -INFINITY; }
 
@@ -68,30 +70,35 @@ __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (
 // the staleness has not yet reached the lanes the wavefront owns -- and once per block they are
 // refreshed through LDS, at the one barrier of the block.  States to the right of the target's
 // last pair are computed too (nothing reads them; a state depends only on states to its left);
-// states left of pair 0 stay zero.  The scores lp[t, blank] and lp[t, label] are fetched
-// SCORE_AHEAD frames early into a register ring.  beta is the same recursion on the reversed
-// sequence and reversed time (state index q counts from the end), stored in its own q order.
-// The step body is straight-line code with a fixed number of memory operations (lanes that own
-// no real pair write to a spare pair, steps past the last frame to a spare row).
-// Stored per frame and state: the pair (v, e), e as the bits of the second float.
-// TABLE (the class rows of a block of frames fit the budget below): the scores do not come
+// states left of pair 0 stay zero.  beta is the same recursion on the reversed sequence and
+// reversed time (state index q counts from the end), stored in its own q order.
+// The step body is straight-line code with a fixed number of memory operations: lanes that own
+// no real pair write to a spare pair, and the steps between the last frame and the end of its
+// block of SCORE_AHEAD frames run on like the others -- their rows land in the SCORE_AHEAD spare
+// rows that every utterance's lattice has at either end (alpha runs off the far end, beta off
+// the near one) or in rows t >= T_b that nobody reads.
+// Stored per frame and state: the pair (v, e + EXP_BIAS), the integer as the bits of the second float.
+// NQ > 0 (the class rows of a block of frames fit NQ values per thread): the scores do not come
 // through per-lane loads at all.  The workgroup keeps the rows lp[t, 0..C-1] of the current
-// block of SCORE_AHEAD frames in LDS, already split into (mantissa, exponent), in two buffers:
-// the rows of the next block are loaded (coalesced) before the block's steps start and written
-// to the other buffer after them, so the recursion itself issues no vector loads -- only
-// LDS reads, one frame ahead -- and never waits on the memory counter that its own lattice
-// stores keep busy.
-constexpr int TABLE_LOADS = 8;  // at most this many row elements per thread and block of frames
-template <int PPT, bool TABLE>
+// block of SCORE_AHEAD frames in LDS, already split into (mantissa, exponent), class-major
+// (the frames of one class are adjacent, so a step's read is the lane's fixed address plus a
+// constant), in two buffers: the rows of the next block are loaded (coalesced) before the
+// block's steps start and written to the other buffer after them, so the recursion itself issues
+// no vector loads and never waits on the memory counter that its own lattice stores keep busy.
+// NQ == 0 (large alphabets): the scores lp[t, blank] and lp[t, label] are gathered per lane
+// SCORE_AHEAD frames early into a register ring.
+constexpr int TABLE_PITCH = SCORE_AHEAD + 1;  // table entries per class (one of padding against bank conflicts)
+template <int PPT, int NQ>
 __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp, const int* __restrict__ targets,
                                                     const int* __restrict__ in_len, const int* __restrict__ tgt_len,
                                                     float* __restrict__ loss, double* __restrict__ logp2_out,
                                                     float2* __restrict__ alpha, float2* __restrict__ beta, CtcDims d)
 {
+    constexpr bool TABLE = NQ > 0;
     __shared__ float xbuf[2][16][HALO_LANES][4 * PPT];  // [block parity][wavefront][lane - OWN_LANES][v, e of blank, label]
     __shared__ int bad_len, bad;
     extern __shared__ __align__(16) unsigned char dyn_smem[];
-    float2* const tbl = reinterpret_cast<float2*>(dyn_smem);  // TABLE: [2][SCORE_AHEAD][C] (pm, pe)
+    float2* const tbl = reinterpret_cast<float2*>(dyn_smem);  // TABLE: [2][C][TABLE_PITCH] (pm, pe)
     const int dir = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int T = in_len[b], L = tgt_len[b];
@@ -124,11 +131,11 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     // pair i (in this direction's order) = states q = 2i (blank), 2i+1 (label i, absent for i = L)
     const int gi = wave * OWN_LANES + lane - HALO_LANES;  // this lane's group of PPT pairs; < 0: left of the sequence
     const bool owner = lane >= HALO_LANES;               // not a mirror of the wavefront on the left
-    int cls[PPT];     // class of the label state
-    bool skip[PPT];   // label state may be entered from the label of the pair to the left
-    int slot[PPT];    // lattice position of the pair (the spare pair for lanes that own no real pair)
+    int cls[PPT];        // class of the label state
+    bool skip[PPT];      // label state may be entered from the label of the pair to the left
+    unsigned slot[PPT];  // lattice position of the pair (the spare pair for lanes that own no real pair)
     float vb[PPT], vl[PPT];
-    int eb[PPT], el[PPT];
+    int eb[PPT], el[PPT];  // biased exponents; 0 for a zero state
 #pragma unroll
     for (int j = 0; j < PPT; ++j) {
         const int i = gi * PPT + j;
@@ -136,39 +143,42 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         const int li = dir ? L - 1 - i : i;          // label index in the target
         cls[j] = has_l ? lab[li] : d.blank;
         skip[j] = has_l && i >= 1 && lab[dir ? li + 1 : li - 1] != cls[j];
-        slot[j] = 2 * ((real && owner) ? i : d.Lmax + 1);
+        slot[j] = 2u * (unsigned)((real && owner) ? i : d.Lmax + 1);
         // the state "before frame 0": all mass in front of pair 0, so that frame 0 comes out of the recursion itself
         const bool start = gi >= 0 && i == 0;
         vb[j] = start ? 1.f : 0.f;
-        eb[j] = start ? 0 : EZ;
+        eb[j] = start ? EXP_BIAS : 0;
         vl[j] = 0.f;
-        el[j] = EZ;
+        el[j] = 0;
     }
     const float* lpb = lp + (size_t)b * d.Tp * d.C;
-    float2* lat = (dir ? beta : alpha) + (size_t)b * (d.Tp + 1) * d.Sp;
+    float2* lat = (dir ? beta : alpha) + ((size_t)b * d.rows + SCORE_AHEAD) * d.Sp;  // row of frame 0
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
     const float log2e = (float)LOG2E;
 
     const int nwaves = NT >> 6;
     const int tblocks = (T + SCORE_AHEAD - 1) / SCORE_AHEAD;
-    // running pointers instead of per-step index arithmetic: the score row fetched next (clamped
-    // at the last frame) and the lattice row written next
+    // running pointers instead of per-step index arithmetic: the lattice row written next
+    // (and, without the table, the score row fetched next, clamped at the last frame)
     const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)d.Sp : d.Sp;
-    float2* rptr = lat + (size_t)frame(0) * d.Sp;
-    float2* const spare = lat + (size_t)d.Tp * d.Sp;
-    // 2^(lp log2 e) = pm * 2^pe with pm in [1, 2); a score below 2^MIN_LOG2 (-inf included) is probability zero
+    float2* rptr = lat + (long long)frame(0) * d.Sp;
+    // exp(lp) = 2^(lp log2 e) = pm * 2^pe with pm in [1, 2); a score below 2^MIN_LOG2 (-inf included) is probability zero
     auto split = [&](float s, float& pm, int& pe) {
         const float xr = s * log2e;
-        const float x = fmaxf(xr, MIN_LOG2);
+        const float x = fminf(fmaxf(xr, MIN_LOG2), -MIN_LOG2);
         const float fl = floorf(x);
-        pe = (int)fl;
-        pm = xr >= MIN_LOG2 ? fast_exp2(x - fl) : 0.f;
+        const bool pos = xr >= MIN_LOG2;
+        pe = pos ? (int)fl : PE_ZERO;
+        pm = pos ? fast_exp2(x - fl) : 0.f;
     };
-    // one frame of the recursion for this lane's pairs, given the split scores
+    // one frame of the recursion for this lane's pairs, given the split scores.  A sum of states brings
+    // them to their largest exponent (exact) and adds; a zero state (v = 0, exponent 0, far below any
+    // real state's biased exponent) drops out by itself, and a sum of zeros stays at exponent 0
+    // through the max() (a zero score's exponent pulls any sum below 0).
     auto advance = [&](float2* row, float pmb, int peb, const float (&pml)[PPT], const int (&pel)[PPT]) {
         // label state (previous frame) of the pair to the left of this lane's first pair
-        float cv = from_left_lane(vl[PPT - 1], 0.f);
-        int ce = from_left_lane_i(el[PPT - 1], EZ);
+        float cv = from_left_lane(vl[PPT - 1]);
+        int ce = from_left_lane_i(el[PPT - 1]);
 #pragma unroll
         for (int j = 0; j < PPT; ++j) {
             const float obv = vb[j], olv = vl[j];
@@ -178,16 +188,16 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
             const float s1 = __builtin_amdgcn_ldexpf(obv, obe - E1) + __builtin_amdgcn_ldexpf(cv, ce - E1);
             // label: from itself, from its blank, and (different neighbouring labels) from the label on its left
             const float cvs = skip[j] ? cv : 0.f;
-            const int cs = skip[j] ? ce : EZ;
+            const int cs = skip[j] ? ce : 0;
             const int E2 = max(max(ole, obe), cs);
             const float s2 = (__builtin_amdgcn_ldexpf(olv, ole - E2) + __builtin_amdgcn_ldexpf(obv, obe - E2)) +
                              __builtin_amdgcn_ldexpf(cvs, cs - E2);
             cv = olv;
             ce = ole;
             vb[j] = pmb * s1;
-            eb[j] = s1 > 0.f ? E1 + peb : EZ;
+            eb[j] = max(E1 + peb, 0);
             vl[j] = pml[j] * s2;
-            el[j] = s2 > 0.f ? E2 + pel[j] : EZ;
+            el[j] = max(E2 + pel[j], 0);
             *reinterpret_cast<float4*>(row + slot[j]) = make_float4(vb[j], __int_as_float(eb[j]), vl[j], __int_as_float(el[j]));
         }
     };
@@ -198,9 +208,9 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         for (int j = 0; j < PPT; ++j) {
             const int xb = __builtin_amdgcn_frexp_expf(vb[j]), xl = __builtin_amdgcn_frexp_expf(vl[j]);  // 0 for a zero state
             vb[j] = __builtin_amdgcn_ldexpf(vb[j], -xb);
-            eb[j] += vb[j] > 0.f ? xb : 0;
+            eb[j] += xb;
             vl[j] = __builtin_amdgcn_ldexpf(vl[j], -xl);
-            el[j] += vl[j] > 0.f ? xl : 0;
+            el[j] += xl;
         }
         const int par = tb & 1;
         if (nwaves > 1 && lane >= OWN_LANES) {
@@ -220,42 +230,50 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         }
     };
 
-    if (TABLE) {
-        // element e of a block's rows: step k = e / C of the block, class c = e % C
-        const int nel = SCORE_AHEAD * d.C;
-        float raw[TABLE_LOADS];
-        auto load_rows = [&](int tb) {
+    if constexpr (TABLE) {
+        // element e of a block's rows: step k = e / C of the block, class c = e % C.  In memory the
+        // rows of a block are adjacent (in reversed order for beta), so an element's address is the
+        // block's base plus a per-thread constant; steps past the last frame are clamped to a
+        // valid address (whatever they read only feeds the spare rows).
+        const int nel = SCORE_AHEAD * d.C, per_buf = d.C * TABLE_PITCH, last = T * d.C - 1;
+        int goff[NQ], loff[NQ];
+        float raw[NQ];
 #pragma unroll
-            for (int q = 0; q < TABLE_LOADS; ++q) {
-                const int e = min(tid + q * NT, nel - 1);  // every thread loads something valid: no lane masking around the loads
-                const int k = e / d.C, c = e - k * d.C, step = tb * SCORE_AHEAD + k;
-                raw[q] = lpb[(size_t)frame(step < T ? step : T - 1) * d.C + c];
-            }
+        for (int q = 0; q < NQ; ++q) {
+            const int e = min(tid + q * NT, nel - 1);
+            const int k = e / d.C, c = e - k * d.C;
+            goff[q] = dir ? c - k * d.C : e;
+            loff[q] = (tid + q * NT < nel) ? c * TABLE_PITCH + k : -1;
+        }
+        auto load_rows = [&](int tb) {
+            const int base = dir ? (T - 1 - tb * SCORE_AHEAD) * d.C : tb * SCORE_AHEAD * d.C;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) raw[q] = lpb[min(max(base + goff[q], 0), last)];
         };
         auto write_rows = [&](int buf) {
 #pragma unroll
-            for (int q = 0; q < TABLE_LOADS; ++q) {
-                const int e = tid + q * NT;
-                if (e < nel) {
-                    float pm;
-                    int pe;
-                    split(raw[q], pm, pe);
-                    tbl[buf * nel + e] = make_float2(pm, __int_as_float(pe));
-                }
+            for (int q = 0; q < NQ; ++q) {
+                float pm;
+                int pe;
+                split(raw[q], pm, pe);
+                if (loff[q] >= 0) tbl[buf * per_buf + loff[q]] = make_float2(pm, __int_as_float(pe));
             }
         };
         load_rows(0);
         write_rows(0);
         __syncthreads();
-        for (int tb = 0; tb < tblocks; ++tb) {
-            const float2* cur = tbl + (tb & 1) * nel;
-            load_rows(tb + 1);  // in flight while the block's steps run (past the last block: the last frame again)
-            float2 nb = cur[d.blank], nl[PPT];        // scores of the block's first frame
+        const float2* tb_blank = tbl + d.blank * TABLE_PITCH;
+        const float2* tb_label[PPT];
 #pragma unroll
-            for (int j = 0; j < PPT; ++j) nl[j] = cur[cls[j]];
+        for (int j = 0; j < PPT; ++j) tb_label[j] = tbl + cls[j] * TABLE_PITCH;
+        for (int tb = 0; tb < tblocks; ++tb) {
+            const int cur = (tb & 1) * per_buf;
+            load_rows(tb + 1);  // in flight while the block's steps run
+            float2 nb = tb_blank[cur], nl[PPT];  // scores of the block's first frame
+#pragma unroll
+            for (int j = 0; j < PPT; ++j) nl[j] = tb_label[j][cur];
 #pragma unroll
             for (int k = 0; k < SCORE_AHEAD; ++k) {
-                const int step = tb * SCORE_AHEAD + k;
                 const float pmb = nb.x;
                 const int peb = __float_as_int(nb.y);
                 float pml[PPT];
@@ -263,18 +281,17 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
                 for (int j = 0; j < PPT; ++j) { pml[j] = nl[j].x; pel[j] = __float_as_int(nl[j].y); }
                 if (k + 1 < SCORE_AHEAD) {  // the next frame's scores, one step ahead
-                    nb = cur[(k + 1) * d.C + d.blank];
+                    nb = tb_blank[cur + k + 1];
 #pragma unroll
-                    for (int j = 0; j < PPT; ++j) nl[j] = cur[(k + 1) * d.C + cls[j]];
+                    for (int j = 0; j < PPT; ++j) nl[j] = tb_label[j][cur + k + 1];
                 }
-                float2* const row = step < T ? rptr : spare;
+                advance(rptr, pmb, peb, pml, pel);
                 rptr += rstep;
-                advance(row, pmb, peb, pml, pel);
             }
             // the loaded rows are not touched before the steps are done (tied to a value the last step
             // produced): their wait must not move ahead of the steps, where it would also wait for nothing
 #pragma unroll
-            for (int q = 0; q < TABLE_LOADS; ++q) asm volatile("" : "+v"(raw[q]), "+v"(vb[0]));
+            for (int q = 0; q < NQ; ++q) asm volatile("" : "+v"(raw[q]), "+v"(vb[0]));
             write_rows((tb + 1) & 1);
             boundary(tb, true);
         }
@@ -303,9 +320,8 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
                     for (int j = 0; j < PPT; ++j) sl[j][k] = sptr[cls[j]];
                 }
-                float2* const row = step < T ? rptr : spare;
+                advance(rptr, pmb, peb, pml, pel);
                 rptr += rstep;
-                advance(row, pmb, peb, pml, pel);
             }
             boundary(tb, false);
         }
@@ -319,10 +335,10 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
             const float fbv = __builtin_nontemporal_load(&last[2 * L].x);
             const int fbe = __float_as_int(__builtin_nontemporal_load(&last[2 * L].y));
             const float flv = L > 0 ? __builtin_nontemporal_load(&last[2 * L - 1].x) : 0.f;
-            const int fle = L > 0 ? __float_as_int(__builtin_nontemporal_load(&last[2 * L - 1].y)) : EZ;
+            const int fle = L > 0 ? __float_as_int(__builtin_nontemporal_load(&last[2 * L - 1].y)) : 0;
             const int E = max(fbe, fle);
             const float sum = __builtin_amdgcn_ldexpf(fbv, fbe - E) + __builtin_amdgcn_ldexpf(flv, fle - E);
-            const double lp2 = pair_log2(sum, E);
+            const double lp2 = pair_log2(sum, E - EXP_BIAS);
             logp2_out[b] = lp2;
             loss[b] = sum > 0.f ? (float)(-lp2 * LN2) : INFINITY;
         }
@@ -391,8 +407,8 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
             for (int c = lane; c < d.C; c += 64) grow[c] = 0.f;
             continue;
         }
-        const float2* ar = alpha + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
-        const float2* br = beta + ((size_t)b * (d.Tp + 1) + t) * d.Sp;
+        const float2* ar = alpha + ((size_t)b * d.rows + SCORE_AHEAD + t) * d.Sp;
+        const float2* br = beta + ((size_t)b * d.rows + SCORE_AHEAD + t) * d.Sp;
         const float* lrow = lpb + (size_t)t * d.C;
         // log P split into an integer (taken off the integer exponents exactly) and a fraction
         const int iref = (int)floor(logp2);
@@ -405,8 +421,10 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
             // alpha and beta both carry the frame's own score: one of them is taken off again, split exactly
             // as the lattice kernel split it (integer part off the integer exponents, so nothing large cancels in fp32)
             if (a.x > 0.f && bt.x > 0.f) {
-                const float x = fmaxf(lrow[c] * (float)LOG2E, MIN_LOG2), fl = floorf(x);
-                e = fast_exp2((fast_log2(a.x * bt.x) + (float)(__float_as_int(a.y) + __float_as_int(bt.y) - iref - (int)fl)) +
+                const float x = fminf(fmaxf(lrow[c] * (float)LOG2E, MIN_LOG2), -MIN_LOG2), fl = floorf(x);
+                // both exponents carry the bias: taken off in wrap-around arithmetic
+                const int ex = (int)((unsigned)__float_as_int(a.y) + (unsigned)__float_as_int(bt.y) - 2u * (unsigned)EXP_BIAS);
+                e = fast_exp2((fast_log2(a.x * bt.x) + (float)(ex - iref - (int)fl)) +
                               (shift - (x - fl)));
             }
             ebuf[s] = e;
@@ -444,7 +462,7 @@ WsLayout ws_layout(int B, int Tp, int C, int Lmax)
     size_t off = 0;
     w.lp = off; off += round_up((size_t)B * Tp * C * 4, 256);
     w.logp = off; off += round_up((size_t)B * 8, 256);
-    const size_t lat = round_up((size_t)B * (Tp + 1) * (2 * (size_t)Lmax + 4) * 8, 256);
+    const size_t lat = round_up((size_t)B * (Tp + 2 * SCORE_AHEAD) * (2 * (size_t)Lmax + 4) * 8, 256);
     w.alpha = off; off += lat;
     w.beta = off; off += lat;
     w.total = off;
@@ -482,8 +500,8 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
                                int blank, float grad_scale, void* workspace, size_t ws_bytes, void* stream)
 {
     if (!input || !targets || !in_len || !tgt_len || !loss || !grad) return W2L_ERR_NULL;
-    if (B <= 0 || Tp <= 0 || C <= 0 || C > 4096 || Lmax <= 0 || Lmax > 3000 || blank < 0 || blank >= C ||
-        B > 65535)
+    if (B <= 0 || Tp <= 0 || Tp > MAX_FRAMES || C <= 0 || C > 4096 || Lmax <= 0 || Lmax > 3000 || blank < 0 ||
+        blank >= C || B > 65535)
         return W2L_ERR_SHAPE;
     if (!aligned16(input) || !aligned16(targets) || !aligned16(grad)) return W2L_ERR_ALIGN;
     const WsLayout w = ws_layout(B, Tp, C, Lmax);
@@ -500,7 +518,7 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     double* logp = reinterpret_cast<double*>(ws + w.logp);
     float2* alpha = reinterpret_cast<float2*>(ws + w.alpha);
     float2* beta = reinterpret_cast<float2*>(ws + w.beta);
-    CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 4};
+    CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 4, Tp + 2 * SCORE_AHEAD};
 
     const size_t lds2 = grad_lds_bytes(Lmax, C);
     if (lds2 > 160 * 1024) return W2L_ERR_SHAPE;
@@ -515,20 +533,25 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     const int nt = 64 * (((pairs + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);  // OWN_LANES pair groups per wavefront
     if (nt > 1024) return W2L_ERR_SHAPE;
     const dim3 g1(2, B), b1(nt);
-    // the score table path: a block's class rows must fit TABLE_LOADS elements per thread and 64 KB of LDS
-    const bool table = (long long)SCORE_AHEAD * C <= (long long)TABLE_LOADS * nt && (size_t)2 * SCORE_AHEAD * C * 8 <= 64 * 1024;
-    const size_t lds1 = table ? (size_t)2 * SCORE_AHEAD * C * 8 : 0;
-#define W2L_CTC_LAUNCH(P_, T_)                                                                                        \
+    // the score table path: a block's class rows must fit 8 elements per thread and, in two buffers, 64 KB of LDS
+    const long long nel = (long long)SCORE_AHEAD * C;
+    const size_t table_bytes = (size_t)2 * C * TABLE_PITCH * 8;
+    const int nq = (nel <= 8LL * nt && table_bytes <= 64 * 1024) ? (nel <= 2LL * nt ? 2 : 8) : 0;
+    const size_t lds1 = nq ? table_bytes : 0;
+#define W2L_CTC_LAUNCH(P_, Q_)                                                                                        \
     {                                                                                                                 \
         if (lds1 > 32 * 1024) {                                                                                       \
-            hipError_t e = hipFuncSetAttribute((const void*)ctc_lattice<P_, T_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1); \
+            hipError_t e = hipFuncSetAttribute((const void*)ctc_lattice<P_, Q_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1); \
             if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }                                        \
         }                                                                                                             \
-        hipLaunchKernelGGL((ctc_lattice<P_, T_>), g1, b1, lds1, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d); \
+        hipLaunchKernelGGL((ctc_lattice<P_, Q_>), g1, b1, lds1, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d); \
     }
-    if (ppt == 1) { if (table) W2L_CTC_LAUNCH(1, true) else W2L_CTC_LAUNCH(1, false) }
-    else if (ppt == 2) { if (table) W2L_CTC_LAUNCH(2, true) else W2L_CTC_LAUNCH(2, false) }
-    else { if (table) W2L_CTC_LAUNCH(4, true) else W2L_CTC_LAUNCH(4, false) }
+#define W2L_CTC_LAUNCH_P(P_)                                                                                          \
+    {                                                                                                                 \
+        if (nq == 2) W2L_CTC_LAUNCH(P_, 2) else if (nq == 8) W2L_CTC_LAUNCH(P_, 8) else W2L_CTC_LAUNCH(P_, 0)         \
+    }
+    if (ppt == 1) W2L_CTC_LAUNCH_P(1) else if (ppt == 2) W2L_CTC_LAUNCH_P(2) else W2L_CTC_LAUNCH_P(4)
+#undef W2L_CTC_LAUNCH_P
 #undef W2L_CTC_LAUNCH
     int rc = launch_status();
     if (rc) return rc;
