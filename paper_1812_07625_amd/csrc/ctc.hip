@@ -26,7 +26,6 @@ namespace {
 
 constexpr double LOG2E = 1.4426950408889634074;
 constexpr double LN2 = 0.69314718055994530942;
-constexpr int GRAD_ROWS = 16;   // frames per ctc_grad workgroup (4 per wavefront)
 
 struct CtcDims {
     int B, Tp, C, Lmax, blank;
@@ -92,7 +91,8 @@ template <int PPT, int NQ>
 __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp, const int* __restrict__ targets,
                                                     const int* __restrict__ in_len, const int* __restrict__ tgt_len,
                                                     float* __restrict__ loss, double* __restrict__ logp2_out,
-                                                    float2* __restrict__ alpha, float2* __restrict__ beta, CtcDims d)
+                                                    float2* __restrict__ alpha, float2* __restrict__ beta,
+                                                    int* __restrict__ sort_order, int* __restrict__ sort_start, CtcDims d)
 {
     constexpr bool TABLE = NQ > 0;
     __shared__ float xbuf[2][16][HALO_LANES][4 * PPT];  // [block parity][wavefront][lane - OWN_LANES][v, e of blank, label]
@@ -125,6 +125,29 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         if (dir == 0 && tid == 0) {
             loss[b] = (L == 0) ? 0.f : INFINITY;
             logp2_out[b] = (L == 0) ? 0.0 : -INFINITY;
+        }
+        return;
+    }
+    if (dir == 2) {
+        // third workgroup of the utterance, beside the two recursions: the label positions sorted by
+        // (class, position) and the start of every class in that order -- the fixed summation order
+        // of the gradient kernel.  A plain rank count (no atomics): position i goes to
+        // #{j : l_j < l_i} + #{j < i : l_j = l_i}.
+        int* ord = sort_order + (size_t)b * d.Lmax;
+        int* cst = sort_start + (size_t)b * (d.C + 1);
+        for (int i = tid; i < L; i += NT) {
+            const int c = lab[i];
+            int r = 0;
+            for (int j = 0; j < L; ++j) {
+                const int l = lab[j];
+                r += (l < c || (l == c && j < i)) ? 1 : 0;
+            }
+            ord[r] = i;
+        }
+        for (int c = tid; c <= d.C; c += NT) {
+            int r = 0;
+            for (int j = 0; j < L; ++j) r += lab[j] < c ? 1 : 0;
+            cst[c] = r;
         }
         return;
     }
@@ -352,27 +375,31 @@ __device__ __forceinline__ float wsum(float v)
     return v;
 }
 
+// One wavefront per frame; a workgroup of 4 wavefronts takes `rows_per_wg` consecutive frames of one
+// utterance.  The loads of a frame (both lattice rows, the gathered scores) are issued together,
+// GRAD_UNROLL states per lane at a time.
+constexpr int GRAD_UNROLL = 4;
 __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, const int* __restrict__ targets,
                                                 const int* __restrict__ in_len,
                                                 const int* __restrict__ tgt_len,
                                                 const float* __restrict__ loss,
                                                 const double* __restrict__ logp2_in,
                                                 const float2* __restrict__ alpha,
-                                                const float2* __restrict__ beta, float* __restrict__ grad,
-                                                CtcDims d, int is_logits, float grad_scale)
+                                                const float2* __restrict__ beta,
+                                                const int* __restrict__ sort_order,
+                                                const int* __restrict__ sort_start, float* __restrict__ grad,
+                                                CtcDims d, int rows_per_wg, int is_logits, float grad_scale)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    const int b = blockIdx.y, t0 = blockIdx.x * GRAD_ROWS;
+    const int b = blockIdx.y, t0 = blockIdx.x * rows_per_wg;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float* gb = grad + (size_t)b * d.Tp * d.C;
     const float ls = loss[b];
     const int T = in_len[b];
     const bool live = isfinite(ls) && T > 0;  // NaN (invalid) and +inf (no alignment) give zero rows
-    if (!live) {
-        for (int e = tid; e < GRAD_ROWS * d.C; e += 256) {
-            const int t = t0 + e / d.C;
-            if (t < d.Tp) gb[(size_t)t0 * d.C + e] = 0.f;
-        }
+    const int t_end = min(t0 + rows_per_wg, d.Tp);
+    if (!live || t0 >= T) {
+        for (int e = t0 * d.C + tid; e < t_end * d.C; e += 256) gb[e] = 0.f;
         return;
     }
     const int L = tgt_len[b], S = 2 * L + 1;
@@ -381,27 +408,19 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
     int* cstart = order + d.Lmax;                      // [C+1]
     float* ebuf = reinterpret_cast<float*>(cstart + d.C + 1) + (size_t)wave * d.Sp;  // [4][Sp]
 
-    for (int i = tid; i < L; i += 256) lab[i] = targets[(size_t)b * d.Lmax + i];
-    for (int c = tid; c <= d.C; c += 256) cstart[c] = 0;
-    __syncthreads();
-    for (int i = tid; i < L; i += 256) atomicAdd(&cstart[lab[i] + 1], 1);  // integer: order-independent
-    __syncthreads();
-    if (tid == 0)
-        for (int c = 0; c < d.C; ++c) cstart[c + 1] += cstart[c];
-    __syncthreads();
     for (int i = tid; i < L; i += 256) {
-        const int c = lab[i];
-        int r = cstart[c];
-        for (int j = 0; j < i; ++j) r += (lab[j] == c);
-        order[r] = i;
+        lab[i] = targets[(size_t)b * d.Lmax + i];
+        order[i] = sort_order[(size_t)b * d.Lmax + i];
     }
+    for (int c = tid; c <= d.C; c += 256) cstart[c] = sort_start[(size_t)b * (d.C + 1) + c];
     __syncthreads();
 
     const double logp2 = logp2_in[b];
+    // log P split into an integer (taken off the integer exponents exactly) and a fraction
+    const int iref = (int)floor(logp2);
+    const float shift = (float)((double)iref - logp2);
     const float* lpb = lp + (size_t)b * d.Tp * d.C;
-    for (int rr = wave; rr < GRAD_ROWS; rr += 4) {
-        const int t = t0 + rr;
-        if (t >= d.Tp) break;
+    for (int t = t0 + wave; t < t_end; t += 4) {
         float* grow = gb + (size_t)t * d.C;
         if (t >= T) {
             for (int c = lane; c < d.C; c += 64) grow[c] = 0.f;
@@ -410,26 +429,36 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
         const float2* ar = alpha + ((size_t)b * d.rows + SCORE_AHEAD + t) * d.Sp;
         const float2* br = beta + ((size_t)b * d.rows + SCORE_AHEAD + t) * d.Sp;
         const float* lrow = lpb + (size_t)t * d.C;
-        // log P split into an integer (taken off the integer exponents exactly) and a fraction
-        const int iref = (int)floor(logp2);
-        const float shift = (float)((double)iref - logp2);
         float z = 0.f, zb = 0.f;
-        for (int s = lane; s < S; s += 64) {
-            const int c = (s & 1) ? lab[(s - 1) >> 1] : d.blank;
-            const float2 a = ar[s], bt = br[S - 1 - s];  // beta rows are stored in reversed state order
-            float e = 0.f;
-            // alpha and beta both carry the frame's own score: one of them is taken off again, split exactly
-            // as the lattice kernel split it (integer part off the integer exponents, so nothing large cancels in fp32)
-            if (a.x > 0.f && bt.x > 0.f) {
-                const float x = fminf(fmaxf(lrow[c] * (float)LOG2E, MIN_LOG2), -MIN_LOG2), fl = floorf(x);
-                // both exponents carry the bias: taken off in wrap-around arithmetic
-                const int ex = (int)((unsigned)__float_as_int(a.y) + (unsigned)__float_as_int(bt.y) - 2u * (unsigned)EXP_BIAS);
-                e = fast_exp2((fast_log2(a.x * bt.x) + (float)(ex - iref - (int)fl)) +
-                              (shift - (x - fl)));
+        for (int s0 = lane; s0 < S; s0 += 64 * GRAD_UNROLL) {
+            float2 a[GRAD_UNROLL], bt[GRAD_UNROLL];
+            float sc[GRAD_UNROLL];
+#pragma unroll
+            for (int u = 0; u < GRAD_UNROLL; ++u) {
+                const int s = min(s0 + 64 * u, S - 1);  // clamped lanes repeat a valid state and are dropped below
+                const int c = (s & 1) ? lab[(s - 1) >> 1] : d.blank;
+                a[u] = ar[s];
+                bt[u] = br[S - 1 - s];  // beta rows are stored in reversed state order
+                sc[u] = lrow[c];
             }
-            ebuf[s] = e;
-            z += e;
-            if (!(s & 1)) zb += e;
+#pragma unroll
+            for (int u = 0; u < GRAD_UNROLL; ++u) {
+                const int s = s0 + 64 * u;
+                float e = 0.f;
+                // alpha and beta both carry the frame's own score: one of them is taken off again, split exactly
+                // as the lattice kernel split it (integer part off the integer exponents, so nothing large cancels in fp32)
+                if (a[u].x > 0.f && bt[u].x > 0.f) {
+                    const float x = fminf(fmaxf(sc[u] * (float)LOG2E, MIN_LOG2), -MIN_LOG2), fl = floorf(x);
+                    // both exponents carry the bias: taken off in wrap-around arithmetic
+                    const int ex = (int)((unsigned)__float_as_int(a[u].y) + (unsigned)__float_as_int(bt[u].y) - 2u * (unsigned)EXP_BIAS);
+                    e = fast_exp2((fast_log2(a[u].x * bt[u].x) + (float)(ex - iref - (int)fl)) + (shift - (x - fl)));
+                }
+                if (s < S) {
+                    ebuf[s] = e;
+                    z += e;
+                    if (!(s & 1)) zb += e;
+                }
+            }
         }
         z = wsum(z);
         zb = wsum(zb);
@@ -455,13 +484,15 @@ size_t grad_lds_bytes(int Lmax, int C)
     return (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (2 * Lmax + 4);
 }
 
-struct WsLayout { size_t lp, logp, alpha, beta, total; };
+struct WsLayout { size_t lp, logp, order, cstart, alpha, beta, total; };
 WsLayout ws_layout(int B, int Tp, int C, int Lmax)
 {
     WsLayout w;
     size_t off = 0;
     w.lp = off; off += round_up((size_t)B * Tp * C * 4, 256);
     w.logp = off; off += round_up((size_t)B * 8, 256);
+    w.order = off; off += round_up((size_t)B * Lmax * 4, 256);
+    w.cstart = off; off += round_up((size_t)B * (C + 1) * 4, 256);
     const size_t lat = round_up((size_t)B * (Tp + 2 * SCORE_AHEAD) * (2 * (size_t)Lmax + 4) * 8, 256);
     w.alpha = off; off += lat;
     w.beta = off; off += lat;
@@ -518,6 +549,8 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     double* logp = reinterpret_cast<double*>(ws + w.logp);
     float2* alpha = reinterpret_cast<float2*>(ws + w.alpha);
     float2* beta = reinterpret_cast<float2*>(ws + w.beta);
+    int* sort_order = reinterpret_cast<int*>(ws + w.order);
+    int* sort_start = reinterpret_cast<int*>(ws + w.cstart);
     CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 4, Tp + 2 * SCORE_AHEAD};
 
     const size_t lds2 = grad_lds_bytes(Lmax, C);
@@ -532,7 +565,7 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     const int ppt = pairs <= 16 * OWN_LANES ? 1 : (pairs <= 32 * OWN_LANES ? 2 : 4);
     const int nt = 64 * (((pairs + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);  // OWN_LANES pair groups per wavefront
     if (nt > 1024) return W2L_ERR_SHAPE;
-    const dim3 g1(2, B), b1(nt);
+    const dim3 g1(3, B), b1(nt);  // alpha, beta, and the sort of the target for the gradient kernel
     // the score table path: a block's class rows must fit 8 elements per thread and, in two buffers, 64 KB of LDS
     const long long nel = (long long)SCORE_AHEAD * C;
     const size_t table_bytes = (size_t)2 * C * TABLE_PITCH * 8;
@@ -544,7 +577,7 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
             hipError_t e = hipFuncSetAttribute((const void*)ctc_lattice<P_, Q_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1); \
             if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }                                        \
         }                                                                                                             \
-        hipLaunchKernelGGL((ctc_lattice<P_, Q_>), g1, b1, lds1, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, d); \
+        hipLaunchKernelGGL((ctc_lattice<P_, Q_>), g1, b1, lds1, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, sort_order, sort_start, d); \
     }
 #define W2L_CTC_LAUNCH_P(P_)                                                                                          \
     {                                                                                                                 \
@@ -555,7 +588,11 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
 #undef W2L_CTC_LAUNCH
     int rc = launch_status();
     if (rc) return rc;
-    hipLaunchKernelGGL(ctc_grad, dim3((Tp + GRAD_ROWS - 1) / GRAD_ROWS, B), dim3(256), lds2, st, lp, targets,
-                       in_len, tgt_len, loss, logp, alpha, beta, grad, d, is_logits, grad_scale);
+    // frames per gradient workgroup: one per wavefront while the per-workgroup copy of the target's sort
+    // (2 Lmax + C + 1 integers) is small beside the frames' own lattice rows, more otherwise
+    const int rows_per_wg = (2 * Lmax + C + 1 <= 1024) ? 4 : 16;
+    hipLaunchKernelGGL(ctc_grad, dim3((Tp + rows_per_wg - 1) / rows_per_wg, B), dim3(256), lds2, st, lp, targets,
+                       in_len, tgt_len, loss, logp, alpha, beta, sort_order, sort_start, grad, d, rows_per_wg, is_logits,
+                       grad_scale);
     return launch_status();
 }
