@@ -30,7 +30,7 @@ constexpr double LN2 = 0.69314718055994530942;
 struct CtcDims {
     int B, Tp, C, Lmax, blank;
     int Sp;    // lattice row pitch in states = 2*Lmax+4 (the last pair is a spare); a state is 8 bytes
-    int rows;  // lattice rows per utterance = Tp + 2*SCORE_AHEAD: frame t is row SCORE_AHEAD + t
+    int rows;  // lattice rows per utterance = Tp + 2*LAT_PAD: frame t is row LAT_PAD + t
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -43,10 +43,7 @@ __device__ __forceinline__ int from_left_lane_i(int v)
 }
 __device__ __forceinline__ float from_left_lane(float v) { return __int_as_float(from_left_lane_i(__float_as_int(v))); }
 
-constexpr int SCORE_AHEAD = 16;  // frames per block: the period of the score staging, of the hand-over
-                                 // between wavefronts and of the renormalisation
-constexpr int HALO_LANES = SCORE_AHEAD;     // lanes of a wavefront that mirror the wavefront on its left
-constexpr int OWN_LANES = 64 - HALO_LANES;  // lanes whose states a wavefront owns (and stores)
+constexpr int LAT_PAD = 16;  // spare lattice rows at either end of an utterance = the longest block of frames
 
 // A state's exponent is kept with a bias, so that 0 can stand for "zero state" (the value a lane
 // shift fills in at the edge) and compares below every real exponent.  Real exponents stay within
@@ -63,9 +60,9 @@ __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (
 // (blank 2i, label 2i+1); a lane holds PPT consecutive pairs in registers, so per frame it needs
 // exactly one value from outside: the label state of the pair to its left, which a DPP
 // whole-wavefront shift delivers from the neighbouring lane.  No value crosses a wavefront
-// boundary inside a block of SCORE_AHEAD frames: the first HALO_LANES lanes of every wavefront
+// boundary inside a block of BLK frames: the first BLK lanes of every wavefront
 // recompute the pairs owned by the last lanes of the wavefront on its left.  Their leftmost input
-// is missing, so they go stale from the left at one pair per frame -- after SCORE_AHEAD frames
+// is missing, so they go stale from the left at one pair per frame -- after BLK frames
 // the staleness has not yet reached the lanes the wavefront owns -- and once per block they are
 // refreshed through LDS, at the one barrier of the block.  States to the right of the target's
 // last pair are computed too (nothing reads them; a state depends only on states to its left);
@@ -73,21 +70,24 @@ __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (
 // reversed time (state index q counts from the end), stored in its own q order.
 // The step body is straight-line code with a fixed number of memory operations: lanes that own
 // no real pair write to a spare pair, and the steps between the last frame and the end of its
-// block of SCORE_AHEAD frames run on like the others -- their rows land in the SCORE_AHEAD spare
+// block of BLK frames run on like the others -- their rows land in the LAT_PAD spare
 // rows that every utterance's lattice has at either end (alpha runs off the far end, beta off
 // the near one) or in rows t >= T_b that nobody reads.
 // Stored per frame and state: the pair (v, e + EXP_BIAS), the integer as the bits of the second float.
 // NQ > 0 (the class rows of a block of frames fit NQ values per thread): the scores do not come
 // through per-lane loads at all.  The workgroup keeps the rows lp[t, 0..C-1] of the current
-// block of SCORE_AHEAD frames in LDS, already split into (mantissa, exponent), class-major
+// block of BLK frames in LDS, already split into (mantissa, exponent), class-major
 // (the frames of one class are adjacent, so a step's read is the lane's fixed address plus a
 // constant), in two buffers: the rows of the next block are loaded (coalesced) before the
 // block's steps start and written to the other buffer after them, so the recursion itself issues
 // no vector loads and never waits on the memory counter that its own lattice stores keep busy.
 // NQ == 0 (large alphabets): the scores lp[t, blank] and lp[t, label] are gathered per lane
-// SCORE_AHEAD frames early into a register ring.
-constexpr int TABLE_PITCH = SCORE_AHEAD + 1;  // table entries per class (one of padding against bank conflicts)
-template <int PPT, int NQ>
+// BLK frames early into a register ring.
+// BLK = 16, or 12 where that brings the target onto four wavefronts (64 - BLK owned lanes each):
+// the step is bound by instruction issue -- one wavefront alone on its SIMD issues the ~30
+// instructions of a step at the 4-cycle cadence -- so a fifth wavefront, which has to share a
+// SIMD, costs more than a hand-over between wavefronts every 12 frames instead of every 16.
+template <int PPT, int NQ, int BLK>
 __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp, const int* __restrict__ targets,
                                                     const int* __restrict__ in_len, const int* __restrict__ tgt_len,
                                                     float* __restrict__ loss, double* __restrict__ logp2_out,
@@ -95,6 +95,9 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                                                     int* __restrict__ sort_order, int* __restrict__ sort_start, CtcDims d)
 {
     constexpr bool TABLE = NQ > 0;
+    constexpr int HALO_LANES = BLK;             // lanes of a wavefront that mirror the wavefront on its left
+    constexpr int OWN_LANES = 64 - HALO_LANES;  // lanes whose states a wavefront owns (and stores)
+    constexpr int TABLE_PITCH = BLK + 1;        // table entries per class (one of padding against bank conflicts)
     __shared__ float xbuf[2][16][HALO_LANES][4 * PPT];  // [block parity][wavefront][lane - OWN_LANES][v, e of blank, label]
     __shared__ int bad_len, bad;
     extern __shared__ __align__(16) unsigned char dyn_smem[];
@@ -175,12 +178,12 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         el[j] = 0;
     }
     const float* lpb = lp + (size_t)b * d.Tp * d.C;
-    float2* lat = (dir ? beta : alpha) + ((size_t)b * d.rows + SCORE_AHEAD) * d.Sp;  // row of frame 0
+    float2* lat = (dir ? beta : alpha) + ((size_t)b * d.rows + LAT_PAD) * d.Sp;  // row of frame 0
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
     const float log2e = (float)LOG2E;
 
     const int nwaves = NT >> 6;
-    const int tblocks = (T + SCORE_AHEAD - 1) / SCORE_AHEAD;
+    const int tblocks = (T + BLK - 1) / BLK;
     // running pointers instead of per-step index arithmetic: the lattice row written next
     // (and, without the table, the score row fetched next, clamped at the last frame)
     const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)d.Sp : d.Sp;
@@ -226,7 +229,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     };
     // block boundary: every lane moves the exponents of its mantissas into e; the mirror lanes
     // are refreshed from the left neighbour (one workgroup barrier)
-    auto boundary = [&](int tb, bool sync_always) {
+    auto boundary = [&](int tb, bool sync_always, auto&& before_barrier) {
 #pragma unroll
         for (int j = 0; j < PPT; ++j) {
             const int xb = __builtin_amdgcn_frexp_expf(vb[j]), xl = __builtin_amdgcn_frexp_expf(vl[j]);  // 0 for a zero state
@@ -243,6 +246,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                 q[0] = vb[j]; q[1] = __int_as_float(eb[j]); q[2] = vl[j]; q[3] = __int_as_float(el[j]);
             }
         }
+        before_barrier();  // work that only has to be done by the barrier: issued while the hand-over writes are on their way
         if (nwaves > 1 || sync_always) __syncthreads();
         if (nwaves > 1 && wave > 0 && !owner) {
 #pragma unroll
@@ -258,9 +262,9 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         // rows of a block are adjacent (in reversed order for beta), so an element's address is the
         // block's base plus a per-thread constant; steps past the last frame are clamped to a
         // valid address (whatever they read only feeds the spare rows).
-        const int nel = SCORE_AHEAD * d.C, per_buf = d.C * TABLE_PITCH, last = T * d.C - 1;
+        const int nel = BLK * d.C, per_buf = d.C * TABLE_PITCH, last = T * d.C - 1;
         int goff[NQ], loff[NQ];
-        float raw[NQ];
+        float raw0[NQ], raw1[NQ];  // rows in flight: loaded two blocks before the block that uses them
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const int e = min(tid + q * NT, nel - 1);
@@ -268,12 +272,12 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
             goff[q] = dir ? c - k * d.C : e;
             loff[q] = (tid + q * NT < nel) ? c * TABLE_PITCH + k : -1;
         }
-        auto load_rows = [&](int tb) {
-            const int base = dir ? (T - 1 - tb * SCORE_AHEAD) * d.C : tb * SCORE_AHEAD * d.C;
+        auto load_rows = [&](int tb, float (&raw)[NQ]) {
+            const int base = dir ? (T - 1 - tb * BLK) * d.C : tb * BLK * d.C;
 #pragma unroll
             for (int q = 0; q < NQ; ++q) raw[q] = lpb[min(max(base + goff[q], 0), last)];
         };
-        auto write_rows = [&](int buf) {
+        auto write_rows = [&](int buf, const float (&raw)[NQ]) {
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
                 float pm;
@@ -282,63 +286,71 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                 if (loff[q] >= 0) tbl[buf * per_buf + loff[q]] = make_float2(pm, __int_as_float(pe));
             }
         };
-        load_rows(0);
-        write_rows(0);
-        __syncthreads();
         const float2* tb_blank = tbl + d.blank * TABLE_PITCH;
         const float2* tb_label[PPT];
 #pragma unroll
         for (int j = 0; j < PPT; ++j) tb_label[j] = tbl + cls[j] * TABLE_PITCH;
-        for (int tb = 0; tb < tblocks; ++tb) {
+        // block tb: its scores are in table buffer tb & 1; the rows of block tb + 2 are requested into
+        // `load`, the rows of block tb + 1 (requested a block ago) are in `next` and go into the other buffer
+        auto block = [&](int tb, float (&next)[NQ], float (&load)[NQ]) {
             const int cur = (tb & 1) * per_buf;
-            load_rows(tb + 1);  // in flight while the block's steps run
-            float2 nb = tb_blank[cur], nl[PPT];  // scores of the block's first frame
+            load_rows(tb + 2, load);
+            {
+                float2 nb = tb_blank[cur], nl[PPT];  // scores of the block's first frame
 #pragma unroll
-            for (int j = 0; j < PPT; ++j) nl[j] = tb_label[j][cur];
+                for (int j = 0; j < PPT; ++j) nl[j] = tb_label[j][cur];
 #pragma unroll
-            for (int k = 0; k < SCORE_AHEAD; ++k) {
-                const float pmb = nb.x;
-                const int peb = __float_as_int(nb.y);
-                float pml[PPT];
-                int pel[PPT];
+                for (int k = 0; k < BLK; ++k) {
+                    const float pmb = nb.x;
+                    const int peb = __float_as_int(nb.y);
+                    float pml[PPT];
+                    int pel[PPT];
 #pragma unroll
-                for (int j = 0; j < PPT; ++j) { pml[j] = nl[j].x; pel[j] = __float_as_int(nl[j].y); }
-                if (k + 1 < SCORE_AHEAD) {  // the next frame's scores, one step ahead
-                    nb = tb_blank[cur + k + 1];
+                    for (int j = 0; j < PPT; ++j) { pml[j] = nl[j].x; pel[j] = __float_as_int(nl[j].y); }
+                    if (k + 1 < BLK) {  // the next frame's scores, one step ahead
+                        nb = tb_blank[cur + k + 1];
 #pragma unroll
-                    for (int j = 0; j < PPT; ++j) nl[j] = tb_label[j][cur + k + 1];
+                        for (int j = 0; j < PPT; ++j) nl[j] = tb_label[j][cur + k + 1];
+                    }
+                    advance(rptr, pmb, peb, pml, pel);
+                    rptr += rstep;
                 }
-                advance(rptr, pmb, peb, pml, pel);
-                rptr += rstep;
             }
-            // the loaded rows are not touched before the steps are done (tied to a value the last step
-            // produced): their wait must not move ahead of the steps, where it would also wait for nothing
+            // the rows in flight are not touched before the steps are done (tied to a value the last step
+            // produced): their wait must not move ahead of the steps
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) asm volatile("" : "+v"(raw[q]), "+v"(vb[0]));
-            write_rows((tb + 1) & 1);
-            boundary(tb, true);
+            for (int q = 0; q < NQ; ++q) asm volatile("" : "+v"(next[q]), "+v"(vb[0]));
+            boundary(tb, true, [&] { write_rows((tb + 1) & 1, next); });
+        };
+        load_rows(0, raw0);
+        write_rows(0, raw0);
+        load_rows(1, raw1);
+        __syncthreads();
+        for (int tb = 0; tb < tblocks; tb += 2) {
+            block(tb, raw1, raw0);
+            if (tb + 1 < tblocks) block(tb + 1, raw0, raw1);
         }
     } else {
-        float sb[SCORE_AHEAD], sl[PPT][SCORE_AHEAD];
+        float sb[BLK], sl[PPT][BLK];
 #pragma unroll
-        for (int k = 0; k < SCORE_AHEAD; ++k) {
+        for (int k = 0; k < BLK; ++k) {
             const int f = frame(k < T ? k : T - 1);
             sb[k] = lpb[(size_t)f * d.C + d.blank];
 #pragma unroll
             for (int j = 0; j < PPT; ++j) sl[j][k] = lpb[(size_t)f * d.C + cls[j]];
         }
-        const float* sptr = lpb + (size_t)frame(SCORE_AHEAD - 1 < T ? SCORE_AHEAD - 1 : T - 1) * d.C;
+        const float* sptr = lpb + (size_t)frame(BLK - 1 < T ? BLK - 1 : T - 1) * d.C;
         for (int tb = 0; tb < tblocks; ++tb) {
 #pragma unroll
-            for (int k = 0; k < SCORE_AHEAD; ++k) {
-                const int step = tb * SCORE_AHEAD + k;
+            for (int k = 0; k < BLK; ++k) {
+                const int step = tb * BLK + k;
                 float pmb, pml[PPT];
                 int peb, pel[PPT];
                 split(sb[k], pmb, peb);
 #pragma unroll
                 for (int j = 0; j < PPT; ++j) split(sl[j][k], pml[j], pel[j]);
-                {   // refill this ring slot for step + SCORE_AHEAD (past the end: the last frame again)
-                    sptr += (step + SCORE_AHEAD < T) ? sstep : 0;
+                {   // refill this ring slot for step + BLK (past the end: the last frame again)
+                    sptr += (step + BLK < T) ? sstep : 0;
                     sb[k] = sptr[d.blank];
 #pragma unroll
                     for (int j = 0; j < PPT; ++j) sl[j][k] = sptr[cls[j]];
@@ -346,7 +358,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
                 advance(rptr, pmb, peb, pml, pel);
                 rptr += rstep;
             }
-            boundary(tb, false);
+            boundary(tb, false, [] {});
         }
     }
     // log P = log( alpha_{T-1}(S-1) + alpha_{T-1}(S-2) ): blank of pair L, label of pair L-1, read back
@@ -426,8 +438,8 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
             for (int c = lane; c < d.C; c += 64) grow[c] = 0.f;
             continue;
         }
-        const float2* ar = alpha + ((size_t)b * d.rows + SCORE_AHEAD + t) * d.Sp;
-        const float2* br = beta + ((size_t)b * d.rows + SCORE_AHEAD + t) * d.Sp;
+        const float2* ar = alpha + ((size_t)b * d.rows + LAT_PAD + t) * d.Sp;
+        const float2* br = beta + ((size_t)b * d.rows + LAT_PAD + t) * d.Sp;
         const float* lrow = lpb + (size_t)t * d.C;
         float z = 0.f, zb = 0.f;
         for (int s0 = lane; s0 < S; s0 += 64 * GRAD_UNROLL) {
@@ -493,7 +505,7 @@ WsLayout ws_layout(int B, int Tp, int C, int Lmax)
     w.logp = off; off += round_up((size_t)B * 8, 256);
     w.order = off; off += round_up((size_t)B * Lmax * 4, 256);
     w.cstart = off; off += round_up((size_t)B * (C + 1) * 4, 256);
-    const size_t lat = round_up((size_t)B * (Tp + 2 * SCORE_AHEAD) * (2 * (size_t)Lmax + 4) * 8, 256);
+    const size_t lat = round_up((size_t)B * (Tp + 2 * LAT_PAD) * (2 * (size_t)Lmax + 4) * 8, 256);
     w.alpha = off; off += lat;
     w.beta = off; off += lat;
     w.total = off;
@@ -551,7 +563,7 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     float2* beta = reinterpret_cast<float2*>(ws + w.beta);
     int* sort_order = reinterpret_cast<int*>(ws + w.order);
     int* sort_start = reinterpret_cast<int*>(ws + w.cstart);
-    CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 4, Tp + 2 * SCORE_AHEAD};
+    CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 4, Tp + 2 * LAT_PAD};
 
     const size_t lds2 = grad_lds_bytes(Lmax, C);
     if (lds2 > 160 * 1024) return W2L_ERR_SHAPE;
@@ -559,32 +571,44 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
         hipError_t e = hipFuncSetAttribute((const void*)ctc_grad, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
         if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }
     }
-    // one lane per (blank,label) pair of the extended target, OWN_LANES of them per wavefront;
-    // more pairs per lane only when 16 wavefronts cannot cover Lmax+1 pairs
+    // One lane per PPT (blank, label) pairs of the extended target, 64 - BLK of them per wavefront.  The step is
+    // bound by instruction issue, so a wavefront wants a SIMD of its own: the smallest PPT that fits four
+    // wavefronts, with blocks of 16 frames if that fits and of 12 (52 owned lanes) otherwise; targets beyond
+    // 4 * 52 * 4 pairs take four pairs per lane on as many wavefronts as they need.
     const int pairs = Lmax + 1;
-    const int ppt = pairs <= 16 * OWN_LANES ? 1 : (pairs <= 32 * OWN_LANES ? 2 : 4);
-    const int nt = 64 * (((pairs + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);  // OWN_LANES pair groups per wavefront
+    int ppt = 4, blk = 16;
+    for (int p = 1; p <= 4; p *= 2) {
+        if (pairs <= 4 * 48 * p) { ppt = p; blk = 16; break; }
+        if (pairs <= 4 * 52 * p) { ppt = p; blk = 12; break; }
+    }
+    const int own = 64 - blk;
+    const int nt = 64 * (((pairs + ppt - 1) / ppt + own - 1) / own);
     if (nt > 1024) return W2L_ERR_SHAPE;
     const dim3 g1(3, B), b1(nt);  // alpha, beta, and the sort of the target for the gradient kernel
     // the score table path: a block's class rows must fit 8 elements per thread and, in two buffers, 64 KB of LDS
-    const long long nel = (long long)SCORE_AHEAD * C;
-    const size_t table_bytes = (size_t)2 * C * TABLE_PITCH * 8;
+    const long long nel = (long long)blk * C;
+    const size_t table_bytes = (size_t)2 * C * (blk + 1) * 8;
     const int nq = (nel <= 8LL * nt && table_bytes <= 64 * 1024) ? (nel <= 2LL * nt ? 2 : 8) : 0;
     const size_t lds1 = nq ? table_bytes : 0;
-#define W2L_CTC_LAUNCH(P_, Q_)                                                                                        \
+#define W2L_CTC_LAUNCH(P_, Q_, B_)                                                                                    \
     {                                                                                                                 \
         if (lds1 > 32 * 1024) {                                                                                       \
-            hipError_t e = hipFuncSetAttribute((const void*)ctc_lattice<P_, Q_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1); \
+            hipError_t e = hipFuncSetAttribute((const void*)ctc_lattice<P_, Q_, B_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1); \
             if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }                                        \
         }                                                                                                             \
-        hipLaunchKernelGGL((ctc_lattice<P_, Q_>), g1, b1, lds1, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, sort_order, sort_start, d); \
+        hipLaunchKernelGGL((ctc_lattice<P_, Q_, B_>), g1, b1, lds1, st, lp, targets, in_len, tgt_len, loss, logp, alpha, beta, sort_order, sort_start, d); \
+    }
+#define W2L_CTC_LAUNCH_Q(P_, B_)                                                                                      \
+    {                                                                                                                 \
+        if (nq == 2) W2L_CTC_LAUNCH(P_, 2, B_) else if (nq == 8) W2L_CTC_LAUNCH(P_, 8, B_) else W2L_CTC_LAUNCH(P_, 0, B_) \
     }
 #define W2L_CTC_LAUNCH_P(P_)                                                                                          \
     {                                                                                                                 \
-        if (nq == 2) W2L_CTC_LAUNCH(P_, 2) else if (nq == 8) W2L_CTC_LAUNCH(P_, 8) else W2L_CTC_LAUNCH(P_, 0)         \
+        if (blk == 16) W2L_CTC_LAUNCH_Q(P_, 16) else W2L_CTC_LAUNCH_Q(P_, 12)                                          \
     }
     if (ppt == 1) W2L_CTC_LAUNCH_P(1) else if (ppt == 2) W2L_CTC_LAUNCH_P(2) else W2L_CTC_LAUNCH_P(4)
 #undef W2L_CTC_LAUNCH_P
+#undef W2L_CTC_LAUNCH_Q
 #undef W2L_CTC_LAUNCH
     int rc = launch_status();
     if (rc) return rc;

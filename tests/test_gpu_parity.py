@@ -187,7 +187,11 @@ def _check_ctc(loss, grad, loss_o, grad_o):
     dict(B=6, T=200, in_lo=150, in_hi=200, l_lo=30, l_hi=70),     # S spans > 1 wavefront
     dict(B=3, T=97, in_lo=1, in_hi=97, l_lo=0, l_hi=1, Cc=5),
     dict(),                                                         # the full benchmark shape
-    dict(B=2, T=2300, in_lo=2250, in_hi=2300, l_lo=1030, l_hi=1100),  # > 1024 pairs: two pairs per thread
+    dict(B=2, T=2300, in_lo=2250, in_hi=2300, l_lo=1030, l_hi=1100),  # four pairs per lane on six wavefronts
+    dict(B=2, T=700, in_lo=650, in_hi=700, l_lo=250, l_hi=300),       # two pairs per lane, blocks of 16 frames
+    dict(B=2, T=900, in_lo=860, in_hi=900, l_lo=390, l_hi=440),       # two pairs per lane, blocks of 8 frames
+    dict(B=2, T=1300, in_lo=1250, in_hi=1300, l_lo=550, l_hi=600),    # four pairs per lane, blocks of 16
+    dict(B=2, T=1800, in_lo=1750, in_hi=1800, l_lo=800, l_hi=850),    # four pairs per lane, blocks of 8
 ])
 def test_ctc_from_logits(P, kw):
     cfg = W.config2(seed=2, **kw)
