@@ -152,7 +152,7 @@ int w2l_sgd_momentum_step(float *w, float *v, const float *grad, void *w_lowp, l
  * equal to blank or outside [0,C), or a length outside its range, cannot be
  * reported by an asynchronous call: that utterance gets loss NaN and zero
  * gradient (w2l_ctc_check_targets_host() validates host copies beforehand).
- * Limits: C <= 4096, Lmax <= 4000. */
+ * Limits: C <= 4096, Lmax <= 3000, Tp <= 8192 (else W2L_ERR_SHAPE). */
 size_t w2l_ctc_workspace_bytes(int B, int Tp, int C, int Lmax);
 int w2l_ctc_fwd_bwd(const float *input, int is_logits, const int *targets, const int *in_len,
                     const int *tgt_len, float *loss, float *grad,

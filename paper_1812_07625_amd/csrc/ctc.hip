@@ -12,9 +12,10 @@
 //      sum of predecessors aligns their exponents with v_ldexp and adds; the frame's score
 //      enters as 2^(lp * log2 e) split into an integer exponent and a mantissa in [1, 2).
 //      All terms are non-negative, so a mantissa never shrinks and grows by at most 6x per
-//      frame: every 16 frames each lane moves the exponent of its own mantissas into e.
-//      A zero state has v = 0 and a large negative e, which keeps the step free of branches;
-//      the lattice rows hold the (v, e) pairs;
+//      frame: once per block of frames each lane moves the exponent of its own mantissas
+//      into e.  Exponents carry a bias and a zero state has v = 0 and exponent 0, below
+//      every real one, which keeps the step free of branches; the lattice rows hold the
+//      (v, e) pairs.  A third workgroup per utterance sorts the target for kernel 3;
 //   3. ctc_grad: one wavefront per frame combines alpha_t and beta_t (mantissas
 //      multiplied, exponents added, log P taken off) into the state posteriors, normalises
 //      them per frame, and sums them per class in a fixed order given by a (class, position)
