@@ -587,9 +587,6 @@ __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em
         return;
     }
     if (blockIdx.x == 0 && tid == 0) w.status[b] = 0;
-#ifdef ASG_SKIP_KIND
-    if (kind == ASG_SKIP_KIND) return;
-#endif
     const float* emb = em + (size_t)b * d.Tp * d.C;
     if (kind == 0) {
         fal_lattice<PPT>(emb, trans, lab, T, L, dir, w.fal[dir] + (size_t)b * (d.Tp + 1) * d.Sp,
