@@ -589,7 +589,7 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     // the score table path: a block's class rows must fit 8 elements per thread and, in two buffers, 64 KB of LDS
     const long long nel = (long long)blk * C;
     const size_t table_bytes = (size_t)2 * C * (blk + 1) * 8;
-    const int nq = (nel <= 8LL * nt && table_bytes <= 64 * 1024) ? (nel <= 2LL * nt ? 2 : 8) : 0;
+    const int nq = (nel <= 8LL * nt && table_bytes <= 64 * 1024) ? (nel <= 2LL * nt ? 2 : (nel <= 4LL * nt ? 4 : 8)) : 0;
     const size_t lds1 = nq ? table_bytes : 0;
 #define W2L_CTC_LAUNCH(P_, Q_, B_)                                                                                    \
     {                                                                                                                 \
@@ -601,7 +601,8 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
     }
 #define W2L_CTC_LAUNCH_Q(P_, B_)                                                                                      \
     {                                                                                                                 \
-        if (nq == 2) W2L_CTC_LAUNCH(P_, 2, B_) else if (nq == 8) W2L_CTC_LAUNCH(P_, 8, B_) else W2L_CTC_LAUNCH(P_, 0, B_) \
+        if (nq == 2) W2L_CTC_LAUNCH(P_, 2, B_) else if (nq == 4) W2L_CTC_LAUNCH(P_, 4, B_)                             \
+        else if (nq == 8) W2L_CTC_LAUNCH(P_, 8, B_) else W2L_CTC_LAUNCH(P_, 0, B_)                                    \
     }
 #define W2L_CTC_LAUNCH_P(P_)                                                                                          \
     {                                                                                                                 \
