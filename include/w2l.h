@@ -241,7 +241,14 @@ int w2l_logmel_fwd(const float *wav, const int *wav_len, void *feat, int *feat_l
  * The four pointer tables are HOST arrays of DEVICE pointers; x, in_len, targets,
  * tgt_len, loss, logits are device pointers.  With W2L_BF16, activations and
  * gradients between layers are stored as bf16, the last layer's output (logits), the
- * log-softmax and CTC are fp32. */
+ * log-softmax and CTC are fp32.
+ * Concurrency: the step runs the weight gradients on one helper stream (default priority,
+ * created on first use, one per device, never destroyed) tied to `stream` by events, and is
+ * complete in `stream` order when the call's work on `stream` is.  Host threads may call
+ * concurrently for different devices; two steps in flight on the SAME device at the same time
+ * (two streams or two host threads) share that helper stream and its events and are not
+ * supported -- order them on one stream.  Like every call here, steps that share a workspace
+ * must not overlap. */
 size_t w2l_train_step_workspace_bytes(const w2l_layer *layers, int n_layers, int B, int T,
                                       int Lmax, int dtype);
 int w2l_train_step(const w2l_layer *layers, int n_layers,
