@@ -280,13 +280,96 @@ __device__ __forceinline__ int ror_i(int x)
 // one half swap (v_permlane32_swap) adds the two.  Which lane a rotation or a swap delivers is not
 // assumed: the same operations are applied to the lane numbers first and the transition factors
 // are laid out to match.  All 64 lanes end a step with the new state of their class.
+// Two wavefronts share the work.  Wavefront 0 runs the recursion and touches no global memory: it
+// reads a frame's normalised emission factors from an LDS ring and leaves the new (linear) states
+// and the step's scaling exponent in another.  Wavefront 1 works one block of AHEAD frames ahead
+// and one behind: it loads the emission rows of the next block, takes their per-frame maximum and
+// exponentials, and turns the states of the previous block into the stored base-2 logs, the
+// double-precision row offsets and, at the last frame, the lattice's total.  One workgroup
+// barrier per block; both wavefronts pass the same number of them.
+struct FccRings {
+    float e[2][AHEAD][32];   // emission factors 2^(f log2 e - mx) of a block, by class
+    float n[2][AHEAD][32];   // states after each frame of a block, by class
+    float mx[4][AHEAD];      // per-frame maximum of the scaled emissions (kept until the block is written out)
+    int ex[2][AHEAD];        // exponent taken off the input states at each (even) step of a block
+};
 __device__ __forceinline__ void fcc_linear_rows(const float* __restrict__ em, const float* __restrict__ trans, int T, int dir,
                                                 float* __restrict__ lat, double* __restrict__ offs, double* term_out,
-                                                const AsgDims& d, float gmax)
+                                                const AsgDims& d, float gmax, FccRings& ring)
 {
-    const int lane = threadIdx.x & 63, ci = lane & 31;
+    const int lane = threadIdx.x & 63, ci = lane & 31, role = threadIdx.x >> 6;
     const bool real = ci < d.C, upper = lane >= 32;
     const float log2e = (float)LOG2E;
+    const int tblocks = (T + AHEAD - 1) / AHEAD;
+    auto frame = [&](int step) { return dir ? T - 1 - step : step; };
+    if (role == 1) {
+        // ---- wavefront 1: lanes 0..31 take the even frames of a block, lanes 32..63 the odd ones
+        const int cl = real ? ci : 0;
+        auto prepare = [&](int tb) {  // emission factors of block tb (frames past the end: the last frame again)
+            float s[AHEAD / 2];
+#pragma unroll
+            for (int q = 0; q < AHEAD / 2; ++q) {
+                const int step = tb * AHEAD + 2 * q + (upper ? 1 : 0);
+                s[q] = em[(size_t)frame(step < T ? step : T - 1) * d.C + cl];
+            }
+#pragma unroll
+            for (int q = 0; q < AHEAD / 2; ++q) {
+                const int k = 2 * q + (upper ? 1 : 0);
+                const float x = real ? s[q] * log2e : NEG;
+                float m = x;
+                m = fmaxf(m, dpp_f<0x111, 0xf>(m, m));  // row_shr:1
+                m = fmaxf(m, dpp_f<0x112, 0xf>(m, m));  // row_shr:2
+                m = fmaxf(m, dpp_f<0x114, 0xf>(m, m));  // row_shr:4
+                m = fmaxf(m, dpp_f<0x118, 0xf>(m, m));  // row_shr:8
+                m = fmaxf(m, dpp_f<0x142, 0xa>(m, m));  // row_bcast:15: lanes 31 and 63 hold the maximum of their half
+                const float m_lo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 31));
+                const float m_hi = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 63));
+                const float mk = upper ? m_hi : m_lo;
+                ring.e[tb & 1][k][ci] = fast_exp2(x - mk);
+                if (ci == 0) ring.mx[tb & 3][k] = mk;
+            }
+        };
+        double offset = 0;
+        const double gmax_d = (double)gmax;
+        auto write_out = [&](int tb) {  // rows and offsets of block tb
+            double off_k[AHEAD];
+#pragma unroll
+            for (int k = 0; k < AHEAD; ++k) {
+                const int step = tb * AHEAD + k;
+                const int ex = (k & 1) ? 0 : ring.ex[tb & 1][k];
+                offset += (double)ring.mx[tb & 3][k] + (step == 0 ? 0.0 : gmax_d + (double)ex);
+                off_k[k] = offset;
+            }
+#pragma unroll
+            for (int q = 0; q < AHEAD / 2; ++q) {
+                const int k = 2 * q + (upper ? 1 : 0), step = tb * AHEAD + k;
+                const float n = ring.n[tb & 1][k][ci];
+                const double off = upper ? off_k[2 * q + 1] : off_k[2 * q];
+                const size_t r = step < T ? (size_t)frame(step) : (size_t)d.Tp;  // frames past the end: the spare row
+                lat[r * CP + ci] = fmaxf(fast_log2(n), NEG);
+                offs[r] = off;
+                if (dir == 0) {  // FCC = log2 sum_i 2^(A_{T-1}[i])
+                    float sx = real ? n : 0.f;
+                    sx += dpp_f<0x111, 0xf>(0.f, sx);
+                    sx += dpp_f<0x112, 0xf>(0.f, sx);
+                    sx += dpp_f<0x114, 0xf>(0.f, sx);
+                    sx += dpp_f<0x118, 0xf>(0.f, sx);
+                    sx += dpp_f<0x142, 0xa>(0.f, sx);
+                    if (step == T - 1 && ci == 31) *term_out = (double)fast_log2(sx) + off;
+                }
+            }
+        };
+        prepare(0);
+        __syncthreads();
+        for (int tb = 0; tb < tblocks; ++tb) {
+            prepare(tb + 1);
+            if (tb > 0) write_out(tb - 1);
+            __syncthreads();
+        }
+        write_out(tblocks - 1);
+        return;
+    }
+    // ---- wavefront 0: the recursion
     // The row swap returns two registers.  Applied to the lane numbers it tells which of the two a
     // lane has to take: lanes 0..31 the one that still holds their own number, lanes 32..63 the one
     // that holds a lane of the other row.  (The half swap needs no such choice: the sum of its two
@@ -303,48 +386,17 @@ __device__ __forceinline__ void fcc_linear_rows(const float* __restrict__ em, co
     W2L_E(0) W2L_E(1) W2L_E(2) W2L_E(3) W2L_E(4) W2L_E(5) W2L_E(6) W2L_E(7)
     W2L_E(8) W2L_E(9) W2L_E(10) W2L_E(11) W2L_E(12) W2L_E(13) W2L_E(14) W2L_E(15)
 #undef W2L_E
-    auto frame = [&](int step) { return dir ? T - 1 - step : step; };
-    const int cl = real ? ci : 0;
-    float sc[AHEAD];
-#pragma unroll
-    for (int k = 0; k < AHEAD; ++k) sc[k] = em[(size_t)frame(k < T ? k : T - 1) * d.C + cl];
-    double offset = 0;
-    const int tblocks = (T + AHEAD - 1) / AHEAD;
-    const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)CP : CP;
-    const float* sptr = em + (size_t)frame(AHEAD - 1 < T ? AHEAD - 1 : T - 1) * d.C;
-    float* rptr = lat + (size_t)frame(0) * CP + ci;
-    float* const spare = lat + (size_t)d.Tp * CP + ci;
-    const double gmax_d = (double)gmax;
     float a = 0.f;
+    __syncthreads();
     for (int tb = 0; tb < tblocks; ++tb) {
-        // the block's 16 frames of scores at once: per-frame maximum (16 interleaved DPP reductions)
-        // and normalised emission factors; then the ring is refilled for the next block
-        float s2[AHEAD], mx[AHEAD];
-#pragma unroll
-        for (int k = 0; k < AHEAD; ++k) mx[k] = s2[k] = real ? sc[k] * log2e : NEG;
-#pragma unroll
-        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x111, 0xf>(mx[k], mx[k]));
-#pragma unroll
-        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x112, 0xf>(mx[k], mx[k]));
-#pragma unroll
-        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x114, 0xf>(mx[k], mx[k]));
-#pragma unroll
-        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x118, 0xf>(mx[k], mx[k]));
-#pragma unroll
-        for (int k = 0; k < AHEAD; ++k) mx[k] = fmaxf(mx[k], dpp_f<0x142, 0xa>(mx[k], mx[k]));
+        const float* eb = &ring.e[tb & 1][0][ci];
+        float* nb = &ring.n[tb & 1][0][ci];
+        int* xb = &ring.ex[tb & 1][0];
+        float e_next = eb[0];
 #pragma unroll
         for (int k = 0; k < AHEAD; ++k) {
-            mx[k] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx[k]), 31));  // lanes 0..31 hold every class
-            s2[k] = fast_exp2(s2[k] - mx[k]);  // e
-            const int step = tb * AHEAD + k;
-            sptr += (step + AHEAD < T) ? sstep : 0;
-            sc[k] = sptr[cl];
-        }
-#pragma unroll
-        for (int k = 0; k < AHEAD; ++k) {
-            const int step = tb * AHEAD + k;
-            float* const row = step < T ? rptr : spare;
-            rptr += rstep;
+            const float s2 = e_next;
+            if (k + 1 < AHEAD) e_next = eb[(k + 1) * 32];  // the next frame's factors, one step ahead
             // every second step: the exponent of the largest input state (0 for an all-zero input), folded
             // into the emission factor.  The five links of that reduction are dependent DPP instructions;
             // they are spread between the independent multiply-adds below, which cover their wait states.
@@ -375,28 +427,23 @@ __device__ __forceinline__ void fcc_linear_rows(const float* __restrict__ em, co
             W2L_FMAC_ROR(acc[3], x, E[15], 15);
             if (scale) W2L_MAX_LINK(mb, "row_bcast:15 row_mask:0xa");
             const int ex = scale ? __builtin_amdgcn_frexp_expf(__uint_as_float((unsigned)__builtin_amdgcn_readlane((int)mb, 31))) : 0;
-            const float e = scale ? __builtin_amdgcn_ldexpf(s2[k], -ex) : s2[k];
+            const float e = scale ? __builtin_amdgcn_ldexpf(s2, -ex) : s2;
+            if (scale) xb[k] = ex;  // every lane the same value to the same place
             const float part = (acc[0] + acc[1]) + (acc[2] + acc[3]);
             const auto o32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(part), __float_as_uint(part), false, false);
             const float raw = __uint_as_float(o32[0]) + __uint_as_float(o32[1]);  // lower half + upper half, in every lane
-            const float n = step == 0 ? s2[k] : e * raw;
-            offset += (double)mx[k] + (step == 0 ? 0.0 : gmax_d + (double)ex);
-            if (dir == 0 && step == T - 1) {  // FCC = log2 sum_i 2^(A_{T-1}[i])
-                const float sx = wave_sum_bcast(real && !upper ? n : 0.f);
-                if (lane == 0) *term_out = (double)fast_log2(sx) + offset;
-            }
+            const float n = (k == 0 && tb == 0) ? s2 : e * raw;
             a = n;
-            // both halves store the same values to the same places: no lane masking in the loop
-            *row = fmaxf(fast_log2(n), NEG);
-            offs[step < T ? frame(step) : d.Tp] = offset;
+            nb[k * 32] = n;  // both halves store the same values to the same places: no lane masking in the loop
         }
+        __syncthreads();
     }
 }
 
 template <int CMAX>
 __device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const float* __restrict__ trans, int T, int dir,
                                             float* __restrict__ lat, double* __restrict__ offs, double* term_out,
-                                            const AsgDims& d, float* abuf)
+                                            const AsgDims& d, float* abuf, FccRings& ring)
 {
     constexpr int LPC = CMAX <= 32 ? 2 : 1;  // lanes per class
     constexpr int NSRC = CMAX / LPC;         // source classes per lane
@@ -419,9 +466,10 @@ __device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const 
     gmin = wave_min_bcast(gmin);
     const bool linear = gmax - gmin <= LINEAR_RANGE;  // uniform (false also for NaN or infinite scores)
     if (CMAX <= 32 && linear) {
-        fcc_linear_rows(em, trans, T, dir, lat, offs, term_out, d, gmax);
+        fcc_linear_rows(em, trans, T, dir, lat, offs, term_out, d, gmax, ring);
         return;
     }
+    if (threadIdx.x >= 64) return;  // the other paths run on one wavefront
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
     const int cl = real ? ci : 0;
     float sc[AHEAD];
@@ -560,6 +608,7 @@ __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em
     __shared__ float xbuf[2][16][HALO_LANES][4];
     __shared__ float wmax[2][16];
     __shared__ __align__(16) float abuf[64];
+    __shared__ FccRings ring;
     __shared__ int bad;
     const int kind = blockIdx.x >> 1, dir = blockIdx.x & 1, b = blockIdx.y;
     const int tid = threadIdx.x, NT = blockDim.x;
@@ -592,9 +641,9 @@ __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em
         fal_lattice<PPT>(emb, trans, lab, T, L, dir, w.fal[dir] + (size_t)b * (d.Tp + 1) * d.Sp,
                          w.faloff[dir] + (size_t)b * (d.Tp + 1), w.terms + 2 * b + 1, d, xbuf, wmax);
     } else {
-        if (tid >= 64) return;
+        if (tid >= 128) return;  // two wavefronts: the recursion and its helper (the launch has at least two)
         fcc_lattice<CMAX>(emb, trans, T, dir, w.fcc[dir] + (size_t)b * (d.Tp + 1) * CP,
-                          w.fccoff[dir] + (size_t)b * (d.Tp + 1), w.terms + 2 * b, d, abuf);
+                          w.fccoff[dir] + (size_t)b * (d.Tp + 1), w.terms + 2 * b, d, abuf, ring);
     }
 }
 
@@ -928,8 +977,9 @@ extern "C" int w2l_asg_fwd_bwd(const float* emissions, const float* trans, const
     // one lane per target position, OWN_LANES of them per wavefront; more positions per lane only
     // when 16 wavefronts cannot cover Lmax
     const int ppt = Lmax <= 16 * OWN_LANES ? 1 : (Lmax <= 32 * OWN_LANES ? 2 : 4);
-    const int nt = 64 * (((Lmax + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);
+    int nt = 64 * (((Lmax + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);
     if (nt > 1024) return W2L_ERR_SHAPE;
+    if (nt < 128) nt = 128;  // the fully connected lattice runs on two wavefronts
     const dim3 g1(4, B), b1(nt);
     if (ppt == 1) launch_lattice<1>(C, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
     else if (ppt == 2) launch_lattice<2>(C, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
