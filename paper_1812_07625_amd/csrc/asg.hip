@@ -29,6 +29,7 @@
 //   4. asg_trans_utt: per utterance, FCC edge sums minus FAL edge sums as a C x C table (the FAL
 //      sums are scattered with 64-bit fixed-point integer atomics, which are order-independent).
 //   5. asg_trans_reduce: sum over utterances in a fixed order.
+#include <type_traits>
 #include "common.h"
 
 namespace w2l {
@@ -331,31 +332,41 @@ __device__ __forceinline__ void fcc_linear_rows(const float* __restrict__ em, co
         };
         double offset = 0;
         const double gmax_d = (double)gmax;
+        auto shr_d = [](double v, auto ctrl) {  // the value of the lane `n` to the left within a row of 16; 0 where there is none
+            constexpr int CTRL = decltype(ctrl)::value;
+            const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, true);
+            const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, true);
+            return __hiloint2double(hi, lo);
+        };
         auto write_out = [&](int tb) {  // rows and offsets of block tb
-            double off_k[AHEAD];
-#pragma unroll
-            for (int k = 0; k < AHEAD; ++k) {
-                const int step = tb * AHEAD + k;
-                const int ex = (k & 1) ? 0 : ring.ex[tb & 1][k];
-                offset += (double)ring.mx[tb & 3][k] + (step == 0 ? 0.0 : gmax_d + (double)ex);
-                off_k[k] = offset;
-            }
+            // offsets: lane k of every row of 16 lanes takes frame k's increment; an inclusive scan over the row
+            // (double precision) gives all 16 offsets at once, and lanes 0..15 store them
+            const int kk = lane & 15, step_k = tb * AHEAD + kk;
+            const int exk = (kk & 1) ? 0 : ring.ex[tb & 1][kk];
+            double run = (double)ring.mx[tb & 3][kk] + (step_k == 0 ? 0.0 : gmax_d + (double)exk);
+            run += shr_d(run, std::integral_constant<int, 0x111>{});  // row_shr:1
+            run += shr_d(run, std::integral_constant<int, 0x112>{});  // row_shr:2
+            run += shr_d(run, std::integral_constant<int, 0x114>{});  // row_shr:4
+            run += shr_d(run, std::integral_constant<int, 0x118>{});  // row_shr:8
+            const double off = offset + run;
+            if (lane < AHEAD) offs[step_k < T ? (size_t)frame(step_k) : (size_t)d.Tp] = off;  // frames past the end: the spare row
+            offset = __shfl(off, AHEAD - 1, 64);
+            const bool last = dir == 0 && tb == tblocks - 1;  // this block holds frame T-1: the lattice's total
+            const double off_last = last ? __shfl(off, (T - 1) - tb * AHEAD, 64) : 0.0;
 #pragma unroll
             for (int q = 0; q < AHEAD / 2; ++q) {
                 const int k = 2 * q + (upper ? 1 : 0), step = tb * AHEAD + k;
                 const float n = ring.n[tb & 1][k][ci];
-                const double off = upper ? off_k[2 * q + 1] : off_k[2 * q];
-                const size_t r = step < T ? (size_t)frame(step) : (size_t)d.Tp;  // frames past the end: the spare row
+                const size_t r = step < T ? (size_t)frame(step) : (size_t)d.Tp;
                 lat[r * CP + ci] = fmaxf(fast_log2(n), NEG);
-                offs[r] = off;
-                if (dir == 0) {  // FCC = log2 sum_i 2^(A_{T-1}[i])
+                if (last) {  // FCC = log2 sum_i 2^(A_{T-1}[i])
                     float sx = real ? n : 0.f;
                     sx += dpp_f<0x111, 0xf>(0.f, sx);
                     sx += dpp_f<0x112, 0xf>(0.f, sx);
                     sx += dpp_f<0x114, 0xf>(0.f, sx);
                     sx += dpp_f<0x118, 0xf>(0.f, sx);
-                    sx += dpp_f<0x142, 0xa>(0.f, sx);
-                    if (step == T - 1 && ci == 31) *term_out = (double)fast_log2(sx) + off;
+                    sx += dpp_f<0x142, 0xa>(0.f, sx);  // lanes 31 and 63: the sum over their half
+                    if (step == T - 1 && ci == 31) *term_out = (double)fast_log2(sx) + off_last;
                 }
             }
         };
