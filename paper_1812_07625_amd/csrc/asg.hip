@@ -41,8 +41,6 @@ constexpr float NEG = -1.0e30f;       // log zero: absorbs every finite addend, 
 constexpr float NEG_TEST = -1.0e29f;  // anything below is "log zero"
 constexpr int AHEAD = 16;             // frames of scores held in registers ahead of the recursion; period of the
                                       // hand-over between wavefronts and of the renormalisation
-constexpr int HALO_LANES = AHEAD;     // lanes of a wavefront that mirror the wavefront on its left
-constexpr int OWN_LANES = 64 - HALO_LANES;
 constexpr int CP = 64;                // pitch of an FCC lattice row; the class limit
 constexpr int GRAD_ROWS = 16;         // frames per asg_grad_em workgroup (4 per wavefront)
 constexpr int CHUNK = 32;             // frames per asg_trans_partial workgroup
@@ -124,15 +122,17 @@ __device__ __forceinline__ float wave_sum_bcast(float v)
 // Frame 0 comes out of the recursion itself: "before frame 0" all mass sits on a virtual
 // position -1 that can only advance (into position 0, at no cost).  Mirror lanes, score ring,
 // spare slots and renormalisation as described at the top of the file.
-template <int PPT>
+template <int PPT, int BLK, int NQ>
 __device__ __forceinline__ void fal_lattice(const float* __restrict__ em, const float* __restrict__ trans,
                                             const int* __restrict__ lab, int T, int L, int dir,
                                             float* __restrict__ lat, double* __restrict__ offs, double* term_out,
-                                            const AsgDims& d, float (*xbuf)[16][HALO_LANES][4], float (*wmax)[16])
+                                            const AsgDims& d, float (*xbuf)[16][AHEAD][4], float (*wmax)[16], float* tbl)
 {
+    constexpr int HALO = BLK, OWN = 64 - BLK;  // mirror lanes / owned lanes of a wavefront
+    constexpr int PITCH = BLK + 1;             // table entries per class (one of padding against bank conflicts)
     const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
-    const int gi = wave * OWN_LANES + lane - HALO_LANES;
-    const bool owner = lane >= HALO_LANES;
+    const int gi = wave * OWN + lane - HALO;
+    const bool owner = lane >= HALO;
     const float log2e = (float)LOG2E;
     int cls[PPT], slot[PPT];
     bool cnt[PPT];
@@ -156,60 +156,95 @@ __device__ __forceinline__ void fal_lattice(const float* __restrict__ em, const 
         a[j] = (i == -1) ? 0.f : NEG;
     }
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
-    float sl[PPT][AHEAD];
-#pragma unroll
-    for (int k = 0; k < AHEAD; ++k) {
-        const int f = frame(k < T ? k : T - 1);
-#pragma unroll
-        for (int j = 0; j < PPT; ++j) sl[j][k] = em[(size_t)f * d.C + cls[j]];
-    }
     double offset = 0;  // true log2 value = relative value + offset
     const int nwaves = NT >> 6;
-    const int tblocks = (T + AHEAD - 1) / AHEAD;
-    const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)d.Sp : d.Sp;
-    const float* sptr = em + (size_t)frame(AHEAD - 1 < T ? AHEAD - 1 : T - 1) * d.C;
+    const int tblocks = (T + BLK - 1) / BLK;
+    const long long rstep = dir ? -(long long)d.Sp : d.Sp;
     float* rptr = lat + (size_t)frame(0) * d.Sp;
     float* const spare = lat + (size_t)d.Tp * d.Sp;
 
-    for (int tb = 0; tb < tblocks; ++tb) {
+    // The emission rows of a block of BLK frames are staged in LDS by the whole workgroup (scaled to
+    // base-2 logs, class-major: a step's read is the lane's fixed address plus a constant), in two
+    // buffers; the rows are requested two blocks ahead and written to LDS at the block boundary, so
+    // the recursion itself issues no vector loads and never waits on the memory counter that its own
+    // lattice stores keep busy.  Element e of a block: step k = e / C, class c = e % C; in memory
+    // the rows of a block are adjacent (reversed for the backward direction); steps past the last
+    // frame are clamped to a valid address (what they read only feeds the spare row).
+    const int nel = BLK * d.C, per_buf = d.C * PITCH, last_el = T * d.C - 1;
+    int goff[NQ], loff[NQ];
+    float raw0[NQ], raw1[NQ];
 #pragma unroll
-        for (int k = 0; k < AHEAD; ++k) {
-            const int step = tb * AHEAD + k;
+    for (int q = 0; q < NQ; ++q) {
+        const int e = min(tid + q * NT, nel - 1);
+        const int k = e / d.C, c = e - k * d.C;
+        goff[q] = dir ? c - k * d.C : e;
+        loff[q] = (tid + q * NT < nel) ? c * PITCH + k : -1;
+    }
+    auto load_rows = [&](int tb, float (&raw)[NQ]) {
+        const int base = dir ? (T - 1 - tb * BLK) * d.C : tb * BLK * d.C;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) raw[q] = em[min(max(base + goff[q], 0), last_el)];
+    };
+    auto write_rows = [&](int buf, const float (&raw)[NQ]) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+            if (loff[q] >= 0) tbl[buf * per_buf + loff[q]] = raw[q] * log2e;
+    };
+    const float* tl[PPT];
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) tl[j] = tbl + cls[j] * PITCH;
+
+    auto block = [&](int tb, float (&next)[NQ], float (&load)[NQ]) {
+        const int cur = (tb & 1) * per_buf;
+        load_rows(tb + 2, load);
+        float sn[PPT];
+#pragma unroll
+        for (int j = 0; j < PPT; ++j) sn[j] = tl[j][cur];
+#pragma unroll
+        for (int k = 0; k < BLK; ++k) {
+            const int step = tb * BLK + k;
             float s[PPT];
 #pragma unroll
-            for (int j = 0; j < PPT; ++j) s[j] = sl[j][k];
-            sptr += (step + AHEAD < T) ? sstep : 0;  // refill this ring slot (past the end: the last frame again)
+            for (int j = 0; j < PPT; ++j) s[j] = sn[j];
+            if (k + 1 < BLK) {  // the next frame's scores, one step ahead
 #pragma unroll
-            for (int j = 0; j < PPT; ++j) sl[j][k] = sptr[cls[j]];
+                for (int j = 0; j < PPT; ++j) sn[j] = tl[j][cur + k + 1];
+            }
             float* const row = step < T ? rptr : spare;
             rptr += rstep;
             float carry = from_left_lane(a[PPT - 1], NEG);
 #pragma unroll
             for (int j = 0; j < PPT; ++j) {
                 const float o = a[j];
-                const float n = fmaf(s[j], log2e, lse2_log2(o + gs[j], carry + ga[j]));
+                const float n = s[j] + lse2_log2(o + gs[j], carry + ga[j]);
                 carry = o;
                 a[j] = n;
                 row[slot[j]] = n;
             }
         }
-        if (tid < AHEAD) {
-            const int step = tb * AHEAD + tid;
+        if (tid < BLK) {
+            const int step = tb * BLK + tid;
             offs[step < T ? frame(step) : d.Tp] = offset;
         }
+        // the rows in flight are not touched before the steps are done (tied to a value the last step produced)
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) asm volatile("" : "+v"(next[q]), "+v"(a[0]));
         // ---- block boundary: refresh the mirror lanes from the left neighbour, renormalise
         const int par = tb & 1;
         float m = NEG;
 #pragma unroll
         for (int j = 0; j < PPT; ++j) m = fmaxf(m, cnt[j] ? a[j] : NEG);
-        m = wave_max_f(m);
+        m = wave_max_bcast(m);
         if (nwaves > 1) {
             if (lane == 0) wmax[par][wave] = m;
-            if (lane >= OWN_LANES) {
+            if (lane >= OWN) {
 #pragma unroll
-                for (int j = 0; j < PPT; ++j) xbuf[par][wave][lane - OWN_LANES][j] = a[j];
+                for (int j = 0; j < PPT; ++j) xbuf[par][wave][lane - OWN][j] = a[j];
             }
-            __syncthreads();
+        }
+        write_rows((tb + 1) & 1, next);
+        __syncthreads();
+        if (nwaves > 1) {
             if (wave > 0 && !owner) {
 #pragma unroll
                 for (int j = 0; j < PPT; ++j) a[j] = xbuf[par][wave - 1][lane][j];
@@ -222,6 +257,14 @@ __device__ __forceinline__ void fal_lattice(const float* __restrict__ em, const 
             for (int j = 0; j < PPT; ++j) a[j] = a[j] > NEG_TEST ? a[j] - m : NEG;
             offset += (double)m;
         }
+    };
+    load_rows(0, raw0);
+    write_rows(0, raw0);
+    load_rows(1, raw1);
+    __syncthreads();
+    for (int tb = 0; tb < tblocks; tb += 2) {
+        block(tb, raw1, raw0);
+        if (tb + 1 < tblocks) block(tb + 1, raw0, raw1);
     }
     if (dir == 0) {  // FAL = a_{T-1}[L-1], read back from the stored row of the last frame
         __syncthreads();
@@ -611,12 +654,13 @@ __device__ __forceinline__ void fcc_lattice(const float* __restrict__ em, const 
 }
 
 // grid (4, B): x = 0/1 FAL forward/backward, 2/3 FCC forward/backward
-template <int PPT, int CMAX, int MAXT>
+template <int PPT, int CMAX, int MAXT, int BLK, int NQ>
 __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em, const float* __restrict__ trans,
                                                     const int* __restrict__ targets, const int* __restrict__ in_len,
                                                     const int* __restrict__ tgt_len, AsgWs w, AsgDims d)
 {
-    __shared__ float xbuf[2][16][HALO_LANES][4];
+    __shared__ float xbuf[2][16][AHEAD][4];
+    __shared__ float ftbl[2 * CP * (AHEAD + 1)];  // forced alignment: emission rows of two blocks of frames, class-major
     __shared__ float wmax[2][16];
     __shared__ __align__(16) float abuf[64];
     __shared__ FccRings ring;
@@ -649,8 +693,8 @@ __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em
     if (blockIdx.x == 0 && tid == 0) w.status[b] = 0;
     const float* emb = em + (size_t)b * d.Tp * d.C;
     if (kind == 0) {
-        fal_lattice<PPT>(emb, trans, lab, T, L, dir, w.fal[dir] + (size_t)b * (d.Tp + 1) * d.Sp,
-                         w.faloff[dir] + (size_t)b * (d.Tp + 1), w.terms + 2 * b + 1, d, xbuf, wmax);
+        fal_lattice<PPT, BLK, NQ>(emb, trans, lab, T, L, dir, w.fal[dir] + (size_t)b * (d.Tp + 1) * d.Sp,
+                                  w.faloff[dir] + (size_t)b * (d.Tp + 1), w.terms + 2 * b + 1, d, xbuf, wmax, ftbl);
     } else {
         if (tid >= 128) return;  // two wavefronts: the recursion and its helper (the launch has at least two)
         fcc_lattice<CMAX>(emb, trans, T, dir, w.fcc[dir] + (size_t)b * (d.Tp + 1) * CP,
@@ -911,18 +955,18 @@ WsLayout ws_layout(int B, int Tp, int C, int Lmax)
     return w;
 }
 
-template <int PPT>
-void launch_lattice(int cmax, dim3 grid, dim3 block, hipStream_t st, const float* em, const float* trans, const int* targets,
-                    const int* in_len, const int* tgt_len, const AsgWs& w, const AsgDims& d)
+template <int PPT, int MAXT, int BLK>
+void launch_lattice(int cmax, int nq, dim3 grid, dim3 block, hipStream_t st, const float* em, const float* trans,
+                    const int* targets, const int* in_len, const int* tgt_len, const AsgWs& w, const AsgDims& d)
 {
-    // the register budget follows the workgroup size: up to four wavefronts get a whole SIMD each
-    if (block.x <= 256) {
-        if (cmax <= 32) hipLaunchKernelGGL((asg_lattice<PPT, 32, 256>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d);
-        else hipLaunchKernelGGL((asg_lattice<PPT, 64, 256>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d);
+#define W2L_ASG_LAUNCH(C_, Q_) \
+    hipLaunchKernelGGL((asg_lattice<PPT, C_, MAXT, BLK, Q_>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d)
+    if (cmax <= 32) {
+        if (nq == 2) W2L_ASG_LAUNCH(32, 2); else W2L_ASG_LAUNCH(32, 8);
     } else {
-        if (cmax <= 32) hipLaunchKernelGGL((asg_lattice<PPT, 32, 1024>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d);
-        else hipLaunchKernelGGL((asg_lattice<PPT, 64, 1024>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d);
+        if (nq == 2) W2L_ASG_LAUNCH(64, 2); else W2L_ASG_LAUNCH(64, 8);
     }
+#undef W2L_ASG_LAUNCH
 }
 
 }  // namespace
@@ -985,16 +1029,28 @@ extern "C" int w2l_asg_fwd_bwd(const float* emissions, const float* trans, const
         hipError_t e = hipFuncSetAttribute((const void*)asg_grad_em, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_em);
         if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }
     }
-    // one lane per target position, OWN_LANES of them per wavefront; more positions per lane only
-    // when 16 wavefronts cannot cover Lmax
-    const int ppt = Lmax <= 16 * OWN_LANES ? 1 : (Lmax <= 32 * OWN_LANES ? 2 : 4);
-    int nt = 64 * (((Lmax + ppt - 1) / ppt + OWN_LANES - 1) / OWN_LANES);
+    // Forced alignment: one lane per PPT target positions, 64 - BLK of them per wavefront.  A step is bound by
+    // instruction issue, so a wavefront wants a SIMD of its own: the smallest PPT that fits four wavefronts, with
+    // blocks of 16 frames if that fits and of 12 (52 owned lanes) otherwise; longer targets take four positions
+    // per lane on as many wavefronts as they need.  (The register budget follows the workgroup size.)
+    int ppt = 4, blk = 16;
+    for (int p = 1; p <= 4; p *= 2) {
+        if (Lmax <= 4 * 48 * p) { ppt = p; blk = 16; break; }
+        if (Lmax <= 4 * 52 * p) { ppt = p; blk = 12; break; }
+    }
+    const int own = 64 - blk;
+    int nt = 64 * (((Lmax + ppt - 1) / ppt + own - 1) / own);
     if (nt > 1024) return W2L_ERR_SHAPE;
     if (nt < 128) nt = 128;  // the fully connected lattice runs on two wavefronts
+    const int nq = blk * C <= 2 * nt ? 2 : 8;  // emission-row elements a thread stages per block (blk * C <= 1024 <= 8 nt)
     const dim3 g1(4, B), b1(nt);
-    if (ppt == 1) launch_lattice<1>(C, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
-    else if (ppt == 2) launch_lattice<2>(C, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
-    else launch_lattice<4>(C, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    if (nt > 256) launch_lattice<4, 1024, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (ppt == 1 && blk == 16) launch_lattice<1, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (ppt == 1) launch_lattice<1, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (ppt == 2 && blk == 16) launch_lattice<2, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (ppt == 2) launch_lattice<2, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (blk == 16) launch_lattice<4, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else launch_lattice<4, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
     int rc = launch_status();
     if (rc) return rc;
     hipLaunchKernelGGL(asg_grad_em, dim3((Tp + GRAD_ROWS - 1) / GRAD_ROWS, B), dim3(256), lds_em, st, emissions, targets,

@@ -68,11 +68,13 @@ def check_asg(got, em, trans, targets, in_len, tgt_len, grad_scale=1.0):
     dict(B=3, T=97, in_lo=1, in_hi=97, l_lo=1, l_hi=2, Cc=5),
     dict(B=5, T=130, in_lo=100, in_hi=130, l_lo=20, l_hi=60, Cc=40, allow_repeats=True),  # more than 32 classes
     dict(B=3, T=90, in_lo=70, in_hi=90, l_lo=5, l_hi=30, Cc=64),          # the class limit
-    dict(B=2, T=300, in_lo=280, in_hi=300, l_lo=200, l_hi=250, Cc=40, allow_repeats=True),  # > 32 classes and > 4 wavefronts
+    dict(B=2, T=300, in_lo=280, in_hi=300, l_lo=210, l_hi=250, Cc=40, allow_repeats=True),  # > 32 classes, two positions per lane
     dict(B=2, T=50, in_lo=30, in_hi=50, l_lo=1, l_hi=9, Cc=1),            # a single class: loss = log(#alignments)
     dict(),                                                                 # the full benchmark shape
-    dict(B=2, T=900, in_lo=850, in_hi=900, l_lo=780, l_hi=840),           # > 768 positions: two per lane
-    dict(B=2, T=1700, in_lo=1650, in_hi=1700, l_lo=1540, l_hi=1600),      # > 1536 positions: four per lane
+    dict(B=2, T=450, in_lo=430, in_hi=450, l_lo=390, l_hi=416),           # two positions per lane, blocks of 12 frames
+    dict(B=2, T=700, in_lo=650, in_hi=700, l_lo=500, l_hi=600),           # four per lane, four wavefronts
+    dict(B=2, T=900, in_lo=850, in_hi=900, l_lo=780, l_hi=832),           # four per lane, blocks of 12 frames
+    dict(B=2, T=1700, in_lo=1650, in_hi=1700, l_lo=1540, l_hi=1600),      # four per lane on nine wavefronts
 ])
 def test_asg_matches_oracle(P, kw):
     cfg = W.asg_batch(seed=12, **kw)
