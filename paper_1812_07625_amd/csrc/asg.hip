@@ -15,13 +15,14 @@
 //      stored as base-2 logs, fp32, relative to a double-precision offset per frame; "log zero" is
 //      a large negative finite number.
 //      FAL: log domain (hardware exp2/log2), one lane per target position, the value of the
-//      position to the left by a DPP wavefront shift; wavefronts overlap by 16 mirrored positions
-//      so that nothing crosses a wavefront boundary inside a block of 16 frames, at whose end the
-//      largest state moves into the offset.
-//      FCC: one wavefront.  While the transition scores span at most LINEAR_RANGE bits the states
-//      are plain numbers and a step is a matrix-vector product with exact power-of-two rescaling
-//      (up to 32 classes: lane rotations and swaps only; up to 64: through a small LDS array);
-//      beyond that range a log-domain recursion with a full log-sum-exp per state takes over.
+//      position to the left by a DPP wavefront shift; wavefronts overlap by BLK mirrored positions
+//      so that nothing crosses a wavefront boundary inside a block of BLK frames (16 or 12), at
+//      whose end the largest state moves into the offset; the block's emission rows come from LDS.
+//      FCC: while the transition scores span at most LINEAR_RANGE bits the states are plain numbers
+//      and a step is a matrix-vector product with exact power-of-two rescaling (up to 32 classes:
+//      lane rotations and swaps only, on one wavefront, with a second wavefront doing all memory
+//      work and bookkeeping; up to 64: one wavefront, through a small LDS array); beyond that
+//      range a log-domain recursion with a full log-sum-exp per state takes over.
 //   2. asg_grad_em: per frame, node occupancies of both lattices, each normalised per frame;
 //      FAL positions are summed per class in a fixed order ((class, position) sort).
 //   3. asg_trans_partial: per (utterance, 32 frames), edge occupancies summed over the frames:
@@ -276,7 +277,7 @@ __device__ __forceinline__ void fal_lattice(const float* __restrict__ em, const 
     }
 }
 
-// ---- fully connected lattice, one direction, one wavefront.
+// ---- fully connected lattice, one direction (one wavefront; two in the rotation path further down).
 //   A_0[i] = f[0][i];  A_t[i] = f[t][i] + lse_j( A_{t-1}[j] + G[i][j] ),  G = g (forward) or g^T (backward)
 // Up to 32 classes: two lanes per class (lane = 2 * class + half), each taking half of the source
 // classes j, combined with one DPP lane swap; up to 64 classes: one lane per class.  A step
@@ -349,13 +350,14 @@ __device__ __forceinline__ void fcc_linear_rows(const float* __restrict__ em, co
     if (role == 1) {
         // ---- wavefront 1: lanes 0..31 take the even frames of a block, lanes 32..63 the odd ones
         const int cl = real ? ci : 0;
-        auto prepare = [&](int tb) {  // emission factors of block tb (frames past the end: the last frame again)
-            float s[AHEAD / 2];
+        auto request = [&](int tb, float (&s)[AHEAD / 2]) {  // emission rows of block tb (frames past the end: the last frame again)
 #pragma unroll
             for (int q = 0; q < AHEAD / 2; ++q) {
                 const int step = tb * AHEAD + 2 * q + (upper ? 1 : 0);
                 s[q] = em[(size_t)frame(step < T ? step : T - 1) * d.C + cl];
             }
+        };
+        auto prepare = [&](int tb, const float (&s)[AHEAD / 2]) {  // emission factors of block tb from its rows
 #pragma unroll
             for (int q = 0; q < AHEAD / 2; ++q) {
                 const int k = 2 * q + (upper ? 1 : 0);
@@ -413,12 +415,23 @@ __device__ __forceinline__ void fcc_linear_rows(const float* __restrict__ em, co
                 }
             }
         };
-        prepare(0);
+        // rows are requested two blocks before the recursion needs their factors: a block to arrive, a block to be worked on
+        float rows0[AHEAD / 2], rows1[AHEAD / 2];
+        request(0, rows0);
+        request(1, rows1);
+        prepare(0, rows0);
         __syncthreads();
-        for (int tb = 0; tb < tblocks; ++tb) {
-            prepare(tb + 1);
+        for (int tb = 0; tb < tblocks; tb += 2) {
+            request(tb + 2, rows0);
+            prepare(tb + 1, rows1);
             if (tb > 0) write_out(tb - 1);
             __syncthreads();
+            if (tb + 1 < tblocks) {
+                request(tb + 3, rows1);
+                prepare(tb + 2, rows0);
+                write_out(tb);
+                __syncthreads();
+            }
         }
         write_out(tblocks - 1);
         return;
