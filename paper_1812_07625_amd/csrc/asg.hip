@@ -43,7 +43,7 @@ constexpr float NEG_TEST = -1.0e29f;  // anything below is "log zero"
 constexpr int AHEAD = 16;             // frames of scores held in registers ahead of the recursion; period of the
                                       // hand-over between wavefronts and of the renormalisation
 constexpr int CP = 64;                // pitch of an FCC lattice row; the class limit
-constexpr int GRAD_ROWS = 16;         // frames per asg_grad_em workgroup (4 per wavefront)
+constexpr int GRAD_UNROLL = 4;        // target positions per lane whose loads asg_grad_em issues together
 constexpr int CHUNK = 32;             // frames per asg_trans_partial workgroup
 
 struct AsgDims {
@@ -60,6 +60,7 @@ struct AsgWs {
     int* status;                     // [B]: 0 live, 1 no alignment, 2 invalid
     float *izf, *iza;                // [B][Tp] inverse per-frame normalisers of the node occupancies
     float *partF, *partA, *tabD;     // [B][nch][C*C], [B][nch][2][Lmax], [B][C*C] (per-utterance d loss / d g)
+    int *order, *cstart;             // [B][Lmax] target positions sorted by (class, position); [B][C+1] start of every class in it
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -704,6 +705,29 @@ __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em
         return;
     }
     if (blockIdx.x == 0 && tid == 0) w.status[b] = 0;
+    if (kind == 2) {
+        // fifth workgroup of the utterance, beside the four recursions: the target positions sorted by
+        // (class, position) and the start of every class in that order -- the fixed summation order of
+        // the emission-gradient kernel.  A plain rank count (no atomics): position i goes to
+        // #{j : y_j < y_i} + #{j < i : y_j = y_i}.
+        int* ord = w.order + (size_t)b * d.Lmax;
+        int* cst = w.cstart + (size_t)b * (d.C + 1);
+        for (int i = tid; i < L; i += NT) {
+            const int c = lab[i];
+            int r = 0;
+            for (int j = 0; j < L; ++j) {
+                const int l = lab[j];
+                r += (l < c || (l == c && j < i)) ? 1 : 0;
+            }
+            ord[r] = i;
+        }
+        for (int c = tid; c <= d.C; c += NT) {
+            int r = 0;
+            for (int j = 0; j < L; ++j) r += lab[j] < c ? 1 : 0;
+            cst[c] = r;
+        }
+        return;
+    }
     const float* emb = em + (size_t)b * d.Tp * d.C;
     if (kind == 0) {
         fal_lattice<PPT, BLK, NQ>(emb, trans, lab, T, L, dir, w.fal[dir] + (size_t)b * (d.Tp + 1) * d.Sp,
@@ -715,15 +739,15 @@ __global__ __launch_bounds__(MAXT) void asg_lattice(const float* __restrict__ em
     }
 }
 
-// Node occupancies and the loss.  One workgroup per (16 frames, utterance), one wavefront per frame.
+// Node occupancies and the loss.  One wavefront per frame; a workgroup of 4 wavefronts takes `rows_per_wg` consecutive frames of one utterance.
 //   grad_em[t][c] = grad_scale * ( P_fcc(pi_t = c) - P_fal(pi_t = c) )
 __global__ __launch_bounds__(256) void asg_grad_em(const float* __restrict__ em, const int* __restrict__ targets,
                                                    const int* __restrict__ in_len, const int* __restrict__ tgt_len,
                                                    float* __restrict__ loss, float* __restrict__ grad, AsgWs w, AsgDims d,
-                                                   float grad_scale)
+                                                   int rows_per_wg, float grad_scale)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    const int b = blockIdx.y, t0 = blockIdx.x * GRAD_ROWS;
+    const int b = blockIdx.y, t0 = blockIdx.x * rows_per_wg;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float* gb = grad + (size_t)b * d.Tp * d.C;
     const int status = w.status[b];
@@ -731,11 +755,9 @@ __global__ __launch_bounds__(256) void asg_grad_em(const float* __restrict__ em,
     const double fcc2 = w.terms[2 * b], fal2 = w.terms[2 * b + 1];
     if (blockIdx.x == 0 && tid == 0)
         loss[b] = status == 2 ? NAN : (status == 1 ? INFINITY : (float)((fcc2 - fal2) * LN2));
-    if (status != 0 || T <= 0) {
-        for (int e = tid; e < GRAD_ROWS * d.C; e += 256) {
-            const int t = t0 + e / d.C;
-            if (t < d.Tp) gb[(size_t)t0 * d.C + e] = 0.f;
-        }
+    const int t_end = min(t0 + rows_per_wg, d.Tp);
+    if (status != 0 || t0 >= T) {
+        for (int e = t0 * d.C + tid; e < t_end * d.C; e += 256) gb[e] = 0.f;
         return;
     }
     const int L = tgt_len[b];
@@ -743,27 +765,16 @@ __global__ __launch_bounds__(256) void asg_grad_em(const float* __restrict__ em,
     int* order = lab + d.Lmax;                    // [Lmax] positions sorted by (class, position)
     int* cstart = order + d.Lmax;                 // [C+1]
     float* ebuf = reinterpret_cast<float*>(cstart + d.C + 1) + (size_t)wave * d.Sp;  // [4][Sp]
-    for (int i = tid; i < L; i += 256) lab[i] = targets[(size_t)b * d.Lmax + i];
-    for (int c = tid; c <= d.C; c += 256) cstart[c] = 0;
-    __syncthreads();
-    for (int i = tid; i < L; i += 256) atomicAdd(&cstart[lab[i] + 1], 1);  // integer: order-independent
-    __syncthreads();
-    if (tid == 0)
-        for (int c = 0; c < d.C; ++c) cstart[c + 1] += cstart[c];
-    __syncthreads();
     for (int i = tid; i < L; i += 256) {
-        const int c = lab[i];
-        int r = cstart[c];
-        for (int j = 0; j < i; ++j) r += (lab[j] == c);
-        order[r] = i;
+        lab[i] = targets[(size_t)b * d.Lmax + i];
+        order[i] = w.order[(size_t)b * d.Lmax + i];
     }
+    for (int c = tid; c <= d.C; c += 256) cstart[c] = w.cstart[(size_t)b * (d.C + 1) + c];
     __syncthreads();
 
     const float log2e = (float)LOG2E;
     const size_t rowb = (size_t)b * (d.Tp + 1);
-    for (int rr = wave; rr < GRAD_ROWS; rr += 4) {
-        const int t = t0 + rr;
-        if (t >= d.Tp) break;
+    for (int t = t0 + wave; t < t_end; t += 4) {
         float* grow = gb + (size_t)t * d.C;
         if (t >= T) {
             for (int c = lane; c < d.C; c += 64) grow[c] = 0.f;
@@ -777,20 +788,34 @@ __global__ __launch_bounds__(256) void asg_grad_em(const float* __restrict__ em,
             const float av = w.fcc[0][(rowb + t) * CP + lane], bv = w.fcc[1][(rowb + t) * CP + lane];
             if (av > NEG_TEST && bv > NEG_TEST) pf = fast_exp2((av + bv) + (shiftF - erow[lane] * log2e));
         }
-        const float zf = wave_sum_f(pf);
-        // forced alignment: lanes stride over the positions (backward rows are stored in reversed order)
+        const float zf = wave_sum_bcast(pf);
+        // forced alignment: lanes stride over the positions (backward rows are stored in reversed order);
+        // the loads of GRAD_UNROLL positions per lane are issued together
         const float shiftA = (float)(w.faloff[0][rowb + t] + w.faloff[1][rowb + t] - fal2);
         const float* ar = w.fal[0] + (rowb + t) * d.Sp;
         const float* br = w.fal[1] + (rowb + t) * d.Sp;
         float za = 0.f;
-        for (int s = lane; s < L; s += 64) {
-            const float av = ar[s], bv = br[L - 1 - s];
-            float e = 0.f;
-            if (av > NEG_TEST && bv > NEG_TEST) e = fast_exp2((av + bv) + (shiftA - erow[lab[s]] * log2e));
-            ebuf[s] = e;
-            za += e;
+        for (int s0 = lane; s0 < L; s0 += 64 * GRAD_UNROLL) {
+            float av[GRAD_UNROLL], bv[GRAD_UNROLL], sc[GRAD_UNROLL];
+#pragma unroll
+            for (int u = 0; u < GRAD_UNROLL; ++u) {
+                const int sidx = min(s0 + 64 * u, L - 1);  // clamped lanes repeat a valid position and are dropped below
+                av[u] = ar[sidx];
+                bv[u] = br[L - 1 - sidx];
+                sc[u] = erow[lab[sidx]];
+            }
+#pragma unroll
+            for (int u = 0; u < GRAD_UNROLL; ++u) {
+                const int sidx = s0 + 64 * u;
+                float e = 0.f;
+                if (av[u] > NEG_TEST && bv[u] > NEG_TEST) e = fast_exp2((av[u] + bv[u]) + (shiftA - sc[u] * log2e));
+                if (sidx < L) {
+                    ebuf[sidx] = e;
+                    za += e;
+                }
+            }
         }
-        za = wave_sum_f(za);
+        za = wave_sum_bcast(za);
         const float izf = zf > 0.f ? 1.f / zf : 0.f, iza = za > 0.f ? 1.f / za : 0.f;
         if (lane == 0) {
             w.izf[(size_t)b * d.Tp + t] = izf;
@@ -946,7 +971,7 @@ __global__ __launch_bounds__(64) void asg_trans_reduce(float* __restrict__ grad_
     grad_trans[p] = grad_scale * acc;
 }
 
-struct WsLayout { size_t fal[2], fcc[2], faloff[2], fccoff[2], terms, status, izf, iza, partF, partA, tabD, total; };
+struct WsLayout { size_t fal[2], fcc[2], faloff[2], fccoff[2], terms, status, izf, iza, partF, partA, tabD, order, cstart, total; };
 WsLayout ws_layout(int B, int Tp, int C, int Lmax)
 {
     WsLayout w;
@@ -964,6 +989,8 @@ WsLayout ws_layout(int B, int Tp, int C, int Lmax)
     w.partF = off; off += round_up((size_t)B * nch * C * C * 4, 256);
     w.partA = off; off += round_up((size_t)B * nch * 2 * Lmax * 4, 256);
     w.tabD = off; off += round_up((size_t)B * C * C * 4, 256);
+    w.order = off; off += round_up((size_t)B * Lmax * 4, 256);
+    w.cstart = off; off += round_up((size_t)B * (C + 1) * 4, 256);
     w.total = off;
     return w;
 }
@@ -1034,6 +1061,8 @@ extern "C" int w2l_asg_fwd_bwd(const float* emissions, const float* trans, const
     w.partF = reinterpret_cast<float*>(ws + l.partF);
     w.partA = reinterpret_cast<float*>(ws + l.partA);
     w.tabD = reinterpret_cast<float*>(ws + l.tabD);
+    w.order = reinterpret_cast<int*>(ws + l.order);
+    w.cstart = reinterpret_cast<int*>(ws + l.cstart);
 
     const size_t lds_em = (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (Lmax + 4);
     const size_t lds_tab = (size_t)8 * C * C;
@@ -1056,7 +1085,7 @@ extern "C" int w2l_asg_fwd_bwd(const float* emissions, const float* trans, const
     if (nt > 1024) return W2L_ERR_SHAPE;
     if (nt < 128) nt = 128;  // the fully connected lattice runs on two wavefronts
     const int nq = blk * C <= 2 * nt ? 2 : 8;  // emission-row elements a thread stages per block (blk * C <= 1024 <= 8 nt)
-    const dim3 g1(4, B), b1(nt);
+    const dim3 g1(5, B), b1(nt);  // four recursions and the sort of the target
     if (nt > 256) launch_lattice<4, 1024, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
     else if (ppt == 1 && blk == 16) launch_lattice<1, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
     else if (ppt == 1) launch_lattice<1, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
@@ -1066,8 +1095,11 @@ extern "C" int w2l_asg_fwd_bwd(const float* emissions, const float* trans, const
     else launch_lattice<4, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
     int rc = launch_status();
     if (rc) return rc;
-    hipLaunchKernelGGL(asg_grad_em, dim3((Tp + GRAD_ROWS - 1) / GRAD_ROWS, B), dim3(256), lds_em, st, emissions, targets,
-                       in_len, tgt_len, loss, grad_emissions, w, d, grad_scale);
+    // frames per emission-gradient workgroup: one per wavefront while the per-workgroup copy of the target's
+    // sort (2 Lmax + C + 1 integers) is small beside the frames' own lattice rows, more otherwise
+    const int rows_per_wg = (2 * Lmax + C + 1 <= 1024) ? 4 : 16;
+    hipLaunchKernelGGL(asg_grad_em, dim3((Tp + rows_per_wg - 1) / rows_per_wg, B), dim3(256), lds_em, st, emissions, targets,
+                       in_len, tgt_len, loss, grad_emissions, w, d, rows_per_wg, grad_scale);
     rc = launch_status();
     if (rc || !grad_trans) return rc;
     hipLaunchKernelGGL(asg_trans_partial, dim3(d.nch, B), dim3(256), 0, st, trans, targets, in_len, tgt_len, w, d);
