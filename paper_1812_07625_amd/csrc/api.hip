@@ -67,19 +67,25 @@ size_t conv_wgrad_scratch_bytes(int Cin, int Cout, int k)
     return round_up((size_t)DBIAS_CHUNKS * Cout * 4, 256) + conv_wgrad_skinny_scratch(Cin, Cout, k);
 }
 
+bool conv_wgrad_fuses_dbias(const ConvDesc& d, int dt, int dydt)
+{
+    return d.Cout > 32 && dt == W2L_BF16 && dydt == W2L_BF16 && conv_wgrad_mfma_takes_dbias(d);
+}
+
 int conv_wgrad(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int dt, int dydt,
                int accumulate, void* scratch, hipStream_t st)
 {
     float* dbias_scratch = static_cast<float*>(scratch);
     float* skinny_scratch =
         reinterpret_cast<float*>(static_cast<unsigned char*>(scratch) + round_up((size_t)DBIAS_CHUNKS * d.Cout * 4, 256));
+    if (dbias && conv_wgrad_fuses_dbias(d, dt, dydt)) return conv_wgrad_mfma(d, x, dy, dw, dbias, accumulate, st);
     if (dbias) {
         // halo frames hold zeros, so summing every frame of the allocation is the same sum
         const int rc = dbias_reduce(dy, dbias, (long long)d.B * d.y_pitch, d.Cout, dydt, accumulate, dbias_scratch, st);
         if (rc) return rc;
     }
     if (d.Cout <= 32) return conv_wgrad_skinny(d, x, dy, dw, dt, dydt, accumulate, skinny_scratch, st);
-    if (dt == W2L_BF16 && dydt == W2L_BF16 && conv_wgrad_mfma_ok(d)) return conv_wgrad_mfma(d, x, dy, dw, accumulate, st);
+    if (dt == W2L_BF16 && dydt == W2L_BF16 && conv_wgrad_mfma_ok(d)) return conv_wgrad_mfma(d, x, dy, dw, nullptr, accumulate, st);
     return conv_wgrad_generic(d, x, dy, dw, dt, dydt, accumulate, st);
 }
 

@@ -81,6 +81,8 @@ int conv_dgrad(const ConvDesc& d, const void* dy, const void* w, void* dx, int d
 size_t conv_dgrad_scratch_bytes(const ConvDesc& d);
 // scratch: conv_wgrad_scratch_bytes() bytes of device memory
 size_t conv_wgrad_scratch_bytes(int Cin, int Cout, int k);
+// true where conv_wgrad() produces dbias inside the weight-gradient launch (no separate column-sum kernels)
+bool conv_wgrad_fuses_dbias(const ConvDesc& d, int dt, int dydt);
 int conv_wgrad(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int dt, int dydt,
                int accumulate, void* scratch, hipStream_t st);
 
@@ -120,7 +122,9 @@ int conv_dgrad_glu(const ConvDesc& d, const void* dy, const void* w, const void*
                    size_t scratch_bytes, hipStream_t st);
 bool dgrad_split_ok(const ConvDesc& d);
 bool conv_wgrad_mfma_ok(const ConvDesc& d);
-int conv_wgrad_mfma(const ConvDesc& d, const void* x, const void* dy, float* dw, int accumulate, hipStream_t st);
+// dbias (nullable): only where conv_wgrad_mfma_takes_dbias(d) -- the bias gradient comes out of the same launch
+bool conv_wgrad_mfma_takes_dbias(const ConvDesc& d);
+int conv_wgrad_mfma(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int accumulate, hipStream_t st);
 
 // GLU with an explicit output layout (elementwise.hip).  y (and dh) are dense [B*Tp, Cout]
 // ([B*Tp, Cout/2]); the output is written with the given pitch and halo, halo and slack

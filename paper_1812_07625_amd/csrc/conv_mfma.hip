@@ -52,6 +52,9 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
 
 __device__ __align__(16) unsigned int g_zero16[4];  // source of every out-of-range chunk
+// A row (1, 0, 0, ...) in bf16: the second operand of the weight gradient's extra column tile, whose first
+// column is the bias gradient (sum of dy over the frames); every reduction row of that tile reads this row.
+__device__ __align__(16) const unsigned short g_one_then_zeros[256] = {0x3F80};
 
 typedef ConvDesc ConvGeom;
 
@@ -1126,9 +1129,12 @@ __global__ __launch_bounds__(256) void zero_rows_k(bf16_t* __restrict__ p, long 
 // reduction runs straight through the frames of all utterances including the halo frames
 // between them -- dy is zero there, so they add nothing -- which makes every panel a dense
 // block of BKT consecutive frames of both tensors.
+// FAST with dbias != nullptr: the grid has one more column of tiles.  Its second operand is the constant
+// row (1, 0, 0, ...) for every frame, so its first output column is sum_t dy[t, co] -- the bias
+// gradient -- computed by the same pipeline with the same loads per phase, in a fixed order.
 template <int BM, int BN, int BKT, int STAGES, int KG, int GN, bool FAST>
 __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
-                                                   float* __restrict__ dw, ConvGeom g, int accumulate)
+                                                   float* __restrict__ dw, float* __restrict__ dbias, ConvGeom g, int accumulate)
 {
     using PA = PanelMN<BM, BKT, 4 * KG * GN>;
     using PB = PanelMN<BN, BKT, 4 * KG * GN>;
@@ -1136,18 +1142,24 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __re
     constexpr int STAGE = PA::BYTES + PB::BYTES;
     static_assert(KG == 1 || BM * BN * 4 <= STAGES * STAGE, "the group reduction reuses the panel ring");
     const int M = g.Cout, N = g.k * g.Cin;
+    const int tiles_n = (N + BN - 1) / BN;
+    const bool with_bias = FAST && dbias != nullptr;
     int tm, tn;
-    tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
+    tile_of_block((M + BM - 1) / BM, tiles_n + (with_bias ? 1 : 0), tm, tn);
+    const bool bias_tile = with_bias && tn == tiles_n;  // uniform over the workgroup
     const int m0 = tm * BM, n0 = tn * BN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = wave >> 2, w4 = wave & 3, wm = w4 >> 1;
     const int kg = (KG == 2) ? grp : 0, wn = (GN == 2 ? 2 * grp : 0) + (w4 & 1);
+    const bf16_t* const ones = reinterpret_cast<const bf16_t*>(g_one_then_zeros);
+    static_assert(BN <= 256, "the constant row covers one tile width");
 
     PA pa;
     PB pb;
     if (FAST) {
         pa.init_fast(dy, g.Cout, M - m0);
-        pb.init_fast(x, g.Cin, N - n0);
+        if (bias_tile) pb.init_fast(ones, 0, BN);  // row pitch 0: every reduction row is the same row
+        else pb.init_fast(x, g.Cin, N - n0);
     } else {
         pa.init(dy);
         pb.init(x);
@@ -1163,7 +1175,7 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __re
             if (FAST) {
                 const long long f0 = (long long)(st < nsteps ? st : nsteps - 1) * BKT;
                 if (i < PA::NI) pa.issue_fast(i, dy + (g.y_halo + f0) * g.Cout + m0, dst);
-                else pb.issue_fast(i - PA::NI, x + (g.x_halo - g.p + f0) * g.Cin + n0, dst + PA::BYTES);
+                else pb.issue_fast(i - PA::NI, bias_tile ? ones : x + (g.x_halo - g.p + f0) * g.Cin + n0, dst + PA::BYTES);
                 return;
             }
             const int b = st / spb, tp0 = (st - b * spb) * BKT;
@@ -1196,6 +1208,13 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __re
         grp, kg, wm, wn, lane);
     core.reduce_groups(lds, kg, w4, lane);
     if (kg != 0) return;
+    if (bias_tile) {
+        core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
+            const int m = m0 + mm;
+            if (nn == 0 && m < M) dbias[m] = accumulate ? dbias[m] + v : v;
+        });
+        return;
+    }
     core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
         const int m = m0 + mm, n = n0 + nn;
         if (m < M && n < N) {
@@ -1451,21 +1470,30 @@ bool conv_wgrad_mfma_ok(const ConvDesc& d)
     return common_ok(d) && d.Cout >= 64 && (long long)d.k * d.Cin >= 64;
 }
 
-int conv_wgrad_mfma(const ConvDesc& g, const void* x, const void* dy, float* dw, int accumulate, hipStream_t st)
+// FAST walks the frames of both tensors in lock step and over-reads up to 64 + p frames
+static bool wgrad_fast(const ConvDesc& g)
+{
+    return g.s == 1 && g.x_pitch == g.y_pitch && g.x_halo == g.y_halo && g.x_halo >= g.p && g.slack >= 64 &&
+           (g.B == 1 || g.x_halo > 0 || g.p == 0);
+}
+
+bool conv_wgrad_mfma_takes_dbias(const ConvDesc& d) { return conv_wgrad_mfma_ok(d) && wgrad_fast(d); }
+
+int conv_wgrad_mfma(const ConvDesc& g, const void* x, const void* dy, float* dw, float* dbias, int accumulate, hipStream_t st)
 {
     const long long M = g.Cout, N = (long long)g.k * g.Cin;
     const TileChoice tc = choose_tile(M, N);
-    // FAST walks the frames of both tensors in lock step and over-reads up to 64 + p frames
-    const bool fast = g.s == 1 && g.x_pitch == g.y_pitch && g.x_halo == g.y_halo && g.x_halo >= g.p && g.slack >= 64 &&
-                      (g.B == 1 || g.x_halo > 0 || g.p == 0);
+    const bool fast = wgrad_fast(g);
+    if (dbias && !fast) return W2L_ERR_SHAPE;  // callers ask conv_wgrad_mfma_takes_dbias() first
+    const long long extra = dbias ? 1 : 0;     // the column of tiles that yields the bias gradient
     int rc = W2L_OK;
 #define CALL(BM_, BN_, BK_, ST_, KG_, GN_)                                                                     \
     {                                                                                                     \
         constexpr int bytes = ST_ * (BM_ + BN_) * BK_ * 2;                                                \
         const unsigned nthreads = 256 * KG_ * GN_;                                                              \
-        const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_));                  \
-        if (fast) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, true>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate) \
-        else LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, g, accumulate)     \
+        const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_ + extra));          \
+        if (fast) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, true>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, dbias, g, accumulate) \
+        else LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, (float*)nullptr, g, accumulate) \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL

@@ -274,12 +274,14 @@ static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers,
                 return W2L_ERR_LAUNCH;
         }
         const void* xin = (i == 0) ? x : (const void*)(ws + p.post[i - 1]);
-        // weight gradient on the side stream; the (small, bandwidth-bound) bias gradient stays on
-        // the main stream, which has the shorter chain
-        rc = conv_wgrad(d, xin, dy, dweights[i], side ? nullptr : dbiases[i], dtype, dy_dt, 0, ws + p.conv, wst);
+        // weight gradient on the side stream.  Where the MFMA kernel takes it, the bias gradient is one more
+        // column of tiles of the same launch; otherwise it is a (small, bandwidth-bound) column sum that stays
+        // on the main stream, which has the shorter chain
+        const bool fused_dbias = dbiases[i] && conv_wgrad_fuses_dbias(d, dtype, dy_dt);
+        rc = conv_wgrad(d, xin, dy, dweights[i], (fused_dbias || !side) ? dbiases[i] : nullptr, dtype, dy_dt, 0, ws + p.conv, wst);
         if (rc) return rc;
         if (on_side && !hip_ok(hipEventRecord(side->done[i], wst))) return W2L_ERR_LAUNCH;
-        if (side && dbiases[i]) {
+        if (side && dbiases[i] && !fused_dbias) {
             // halo frames hold zeros, so summing every frame of the allocation is the same sum
             rc = dbias_reduce(dy, dbiases[i], (long long)d.B * d.y_pitch, d.Cout, dy_dt, 0,
                               reinterpret_cast<float*>(ws + p.dbias), st);
