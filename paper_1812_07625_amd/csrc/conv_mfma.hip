@@ -1132,10 +1132,11 @@ __global__ __launch_bounds__(256) void zero_rows_k(bf16_t* __restrict__ p, long 
 // FAST with dbias != nullptr: the grid has one more column of tiles.  Its second operand is the constant
 // row (1, 0, 0, ...) for every frame, so its first output column is sum_t dy[t, co] -- the bias
 // gradient -- computed by the same pipeline with the same loads per phase, in a fixed order.
-template <int BM, int BN, int BKT, int STAGES, int KG, int GN, bool FAST>
+template <int BM, int BN, int BKT, int STAGES, int KG, int GN, bool FAST, bool BIAS>
 __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
                                                    float* __restrict__ dw, float* __restrict__ dbias, ConvGeom g, int accumulate)
 {
+    static_assert(FAST || !BIAS, "the bias column rides on the dense walk through the frames");
     using PA = PanelMN<BM, BKT, 4 * KG * GN>;
     using PB = PanelMN<BN, BKT, 4 * KG * GN>;
     extern __shared__ __align__(1024) unsigned char lds[];
@@ -1143,10 +1144,9 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __re
     static_assert(KG == 1 || BM * BN * 4 <= STAGES * STAGE, "the group reduction reuses the panel ring");
     const int M = g.Cout, N = g.k * g.Cin;
     const int tiles_n = (N + BN - 1) / BN;
-    const bool with_bias = FAST && dbias != nullptr;
     int tm, tn;
-    tile_of_block((M + BM - 1) / BM, tiles_n + (with_bias ? 1 : 0), tm, tn);
-    const bool bias_tile = with_bias && tn == tiles_n;  // uniform over the workgroup
+    tile_of_block((M + BM - 1) / BM, tiles_n + (BIAS ? 1 : 0), tm, tn);
+    const bool bias_tile = BIAS && tn == tiles_n;  // uniform over the workgroup
     const int m0 = tm * BM, n0 = tn * BN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = wave >> 2, w4 = wave & 3, wm = w4 >> 1;
@@ -1492,8 +1492,9 @@ int conv_wgrad_mfma(const ConvDesc& g, const void* x, const void* dy, float* dw,
         constexpr int bytes = ST_ * (BM_ + BN_) * BK_ * 2;                                                \
         const unsigned nthreads = 256 * KG_ * GN_;                                                              \
         const unsigned grid = (unsigned)(((M + BM_ - 1) / BM_) * ((N + BN_ - 1) / BN_ + extra));          \
-        if (fast) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, true>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, dbias, g, accumulate) \
-        else LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, (float*)nullptr, g, accumulate) \
+        if (fast && dbias) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, true, true>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, dbias, g, accumulate) \
+        else if (fast) LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, true, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, (float*)nullptr, g, accumulate) \
+        else LAUNCH((conv_wgrad_k<BM_, BN_, BK_, ST_, KG_, GN_, false, false>), bytes, (const bf16_t*)x, (const bf16_t*)dy, dw, (float*)nullptr, g, accumulate) \
     }
     W2L_TILE_DISPATCH(CALL)
 #undef CALL
