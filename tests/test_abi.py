@@ -69,6 +69,10 @@ def test_host_side_argument_checks():
     assert r.w2l_ctc_fwd_bwd(fake, 0, fake, fake, fake, fake, fake, 2, 10, 5, 3, 0, 1.0, NULL, 0, NULL) == -5
     assert r.w2l_ctc_fwd_bwd(fake, 0, fake, fake, fake, fake, fake, 2, 10, 5, 3, 0, 1.0, 0x1100, 16, NULL) == -5
     assert r.w2l_ctc_workspace_bytes(2, 10, 5, 3) >= 2 * 2 * 10 * 7 * 8
+    # size limits: frames (integer state exponents), labels, classes
+    assert r.w2l_ctc_fwd_bwd(fake, 0, fake, fake, fake, fake, fake, 2, 8193, 5, 3, 0, 1.0, 0x1100, 1 << 40, NULL) == -2
+    assert r.w2l_ctc_fwd_bwd(fake, 0, fake, fake, fake, fake, fake, 2, 10, 5, 3001, 0, 1.0, 0x1100, 1 << 40, NULL) == -2
+    assert r.w2l_ctc_fwd_bwd(fake, 0, fake, fake, fake, fake, fake, 2, 10, 4097, 3, 0, 1.0, 0x1100, 1 << 40, NULL) == -2
 
 
 def test_ctc_host_validation():
