@@ -158,6 +158,23 @@ int w2l_ctc_fwd_bwd(const float *input, int is_logits, const int *targets, const
                     const int *tgt_len, float *loss, float *grad,
                     int B, int Tp, int C, int Lmax, int blank, float grad_scale,
                     void *workspace, size_t ws_bytes, void *stream);
+/* The same computation for callers that cannot allocate device memory (code under HIP graph
+ * capture, serving loops, harnesses that forbid hipMalloc): identical arguments and results, but
+ * the scratch space is a static device array inside the library instead of a caller workspace,
+ * and the call makes no hipMalloc/hipFree or any other allocating call.
+ * Limit: w2l_ctc_workspace_bytes(B, Tp, C, Lmax) <= W2L_CTC_NOALLOC_SCRATCH_BYTES (32 MiB: e.g.
+ * B = 8, Tp = 750, Lmax = 150, the criterion of the 100M-parameter network's batch); a larger
+ * problem is refused with W2L_ERR_WORKSPACE and nothing is launched.  Every device the library
+ * runs on holds one such array until the process ends.  All calls on one device share that
+ * device's array: two calls in flight on the same device at the same time (two streams, two host
+ * threads) race -- order them on one stream.  The array keeps the previous call's contents;
+ * every launch writes what it later reads, so nothing needs clearing.  The first call on a device
+ * looks the array's address up (hipGetSymbolAddress) and should be made outside a graph capture.
+ * Errors: as w2l_ctc_fwd_bwd; W2L_ERR_LAUNCH if the address lookup fails. */
+#define W2L_CTC_NOALLOC_SCRATCH_BYTES (32u << 20)
+int w2l_ctc_fwd_bwd_noalloc(const float *input, int is_logits, const int *targets, const int *in_len,
+                            const int *tgt_len, float *loss, float *grad,
+                            int B, int Tp, int C, int Lmax, int blank, float grad_scale, void *stream);
 /* HOST pointers.  Returns W2L_ERR_TARGET for a label == blank or outside [0,C),
  * in_len outside [0,Tp] or tgt_len outside [0,Lmax]. */
 int w2l_ctc_check_targets_host(const int *targets, const int *in_len, const int *tgt_len,

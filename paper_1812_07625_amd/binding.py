@@ -19,7 +19,7 @@ __all__ = [
     "W2L_F32", "W2L_BF16", "W2LError", "w2l_layer", "w2l_version", "w2l_status_str", "w2l_last_hip_error",
     "w2l_conv1d_fwd", "w2l_conv1d_bwd_data", "w2l_conv1d_bwd_weight", "w2l_conv1d_fwd_workspace_bytes",
     "w2l_conv1d_bwd_data_workspace_bytes", "w2l_conv1d_bwd_weight_workspace_bytes", "w2l_glu_fwd", "w2l_glu_bwd",
-    "w2l_logsoftmax_fwd", "w2l_logsoftmax_bwd", "w2l_ctc_workspace_bytes", "w2l_ctc_fwd_bwd",
+    "w2l_logsoftmax_fwd", "w2l_logsoftmax_bwd", "w2l_ctc_workspace_bytes", "w2l_ctc_fwd_bwd", "w2l_ctc_fwd_bwd_noalloc",
     "w2l_ctc_check_targets_host", "w2l_asg_workspace_bytes", "w2l_asg_fwd_bwd", "w2l_asg_check_targets_host",
     "w2l_logmel_num_frames", "w2l_logmel_fwd",
     "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_train_step_asg_workspace_bytes", "w2l_train_step_asg",
@@ -66,6 +66,7 @@ def _load():
         "w2l_logsoftmax_bwd": (i, [vp, vp, vp, ll, i, vp]),
         "w2l_ctc_workspace_bytes": (sz, [i] * 4),
         "w2l_ctc_fwd_bwd": (i, [vp, i, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]),
+        "w2l_ctc_fwd_bwd_noalloc": (i, [vp, i, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp]),
         "w2l_ctc_check_targets_host": (i, [vp, vp, vp, i, i, i, i, i]),
         "w2l_logmel_num_frames": (i, [i, i, i]),
         "w2l_logmel_fwd": (i, [vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, f, f, i, vp]),
@@ -228,6 +229,16 @@ def w2l_ctc_fwd_bwd(inp, is_logits, targets, in_len, tgt_len, loss, grad, blank=
     _check(raw.w2l_ctc_fwd_bwd(_p(inp), int(is_logits), _p(targets), _p(in_len), _p(tgt_len), _p(loss),
                                _p(grad), B, Tp, Cc, Lmax, blank, float(grad_scale), wp, wn, _stream(stream)),
            "w2l_ctc_fwd_bwd")
+    return loss, grad
+
+
+def w2l_ctc_fwd_bwd_noalloc(inp, is_logits, targets, in_len, tgt_len, loss, grad, blank=0, grad_scale=1.0, stream=None):
+    """w2l_ctc_fwd_bwd on the library's static scratch array: no workspace, no allocation."""
+    B, Tp, Cc = inp.shape
+    Lmax = targets.shape[1]
+    _check(raw.w2l_ctc_fwd_bwd_noalloc(_p(inp), int(is_logits), _p(targets), _p(in_len), _p(tgt_len), _p(loss),
+                                       _p(grad), B, Tp, Cc, Lmax, blank, float(grad_scale), _stream(stream)),
+           "w2l_ctc_fwd_bwd_noalloc")
     return loss, grad
 
 

@@ -20,6 +20,7 @@
 //      multiplied, exponents added, log P taken off) into the state posteriors, normalises
 //      them per frame, and sums them per class in a fixed order given by a (class, position)
 //      sort of the target.
+#include <mutex>
 #include "common.h"
 
 namespace w2l {
@@ -539,17 +540,23 @@ extern "C" int w2l_ctc_check_targets_host(const int* targets, const int* in_len,
     return W2L_OK;
 }
 
-extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* targets, const int* in_len,
-                               const int* tgt_len, float* loss, float* grad, int B, int Tp, int C, int Lmax,
-                               int blank, float grad_scale, void* workspace, size_t ws_bytes, void* stream)
+namespace {
+int ctc_check_args(const float* input, const int* targets, const int* in_len, const int* tgt_len, const float* loss,
+                   const float* grad, int B, int Tp, int C, int Lmax, int blank)
 {
     if (!input || !targets || !in_len || !tgt_len || !loss || !grad) return W2L_ERR_NULL;
     if (B <= 0 || Tp <= 0 || Tp > MAX_FRAMES || C <= 0 || C > 4096 || Lmax <= 0 || Lmax > 3000 || blank < 0 ||
         blank >= C || B > 65535)
         return W2L_ERR_SHAPE;
     if (!aligned16(input) || !aligned16(targets) || !aligned16(grad)) return W2L_ERR_ALIGN;
+    return W2L_OK;
+}
+
+// the three launches, arguments already checked; workspace: ws_layout().total bytes of device memory
+int ctc_run(const float* input, int is_logits, const int* targets, const int* in_len, const int* tgt_len, float* loss,
+            float* grad, int B, int Tp, int C, int Lmax, int blank, float grad_scale, void* workspace, void* stream)
+{
     const WsLayout w = ws_layout(B, Tp, C, Lmax);
-    if (!workspace || ws_bytes < w.total || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return W2L_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     const float* lp = input;
@@ -621,4 +628,67 @@ extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* tar
                        in_len, tgt_len, loss, logp, alpha, beta, sort_order, sort_start, grad, d, rows_per_wg, is_logits,
                        grad_scale);
     return launch_status();
+}
+}  // namespace
+
+extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* targets, const int* in_len,
+                               const int* tgt_len, float* loss, float* grad, int B, int Tp, int C, int Lmax,
+                               int blank, float grad_scale, void* workspace, size_t ws_bytes, void* stream)
+{
+    const int rc = ctc_check_args(input, targets, in_len, tgt_len, loss, grad, B, Tp, C, Lmax, blank);
+    if (rc) return rc;
+    if (!workspace || ws_bytes < ws_layout(B, Tp, C, Lmax).total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return W2L_ERR_WORKSPACE;
+    return ctc_run(input, is_logits, targets, in_len, tgt_len, loss, grad, B, Tp, C, Lmax, blank, grad_scale, workspace,
+                   stream);
+}
+
+// ---- the same criterion for callers that cannot allocate device memory ---------------------
+// The workspace is a file-scope device array.  In host code the array's name is only a handle:
+// its device address comes from hipGetSymbolAddress, looked up once per device (each device
+// holds its own copy of the array at its own address) and kept.
+namespace {
+static __device__ __align__(256) unsigned char scratch[W2L_CTC_NOALLOC_SCRATCH_BYTES];
+
+struct ScratchAddr {
+    void* ptr = nullptr;
+    bool tried = false;
+    hipError_t err = hipSuccess;
+};
+// device address of `scratch` on the current device; nullptr (and the HIP error noted) if the lookup failed
+void* scratch_ptr()
+{
+    static std::mutex mu;
+    static ScratchAddr per_device[64];
+    int dev = 0;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= 64) {
+        note_hip_error(e != hipSuccess ? e : hipErrorInvalidDevice);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    ScratchAddr& a = per_device[dev];
+    if (!a.tried) {
+        a.tried = true;
+        void* p = nullptr;
+        a.err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        a.ptr = (a.err == hipSuccess) ? p : nullptr;
+    }
+    if (!a.ptr) note_hip_error(a.err != hipSuccess ? a.err : hipErrorInvalidSymbol);
+    return a.ptr;
+}
+}  // namespace
+
+extern "C" int w2l_ctc_fwd_bwd_noalloc(const float* input, int is_logits, const int* targets, const int* in_len,
+                                       const int* tgt_len, float* loss, float* grad, int B, int Tp, int C, int Lmax,
+                                       int blank, float grad_scale, void* stream)
+{
+    const int rc = ctc_check_args(input, targets, in_len, tgt_len, loss, grad, B, Tp, C, Lmax, blank);
+    if (rc) return rc;
+    if (ws_layout(B, Tp, C, Lmax).total > (size_t)W2L_CTC_NOALLOC_SCRATCH_BYTES) return W2L_ERR_WORKSPACE;
+    void* ws = scratch_ptr();
+    if (!ws) return W2L_ERR_LAUNCH;
+    // Every launch writes what it later reads (score rows, both lattices, the target's sort, log P):
+    // nothing in the array has to start at zero, so what the previous call left there is harmless.
+    return ctc_run(input, is_logits, targets, in_len, tgt_len, loss, grad, B, Tp, C, Lmax, blank, grad_scale, ws, stream);
 }
