@@ -63,8 +63,7 @@ def main():
     import torch
     import workloads as W
     import paper_1812_07625_amd as P
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import to_dev, empty
+    from workloads.device import to_dev, empty
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = W.config4()

@@ -175,6 +175,13 @@ int w2l_ctc_fwd_bwd(const float *input, int is_logits, const int *targets, const
 int w2l_ctc_fwd_bwd_noalloc(const float *input, int is_logits, const int *targets, const int *in_len,
                             const int *tgt_len, float *loss, float *grad,
                             int B, int Tp, int C, int Lmax, int blank, float grad_scale, void *stream);
+/* Host-only query: which variant of the alpha/beta kernel w2l_ctc_fwd_bwd launches for C classes
+ * and targets of up to Lmax labels -- (blank, label) pairs per lane (1, 2 or 4), score-table values
+ * a thread stages per block of frames (2, 4, 8; 0 = scores gathered per lane, large alphabets),
+ * frames per block (16 or 12) and threads per workgroup.  For tests and tuning; launches nothing.
+ * W2L_ERR_SHAPE for sizes w2l_ctc_fwd_bwd refuses. */
+int w2l_ctc_launch_config(int C, int Lmax, int *pairs_per_lane, int *table_values_per_thread,
+                          int *frames_per_block, int *threads);
 /* HOST pointers.  Returns W2L_ERR_TARGET for a label == blank or outside [0,C),
  * in_len outside [0,Tp] or tgt_len outside [0,Lmax]. */
 int w2l_ctc_check_targets_host(const int *targets, const int *in_len, const int *tgt_len,
@@ -213,6 +220,13 @@ int w2l_asg_fwd_bwd(const float *emissions, const float *trans, const int *targe
                     float *grad_emissions, float *grad_trans,
                     int B, int Tp, int C, int Lmax, float grad_scale,
                     void *workspace, size_t ws_bytes, void *stream);
+/* Host-only query: which variant of the lattice kernel w2l_asg_fwd_bwd launches -- target positions
+ * per lane (1, 2 or 4), lanes per class row of the fully connected recursion (32 or 64), the
+ * workgroup-size bound it is compiled for (256 or 1024), frames per block (16 or 12), emission-row
+ * values a thread stages per block (2 or 8) and threads per workgroup.  For tests and tuning;
+ * launches nothing.  W2L_ERR_SHAPE for sizes w2l_asg_fwd_bwd refuses. */
+int w2l_asg_launch_config(int C, int Lmax, int *positions_per_lane, int *class_lanes, int *max_threads,
+                          int *frames_per_block, int *row_values_per_thread, int *threads);
 /* HOST pointers.  Returns W2L_ERR_TARGET for a label outside [0,C), in_len outside [0,Tp]
  * or tgt_len outside [0,Lmax]. */
 int w2l_asg_check_targets_host(const int *targets, const int *in_len, const int *tgt_len,

@@ -20,7 +20,7 @@ __all__ = [
     "w2l_conv1d_fwd", "w2l_conv1d_bwd_data", "w2l_conv1d_bwd_weight", "w2l_conv1d_fwd_workspace_bytes",
     "w2l_conv1d_bwd_data_workspace_bytes", "w2l_conv1d_bwd_weight_workspace_bytes", "w2l_glu_fwd", "w2l_glu_bwd",
     "w2l_logsoftmax_fwd", "w2l_logsoftmax_bwd", "w2l_ctc_workspace_bytes", "w2l_ctc_fwd_bwd", "w2l_ctc_fwd_bwd_noalloc",
-    "w2l_ctc_check_targets_host", "w2l_asg_workspace_bytes", "w2l_asg_fwd_bwd", "w2l_asg_check_targets_host",
+    "w2l_ctc_check_targets_host", "w2l_ctc_launch_config", "w2l_asg_launch_config", "w2l_asg_workspace_bytes", "w2l_asg_fwd_bwd", "w2l_asg_check_targets_host",
     "w2l_logmel_num_frames", "w2l_logmel_fwd",
     "w2l_train_step_workspace_bytes", "w2l_train_step", "w2l_train_step_asg_workspace_bytes", "w2l_train_step_asg",
     "w2l_sgd_momentum_step",
@@ -68,6 +68,8 @@ def _load():
         "w2l_ctc_fwd_bwd": (i, [vp, i, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]),
         "w2l_ctc_fwd_bwd_noalloc": (i, [vp, i, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp]),
         "w2l_ctc_check_targets_host": (i, [vp, vp, vp, i, i, i, i, i]),
+        "w2l_ctc_launch_config": (i, [i, i] + [C.POINTER(C.c_int)] * 4),
+        "w2l_asg_launch_config": (i, [i, i] + [C.POINTER(C.c_int)] * 6),
         "w2l_logmel_num_frames": (i, [i, i, i]),
         "w2l_logmel_fwd": (i, [vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, f, f, i, vp]),
         "w2l_asg_workspace_bytes": (sz, [i] * 4),
@@ -250,6 +252,20 @@ def w2l_ctc_check_targets_host(targets, in_len, tgt_len, Tp, Cc, blank=0) -> int
     tl = np.ascontiguousarray(tgt_len, dtype=np.int32)
     return raw.w2l_ctc_check_targets_host(t.ctypes.data, il.ctypes.data, tl.ctypes.data, t.shape[0], Tp, Cc,
                                           t.shape[1], blank)
+
+
+def w2l_ctc_launch_config(Cc, Lmax):
+    """(pairs per lane, table values per thread, frames per block, threads) of the alpha/beta kernel; host only."""
+    out = [C.c_int() for _ in range(4)]
+    _check(raw.w2l_ctc_launch_config(Cc, Lmax, *[C.byref(o) for o in out]), "w2l_ctc_launch_config")
+    return tuple(o.value for o in out)
+
+
+def w2l_asg_launch_config(Cc, Lmax):
+    """(positions per lane, class lanes, max threads, frames per block, row values per thread, threads); host only."""
+    out = [C.c_int() for _ in range(6)]
+    _check(raw.w2l_asg_launch_config(Cc, Lmax, *[C.byref(o) for o in out]), "w2l_asg_launch_config")
+    return tuple(o.value for o in out)
 
 
 def w2l_logmel_num_frames(n_samples, win=400, hop=160) -> int:

@@ -995,16 +995,50 @@ WsLayout ws_layout(int B, int Tp, int C, int Lmax)
     return w;
 }
 
+// Which asg_lattice<PPT, CMAX, MAXT, BLK, NQ> variant a problem takes, and its launch shape.
+// Forced alignment: one lane per PPT target positions, 64 - BLK of them per wavefront.  A step is bound by
+// instruction issue, so a wavefront wants a SIMD of its own: the smallest PPT that fits four wavefronts, with
+// blocks of 16 frames if that fits and of 12 (52 owned lanes) otherwise; longer targets take four positions
+// per lane on as many wavefronts as they need.  (The register budget, MAXT, follows the workgroup size.)
+// NQ: emission-row elements a thread stages per block (BLK * C <= 1024 <= 8 threads).
+struct AsgLaunch { int ppt, blk, nt, nq, cmax, maxt; };
+AsgLaunch asg_launch_config(int C, int Lmax)
+{
+    int ppt = 4, blk = 16;
+    for (int p = 1; p <= 4; p *= 2) {
+        if (Lmax <= 4 * 48 * p) { ppt = p; blk = 16; break; }
+        if (Lmax <= 4 * 52 * p) { ppt = p; blk = 12; break; }
+    }
+    const int own = 64 - blk;
+    int nt = 64 * (((Lmax + ppt - 1) / ppt + own - 1) / own);
+    if (nt < 128) nt = 128;  // the fully connected lattice runs on two wavefronts
+    const int maxt = nt > 256 ? 1024 : 256;
+    if (maxt == 1024) { ppt = 4; blk = 16; }
+    const int nq = blk * C <= 2 * nt ? 2 : 8;
+    return AsgLaunch{ppt, blk, nt, nq, C <= 32 ? 32 : 64, maxt};
+}
+
 template <int PPT, int MAXT, int BLK>
 void launch_lattice(int cmax, int nq, dim3 grid, dim3 block, hipStream_t st, const float* em, const float* trans,
                     const int* targets, const int* in_len, const int* tgt_len, const AsgWs& w, const AsgDims& d)
 {
 #define W2L_ASG_LAUNCH(C_, Q_) \
     hipLaunchKernelGGL((asg_lattice<PPT, C_, MAXT, BLK, Q_>), grid, block, 0, st, em, trans, targets, in_len, tgt_len, w, d)
+    // only the combinations asg_launch_config() can produce are compiled: with at most 32 classes a block of 12
+    // frames (or a workgroup of more than 256 threads) always stages 2 values per thread, and with more than
+    // 32 classes a block of 16 frames on at most 256 threads always stages 8
     if (cmax <= 32) {
-        if (nq == 2) W2L_ASG_LAUNCH(32, 2); else W2L_ASG_LAUNCH(32, 8);
+        if constexpr (BLK == 12 || MAXT == 1024) {
+            W2L_ASG_LAUNCH(32, 2);
+        } else {
+            if (nq == 2) W2L_ASG_LAUNCH(32, 2); else W2L_ASG_LAUNCH(32, 8);
+        }
     } else {
-        if (nq == 2) W2L_ASG_LAUNCH(64, 2); else W2L_ASG_LAUNCH(64, 8);
+        if constexpr (BLK == 16 && MAXT == 256) {
+            W2L_ASG_LAUNCH(64, 8);
+        } else {
+            if (nq == 2) W2L_ASG_LAUNCH(64, 2); else W2L_ASG_LAUNCH(64, 8);
+        }
     }
 #undef W2L_ASG_LAUNCH
 }
@@ -1018,6 +1052,23 @@ extern "C" size_t w2l_asg_workspace_bytes(int B, int Tp, int C, int Lmax)
 {
     if (B <= 0 || Tp <= 0 || C <= 0 || C > CP || Lmax <= 0) return 0;
     return ws_layout(B, Tp, C, Lmax).total;
+}
+
+extern "C" int w2l_asg_launch_config(int C, int Lmax, int* positions_per_lane, int* class_lanes, int* max_threads,
+                                     int* frames_per_block, int* row_values_per_thread, int* threads)
+{
+    if (!positions_per_lane || !class_lanes || !max_threads || !frames_per_block || !row_values_per_thread || !threads)
+        return W2L_ERR_NULL;
+    if (C <= 0 || C > CP || Lmax <= 0 || Lmax > 3000) return W2L_ERR_SHAPE;
+    const AsgLaunch cfg = asg_launch_config(C, Lmax);
+    if (cfg.nt > 1024) return W2L_ERR_SHAPE;
+    *positions_per_lane = cfg.ppt;
+    *class_lanes = cfg.cmax;
+    *max_threads = cfg.maxt;
+    *frames_per_block = cfg.blk;
+    *row_values_per_thread = cfg.nq;
+    *threads = cfg.nt;
+    return W2L_OK;
 }
 
 extern "C" int w2l_asg_check_targets_host(const int* targets, const int* in_len, const int* tgt_len, int B, int Tp,
@@ -1071,27 +1122,16 @@ extern "C" int w2l_asg_fwd_bwd(const float* emissions, const float* trans, const
         hipError_t e = hipFuncSetAttribute((const void*)asg_grad_em, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_em);
         if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }
     }
-    // Forced alignment: one lane per PPT target positions, 64 - BLK of them per wavefront.  A step is bound by
-    // instruction issue, so a wavefront wants a SIMD of its own: the smallest PPT that fits four wavefronts, with
-    // blocks of 16 frames if that fits and of 12 (52 owned lanes) otherwise; longer targets take four positions
-    // per lane on as many wavefronts as they need.  (The register budget follows the workgroup size.)
-    int ppt = 4, blk = 16;
-    for (int p = 1; p <= 4; p *= 2) {
-        if (Lmax <= 4 * 48 * p) { ppt = p; blk = 16; break; }
-        if (Lmax <= 4 * 52 * p) { ppt = p; blk = 12; break; }
-    }
-    const int own = 64 - blk;
-    int nt = 64 * (((Lmax + ppt - 1) / ppt + own - 1) / own);
-    if (nt > 1024) return W2L_ERR_SHAPE;
-    if (nt < 128) nt = 128;  // the fully connected lattice runs on two wavefronts
-    const int nq = blk * C <= 2 * nt ? 2 : 8;  // emission-row elements a thread stages per block (blk * C <= 1024 <= 8 nt)
+    const AsgLaunch cfg = asg_launch_config(C, Lmax);
+    if (cfg.nt > 1024) return W2L_ERR_SHAPE;
+    const int nt = cfg.nt, nq = cfg.nq;
     const dim3 g1(5, B), b1(nt);  // four recursions and the sort of the target
-    if (nt > 256) launch_lattice<4, 1024, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
-    else if (ppt == 1 && blk == 16) launch_lattice<1, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
-    else if (ppt == 1) launch_lattice<1, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
-    else if (ppt == 2 && blk == 16) launch_lattice<2, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
-    else if (ppt == 2) launch_lattice<2, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
-    else if (blk == 16) launch_lattice<4, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    if (cfg.maxt == 1024) launch_lattice<4, 1024, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (cfg.ppt == 1 && cfg.blk == 16) launch_lattice<1, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (cfg.ppt == 1) launch_lattice<1, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (cfg.ppt == 2 && cfg.blk == 16) launch_lattice<2, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (cfg.ppt == 2) launch_lattice<2, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
+    else if (cfg.blk == 16) launch_lattice<4, 256, 16>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
     else launch_lattice<4, 256, 12>(C, nq, g1, b1, st, emissions, trans, targets, in_len, tgt_len, w, d);
     int rc = launch_status();
     if (rc) return rc;

@@ -136,6 +136,8 @@ int glu_bwd_layout(const void* y, const void* dh, void* dy, int B, int Tp, int C
 
 // dense bf16 [B*Tp, C] (C % 8 == 0) -> layout with the given pitch / halo / slack, zeros outside the real frames
 int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch, int halo, int slack, hipStream_t st);
+// any dtype, any channel count
+int pad_layout(const void* src, void* dst, int B, int Tp, int C, int dtype, int pitch, int halo, int slack, hipStream_t st);
 // the same for two tensors that share B, Tp and the layout, in one launch
 int pad_layout2_bf16(const void* src0, void* dst0, int C0, const void* src1, void* dst1, int C1, int B, int Tp, int pitch,
                      int halo, int slack, hipStream_t st);

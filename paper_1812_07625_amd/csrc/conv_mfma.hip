@@ -38,6 +38,9 @@
 // (k-1)/2 frames around every utterance (the train step keeps its activations that way): every
 // window is then plain in-bounds memory, the per-lane byte offsets are loop invariants, the
 // panel advance is a scalar add on the base pointer, and a load costs three instructions.
+#include <map>
+#include <mutex>
+#include <utility>
 #include "common.h"
 
 namespace w2l {
@@ -1224,13 +1227,23 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __re
     });
 }
 
-template <class K>
-int set_lds(K kern, int bytes)
+// Raise a kernel's dynamic-LDS limit: once per (device, kernel), remembered afterwards.
+int set_lds_once(const void* kern, int bytes)
 {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    static std::mutex mu;
+    static std::map<std::pair<int, const void*>, int> done;  // largest size already granted
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) dev = -1;
+    std::lock_guard<std::mutex> lock(mu);
+    int& have = done[std::make_pair(dev, kern)];
+    if (dev >= 0 && have >= bytes) return W2L_OK;
+    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }
+    have = bytes;
     return W2L_OK;
 }
+template <class K>
+int set_lds(K kern, int bytes) { return set_lds_once((const void*)kern, bytes); }
 
 // pick the tile whose grid wastes the fewest CU-rounds on a 256-CU part
 struct TileChoice { int bm, bn; };

@@ -498,6 +498,29 @@ size_t grad_lds_bytes(int Lmax, int C)
     return (size_t)4 * (2 * Lmax + C + 1) + (size_t)4 * 4 * (2 * Lmax + 4);
 }
 
+// Which ctc_lattice<PPT, NQ, BLK> variant a problem takes, and its launch shape.
+// One lane per PPT (blank, label) pairs of the extended target, 64 - BLK of them per wavefront.  The step is
+// bound by instruction issue, so a wavefront wants a SIMD of its own: the smallest PPT that fits four
+// wavefronts, with blocks of 16 frames if that fits and of 12 (52 owned lanes) otherwise; targets beyond
+// 4 * 52 * 4 pairs take four pairs per lane on as many wavefronts as they need.
+// NQ > 0 (score table in LDS): a block's class rows must fit 8 elements per thread and, in two buffers, 64 KB.
+struct CtcLaunch { int ppt, blk, nt, nq; size_t lds; };
+CtcLaunch ctc_launch_config(int C, int Lmax)
+{
+    const int pairs = Lmax + 1;
+    int ppt = 4, blk = 16;
+    for (int p = 1; p <= 4; p *= 2) {
+        if (pairs <= 4 * 48 * p) { ppt = p; blk = 16; break; }
+        if (pairs <= 4 * 52 * p) { ppt = p; blk = 12; break; }
+    }
+    const int own = 64 - blk;
+    const int nt = 64 * (((pairs + ppt - 1) / ppt + own - 1) / own);
+    const long long nel = (long long)blk * C;
+    const size_t table_bytes = (size_t)2 * C * (blk + 1) * 8;
+    const int nq = (nel <= 8LL * nt && table_bytes <= 64 * 1024) ? (nel <= 2LL * nt ? 2 : (nel <= 4LL * nt ? 4 : 8)) : 0;
+    return CtcLaunch{ppt, blk, nt, nq, nq ? table_bytes : 0};
+}
+
 struct WsLayout { size_t lp, logp, order, cstart, alpha, beta, total; };
 WsLayout ws_layout(int B, int Tp, int C, int Lmax)
 {
@@ -523,6 +546,20 @@ extern "C" size_t w2l_ctc_workspace_bytes(int B, int Tp, int C, int Lmax)
 {
     if (B <= 0 || Tp <= 0 || C <= 0 || Lmax <= 0) return 0;
     return ws_layout(B, Tp, C, Lmax).total;
+}
+
+extern "C" int w2l_ctc_launch_config(int C, int Lmax, int* pairs_per_lane, int* table_values_per_thread,
+                                     int* frames_per_block, int* threads)
+{
+    if (!pairs_per_lane || !table_values_per_thread || !frames_per_block || !threads) return W2L_ERR_NULL;
+    if (C <= 0 || C > 4096 || Lmax <= 0 || Lmax > 3000) return W2L_ERR_SHAPE;
+    const CtcLaunch cfg = ctc_launch_config(C, Lmax);
+    if (cfg.nt > 1024) return W2L_ERR_SHAPE;
+    *pairs_per_lane = cfg.ppt;
+    *table_values_per_thread = cfg.nq;
+    *frames_per_block = cfg.blk;
+    *threads = cfg.nt;
+    return W2L_OK;
 }
 
 extern "C" int w2l_ctc_check_targets_host(const int* targets, const int* in_len, const int* tgt_len, int B,
@@ -579,25 +616,11 @@ int ctc_run(const float* input, int is_logits, const int* targets, const int* in
         hipError_t e = hipFuncSetAttribute((const void*)ctc_grad, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
         if (e != hipSuccess) { note_hip_error(e); return W2L_ERR_LAUNCH; }
     }
-    // One lane per PPT (blank, label) pairs of the extended target, 64 - BLK of them per wavefront.  The step is
-    // bound by instruction issue, so a wavefront wants a SIMD of its own: the smallest PPT that fits four
-    // wavefronts, with blocks of 16 frames if that fits and of 12 (52 owned lanes) otherwise; targets beyond
-    // 4 * 52 * 4 pairs take four pairs per lane on as many wavefronts as they need.
-    const int pairs = Lmax + 1;
-    int ppt = 4, blk = 16;
-    for (int p = 1; p <= 4; p *= 2) {
-        if (pairs <= 4 * 48 * p) { ppt = p; blk = 16; break; }
-        if (pairs <= 4 * 52 * p) { ppt = p; blk = 12; break; }
-    }
-    const int own = 64 - blk;
-    const int nt = 64 * (((pairs + ppt - 1) / ppt + own - 1) / own);
-    if (nt > 1024) return W2L_ERR_SHAPE;
+    const CtcLaunch cfg = ctc_launch_config(C, Lmax);
+    if (cfg.nt > 1024) return W2L_ERR_SHAPE;
+    const int ppt = cfg.ppt, blk = cfg.blk, nt = cfg.nt, nq = cfg.nq;
     const dim3 g1(3, B), b1(nt);  // alpha, beta, and the sort of the target for the gradient kernel
-    // the score table path: a block's class rows must fit 8 elements per thread and, in two buffers, 64 KB of LDS
-    const long long nel = (long long)blk * C;
-    const size_t table_bytes = (size_t)2 * C * (blk + 1) * 8;
-    const int nq = (nel <= 8LL * nt && table_bytes <= 64 * 1024) ? (nel <= 2LL * nt ? 2 : (nel <= 4LL * nt ? 4 : 8)) : 0;
-    const size_t lds1 = nq ? table_bytes : 0;
+    const size_t lds1 = cfg.lds;
 #define W2L_CTC_LAUNCH(P_, Q_, B_)                                                                                    \
     {                                                                                                                 \
         if (lds1 > 32 * 1024) {                                                                                       \

@@ -179,6 +179,20 @@ __global__ __launch_bounds__(256) void pad_layout2_k(const bf16_t* __restrict__ 
     }
 }
 
+// the same for any dtype and channel count, one element per thread
+template <typename T>
+__global__ __launch_bounds__(256) void pad_layout_any_k(const T* __restrict__ src, T* __restrict__ dst, long long out_rows,
+                                                        int C, RowMap map)
+{
+    const long long total = out_rows * C;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long f = i / C;
+        const long long r = map.src(f);
+        dst[i] = r >= 0 ? src[r * C + (i - f * C)] : T(0);
+    }
+}
+
 inline unsigned grid_for(long long items)
 {
     long long b = (items + 255) / 256;
@@ -288,6 +302,19 @@ int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch,
     const RowMap map{Tp, pitch, halo, (long long)B * pitch};
     hipLaunchKernelGGL(pad_layout_k, dim3(grid_for(out_rows * (C / 8))), dim3(256), 0, st, (const bf16_t*)src,
                        (bf16_t*)dst, out_rows, C, map);
+    return launch_status();
+}
+
+int pad_layout(const void* src, void* dst, int B, int Tp, int C, int dtype, int pitch, int halo, int slack, hipStream_t st)
+{
+    if (dtype == W2L_BF16 && C % 8 == 0) return pad_layout_bf16(src, dst, B, Tp, C, pitch, halo, slack, st);
+    const long long out_rows = (long long)B * pitch + slack;
+    const RowMap map{Tp, pitch, halo, (long long)B * pitch};
+    const dim3 g(grid_for(out_rows * C)), b(256);
+    if (dtype == W2L_BF16)
+        hipLaunchKernelGGL(pad_layout_any_k<bf16_t>, g, b, 0, st, (const bf16_t*)src, (bf16_t*)dst, out_rows, C, map);
+    else
+        hipLaunchKernelGGL(pad_layout_any_k<float>, g, b, 0, st, (const float*)src, (float*)dst, out_rows, C, map);
     return launch_status();
 }
 

@@ -58,7 +58,7 @@ struct Plan {
     int n = 0, C = 0, Tlast = 0, tot_stride = 1;
     std::vector<int> Tin, Tout, outch;
     std::vector<size_t> pre, post;  // workspace offsets of conv output (dense) and GLU output (haloed) per layer
-    size_t dlogits = 0, crit_len = 0, gdy[3] = {0, 0, 0}, gdh = 0, ctc = 0, conv = 0, dbias = 0, dgs = 0, total = 0;
+    size_t dlogits = 0, crit_len = 0, gdy[3] = {0, 0, 0}, gdh[2] = {0, 0}, ctc = 0, conv = 0, conv0 = 0, dbias = 0, dgs = 0, total = 0;
     size_t ctc_bytes = 0, conv_bytes = 0, dgs_bytes = 0;
     int status = W2L_OK;
 };
@@ -94,6 +94,10 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype, int
             off += round_up(haloed_bytes(B, to, l.cout / 2, es), 256);
             const size_t g1 = haloed_bytes(B, to, l.cout, es);
             dymax = g1 > dymax ? g1 : dymax;
+        } else if (i < n - 1) {
+            // a layer without GLU that feeds another layer: its output is copied into the haloed layout too
+            p.post.push_back(off);
+            off += round_up(haloed_bytes(B, to, l.cout, es), 256);
         } else {
             p.post.push_back(p.pre.back());
         }
@@ -114,11 +118,13 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype, int
     p.dlogits = off; off += round_up((size_t)B * p.Tlast * p.C * 4, 256);
     p.crit_len = off; off += round_up((size_t)B * 4, 256);
     for (int q = 0; q < 3; ++q) { p.gdy[q] = off; off += round_up(dymax, 256); }
-    p.gdh = off; off += round_up(dhmax, 256);
+    for (int q = 0; q < 2; ++q) { p.gdh[q] = off; off += round_up(dhmax, 256); }
     p.ctc_bytes = criterion == CRIT_ASG ? w2l_asg_workspace_bytes(B, p.Tlast, p.C, Lmax) : w2l_ctc_workspace_bytes(B, p.Tlast, p.C, Lmax);
     if (p.ctc_bytes == 0) { p.status = W2L_ERR_SHAPE; return p; }  // more classes or labels than the criterion takes
     p.ctc = off; off += round_up(p.ctc_bytes, 256);
     p.conv = off; off += round_up(p.conv_bytes, 256);
+    // layer 0's weight gradient runs on the caller's stream next to the helper stream's launches: its own scratch
+    p.conv0 = off; off += round_up(conv_wgrad_scratch_bytes(L[0].cin, L[0].cout, L[0].k), 256);
     int cmax = 0;
     for (int i = 0; i < n; ++i) cmax = L[i].cout > cmax ? L[i].cout : cmax;
     p.dbias = off; off += round_up((size_t)DBIAS_CHUNKS * cmax * 4, 256);
@@ -203,6 +209,10 @@ static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers,
             rc = glu_fwd_layout(ws + p.pre[i], ws + p.post[i], B, p.Tout[i], l.cout, dtype, p.Tout[i] + 2 * HALO, HALO,
                                 SLACK_ZERO, st);
             if (rc) return rc;
+        } else if (i < n - 1) {
+            rc = pad_layout(ws + p.pre[i], ws + p.post[i], B, p.Tout[i], l.cout, dtype, p.Tout[i] + 2 * HALO, HALO,
+                            SLACK_ZERO, st);
+            if (rc) return rc;
         }
         h = ws + p.post[i];
     }
@@ -239,7 +249,12 @@ static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers,
         if (!side || layer >= n) return true;
         return hip_ok(hipStreamWaitEvent(st, side->done[layer], 0));
     };
-    void* gdh = ws + p.gdh;
+    // dh tensors that go to memory alternate between two buffers: a layer without GLU takes dh itself as its dy,
+    // so its data gradient must not write the buffer it reads, nor one the helper stream's weight gradient
+    // of the layer above still reads (gdh_reader: that layer, or -1)
+    void* const gdhb[2] = {ws + p.gdh[0], ws + p.gdh[1]};
+    int gdh_reader[2] = {-1, -1};
+    int cur = -1;  // the buffer that holds dh; -1: dh is the criterion's gradient
     const void* dh = dz;
     int dh_dt = W2L_F32;
     bool dy_ready = false;  // dy of the current layer was already written by the layer above
@@ -263,6 +278,7 @@ static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers,
             d.slack = SLACK;
         } else {
             d.slack = 0;  // dy is dense here: nothing may be read past its end
+            if (side && i > 0 && cur >= 0) gdh_reader[cur] = i;
         }
         dy_ready = false;
         // layer 0 has no data gradient: its weight gradient takes the main stream, next to the
@@ -278,7 +294,8 @@ static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers,
         // column of tiles of the same launch; otherwise it is a (small, bandwidth-bound) column sum that stays
         // on the main stream, which has the shorter chain
         const bool fused_dbias = dbiases[i] && conv_wgrad_fuses_dbias(d, dtype, dy_dt);
-        rc = conv_wgrad(d, xin, dy, dweights[i], (fused_dbias || !side) ? dbiases[i] : nullptr, dtype, dy_dt, 0, ws + p.conv, wst);
+        rc = conv_wgrad(d, xin, dy, dweights[i], (fused_dbias || !side) ? dbiases[i] : nullptr, dtype, dy_dt, 0,
+                        ws + (i == 0 ? p.conv0 : p.conv), wst);
         if (rc) return rc;
         if (on_side && !hip_ok(hipEventRecord(side->done[i], wst))) return W2L_ERR_LAUNCH;
         if (side && dbiases[i] && !fused_dbias) {
@@ -298,9 +315,15 @@ static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers,
             ConvDesc dd = d;   // dx = dh_{i-1} is written dense
             dd.x_pitch = p.Tin[i];
             dd.x_halo = 0;
-            rc = conv_dgrad(dd, dy, weights[i], gdh, dtype, dy_dt, st);
+            const int q = (cur == 0) ? 1 : 0;
+            if (gdh_reader[q] >= 0) {
+                if (!wait_wgrad(gdh_reader[q])) return W2L_ERR_LAUNCH;
+                gdh_reader[q] = -1;
+            }
+            rc = conv_dgrad(dd, dy, weights[i], gdhb[q], dtype, dy_dt, st);
             if (rc) return rc;
-            dh = gdh;
+            dh = gdhb[q];
+            cur = q;
             dh_dt = dtype;
         }
     }

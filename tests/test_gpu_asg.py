@@ -16,6 +16,7 @@ import torch
 import oracle
 import workloads as W
 from gpu_util import empty, to_dev, to_host
+from variant_cases import ASG_CASES, asg_variant
 
 pytestmark = pytest.mark.gpu
 
@@ -71,13 +72,28 @@ def check_asg(got, em, trans, targets, in_len, tgt_len, grad_scale=1.0):
     dict(B=2, T=300, in_lo=280, in_hi=300, l_lo=210, l_hi=250, Cc=40, allow_repeats=True),  # > 32 classes, two positions per lane
     dict(B=2, T=50, in_lo=30, in_hi=50, l_lo=1, l_hi=9, Cc=1),            # a single class: loss = log(#alignments)
     dict(),                                                                 # the full benchmark shape
-    dict(B=2, T=450, in_lo=430, in_hi=450, l_lo=390, l_hi=416),           # two positions per lane, blocks of 12 frames
-    dict(B=2, T=700, in_lo=650, in_hi=700, l_lo=500, l_hi=600),           # four per lane, four wavefronts
-    dict(B=2, T=900, in_lo=850, in_hi=900, l_lo=780, l_hi=832),           # four per lane, blocks of 12 frames
-    dict(B=2, T=1700, in_lo=1650, in_hi=1700, l_lo=1540, l_hi=1600),      # four per lane on nine wavefronts
 ])
 def test_asg_matches_oracle(P, kw):
     cfg = W.asg_batch(seed=12, **kw)
+    got = run_asg(P, cfg["emissions"], cfg["trans"], cfg["targets"], cfg["in_len"], cfg["tgt_len"])
+    check_asg(got, cfg["emissions"], cfg["trans"], cfg["targets"], cfg["in_len"], cfg["tgt_len"])
+
+
+def _variant_id(case):
+    import paper_1812_07625_amd as Pm
+    return "C%d-L%d-ppt%d-lanes%d-maxt%d-blk%d-nq%d" % (case + asg_variant(Pm, *case))
+
+
+@pytest.mark.parametrize("case", ASG_CASES, ids=_variant_id)
+def test_asg_every_lattice_variant(P, case):
+    """One case per variant of the lattice kernel (positions per lane x class lanes x workgroup
+    bound x block length x staged values; the id names the variant the library's own launch query
+    reports for the size): targets padded to Lmax, one utterance using all of it, one a third."""
+    Cc, Lmax = case
+    T = Lmax + 40
+    cfg = W.asg_batch(seed=200 + Lmax + Cc, B=2, T=T, Cc=Cc, in_lo=T - 9, in_hi=T, l_lo=Lmax, l_hi=Lmax)
+    assert cfg["targets"].shape[1] == Lmax
+    cfg["tgt_len"][1] = max(1, Lmax // 3)
     got = run_asg(P, cfg["emissions"], cfg["trans"], cfg["targets"], cfg["in_len"], cfg["tgt_len"])
     check_asg(got, cfg["emissions"], cfg["trans"], cfg["targets"], cfg["in_len"], cfg["tgt_len"])
 
