@@ -40,7 +40,8 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # W2L_ORACLE_LIB: a build of w2l_oracle.c made elsewhere (the sanitizer run of the tests uses this)
+        _lib = C.CDLL(os.environ.get("W2L_ORACLE_LIB") or build())
     return _lib
 
 

@@ -13,7 +13,8 @@ import torch
 
 W2L_F32, W2L_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libw2l.so")
+# W2L_LIB: another build of the same sources (the sanitizer run of the host-side tests uses this)
+_LIB_PATH = os.environ.get("W2L_LIB") or os.path.join(_HERE, "libw2l.so")
 
 __all__ = [
     "W2L_F32", "W2L_BF16", "W2LError", "w2l_layer", "w2l_version", "w2l_status_str", "w2l_last_hip_error",

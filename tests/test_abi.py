@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-LIB = os.path.join(ROOT, "paper_1812_07625_amd", "libw2l.so")
+LIB = os.environ.get("W2L_LIB") or os.path.join(ROOT, "paper_1812_07625_amd", "libw2l.so")
 
 
 def declared_symbols():
