@@ -100,6 +100,11 @@ size_t haloed_bytes(int B, int frames, int C) { return round_up(((size_t)B * (fr
 bool stage_fwd(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cin % 64 == 0 && Cout >= 16 && s >= 1; }
 bool stage_dgrad(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && s == 1 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cout % 64 == 0 && Cin % 8 == 0 && Cin >= 64; }
 bool stage_wgrad(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && s == 1 && (k - 1) / 2 <= ABI_HALO && Cin % 8 == 0 && Cout % 8 == 0 && Cout >= 64 && (long long)k * Cin >= 64; }
+// a strided layer whose stride folds into the channels (fold_stride) is staged as the stride-1 layer it folds to
+bool stage_wgrad_folded(int B, int T, int Cin, int Cout, int k, int s, int dt, ConvDesc& f)
+{
+    return s > 1 && fold_stride(dense_desc(B, T, Cin, Cout, k, s), f) && stage_wgrad(f.Cin, Cout, f.k, 1, dt);
+}
 }  // namespace
 
 extern "C" size_t w2l_conv1d_fwd_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype)
@@ -182,7 +187,9 @@ extern "C" size_t w2l_conv1d_bwd_weight_workspace_bytes(int B, int T, int Cin, i
 {
     if (check_conv_shape(B, T, Cin, Cout, k, stride)) return 0;
     size_t n = conv_wgrad_scratch_bytes(Cin, Cout, k);
+    ConvDesc f;
     if (stage_wgrad(Cin, Cout, k, stride, dtype)) n += haloed_bytes(B, T, Cin) + haloed_bytes(B, T, Cout);
+    else if (stage_wgrad_folded(B, T, Cin, Cout, k, stride, dtype, f)) n += haloed_bytes(B, f.T, f.Cin) + haloed_bytes(B, f.T, Cout);
     return n;
 }
 
@@ -201,6 +208,17 @@ extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, f
     hipStream_t st = (hipStream_t)stream;
     ConvDesc d = dense_desc(B, T, Cin, Cout, k, stride);
     unsigned char* ws = static_cast<unsigned char*>(workspace);
+    ConvDesc f;
+    if (dy_dtype == W2L_BF16 && stage_wgrad_folded(B, T, Cin, Cout, k, stride, dtype, f)) {
+        unsigned char* xp = ws + conv_wgrad_scratch_bytes(Cin, Cout, k);
+        unsigned char* dyp = xp + haloed_bytes(B, f.T, f.Cin);
+        rc = pad_layout2_bf16(x, xp, f.Cin, dy, dyp, Cout, B, f.T, f.T + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
+        if (rc) return rc;
+        f.x_pitch = f.y_pitch = f.T + 2 * ABI_HALO;
+        f.x_halo = f.y_halo = ABI_HALO;
+        f.slack = ABI_SLACK;
+        return conv_wgrad(f, xp, dyp, dw, dbias, dtype, dy_dtype, accumulate, workspace, st);
+    }
     if (dy_dtype == W2L_BF16 && stage_wgrad(Cin, Cout, k, stride, dtype)) {
         unsigned char* xp = ws + conv_wgrad_scratch_bytes(Cin, Cout, k);
         unsigned char* dyp = xp + haloed_bytes(B, T, Cin);

@@ -62,13 +62,36 @@ template <> struct Elem<bf16_t> {
 struct ConvDesc {
     int B, T, Tp, Cin, Cout, k, s, p;
     int x_pitch, x_halo, y_pitch, y_halo, slack;
+    int xcd_m = 0;  // set by the launchers: how the tile grid is cut over the 8 XCDs (see tile_of_block)
+    int w_cols = 0; // weight gradient only: columns of a dw row that exist (0: all k * Cin).  A strided layer
+                    // folded into a stride-1 one (fold_stride) has k * Cin rounded up to whole folded frames.
 };
 inline ConvDesc dense_desc(int B, int T, int Cin, int Cout, int k, int s)
 {
-    ConvDesc d{B, T, out_len(T, s), Cin, Cout, k, s, (k - 1) / 2, 0, 0, 0, 0, 0};
+    ConvDesc d{B, T, out_len(T, s), Cin, Cout, k, s, (k - 1) / 2, 0, 0, 0, 0, 0, 0, 0};
     d.x_pitch = T;
     d.y_pitch = d.Tp;
     return d;
+}
+
+// A layer with stride s > 1 read as a stride-1 layer over frames folded s at a time: x[B,T,Cin] is, as it lies
+// in memory, also [B, T/s, s*Cin], and the window of output frame t' -- frames s t' - p .. s t' - p + k - 1 -- is
+// the folded frames t' - p/s .. of a kernel of width ceil(k/s) whose weight rows are the same memory, k * Cin long
+// (the folded kernel's last, partial tap has no weights: w_cols marks where a row ends).  Needs p % s == 0 and
+// T % s == 0.  Used for the weight gradient of the strided first layer, whose reduction then runs densely through
+// the frames like every other layer's.  Returns false if the layer does not fold.
+inline bool fold_stride(const ConvDesc& d, ConvDesc& f)
+{
+    if (d.s <= 1 || d.p % d.s != 0 || d.T % d.s != 0) return false;
+    f = d;
+    f.T = f.Tp = d.T / d.s;
+    f.Cin = d.Cin * d.s;
+    f.k = 2 * (d.p / d.s) + 1;               // symmetric: (k - 1) / 2 = p / s frames either side
+    if ((long long)f.k * f.Cin < (long long)d.k * d.Cin) return false;
+    f.s = 1;
+    f.p = d.p / d.s;
+    f.w_cols = d.k * d.Cin;
+    return true;
 }
 
 // dispatchers (api.hip): MFMA kernels where the shape allows, shape-agnostic kernels otherwise

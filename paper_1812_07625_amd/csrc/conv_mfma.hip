@@ -613,8 +613,18 @@ __device__ __forceinline__ void store_tile_bf16(const CoreT& core, unsigned char
 // fastest, so that the tiles sharing an L2 cover a compact block of operand panels -- or, with
 // m_fastest, with the row tiles fastest, so that an XCD sees few column tiles and the weight
 // slices it streams stay resident in its L2.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn, bool m_fastest = false)
+// xcd_m > 0 (chosen on the host, see xcd_split): the tile grid is cut into xcd_m x (8 / xcd_m)
+// rectangular blocks, one per XCD, so that an L2 streams only its block's share of either operand;
+// inside a block the column tiles run fastest.
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn, bool m_fastest = false, int xcd_m = 0)
 {
+    if (xcd_m > 0) {
+        const int xn = 8 / xcd_m, am = tiles_m / xcd_m, an = tiles_n / xn;
+        const int x = blockIdx.x % 8, q = blockIdx.x / 8;
+        tn = (x % xn) * an + q % an;
+        tm = (x / xn) * am + q / an;
+        return;
+    }
     const int nb = tiles_m * tiles_n;
     const int per = (nb + 7) / 8;
     int id = (blockIdx.x % 8) * per + blockIdx.x / 8;
@@ -754,7 +764,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
     const int N = g.Cout, K = g.k * g.Cin, H = g.Cout / 2;
     const int tiles_m = (F + BM - 1) / BM;
     int tm, tn;
-    tile_of_block(tiles_m, (N + BN - 1) / BN, tm, tn);
+    tile_of_block(tiles_m, (N + BN - 1) / BN, tm, tn, false, g.xcd_m);
     const int f0 = g.x_halo + tm * BM, n0 = tn * BN;  // layout frame of tile row 0
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
@@ -943,13 +953,18 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_dgrad_k(const bf16_t* __re
 // GLUB: the tile is not stored as dx but pushed through the GLU backward of the layer below
 // (whose pre-GLU activations yprev are dense [B*T, 2N]): dx_out then has 2N channels and the
 // time layout of dy (tile row r -> its frame f0 + r); frames that are not real get zeros.
-// part != nullptr (grid.y = 2): the reduction over channel blocks is split in two between the
-// workgroups (blockIdx.y) of a tile, which then store their fp32 sums to part[blockIdx.y]
-// ([tile rows][N]) for dgrad_combine_k -- twice the workgroups when one per tile leaves CUs idle.
+// part != nullptr (grid.y = 2): the reduction over channel blocks is split in two between the two
+// workgroups (blockIdx.y) of a tile -- twice the workgroups when one per tile leaves CUs idle.  Each
+// stores its fp32 sums to its own slot of `part` and then takes a ticket from the tile's counter
+// (zeroed before the launch); the one that draws the second ticket adds the other's sums to its own
+// and finishes the tile.  Nobody waits for anybody, and since a + b == b + a the result does not
+// depend on which of the two comes second.  The slots hold the accumulators in register order
+// ([wavefront][accumulator quad][lane], 16 bytes per lane: both workgroups map threads to elements
+// alike), so every store and load instruction moves 1 KB of consecutive memory.
 template <int BM, int BN, int SROWS, int KG, bool GLUB>
 __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ w,
                                                               bf16_t* __restrict__ dx, const bf16_t* __restrict__ yprev,
-                                                              float* __restrict__ part, ConvGeom g)
+                                                              float* __restrict__ part, int* __restrict__ tickets, ConvGeom g)
 {
     using PS = PanelK<SROWS, 64, 4 * KG>;
     using PB = PanelMN<BN, 64, 4 * KG>;
@@ -980,13 +995,59 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
         },
         kg, wm, wn, lane);
     core.reduce_groups(lds, kg, w4, lane);
-    if (!GLUB && part) {
-        if (kg != 0) return;
-        float* po = part + (size_t)blockIdx.y * ((size_t)gridDim.x / ((N + BN - 1) / BN) * BM) * N;  // [tiles_m * BM][N]
-        core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
-            if (n0 + nn < N) po[(size_t)(tm * BM + mm) * N + n0 + nn] = v;
-        });
-        return;
+    if (part) {
+        typedef __attribute__((ext_vector_type(4))) float f32x4;
+        constexpr int QUADS = core.TM * core.TN * 4;                       // 16-byte pieces per lane
+        constexpr size_t SLOT = (size_t)4 * QUADS * 64;                    // f32x4 per workgroup slot
+        const int tile = blockIdx.x;
+        f32x4* mine = reinterpret_cast<f32x4*>(part) + ((size_t)tile * 2 + blockIdx.y) * SLOT + ((size_t)w4 * QUADS) * 64 + lane;
+        const f32x4* other = reinterpret_cast<const f32x4*>(part) + ((size_t)tile * 2 + (1 - blockIdx.y)) * SLOT + ((size_t)w4 * QUADS) * 64 + lane;
+        // The sums cross from one XCD's L2 to another's: they are stored and loaded with device-scope
+        // cache policy (sc1: written through to, and read from, memory), and each side waits for its
+        // own accesses to complete around the ticket -- no cache-wide write-back or invalidate, which
+        // would throw out the operand panels the other workgroups of this L2 are streaming.
+        if (kg == 0) {
+#pragma unroll
+            for (int i = 0; i < core.TM; ++i)
+#pragma unroll
+                for (int j = 0; j < core.TN; ++j)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const f32x4 v = {core.acc[i][j][4 * r4], core.acc[i][j][4 * r4 + 1], core.acc[i][j][4 * r4 + 2], core.acc[i][j][4 * r4 + 3]};
+                        asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(mine + (size_t)((i * core.TN + j) * 4 + r4) * 64), "v"(v) : "memory");
+                    }
+        }
+        wait_vmcnt<0>();   // this thread's sums have reached memory
+        __syncthreads();   // ... and every thread's
+        int* ticket_lds = reinterpret_cast<int*>(lds);  // the panel ring is free by now
+        if (threadIdx.x == 0) *ticket_lds = __hip_atomic_fetch_add(tickets + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int ticket = *ticket_lds;
+        if (ticket == 0) return;  // first of the pair: the other workgroup finishes the tile
+        if (kg == 0) {
+#pragma unroll
+            for (int i = 0; i < core.TM; ++i) {
+                // one row of accumulator blocks at a time: its loads in flight together, then one wait
+                f32x4 v[core.TN][4];
+#pragma unroll
+                for (int j = 0; j < core.TN; ++j)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4)
+                        asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[j][r4]) : "v"(other + (size_t)((i * core.TN + j) * 4 + r4) * 64) : "memory");
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int j = 0; j < core.TN; ++j)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        // tie each loaded register to the wait above: no use of it may be scheduled ahead of the wait
+                        asm volatile("" : "+v"(v[j][r4])::"memory");
+                        core.acc[i][j][4 * r4] += v[j][r4][0];
+                        core.acc[i][j][4 * r4 + 1] += v[j][r4][1];
+                        core.acc[i][j][4 * r4 + 2] += v[j][r4][2];
+                        core.acc[i][j][4 * r4 + 3] += v[j][r4][3];
+                    }
+            }
+        }
     }
     float zero[core.TN];
 #pragma unroll
@@ -1040,82 +1101,9 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
     }
 }
 
-// dx = bf16(part[0] + part[1]) for the real frames; part: [2][rows][N] fp32 over the layout frames
-// starting at frame y_halo (tile row r = layout frame y_halo + r), N % 8 == 0
-__global__ __launch_bounds__(256) void dgrad_combine_k(const float* __restrict__ part, bf16_t* __restrict__ dx, long long rows,
-                                                       ConvGeom g)
-{
-    const int N = g.Cin, nv = N / 8;
-    const long long total = rows * nv;
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-        const long long r = i / nv;
-        const int c = (int)(i - r * nv) * 8;
-        const long long f = g.y_halo + r;
-        const int b = (int)(f / g.y_pitch), t = (int)(f - (long long)b * g.y_pitch) - g.y_halo;
-        if (b >= g.B || t < 0 || t >= g.T) continue;
-        const float4* p0 = reinterpret_cast<const float4*>(part + r * N + c);
-        const float4* p1 = reinterpret_cast<const float4*>(part + (rows + r) * N + c);
-        const float4 a0 = p0[0], a1 = p0[1], b0 = p1[0], b1 = p1[1];
-        uint4 o;
-        o.x = (unsigned)f32_to_bf16(a0.x + b0.x) | ((unsigned)f32_to_bf16(a0.y + b0.y) << 16);
-        o.y = (unsigned)f32_to_bf16(a0.z + b0.z) | ((unsigned)f32_to_bf16(a0.w + b0.w) << 16);
-        o.z = (unsigned)f32_to_bf16(a1.x + b1.x) | ((unsigned)f32_to_bf16(a1.y + b1.y) << 16);
-        o.w = (unsigned)f32_to_bf16(a1.z + b1.z) | ((unsigned)f32_to_bf16(a1.w + b1.w) << 16);
-        *reinterpret_cast<uint4*>(dx + ((size_t)b * g.x_pitch + g.x_halo + t) * N + c) = o;
-    }
-}
-
-// Combining pass of the split data gradient fused with the GLU backward of the layer below:
-// dh = bf16(part[0] + part[1]) (rounded as the unfused path stores it), then
-// dyprev[f] = (dh * sigmoid(g), dh * a * sigmoid(g) * (1 - sigmoid(g))) for the real frames and zeros for
-// every other frame of the first `frames` layout frames.  yprev: dense [B*T, 2N]; dyprev: [frames.., 2N].
-__global__ __launch_bounds__(256) void dgrad_combine_glu_k(const float* __restrict__ part, const bf16_t* __restrict__ yprev,
-                                                           bf16_t* __restrict__ dyprev, long long rows, long long frames,
-                                                           ConvGeom g)
-{
-    const int N = g.Cin, nv = N / 8;
-    const long long total = frames * nv;
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-        const long long f = i / nv;
-        const int c = (int)(i - f * nv) * 8;
-        const int b = (int)(f / g.y_pitch), t = (int)(f - (long long)b * g.y_pitch) - g.y_halo;
-        uint4 oa = make_uint4(0, 0, 0, 0), og = oa;
-        if (b < g.B && t >= 0 && t < g.T) {
-            const long long r = f - g.y_halo;
-            const float4* p0 = reinterpret_cast<const float4*>(part + r * N + c);
-            const float4* p1 = reinterpret_cast<const float4*>(part + (rows + r) * N + c);
-            const float4 a0 = p0[0], a1 = p0[1], b0 = p1[0], b1 = p1[1];
-            const float dh[8] = {a0.x + b0.x, a0.y + b0.y, a0.z + b0.z, a0.w + b0.w,
-                                 a1.x + b1.x, a1.y + b1.y, a1.z + b1.z, a1.w + b1.w};
-            const bf16_t* yr = yprev + ((size_t)b * g.T + t) * 2 * N + c;
-            const uint4 ua = *reinterpret_cast<const uint4*>(yr), ug = *reinterpret_cast<const uint4*>(yr + N);
-            const unsigned* pa = &ua.x; const unsigned* pg = &ug.x;
-            unsigned* qa = &oa.x; unsigned* qg = &og.x;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                unsigned ra = 0, rg = 0;
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const float a = bf16_to_f32((bf16_t)(pa[q] >> (16 * hh)));
-                    const float gg = bf16_to_f32((bf16_t)(pg[q] >> (16 * hh)));
-                    const float d = bf16_to_f32(f32_to_bf16(dh[2 * q + hh]));
-                    const float sg = sigmoidf_(gg);
-                    ra |= (unsigned)f32_to_bf16(d * sg) << (16 * hh);
-                    rg |= (unsigned)f32_to_bf16(d * a * sg * (1.f - sg)) << (16 * hh);
-                }
-                qa[q] = ra;
-                qg[q] = rg;
-            }
-        }
-        bf16_t* o = dyprev + (size_t)f * 2 * N + c;
-        *reinterpret_cast<uint4*>(o) = oa;
-        *reinterpret_cast<uint4*>(o + N) = og;
-    }
-}
-
-// zero rows [r0, r1) and [r2, r3) of a [rows, C] bf16 tensor (C % 8 == 0)
+// zero rows [r0, r1) and [r2, r3) of a [rows, C] bf16 tensor (C % 8 == 0), and n_tickets ints
 __global__ __launch_bounds__(256) void zero_rows_k(bf16_t* __restrict__ p, long long r0, long long r1, long long r2,
-                                                   long long r3, int C)
+                                                   long long r3, int C, int* __restrict__ tickets, int n_tickets)
 {
     const int cv = C / 8;
     const long long na = (r1 - r0) * cv, nb = (r3 - r2) * cv;
@@ -1123,6 +1111,7 @@ __global__ __launch_bounds__(256) void zero_rows_k(bf16_t* __restrict__ p, long 
         const long long e = i < na ? r0 * cv + i : r2 * cv + (i - na);
         reinterpret_cast<uint4*>(p)[e] = make_uint4(0, 0, 0, 0);
     }
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_tickets; i += gridDim.x * blockDim.x) tickets[i] = 0;
 }
 
 // =============================== weight gradient ========================================
@@ -1145,7 +1134,7 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __re
     extern __shared__ __align__(1024) unsigned char lds[];
     constexpr int STAGE = PA::BYTES + PB::BYTES;
     static_assert(KG == 1 || BM * BN * 4 <= STAGES * STAGE, "the group reduction reuses the panel ring");
-    const int M = g.Cout, N = g.k * g.Cin;
+    const int M = g.Cout, N = g.w_cols ? g.w_cols : g.k * g.Cin;
     const int tiles_n = (N + BN - 1) / BN;
     int tm, tn;
     tile_of_block((M + BM - 1) / BM, tiles_n + (BIAS ? 1 : 0), tm, tn);
@@ -1263,6 +1252,22 @@ TileChoice choose_tile(long long M, long long N)
     return pick;
 }
 
+// How to cut a tiles_m x tiles_n grid into 8 rectangular blocks, one per XCD: the cut (xm blocks along m,
+// 8 / xm along n) that makes an L2 stream the fewest bytes, given the bytes one row of tiles (bytes_m) and one
+// column of tiles (bytes_n) read.  0 if the grid does not divide.
+int xcd_split(long long tiles_m, long long tiles_n, double bytes_m, double bytes_n)
+{
+    int best = 0;
+    double best_cost = 0;
+    for (int xm = 1; xm <= 8; xm *= 2) {
+        const int xn = 8 / xm;
+        if (tiles_m % xm || tiles_n % xn) continue;
+        const double cost = (double)(tiles_m / xm) * bytes_m + (double)(tiles_n / xn) * bytes_n;
+        if (!best || cost < best_cost) { best = xm; best_cost = cost; }
+    }
+    return best;
+}
+
 bool common_ok(const ConvDesc& d)
 {
     if (d.Cin % 8 || d.Cout % 8) return false;
@@ -1307,8 +1312,16 @@ bool conv_fwd_mfma_ok(const ConvDesc& d)
     return d.Cin % 8 == 0 && common_ok(e) && d.Cout >= 16 && (long long)d.B * d.Tp >= 128;
 }
 
-int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* bias, void* y, int ydt, hipStream_t st)
+// XCD cut of the 192x192 slab forward's tile grid: a row of tiles reads its 192 + k - 1 frames of x, a column
+// of tiles its 192 rows of w
+static int fwd_slab_xcd(const ConvDesc& g, long long tiles_m, long long tiles_n)
 {
+    return xcd_split(tiles_m, tiles_n, (double)(192 + g.k - 1) * g.Cin, 192.0 * g.k * g.Cin);
+}
+
+int conv_fwd_mfma(const ConvDesc& g0, const void* x, const void* w, const float* bias, void* y, int ydt, hipStream_t st)
+{
+    ConvDesc g = g0;
     const long long M = (long long)g.B * g.Tp, N = g.Cout;
     const TileChoice tc = choose_tile(M, N);
     const bool fast = halo_ok_x(g) && ((long long)g.k * g.Cin) % 64 == 0;
@@ -1317,6 +1330,7 @@ int conv_fwd_mfma(const ConvDesc& g, const void* x, const void* w, const float* 
         constexpr int bytes = slab_lds_bytes(192, 192, 256, 2);
         const long long F = (long long)(g.B - 1) * g.x_pitch + g.T;
         const unsigned grid = (unsigned)(((F + 191) / 192) * ((N + 191) / 192));
+        g.xcd_m = fwd_slab_xcd(g, (F + 191) / 192, (N + 191) / 192);
         if (ydt == W2L_BF16) {
             rc = set_lds(conv_fwd_slab_k<192, 192, 256, 2, bf16_t, false>, bytes);
             if (!rc) hipLaunchKernelGGL((conv_fwd_slab_k<192, 192, 256, 2, bf16_t, false>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, (bf16_t*)nullptr, g);
@@ -1358,12 +1372,14 @@ bool conv_fwd_glu_ok(const ConvDesc& d)
            d.T == d.Tp && d.slack >= LAYOUT_SLACK_ZERO && slab_ok(d, 192, 256, d.Cin, d.T, d.x_pitch, d.x_halo);
 }
 
-int conv_fwd_glu(const ConvDesc& g, const void* x, const void* w, const float* bias, void* y, void* h, hipStream_t st)
+int conv_fwd_glu(const ConvDesc& g0, const void* x, const void* w, const float* bias, void* y, void* h, hipStream_t st)
 {
-    if (!conv_fwd_glu_ok(g)) return W2L_ERR_SHAPE;
+    if (!conv_fwd_glu_ok(g0)) return W2L_ERR_SHAPE;
+    ConvDesc g = g0;
     constexpr int bytes = slab_lds_bytes(192, 192, 256, 2);
     const long long F = (long long)(g.B - 1) * g.x_pitch + g.T;
     const unsigned grid = (unsigned)(((F + 191) / 192) * (g.Cout / 192));
+    g.xcd_m = fwd_slab_xcd(g, (F + 191) / 192, g.Cout / 192);
     int rc = set_lds(conv_fwd_slab_k<192, 192, 256, 2, bf16_t, true>, bytes);
     if (!rc) hipLaunchKernelGGL((conv_fwd_slab_k<192, 192, 256, 2, bf16_t, true>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)y, (bf16_t*)h, g);
     return rc ? rc : launch_status();
@@ -1374,9 +1390,12 @@ bool conv_dgrad_mfma_ok(const ConvDesc& d)
     return d.s == 1 && common_ok(d) && d.Cout % 64 == 0 && d.Cin >= 64 && (long long)d.B * d.T >= 128;
 }
 
-// Split-reduction data gradient: 192x192 tiles, two workgroups per tile, fp32 partial sums in
-// scratch, then one combining pass.  Taken when one workgroup per tile would leave more than a
-// third of the CUs idle and two per tile fit the chip in one round.
+// Split-reduction data gradient: 192x192 tiles, two workgroups per tile that each reduce half of the
+// channel blocks; the second of a pair to finish adds the first one's fp32 sums (left in scratch) and
+// writes the tile.  Taken when one workgroup per tile would leave more than a third of the CUs idle
+// and two per tile fit the chip in one round.
+// Scratch: DGRAD_TICKET_BYTES of tickets (one int per tile), then two fp32 slots of 192 x 192 per tile.
+constexpr size_t DGRAD_TICKET_BYTES = 1024;
 bool dgrad_split_ok(const ConvDesc& g)
 {
     if (!conv_dgrad_mfma_ok(g) || !halo_ok_y(g) || g.Cin % 8 != 0 || (g.Cout / 64) % 2 != 0 || g.Cout < 256) return false;
@@ -1391,7 +1410,8 @@ size_t conv_dgrad_scratch_bytes(const ConvDesc& g)
 {
     if (!dgrad_split_ok(g)) return 0;
     const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
-    return round_up((size_t)2 * ((F + 191) / 192 * 192) * g.Cin * 4, 256);
+    const size_t tiles = (size_t)((F + 191) / 192) * ((g.Cin + 191) / 192);
+    return DGRAD_TICKET_BYTES + tiles * 2 * 192 * 192 * 4;
 }
 
 int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, void* scratch, size_t scratch_bytes,
@@ -1404,15 +1424,15 @@ int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, 
     if (scratch && dgrad_split_ok(g) && scratch_bytes >= conv_dgrad_scratch_bytes(g)) {
         constexpr int bytes = slab_lds_bytes(192, 192, 256, 2);
         const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
-        const long long tiles_m = (F + 191) / 192, rows = tiles_m * 192;
-        const dim3 grid((unsigned)(tiles_m * ((N + 191) / 192)), 2);
-        rc = set_lds(conv_dgrad_slab_k<192, 192, 256, 2, false>, bytes);
-        if (rc) return rc;
-        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, false>), grid, dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, (float*)scratch, g);
+        const int tiles = (int)(((F + 191) / 192) * ((N + 191) / 192));
+        int* tickets = static_cast<int*>(scratch);
+        float* part = reinterpret_cast<float*>(static_cast<unsigned char*>(scratch) + DGRAD_TICKET_BYTES);
+        hipLaunchKernelGGL(zero_rows_k, dim3(1), dim3(256), 0, st, (bf16_t*)nullptr, 0LL, 0LL, 0LL, 0LL, 8, tickets, tiles);
         rc = launch_status();
         if (rc) return rc;
-        const long long work = rows * (N / 8);
-        hipLaunchKernelGGL(dgrad_combine_k, dim3((unsigned)((work + 255) / 256 < 4096 ? (work + 255) / 256 : 4096)), dim3(256), 0, st, (const float*)scratch, (bf16_t*)dx, rows, g);
+        rc = set_lds(conv_dgrad_slab_k<192, 192, 256, 2, false>, bytes);
+        if (rc) return rc;
+        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, false>), dim3((unsigned)tiles, 2), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, part, tickets, g);
         return launch_status();
     }
     if (fast && tc.bm == 256 && tc.bn == 128 && slab_ok(g, 256, 320, g.Cout, g.Tp, g.y_pitch, g.y_halo)) {
@@ -1420,7 +1440,7 @@ int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, 
         const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
         const unsigned grid = (unsigned)(((F + 255) / 256) * ((N + 127) / 128));
         rc = set_lds(conv_dgrad_slab_k<256, 128, 320, 2, false>, bytes);
-        if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<256, 128, 320, 2, false>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, (float*)nullptr, g);
+        if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<256, 128, 320, 2, false>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, (float*)nullptr, (int*)nullptr, g);
         return rc ? rc : launch_status();
     }
 #define CALL(BM_, BN_, BK_, ST_, KG_, GN_)                                                                     \
@@ -1447,34 +1467,38 @@ int conv_dgrad_glu(const ConvDesc& g, const void* dy, const void* w, const void*
                    size_t scratch_bytes, hipStream_t st)
 {
     if (!conv_dgrad_glu_ok(g)) return W2L_ERR_SHAPE;
+    const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
+    const long long z_end = (long long)g.B * g.y_pitch + LAYOUT_SLACK_ZERO;
     if (scratch && dgrad_split_ok(g) && scratch_bytes >= conv_dgrad_scratch_bytes(g)) {
-        // two workgroups per 192x192 tile, then the combining pass applies the GLU backward
+        // two workgroups per 192x192 tile; the one that finishes a tile applies the GLU backward in its epilogue
         constexpr int bytes = slab_lds_bytes(192, 192, 256, 2);
-        const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp, N = g.Cin;
-        const long long tiles_m = (F + 191) / 192, rows = tiles_m * 192;
-        const dim3 grid((unsigned)(tiles_m * ((N + 191) / 192)), 2);
-        int rc = set_lds(conv_dgrad_slab_k<192, 192, 256, 2, false>, bytes);
+        const long long tiles_m = (F + 191) / 192;
+        const int tiles = (int)(tiles_m * ((g.Cin + 191) / 192));
+        int* tickets = static_cast<int*>(scratch);
+        float* part = reinterpret_cast<float*>(static_cast<unsigned char*>(scratch) + DGRAD_TICKET_BYTES);
+        // frames the tiles do not cover (leading halo; end of the last tile to the end of the zeroed slack), and the tickets
+        const long long t_end = g.y_halo + tiles_m * 192;
+        hipLaunchKernelGGL(zero_rows_k, dim3(64), dim3(256), 0, st, (bf16_t*)dyprev, 0LL, (long long)g.y_halo, t_end,
+                           t_end > z_end ? t_end : z_end, 2 * g.Cin, tickets, tiles);
+        int rc = launch_status();
         if (rc) return rc;
-        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, false>), grid, dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)nullptr, (const bf16_t*)nullptr, (float*)scratch, g);
-        rc = launch_status();
+        rc = set_lds(conv_dgrad_slab_k<192, 192, 256, 2, true>, bytes);
         if (rc) return rc;
-        const long long frames = (long long)g.B * g.y_pitch + LAYOUT_SLACK_ZERO, work = frames * (N / 8);
-        hipLaunchKernelGGL(dgrad_combine_glu_k, dim3((unsigned)((work + 255) / 256 < 8192 ? (work + 255) / 256 : 8192)), dim3(256), 0, st, (const float*)scratch, (const bf16_t*)yprev, (bf16_t*)dyprev, rows, frames, g);
+        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, true>), dim3((unsigned)tiles, 2), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dyprev, (const bf16_t*)yprev, part, tickets, g);
         return launch_status();
     }
     constexpr int BM = 256, BN = 128;
     constexpr int bytes = slab_lds_bytes(BM, BN, 320, 2);
-    const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
     const long long tiles_m = (F + BM - 1) / BM;
     // frames the tiles do not cover: the leading halo, and from the end of the last tile to the end of the zeroed slack
-    const long long t_end = g.y_halo + tiles_m * BM, z_end = (long long)g.B * g.y_pitch + LAYOUT_SLACK_ZERO;
+    const long long t_end = g.y_halo + tiles_m * BM;
     hipLaunchKernelGGL(zero_rows_k, dim3(64), dim3(256), 0, st, (bf16_t*)dyprev, 0LL, (long long)g.y_halo, t_end,
-                       t_end > z_end ? t_end : z_end, 2 * g.Cin);
+                       t_end > z_end ? t_end : z_end, 2 * g.Cin, (int*)nullptr, 0);
     int rc = launch_status();
     if (rc) return rc;
     const unsigned grid = (unsigned)(tiles_m * ((g.Cin + BN - 1) / BN));
     rc = set_lds(conv_dgrad_slab_k<BM, BN, 320, 2, true>, bytes);
-    if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<BM, BN, 320, 2, true>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dyprev, (const bf16_t*)yprev, (float*)nullptr, g);
+    if (!rc) hipLaunchKernelGGL((conv_dgrad_slab_k<BM, BN, 320, 2, true>), dim3(grid), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dyprev, (const bf16_t*)yprev, (float*)nullptr, (int*)nullptr, g);
     return rc ? rc : launch_status();
 }
 
@@ -1494,9 +1518,10 @@ bool conv_wgrad_mfma_takes_dbias(const ConvDesc& d) { return conv_wgrad_mfma_ok(
 
 int conv_wgrad_mfma(const ConvDesc& g, const void* x, const void* dy, float* dw, float* dbias, int accumulate, hipStream_t st)
 {
-    const long long M = g.Cout, N = (long long)g.k * g.Cin;
+    const long long M = g.Cout, N = g.w_cols ? g.w_cols : (long long)g.k * g.Cin;
     const TileChoice tc = choose_tile(M, N);
     const bool fast = wgrad_fast(g);
+    if (g.w_cols && !fast) return W2L_ERR_SHAPE;  // a folded layer exists only in the dense walk through the frames
     if (dbias && !fast) return W2L_ERR_SHAPE;  // callers ask conv_wgrad_mfma_takes_dbias() first
     const long long extra = dbias ? 1 : 0;     // the column of tiles that yields the bias gradient
     int rc = W2L_OK;

@@ -60,6 +60,8 @@ struct Plan {
     std::vector<size_t> pre, post;  // workspace offsets of conv output (dense) and GLU output (haloed) per layer
     size_t dlogits = 0, crit_len = 0, gdy[3] = {0, 0, 0}, gdh[2] = {0, 0}, ctc = 0, conv = 0, conv0 = 0, dbias = 0, dgs = 0, total = 0;
     size_t ctc_bytes = 0, conv_bytes = 0, dgs_bytes = 0;
+    size_t xfold = 0;      // haloed copy of x with the first layer's stride folded into the channels (0 bytes if unused)
+    bool fold0 = false;
     int status = W2L_OK;
 };
 
@@ -106,9 +108,12 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype, int
         const size_t cw = w2l_conv1d_bwd_weight_workspace_bytes(B, t, l.cin, l.cout, l.k, l.stride, dtype);
         p.conv_bytes = cw > p.conv_bytes ? cw : p.conv_bytes;
         if (i > 0 && L[i - 1].glu) {
-            // fp32 partial sums of a split-reduction data gradient: two copies of dh over the haloed frames, whole tiles
-            const size_t rows = ((size_t)B * (to + 2 * HALO) + 191) / 192 * 192;
-            const size_t sb = 2 * rows * l.cin * 4;
+            // scratch of a split-reduction data gradient (tickets and the fp32 sums of both halves)
+            ConvDesc sd = dense_desc(B, t, l.cin, l.cout, l.k, l.stride);
+            sd.x_pitch = sd.y_pitch = to + 2 * HALO;
+            sd.x_halo = sd.y_halo = HALO;
+            sd.slack = SLACK;
+            const size_t sb = conv_dgrad_scratch_bytes(sd);
             p.dgs_bytes = sb > p.dgs_bytes ? sb : p.dgs_bytes;
         }
         t = to;
@@ -129,6 +134,14 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype, int
     for (int i = 0; i < n; ++i) cmax = L[i].cout > cmax ? L[i].cout : cmax;
     p.dbias = off; off += round_up((size_t)DBIAS_CHUNKS * cmax * 4, 256);
     p.dgs = off; off += round_up(p.dgs_bytes, 256);
+    {
+        // a strided first layer with GLU (its dy is haloed): the weight gradient reads x folded and haloed
+        ConvDesc d0 = dense_desc(B, T, L[0].cin, L[0].cout, L[0].k, L[0].stride), f0;
+        p.fold0 = dtype == W2L_BF16 && L[0].glu && n > 1 && fold_stride(d0, f0) && f0.p <= HALO && f0.Cin % 8 == 0 &&
+                  L[0].cout >= 64;
+        p.xfold = off;
+        if (p.fold0) off += round_up(haloed_bytes(B, f0.T, f0.Cin, es), 256);
+    }
     p.total = off;
     return p;
 }
@@ -290,6 +303,19 @@ static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers,
                 return W2L_ERR_LAUNCH;
         }
         const void* xin = (i == 0) ? x : (const void*)(ws + p.post[i - 1]);
+        if (i == 0 && p.fold0) {
+            // the strided first layer as a stride-1 layer over folded frames: x copied (2 MB) into the haloed time
+            // layout of dy_0, then the same dense weight-gradient kernel as every other layer, bias gradient included
+            ConvDesc f;
+            fold_stride(dense_desc(B, p.Tin[0], l.cin, l.cout, l.k, l.stride), f);
+            f.x_pitch = f.y_pitch = p.Tout[0] + 2 * HALO;
+            f.x_halo = f.y_halo = HALO;
+            f.slack = SLACK;
+            rc = pad_layout_bf16(x, ws + p.xfold, B, f.T, f.Cin, f.x_pitch, HALO, SLACK_ZERO, st);
+            if (rc) return rc;
+            d = f;
+            xin = ws + p.xfold;
+        }
         // weight gradient on the side stream.  Where the MFMA kernel takes it, the bias gradient is one more
         // column of tiles of the same launch; otherwise it is a (small, bandwidth-bound) column sum that stays
         // on the main stream, which has the shorter chain
