@@ -19,6 +19,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA = 2.5e15   # dense bf16 MFMA, FLOP/s (MI355X published)
 PEAK_HBM = 8.0e12         # B/s
+# one step of the criterion recursions on one wavefront with nothing else (no memory traffic, no hand-over):
+# CTC 29 instructions at the 4-cycle issue cadence, ASG's fully connected lattice about 175 cycles, at 2.4 GHz
+CTC_BARE_STEP_NS = 46.0
+ASG_BARE_STEP_NS = 73.0
 
 # HBM bytes per launch of the dominant kernel, from two `rocprofv3 --pmc` runs
 # (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, scaled by the same counters' reading for a
@@ -49,8 +53,8 @@ def event_time_ms(fn, iters, warmup=None):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=200)
     args = ap.parse_args()
@@ -91,6 +95,17 @@ def main():
     dt = (time.perf_counter() - t0) / args.steps
     lv = loss.cpu().numpy()
     assert np.all(np.isfinite(lv)), "non-finite loss in the benchmark step"
+    # the same step over at least half a second of back-to-back launches, whatever --steps was: the part's clock
+    # under a matrix load settles only after some tens of milliseconds, so a short burst reads differently
+    n_sus = max(args.steps, int(0.5 / dt) + 1)
+    for _ in range(10):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_sus):
+        step()
+    torch.cuda.synchronize()
+    dt_sus = (time.perf_counter() - t0) / n_sus
 
     frames = int(cfg["in_len"].sum())
     flops = W.step_flops(layers, B, T)
@@ -167,6 +182,46 @@ def main():
     t_glub_cold = event_time_ms(glu_bwd_rot, args.kernel_iters)
     del ys, hs, dhs, dys
 
+    # config 1: one conv layer k=11, 512 -> 1024, B=16, T=800 (147.64 GFLOP per pass; bar: 118 us = half the MFMA peak)
+    c1 = W.config1()
+    c1x, c1w, c1dy = to_dev(c1["x"], "bf16"), to_dev(c1["w"], "bf16"), to_dev(c1["dy"], "bf16")
+    c1y, c1dx, c1dw = empty(c1["dy"].shape, "bf16"), empty(c1["x"].shape, "bf16"), empty(c1["w"].shape)
+    shp1 = (c1["B"], c1["T"], c1["Cin"], c1["Cout"], c1["k"], 1, P.W2L_BF16)
+    w1f = P.workspace(P.w2l_conv1d_fwd_workspace_bytes(*shp1))
+    w1d = P.workspace(P.w2l_conv1d_bwd_data_workspace_bytes(*shp1))
+    w1w = P.workspace(P.w2l_conv1d_bwd_weight_workspace_bytes(*shp1))
+    gf1 = 2.0 * c1["B"] * c1["T"] * c1["k"] * c1["Cin"] * c1["Cout"]
+    kern1 = {
+        "conv1d_fwd": event_time_ms(lambda: P.w2l_conv1d_fwd(c1x, c1w, None, c1y, 1, w1f), args.kernel_iters),
+        "conv1d_bwd_data": event_time_ms(lambda: P.w2l_conv1d_bwd_data(c1dy, c1w, c1dx, 1, w1d), args.kernel_iters),
+        "conv1d_bwd_weight": event_time_ms(lambda: P.w2l_conv1d_bwd_weight(c1x, c1dy, c1dw, None, 1, False, w1w),
+                                           args.kernel_iters),
+    }
+    del c1y, c1dx, c1dw, w1f, w1d, w1w
+
+    # config 3: the ~10M-parameter model's full step (B=16, T <= 1600)
+    c3 = W.config3()
+    l3 = c3["layers"]
+    x3 = to_dev(c3["x"], "bf16")
+    w3 = [to_dev(w, "bf16") for w in c3["weights"]]
+    b3 = [to_dev(b) for b in c3["biases"]]
+    dw3 = [empty(w.shape) for w in c3["weights"]]
+    db3 = [empty(b.shape) for b in c3["biases"]]
+    tg3, il3, tl3 = to_dev(c3["targets"]), to_dev(c3["in_len"]), to_dev(c3["tgt_len"])
+    ws3 = P.workspace(P.w2l_train_step_workspace_bytes(l3, c3["B"], c3["T"], c3["targets"].shape[1], P.W2L_BF16))
+    loss3 = empty((c3["B"],))
+    t_step3 = event_time_ms(lambda: P.w2l_train_step(l3, w3, b3, dw3, db3, x3, il3, tg3, tl3, loss3, None, 0, 1.0, ws3),
+                            args.kernel_iters)
+    flops3 = W.step_flops(l3, c3["B"], c3["T"])
+    del x3, w3, dw3, ws3
+
+    # per-frame log-softmax forward and backward at the criterion benchmark shape (24000 rows of 29 classes, fp32)
+    lz = to_dev((rng.standard_normal((32 * 750, 29)) * 1.4).astype(np.float32))
+    llp, ldz = empty((32 * 750, 29)), empty((32 * 750, 29))
+    t_lsf = event_time_ms(lambda: P.w2l_logsoftmax_fwd(lz, llp), args.kernel_iters)
+    t_lsb = event_time_ms(lambda: P.w2l_logsoftmax_bwd(llp, lz, ldz), args.kernel_iters)
+    ls_bytes_f, ls_bytes_b = 2 * 32 * 750 * 29 * 4, 3 * 32 * 750 * 29 * 4
+
     # CTC alone at the criterion benchmark shape (B=32, T=750, C=29)
     c2 = W.config2()
     cz, ct, ci, cl = to_dev(c2["logits"]), to_dev(c2["targets"]), to_dev(c2["in_len"]), to_dev(c2["tgt_len"])
@@ -227,6 +282,9 @@ def main():
             "padded_frames_per_step": B * T,
             "gflop_per_step": flops / 1e9,
         },
+        "ms_per_step_sustained": dt_sus * 1e3,
+        "sustained_steps": n_sus,
+        "value_sustained": frames / dt_sus,
         "padded_frames_per_s": B * T / dt,
         "step_tflops": flops / dt / 1e12,
         "step_frac_of_bf16_mfma_peak": flops / dt / PEAK_BF16_MFMA,
@@ -243,6 +301,13 @@ def main():
             "frac_of_measured_ceiling": achieved / mfma_ceiling,
         },
         "measured_ceilings": {"mfma_bf16_tflops": mfma_ceiling / 1e12, "device_copy_GBps": copy_bw / 1e9},
+        "config1_conv(k=11, 512->1024, B=16, T=800; 147.64 GFLOP per pass, bar 0.118 ms)": {
+            k: {"ms": v, "tflops": gf1 / (v * 1e-3) / 1e12, "frac_mfma_peak": gf1 / (v * 1e-3) / PEAK_BF16_MFMA}
+            for k, v in kern1.items()},
+        "config3_train_step(9.2M params, B=16, T<=1600)": {
+            "ms_per_step": t_step3, "frames_per_s": float(c3["in_len"].sum()) / (t_step3 * 1e-3),
+            "gflop_per_step": flops3 / 1e9, "step_tflops": flops3 / (t_step3 * 1e-3) / 1e12,
+            "step_frac_of_bf16_mfma_peak": flops3 / (t_step3 * 1e-3) / PEAK_BF16_MFMA},
         "kernels": {
             **{k: {"ms": v, "tflops": gf / (v * 1e-3) / 1e12, "frac_mfma_peak": gf / (v * 1e-3) / PEAK_BF16_MFMA}
                for k, v in kern.items()},
@@ -254,14 +319,25 @@ def main():
                         "frac_hbm_peak": glub_bytes / (t_glub * 1e-3) / PEAK_HBM,
                         "ms_rotating_buffers": t_glub_cold,
                         "frac_hbm_peak_rotating_buffers": glub_bytes / (t_glub_cold * 1e-3) / PEAK_HBM},
+            "logsoftmax_fwd(24000x29)": {"ms": t_lsf, "GBps": ls_bytes_f / (t_lsf * 1e-3) / 1e9,
+                                         "frac_hbm_peak": ls_bytes_f / (t_lsf * 1e-3) / PEAK_HBM},
+            "logsoftmax_bwd(24000x29)": {"ms": t_lsb, "GBps": ls_bytes_b / (t_lsb * 1e-3) / 1e9,
+                                         "frac_hbm_peak": ls_bytes_b / (t_lsb * 1e-3) / PEAK_HBM},
+            # the criteria are bound by their chain of T_b dependent steps, not by HBM: critical_path_frac = the
+            # longest utterance's serial steps x the time of one bare recursion step on one wavefront (no memory
+            # traffic; measured with a one-wavefront probe) / the whole call (log-softmax, both lattices, gradient)
             "ctc_fwd_bwd(config2)": {"ms": t_ctc, "GBps": ctc_bytes / (t_ctc * 1e-3) / 1e9,
                                      "frac_hbm_peak": ctc_bytes / (t_ctc * 1e-3) / PEAK_HBM,
                                      "serial_steps": int(c2["in_len"].max()),
-                                     "us_per_serial_step": t_ctc * 1e3 / int(c2["in_len"].max())},
+                                     "us_per_serial_step": t_ctc * 1e3 / int(c2["in_len"].max()),
+                                     "bare_step_ns": CTC_BARE_STEP_NS,
+                                     "critical_path_frac": int(c2["in_len"].max()) * CTC_BARE_STEP_NS * 1e-6 / t_ctc},
             "asg_fwd_bwd(B=32,T=750,C=28)": {"ms": t_asg, "GBps": asg_bytes / (t_asg * 1e-3) / 1e9,
                                              "frac_hbm_peak": asg_bytes / (t_asg * 1e-3) / PEAK_HBM,
                                              "serial_steps": int(a2["in_len"].max()),
-                                             "us_per_serial_step": t_asg * 1e3 / int(a2["in_len"].max())},
+                                             "us_per_serial_step": t_asg * 1e3 / int(a2["in_len"].max()),
+                                             "bare_step_ns": ASG_BARE_STEP_NS,
+                                             "critical_path_frac": int(a2["in_len"].max()) * ASG_BARE_STEP_NS * 1e-6 / t_asg},
             "logmel_fwd(B=8,1500x80)": {"ms": t_mel, "GBps": mel_bytes / (t_mel * 1e-3) / 1e9,
                                         "frac_hbm_peak": mel_bytes / (t_mel * 1e-3) / PEAK_HBM,
                                         "frames": mel_frames, "Mframes_per_s": mel_frames / (t_mel * 1e-3) / 1e6},
@@ -287,6 +363,20 @@ def main():
             "sample": "one utterance (b=0, %d valid frames, padded to %d) of the same batch through the same "
                       "11 layers, fp64 oracle train step, %.1f s" % (int(cfg["in_len"][b0]), T, t_cpu),
         }
+        # the oracle's kernels alone: config 1 on two of its 16 utterances (scaled by 8: utterances are independent
+        # and equally long), config 2 (log-softmax + CTC loss and gradient) whole
+        sub = slice(0, 2)
+        f1 = lambda a: np.asarray(a, dtype=np.float64)
+        t1 = time.perf_counter(); oracle.conv1d_fwd(f1(c1["x"][sub]), f1(c1["w"]), None, 1); t_of = time.perf_counter() - t1
+        t1 = time.perf_counter(); oracle.conv1d_bwd_data(f1(c1["dy"][sub]), f1(c1["w"]), c1["T"], 1); t_od = time.perf_counter() - t1
+        t1 = time.perf_counter(); oracle.conv1d_bwd_weight(f1(c1["x"][sub]), f1(c1["dy"][sub]), c1["k"], 1); t_ow = time.perf_counter() - t1
+        t1 = time.perf_counter()
+        oracle.ctc_from_logits(f1(c2["logits"]), c2["targets"], c2["in_len"], c2["tgt_len"])
+        t_oc = time.perf_counter() - t1
+        out["cpu_baseline"]["kernels_ms"] = {
+            "config1_conv1d_fwd": t_of * 8e3, "config1_conv1d_bwd_data": t_od * 8e3, "config1_conv1d_bwd_weight": t_ow * 8e3,
+            "config1_note": "timed on 2 of the 16 utterances, scaled by 8",
+            "config2_logsoftmax_ctc_fwd_bwd": t_oc * 1e3}
     print(json.dumps(out))
 
 

@@ -39,6 +39,7 @@
 // window is then plain in-bounds memory, the per-lane byte offsets are loop invariants, the
 // panel advance is a scalar add on the base pointer, and a load costs three instructions.
 #include <map>
+#include <type_traits>
 #include <mutex>
 #include <utility>
 #include "common.h"
@@ -298,72 +299,165 @@ struct Core {
 #pragma unroll
         for (int u = 0; u < NS; ++u) mfmas(u, [](int) {});
     }
-    // f(m, n, value) for every element this lane holds; m,n relative to the tile
-    template <class F>
-    __device__ __forceinline__ void for_each(int wm, int wn, int lane, F f) const
+    // After reduce_groups() the finished sums of a tile are spread over both reduction groups: group 0 holds
+    // the first OWN0 of a wavefront's TM x TN accumulator blocks, group 1 the rest -- so that the exchange
+    // through LDS and all the epilogue work (rounding, staging, stores) run on all eight wavefronts.
+    // Which blocks a group owns is a compile-time fact inside each of the two branches on the group (which is
+    // uniform over a wavefront), so each branch is straight-line code over statically indexed registers.
+    static constexpr int OWN0 = (TM * TN + 1) / 2;
+    // group G owns blocks [LO<G>, HI<G>) of the wavefront's blocks in (i, j) row-major order
+    template <int G> static constexpr int own_lo() { return (KG == 1 || G == 0) ? 0 : OWN0; }
+    template <int G> static constexpr int own_hi() { return (KG == 1) ? TM * TN : (G == 0 ? OWN0 : TM * TN); }
+    // The two branches on the group are the same code over different registers.  Left alone, the optimiser merges
+    // them into one body that picks its registers by a run-time index -- which turns the accumulators into an
+    // array in scratch memory.  A (comment-only) asm statement that differs between the branches, last in each,
+    // keeps them apart.
+    template <int G> static __device__ __forceinline__ void keep_apart()
+    {
+        if (G == 0) asm volatile("; reduction group 0" ::: "memory");
+        else asm volatile("; reduction group 1" ::: "memory");
+    }
+
+    template <int G, class F>
+    __device__ __forceinline__ void for_each_g(int wm, int wn, int lane, F f) const
     {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int b = own_lo<G>(); b < own_hi<G>(); ++b) {
+                const int i = b / TN, j = b % TN;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) f(m, wn * WTN + j * 32 + (lane & 31), acc[i][j][r]);
+                for (int r = 0; r < 16; ++r) {
+                    const int m = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    f(m, wn * WTN + j * 32 + (lane & 31), acc[i][j][r], j);
+                }
             }
+        keep_apart<G>();
+    }
+    // f(m, n, value, j) for every element this lane holds and whose block its group owns; m,n relative to
+    // the tile, j the element's column block within the wavefront
+    template <class F>
+    __device__ __forceinline__ void for_each(int kg, int wm, int wn, int lane, F f) const
+    {
+        if (KG == 1 || kg == 0) for_each_g<0>(wm, wn, lane, f);
+        else for_each_g<1>(wm, wn, lane, f);
     }
     // bf16 output tile staged in LDS as [rows][BN] (rows padded by 16 bytes so that the two row
     // groups a wavefront writes at once fall on different banks): value + add[j], rounded.
-    // Wavefront rows are taken relative to row_base.
+    // Wavefront rows are taken relative to row_base.  Each group stages the blocks it owns.
     static constexpr int OPITCH = BN * 2 + 16;
-    __device__ __forceinline__ void stage_bf16(unsigned char* buf, const float (&add)[TN], int row_base, int wm, int wn,
-                                               int lane) const
+    template <int G>
+    __device__ __forceinline__ void stage_bf16_g(unsigned char* buf, const float (&add)[TN], int row_base, int wm, int wn,
+                                                 int lane) const
     {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int b = own_lo<G>(); b < own_hi<G>(); ++b) {
+                const int i = b / TN, j = b % TN;
+                const int n = wn * WTN + j * 32 + (lane & 31);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) - row_base;
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int n = wn * WTN + j * 32 + (lane & 31);
+                for (int r = 0; r < 16; ++r) {
+                    const int m = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) - row_base;
                     *reinterpret_cast<bf16_t*>(buf + m * OPITCH + n * 2) = f32_to_bf16(acc[i][j][r] + add[j]);
                 }
             }
+        keep_apart<G>();
     }
-    // KG == 2: add group 1's accumulators into group 0's through LDS (buf: 4 * TM * TN * 4 KB,
-    // free of panel traffic).  Lane-contiguous 16-byte accesses; the sum order is fixed.
+    __device__ __forceinline__ void stage_bf16(unsigned char* buf, const float (&add)[TN], int row_base, int kg, int wm,
+                                               int wn, int lane) const
+    {
+        if (KG == 1 || kg == 0) stage_bf16_g<0>(buf, add, row_base, wm, wn, lane);
+        else stage_bf16_g<1>(buf, add, row_base, wm, wn, lane);
+    }
+    // KG == 2: each group hands the other, through LDS, its accumulators of the blocks the other owns and adds
+    // what it receives to the blocks it owns (buf: 4 * TM * TN * 4 KB, free of panel traffic).  Lane-contiguous
+    // 16-byte accesses; a sum has two terms, so its order is immaterial.
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    template <int G>
+    __device__ __forceinline__ void hand_over(f32x4_t* q) const
+    {
+#pragma unroll
+        for (int b = own_lo<1 - G>(); b < own_hi<1 - G>(); ++b) {
+                const int i = b / TN, j = b % TN;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    f32x4_t v = {acc[i][j][4 * r4], acc[i][j][4 * r4 + 1], acc[i][j][4 * r4 + 2], acc[i][j][4 * r4 + 3]};
+                    q[((i * TN + j) * 4 + r4) * 64] = v;
+                }
+            }
+        keep_apart<G>();
+    }
+    template <int G>
+    __device__ __forceinline__ void take_over(const f32x4_t* q)
+    {
+#pragma unroll
+        for (int b = own_lo<G>(); b < own_hi<G>(); ++b) {
+                const int i = b / TN, j = b % TN;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4_t v = q[((i * TN + j) * 4 + r4) * 64];
+                    acc[i][j][4 * r4] += v[0];
+                    acc[i][j][4 * r4 + 1] += v[1];
+                    acc[i][j][4 * r4 + 2] += v[2];
+                    acc[i][j][4 * r4 + 3] += v[3];
+                }
+            }
+        keep_apart<G>();
+    }
     __device__ __forceinline__ void reduce_groups(unsigned char* buf, int kg, int w4, int lane)
     {
         if (KG == 1) return;
-        typedef __attribute__((ext_vector_type(4))) float f32x4;
-        f32x4* q = reinterpret_cast<f32x4*>(buf) + (size_t)w4 * TM * TN * 4 * 64 + lane;
+        f32x4_t* q = reinterpret_cast<f32x4_t*>(buf) + (size_t)w4 * TM * TN * 4 * 64 + lane;
         __syncthreads();  // every wavefront has finished reading operand panels
-        if (kg == 1) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        f32x4 v = {acc[i][j][4 * r4], acc[i][j][4 * r4 + 1], acc[i][j][4 * r4 + 2], acc[i][j][4 * r4 + 3]};
-                        q[((i * TN + j) * 4 + r4) * 64] = v;
-                    }
-        }
+        if (kg == 0) hand_over<0>(q);
+        else hand_over<1>(q);
         __syncthreads();
-        if (kg == 0) {
+        if (kg == 0) take_over<0>(q);
+        else take_over<1>(q);
+    }
+    // The split data gradient's exchange between the two workgroups of a tile: the blocks this group owns go to
+    // (come from) memory with device-scope cache policy (sc1: written through to, read from, memory).
+    template <int G>
+    __device__ __forceinline__ void store_owned_sc1(f32x4_t* mine) const
+    {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int b = own_lo<G>(); b < own_hi<G>(); ++b) {
+                const int i = b / TN, j = b % TN;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4_t v = {acc[i][j][4 * r4], acc[i][j][4 * r4 + 1], acc[i][j][4 * r4 + 2], acc[i][j][4 * r4 + 3]};
+                    f32x4_t* const dst = mine + (size_t)((i * TN + j) * 4 + r4) * 64;
+                    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v) : "memory");
+                }
+            }
+        keep_apart<G>();
+    }
+    template <int G>
+    __device__ __forceinline__ void add_owned_sc1(const f32x4_t* other)
+    {
+        // all of this group's blocks in flight together (at most OWN0 * 4 loads of 16 bytes per lane), one wait
+        f32x4_t v[TM][TN][4];
 #pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        const f32x4 v = q[((i * TN + j) * 4 + r4) * 64];
-                        acc[i][j][4 * r4] += v[0];
-                        acc[i][j][4 * r4 + 1] += v[1];
-                        acc[i][j][4 * r4 + 2] += v[2];
-                        acc[i][j][4 * r4 + 3] += v[3];
-                    }
-        }
+        for (int b = own_lo<G>(); b < own_hi<G>(); ++b) {
+                const int i = b / TN, j = b % TN;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4_t* const src = other + (size_t)((i * TN + j) * 4 + r4) * 64;
+                    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[i][j][r4]) : "v"(src) : "memory");
+                }
+            }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int b = own_lo<G>(); b < own_hi<G>(); ++b) {
+                const int i = b / TN, j = b % TN;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    // tie each loaded register to the wait above: no use of it may be scheduled ahead of the wait
+                    asm volatile("" : "+v"(v[i][j][r4])::"memory");
+                    acc[i][j][4 * r4] += v[i][j][r4][0];
+                    acc[i][j][4 * r4 + 1] += v[i][j][r4][1];
+                    acc[i][j][4 * r4 + 2] += v[i][j][r4][2];
+                    acc[i][j][4 * r4 + 3] += v[i][j][r4][3];
+                }
+            }
+        keep_apart<G>();
     }
 };
 
@@ -594,7 +688,7 @@ __device__ __forceinline__ void store_tile_bf16(const CoreT& core, unsigned char
 #pragma unroll
     for (int h = 0; h < PASSES; ++h) {
         __syncthreads();  // LDS is free: panels, group reduction or the previous pass are done with
-        if (kg == 0 && (PASSES == 1 || wm == h)) core.stage_bf16(lds, add, h * ROWS, wm, wn, lane);
+        if (PASSES == 1 || wm == h) core.stage_bf16(lds, add, h * ROWS, kg, wm, wn, lane);
         __syncthreads();
 #pragma unroll
         for (int c = threadIdx.x; c < ROWS * CPRW; c += NTHR) {
@@ -720,20 +814,10 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_fwd_k(const bf16_t* __rest
             [&](int r) { return m0 + r < M ? out_row(m0 + r, g.Tp, g.y_pitch, g.y_halo) : -1LL; });
         return;
     }
-    if (kg != 0) return;
-#pragma unroll
-    for (int i = 0; i < core.TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int m = m0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (m >= M) continue;
-            const size_t row = (size_t)out_row(m, g.Tp, g.y_pitch, g.y_halo) * N;
-#pragma unroll
-            for (int j = 0; j < core.TN; ++j) {
-                const int n = n0 + wn * core.WTN + j * 32 + (lane & 31);
-                if (n < N) Elem<TO>::store(y, row + n, core.acc[i][j][r] + bv[j]);
-            }
-        }
+    core.for_each(kg, wm, wn, lane, [&](int mm, int nn, float v, int j) {
+        const int m = m0 + mm, n = n0 + nn;
+        if (m < M && n < N) Elem<TO>::store(y, (size_t)out_row(m, g.Tp, g.y_pitch, g.y_halo) * N + n, v + bv[j]);
+    });
 }
 
 // dynamic LDS of a slab kernel: two slabs + three weight panels, or the fp32 tile of the group reduction
@@ -807,7 +891,7 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
         static_assert(BM * PITCH <= LDS_BYTES, "output tile staging");
         bf16_t* yo = reinterpret_cast<bf16_t*>(y);
         __syncthreads();
-        if (kg == 0) core.stage_bf16(lds, bv, 0, wm, wn, lane);
+        core.stage_bf16(lds, bv, 0, kg, wm, wn, lane);
         __syncthreads();
         const long long zero_end = (long long)g.B * g.x_pitch + LAYOUT_SLACK_ZERO;  // h is zero up to here outside real frames
         const int ch0 = tn * (BN / 2);
@@ -854,19 +938,11 @@ __global__ __launch_bounds__(256 * KG) void conv_fwd_slab_k(const bf16_t* __rest
         store_tile_bf16<BM, BN, 256 * KG, LDS_BYTES>(core, lds, bv, reinterpret_cast<bf16_t*>(y), n0, N, kg, wm, wn, lane, rowoff);
         return;
     }
-    if (kg != 0) return;
-#pragma unroll
-    for (int i = 0; i < core.TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const long long ro = rowoff(wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3));
-            if (ro < 0) continue;
-#pragma unroll
-            for (int j = 0; j < core.TN; ++j) {
-                const int n = n0 + wn * core.WTN + j * 32 + (lane & 31);
-                if (n < N) Elem<TO>::store(y, (size_t)ro * N + n, core.acc[i][j][r] + bv[j]);
-            }
-        }
+    core.for_each(kg, wm, wn, lane, [&](int mm, int nn, float v, int j) {
+        const long long ro = rowoff(mm);
+        const int n = n0 + nn;
+        if (ro >= 0 && n < N) Elem<TO>::store(y, (size_t)ro * N + n, v + bv[j]);
+    });
 }
 
 // =============================== data gradient (stride 1) =============================
@@ -1006,17 +1082,9 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
         // cache policy (sc1: written through to, and read from, memory), and each side waits for its
         // own accesses to complete around the ticket -- no cache-wide write-back or invalidate, which
         // would throw out the operand panels the other workgroups of this L2 are streaming.
-        if (kg == 0) {
-#pragma unroll
-            for (int i = 0; i < core.TM; ++i)
-#pragma unroll
-                for (int j = 0; j < core.TN; ++j)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        const f32x4 v = {core.acc[i][j][4 * r4], core.acc[i][j][4 * r4 + 1], core.acc[i][j][4 * r4 + 2], core.acc[i][j][4 * r4 + 3]};
-                        asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(mine + (size_t)((i * core.TN + j) * 4 + r4) * 64), "v"(v) : "memory");
-                    }
-        }
+        // (each reduction group stores, and later loads, the accumulator blocks it owns)
+        if (kg == 0) core.template store_owned_sc1<0>(mine);
+        else core.template store_owned_sc1<1>(mine);
         wait_vmcnt<0>();   // this thread's sums have reached memory
         __syncthreads();   // ... and every thread's
         int* ticket_lds = reinterpret_cast<int*>(lds);  // the panel ring is free by now
@@ -1024,30 +1092,8 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
         __syncthreads();
         const int ticket = *ticket_lds;
         if (ticket == 0) return;  // first of the pair: the other workgroup finishes the tile
-        if (kg == 0) {
-#pragma unroll
-            for (int i = 0; i < core.TM; ++i) {
-                // one row of accumulator blocks at a time: its loads in flight together, then one wait
-                f32x4 v[core.TN][4];
-#pragma unroll
-                for (int j = 0; j < core.TN; ++j)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4)
-                        asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[j][r4]) : "v"(other + (size_t)((i * core.TN + j) * 4 + r4) * 64) : "memory");
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-                for (int j = 0; j < core.TN; ++j)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        // tie each loaded register to the wait above: no use of it may be scheduled ahead of the wait
-                        asm volatile("" : "+v"(v[j][r4])::"memory");
-                        core.acc[i][j][4 * r4] += v[j][r4][0];
-                        core.acc[i][j][4 * r4 + 1] += v[j][r4][1];
-                        core.acc[i][j][4 * r4 + 2] += v[j][r4][2];
-                        core.acc[i][j][4 * r4 + 3] += v[j][r4][3];
-                    }
-            }
-        }
+        if (kg == 0) core.template add_owned_sc1<0>(other);
+        else core.template add_owned_sc1<1>(other);
     }
     float zero[core.TN];
 #pragma unroll
@@ -1063,7 +1109,7 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
     constexpr int PITCH = core.OPITCH, CPRW = BN / 8, NTHR = 256 * KG;
     static_assert(BM * PITCH <= LDS_BYTES && (BM * CPRW) % NTHR == 0, "dh tile staging");
     __syncthreads();
-    if (kg == 0) core.stage_bf16(lds, zero, 0, wm, wn, lane);
+    core.stage_bf16(lds, zero, 0, kg, wm, wn, lane);
     __syncthreads();
     const long long alloc_frames = (long long)g.B * g.y_pitch + g.slack;
 #pragma unroll 2
@@ -1199,15 +1245,14 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __re
         },
         grp, kg, wm, wn, lane);
     core.reduce_groups(lds, kg, w4, lane);
-    if (kg != 0) return;
     if (bias_tile) {
-        core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
+        core.for_each(kg, wm, wn, lane, [&](int mm, int nn, float v, int) {
             const int m = m0 + mm;
             if (nn == 0 && m < M) dbias[m] = accumulate ? dbias[m] + v : v;
         });
         return;
     }
-    core.for_each(wm, wn, lane, [&](int mm, int nn, float v) {
+    core.for_each(kg, wm, wn, lane, [&](int mm, int nn, float v, int) {
         const int m = m0 + mm, n = n0 + nn;
         if (m < M && n < N) {
             const size_t i = (size_t)m * N + n;
