@@ -149,6 +149,11 @@ bool conv_wgrad_mfma_ok(const ConvDesc& d);
 bool conv_wgrad_mfma_takes_dbias(const ConvDesc& d);
 int conv_wgrad_mfma(const ConvDesc& d, const void* x, const void* dy, float* dw, float* dbias, int accumulate, hipStream_t st);
 
+// w2l_ctc_fwd_bwd with in_len counted before a total stride len_div (ctc.hip): the criterion sees ceil(in_len / len_div)
+int ctc_fwd_bwd_strided(const float* input, int is_logits, const int* targets, const int* in_len, const int* tgt_len,
+                        float* loss, float* grad, int B, int Tp, int C, int Lmax, int blank, float grad_scale,
+                        void* workspace, size_t ws_bytes, void* stream, int len_div);
+
 // GLU with an explicit output layout (elementwise.hip).  y (and dh) are dense [B*Tp, Cout]
 // ([B*Tp, Cout/2]); the output is written with the given pitch and halo, halo and slack
 // frames included (as zeros).

@@ -214,15 +214,24 @@ __global__ __launch_bounds__(256) void wgrad_skinny_stage1(const TX* __restrict_
         }
         __syncthreads();
         if (n < N) {
-            const int rows = (r_end - r0 < SKINNY_ROWS) ? r_end - r0 : SKINNY_ROWS;
-            for (int rr = 0; rr < rows; ++rr) {
-                const int r = r0 + rr;
-                const int b = r / d.Tp, tp = r - b * d.Tp;
-                const int t = d.s * tp + j - d.p;
-                if (t < 0 || t >= d.T) continue;
-                const float xv = Elem<TX>::load(x, ((size_t)b * d.x_pitch + d.x_halo + t) * d.Cin + ci);
+            // eight rows at a time: their x values are loaded together (independent loads, one latency), a row
+            // outside the utterance or past the chunk contributes 0 (its dy row in LDS is 0 as well past the chunk)
+            for (int rr0 = 0; rr0 < SKINNY_ROWS; rr0 += 8) {
+                if (r0 + rr0 >= r_end) break;
+                float xv[8];
 #pragma unroll
-                for (int c = 0; c < 32; ++c) acc[c] = fmaf(dyt[rr][c], xv, acc[c]);
+                for (int u = 0; u < 8; ++u) {
+                    const int r = min(r0 + rr0 + u, r_end - 1);
+                    const int b = r / d.Tp, tp = r - b * d.Tp;
+                    const int t = d.s * tp + j - d.p;
+                    const bool ok = t >= 0 && t < d.T && r0 + rr0 + u < r_end;
+                    const float v = Elem<TX>::load(x, ((size_t)b * d.x_pitch + d.x_halo + (ok ? t : 0)) * d.Cin + ci);
+                    xv[u] = ok ? v : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+#pragma unroll
+                    for (int c = 0; c < 32; ++c) acc[c] = fmaf(dyt[rr0 + u][c], xv[u], acc[c]);
             }
         }
         __syncthreads();
@@ -305,7 +314,13 @@ __global__ void colsum_stage2(const float* part, float* dbias, int chunks, int C
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= Cout) return;
     float acc = 0.f;
-    for (int i = 0; i < chunks; ++i) acc += part[(size_t)i * Cout + c];
+    for (int i0 = 0; i0 < chunks; i0 += 16) {
+        float v[16];  // independent loads, then added in order
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = (i0 + u < chunks) ? part[(size_t)(i0 + u) * Cout + c] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc += v[u];
+    }
     dbias[c] = accumulate ? dbias[c] + acc : acc;
 }
 

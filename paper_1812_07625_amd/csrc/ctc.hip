@@ -31,10 +31,12 @@ constexpr double LN2 = 0.69314718055994530942;
 
 struct CtcDims {
     int B, Tp, C, Lmax, blank;
+    int len_div;  // in_len[] counts frames before the network's total stride: the criterion sees ceil(in_len / len_div)
     int Sp;    // lattice row pitch in states = 2*Lmax+4 (the last pair is a spare); a state is 8 bytes
     int rows;  // lattice rows per utterance = Tp + 2*LAT_PAD: frame t is row LAT_PAD + t
 };
 
+__device__ __forceinline__ int crit_len(int n, int div) { return (n < 0 || div <= 1) ? n : (n + div - 1) / div; }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     float2* const tbl = reinterpret_cast<float2*>(dyn_smem);  // TABLE: [2][C][TABLE_PITCH] (pm, pe)
     const int dir = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
-    const int T = in_len[b], L = tgt_len[b];
+    const int T = crit_len(in_len[b], d.len_div), L = tgt_len[b];
     if (tid == 0) {
         bad_len = (T < 0 || T > d.Tp || L < 0 || L > d.Lmax) ? 1 : 0;
         bad = 0;
@@ -409,7 +411,7 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float* gb = grad + (size_t)b * d.Tp * d.C;
     const float ls = loss[b];
-    const int T = in_len[b];
+    const int T = crit_len(in_len[b], d.len_div);
     const bool live = isfinite(ls) && T > 0;  // NaN (invalid) and +inf (no alignment) give zero rows
     const int t_end = min(t0 + rows_per_wg, d.Tp);
     if (!live || t0 >= T) {
@@ -591,7 +593,8 @@ int ctc_check_args(const float* input, const int* targets, const int* in_len, co
 
 // the three launches, arguments already checked; workspace: ws_layout().total bytes of device memory
 int ctc_run(const float* input, int is_logits, const int* targets, const int* in_len, const int* tgt_len, float* loss,
-            float* grad, int B, int Tp, int C, int Lmax, int blank, float grad_scale, void* workspace, void* stream)
+            float* grad, int B, int Tp, int C, int Lmax, int blank, float grad_scale, void* workspace, void* stream,
+            int len_div = 1)
 {
     const WsLayout w = ws_layout(B, Tp, C, Lmax);
     hipStream_t st = (hipStream_t)stream;
@@ -608,7 +611,7 @@ int ctc_run(const float* input, int is_logits, const int* targets, const int* in
     float2* beta = reinterpret_cast<float2*>(ws + w.beta);
     int* sort_order = reinterpret_cast<int*>(ws + w.order);
     int* sort_start = reinterpret_cast<int*>(ws + w.cstart);
-    CtcDims d{B, Tp, C, Lmax, blank, 2 * Lmax + 4, Tp + 2 * LAT_PAD};
+    CtcDims d{B, Tp, C, Lmax, blank, len_div, 2 * Lmax + 4, Tp + 2 * LAT_PAD};
 
     const size_t lds2 = grad_lds_bytes(Lmax, C);
     if (lds2 > 160 * 1024) return W2L_ERR_SHAPE;
@@ -653,6 +656,22 @@ int ctc_run(const float* input, int is_logits, const int* targets, const int* in
     return launch_status();
 }
 }  // namespace
+
+namespace w2l {
+// w2l_ctc_fwd_bwd for the train step: in_len counts input frames before the network's total stride `len_div`
+int ctc_fwd_bwd_strided(const float* input, int is_logits, const int* targets, const int* in_len, const int* tgt_len,
+                        float* loss, float* grad, int B, int Tp, int C, int Lmax, int blank, float grad_scale,
+                        void* workspace, size_t ws_bytes, void* stream, int len_div)
+{
+    const int rc = ctc_check_args(input, targets, in_len, tgt_len, loss, grad, B, Tp, C, Lmax, blank);
+    if (rc) return rc;
+    if (len_div < 1) return W2L_ERR_SHAPE;
+    if (!workspace || ws_bytes < ws_layout(B, Tp, C, Lmax).total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return W2L_ERR_WORKSPACE;
+    return ctc_run(input, is_logits, targets, in_len, tgt_len, loss, grad, B, Tp, C, Lmax, blank, grad_scale, workspace,
+                   stream, len_div);
+}
+}  // namespace w2l
 
 extern "C" int w2l_ctc_fwd_bwd(const float* input, int is_logits, const int* targets, const int* in_len,
                                const int* tgt_len, float* loss, float* grad, int B, int Tp, int C, int Lmax,

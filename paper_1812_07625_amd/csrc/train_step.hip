@@ -236,17 +236,18 @@ static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers,
     }
 
     // ---- criterion: frames seen = ceil(in_len / total stride)
-    int* clen = reinterpret_cast<int*>(ws + p.crit_len);
-    hipLaunchKernelGGL(crit_len_k, dim3((B + 255) / 256), dim3(256), 0, st, in_len, clen, B, p.tot_stride);
-    rc = launch_status();
-    if (rc) return rc;
     float* dz = reinterpret_cast<float*>(ws + p.dlogits);
-    if (criterion == CRIT_ASG)
+    if (criterion == CRIT_ASG) {
+        int* clen = reinterpret_cast<int*>(ws + p.crit_len);
+        hipLaunchKernelGGL(crit_len_k, dim3((B + 255) / 256), dim3(256), 0, st, in_len, clen, B, p.tot_stride);
+        rc = launch_status();
+        if (rc) return rc;
         rc = w2l_asg_fwd_bwd(z, trans, targets, clen, tgt_len, loss, dz, dtrans, B, p.Tlast, p.C, Lmax, grad_scale,
                              ws + p.ctc, p.ctc_bytes, stream);
-    else
-        rc = w2l_ctc_fwd_bwd(z, 1, targets, clen, tgt_len, loss, dz, B, p.Tlast, p.C, Lmax, blank, grad_scale,
-                             ws + p.ctc, p.ctc_bytes, stream);
+    } else {
+        rc = ctc_fwd_bwd_strided(z, 1, targets, in_len, tgt_len, loss, dz, B, p.Tlast, p.C, Lmax, blank, grad_scale,
+                                 ws + p.ctc, p.ctc_bytes, stream, p.tot_stride);
+    }
     if (rc) return rc;
 
     // ---- backward.  dh = gradient wrt layer i's output (dense); dy = gradient wrt its conv
