@@ -309,10 +309,14 @@ int w2l_train_step_asg(const w2l_layer *layers, int n_layers,
 /* ---- measurement aid (not part of the training path) -----------------------------------
  * Launches `blocks` workgroups of 4 wavefronts, each wavefront issuing 8*iters independent
  * v_mfma_f32_32x32x16_bf16 (32768 FLOP each) and nothing else; out: [blocks*256] fp32 sink.
- * Timed by the caller, it gives the bf16 MFMA rate the part sustains at its clocks under
- * load -- the practical ceiling next to the published 2.5 PFLOP/s (Sec. 4 of the paper
- * reports timings on its own hardware only; rooflines here are measured, not quoted). */
-int w2l_probe_mfma(float *out, int blocks, int iters, void *stream);
+ * random_operands = 0: every operand element is 1.0 or 2.0; != 0: random sign and mantissa bits,
+ * as real activations and weights have.  Timed by the caller, it gives the bf16 MFMA rate the
+ * part sustains at its clocks under load -- the practical ceiling next to the published
+ * 2.5 PFLOP/s.  The part is power-limited and the matrix pipe's power depends on how many operand
+ * bits toggle, so the ceiling that applies to real data is the one measured with random operands
+ * (Sec. 4 of the paper reports timings on its own hardware only; rooflines here are measured,
+ * not quoted). */
+int w2l_probe_mfma(float *out, int blocks, int iters, int random_operands, void *stream);
 
 #ifdef __cplusplus
 }

@@ -76,7 +76,7 @@ def _load():
         "w2l_asg_workspace_bytes": (sz, [i] * 4),
         "w2l_asg_fwd_bwd": (i, [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, f, vp, sz, vp]),
         "w2l_asg_check_targets_host": (i, [vp, vp, vp, i, i, i, i]),
-        "w2l_probe_mfma": (i, [vp, i, i, vp]),
+        "w2l_probe_mfma": (i, [vp, i, i, i, vp]),
         "w2l_sgd_momentum_step": (i, [vp, vp, vp, vp, ll, f, f, f, vp]),
         "w2l_train_step_workspace_bytes": (sz, [C.POINTER(w2l_layer), i, i, i, i, i]),
         "w2l_train_step": (i, [C.POINTER(w2l_layer), i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
@@ -310,9 +310,9 @@ def w2l_asg_check_targets_host(targets, in_len, tgt_len, Tp, Cc) -> int:
                                           t.shape[1])
 
 
-def w2l_probe_mfma(out, blocks, iters, stream=None):
-    """Measurement aid: blocks*4 wavefronts each issue 8*iters MFMAs (32768 FLOP each)."""
-    _check(raw.w2l_probe_mfma(_p(out), blocks, iters, _stream(stream)), "w2l_probe_mfma")
+def w2l_probe_mfma(out, blocks, iters, random_operands=False, stream=None):
+    """Measurement aid: blocks*4 wavefronts each issue 8*iters MFMAs (32768 FLOP each); returns the FLOP count."""
+    _check(raw.w2l_probe_mfma(_p(out), blocks, iters, int(bool(random_operands)), _stream(stream)), "w2l_probe_mfma")
     return 2.0 * 32 * 32 * 16 * 8 * iters * blocks * 4
 
 

@@ -237,16 +237,39 @@ extern "C" int w2l_conv1d_bwd_weight(const void* x, const void* dy, float* dw, f
 namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
 typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned probe_u32x4;
+// RANDOM: operands with random sign and mantissa bits (what real activations look like to the multipliers);
+// otherwise small integers.  The part is power-limited, and the power of the matrix pipe depends on how many
+// operand bits toggle: the two settings sustain different clocks.
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void mfma_probe_k(float* out, int iters)
 {
     probe_f32x16 acc[8];
     for (int i = 0; i < 8; ++i)
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    probe_bf16x8 a, b;
-    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)((threadIdx.x + e) & 7); b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 3); }
+    probe_u32x4 a[4], b[4];
+    unsigned h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    for (int q = 0; q < 4; ++q)
+        for (int e = 0; e < 4; ++e) {
+            h = h * 1664525u + 1013904223u;
+            unsigned va = h;
+            h = h * 1664525u + 1013904223u;
+            unsigned vb = h;
+            if (RANDOM) {  // two bf16 per word: random sign and mantissa, magnitude in [0.5, 1)
+                va = (va & 0x807f807fu) | 0x3f003f00u;
+                vb = (vb & 0x807f807fu) | 0x3f003f00u;
+            } else {       // 1.0 and 2.0 everywhere
+                va = 0x3f803f80u;
+                vb = 0x40004000u;
+            }
+            a[q][e] = va;
+            b[q][e] = vb;
+        }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+        for (int i = 0; i < 8; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(probe_bf16x8, a[i & 3]),
+                                                             __builtin_bit_cast(probe_bf16x8, b[(i + it) & 3]), acc[i], 0, 0, 0);
     }
     float s = 0.f;
     for (int i = 0; i < 8; ++i)
@@ -255,10 +278,11 @@ __global__ __launch_bounds__(256) void mfma_probe_k(float* out, int iters)
 }
 }  // namespace
 
-extern "C" int w2l_probe_mfma(float* out, int blocks, int iters, void* stream)
+extern "C" int w2l_probe_mfma(float* out, int blocks, int iters, int random_operands, void* stream)
 {
     if (!out) return W2L_ERR_NULL;
     if (blocks <= 0 || blocks > 65535 || iters <= 0) return W2L_ERR_SHAPE;
-    hipLaunchKernelGGL(mfma_probe_k, dim3(blocks), dim3(256), 0, (hipStream_t)stream, out, iters);
+    if (random_operands) hipLaunchKernelGGL(mfma_probe_k<true>, dim3(blocks), dim3(256), 0, (hipStream_t)stream, out, iters);
+    else hipLaunchKernelGGL(mfma_probe_k<false>, dim3(blocks), dim3(256), 0, (hipStream_t)stream, out, iters);
     return launch_status();
 }

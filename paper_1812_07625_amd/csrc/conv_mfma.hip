@@ -1048,8 +1048,21 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
     constexpr int LDS_BYTES = slab_lds_bytes(BM, BN, SROWS, KG);
     const int F = (g.B - 1) * g.y_pitch + g.Tp;
     const int N = g.Cin;
-    int tm, tn;
-    tile_of_block((F + BM - 1) / BM, (N + BN - 1) / BN, tm, tn, true);
+    int tm, tn, half = 0;
+    const int tiles_m = (F + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    if (part && g.xcd_m > 0) {
+        // split reduction, 1-D grid of 2 * tiles workgroups: an XCD takes one half of the reduction (its parity)
+        // of one of xcd_m x (4 / xcd_m) rectangular blocks of tiles, so its L2 streams only that block's rows of
+        // dy and columns of w, and of those only its half of the channel blocks
+        const int x = blockIdx.x % 8, q = blockIdx.x / 8, blk = x >> 1;
+        const int xn = 4 / g.xcd_m, am = tiles_m / g.xcd_m, an = tiles_n / xn;
+        half = x & 1;
+        tn = (blk % xn) * an + q % an;
+        tm = (blk / xn) * am + q / an;
+    } else {
+        tile_of_block(tiles_m, tiles_n, tm, tn, true);
+        half = blockIdx.y;
+    }
     const int f0 = g.y_halo + tm * BM, n0 = tn * BN;  // dy layout frame of tile row 0
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kg = wave >> 2, w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
@@ -1062,7 +1075,7 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
     for (int i = 0; i < PS::NI; ++i) ps.set_fast(i, (long long)(f0 - g.p + PS::row_of(i)) * g.Cout);
     Core<BM, BN, 64, KG, 1, PS, PB> core;
     core.zero();
-    const int nparts = gridDim.y, ncb = g.Cout / 64 / nparts, cb0 = blockIdx.y * ncb;  // this workgroup's channel blocks
+    const int nparts = part ? 2 : 1, ncb = g.Cout / 64 / nparts, cb0 = half * ncb;  // this workgroup's channel blocks
     run_slab_pipeline<PS::NI, PB::NI, PS::BYTES, PB::BYTES>(
         core, lds, ncb, g.k,
         [&](int i, int cb, unsigned dst) { ps.issue_fast(i, dy + (cb0 + cb) * 64, dst); },
@@ -1075,9 +1088,9 @@ __global__ __launch_bounds__(256 * KG) void conv_dgrad_slab_k(const bf16_t* __re
         typedef __attribute__((ext_vector_type(4))) float f32x4;
         constexpr int QUADS = core.TM * core.TN * 4;                       // 16-byte pieces per lane
         constexpr size_t SLOT = (size_t)4 * QUADS * 64;                    // f32x4 per workgroup slot
-        const int tile = blockIdx.x;
-        f32x4* mine = reinterpret_cast<f32x4*>(part) + ((size_t)tile * 2 + blockIdx.y) * SLOT + ((size_t)w4 * QUADS) * 64 + lane;
-        const f32x4* other = reinterpret_cast<const f32x4*>(part) + ((size_t)tile * 2 + (1 - blockIdx.y)) * SLOT + ((size_t)w4 * QUADS) * 64 + lane;
+        const int tile = tm * tiles_n + tn;
+        f32x4* mine = reinterpret_cast<f32x4*>(part) + ((size_t)tile * 2 + half) * SLOT + ((size_t)w4 * QUADS) * 64 + lane;
+        const f32x4* other = reinterpret_cast<const f32x4*>(part) + ((size_t)tile * 2 + (1 - half)) * SLOT + ((size_t)w4 * QUADS) * 64 + lane;
         // The sums cross from one XCD's L2 to another's: they are stored and loaded with device-scope
         // cache policy (sc1: written through to, and read from, memory), and each side waits for its
         // own accesses to complete around the ticket -- no cache-wide write-back or invalidate, which
@@ -1313,6 +1326,20 @@ int xcd_split(long long tiles_m, long long tiles_n, double bytes_m, double bytes
     return best;
 }
 
+// The same for the split data gradient: 2 reduction halves x 4 blocks of tiles.  0 if the grid does not divide.
+int xcd_split4(long long tiles_m, long long tiles_n, double bytes_m, double bytes_n)
+{
+    int best = 0;
+    double best_cost = 0;
+    for (int xm = 1; xm <= 4; xm *= 2) {
+        const int xn = 4 / xm;
+        if (tiles_m % xm || tiles_n % xn) continue;
+        const double cost = (double)(tiles_m / xm) * bytes_m + (double)(tiles_n / xn) * bytes_n;
+        if (!best || cost < best_cost) { best = xm; best_cost = cost; }
+    }
+    return best;
+}
+
 bool common_ok(const ConvDesc& d)
 {
     if (d.Cin % 8 || d.Cout % 8) return false;
@@ -1459,9 +1486,18 @@ size_t conv_dgrad_scratch_bytes(const ConvDesc& g)
     return DGRAD_TICKET_BYTES + tiles * 2 * 192 * 192 * 4;
 }
 
-int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, void* scratch, size_t scratch_bytes,
+// grid and XCD cut of the split data gradient's launch (two workgroups per 192x192 tile)
+static dim3 dgrad_split_grid(ConvDesc& g, long long tiles_m, long long tiles_n)
+{
+    g.xcd_m = xcd_split4(tiles_m, tiles_n, (double)(192 + g.k - 1) * g.Cout / 2, 192.0 * g.k * g.Cout / 2);
+    const unsigned tiles = (unsigned)(tiles_m * tiles_n);
+    return g.xcd_m > 0 ? dim3(2 * tiles) : dim3(tiles, 2);
+}
+
+int conv_dgrad_mfma(const ConvDesc& g0, const void* dy, const void* w, void* dx, void* scratch, size_t scratch_bytes,
                     hipStream_t st)
 {
+    ConvDesc g = g0;
     const long long M = (long long)g.B * g.T, N = g.Cin;
     const TileChoice tc = choose_tile(M, N);
     const bool fast = halo_ok_y(g);
@@ -1477,7 +1513,9 @@ int conv_dgrad_mfma(const ConvDesc& g, const void* dy, const void* w, void* dx, 
         if (rc) return rc;
         rc = set_lds(conv_dgrad_slab_k<192, 192, 256, 2, false>, bytes);
         if (rc) return rc;
-        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, false>), dim3((unsigned)tiles, 2), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, part, tickets, g);
+        const dim3 grid = dgrad_split_grid(g, (F + 191) / 192, (N + 191) / 192);
+        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, false>), grid, dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const bf16_t*)nullptr, part, tickets, g);
+        g.xcd_m = 0;
         return launch_status();
     }
     if (fast && tc.bm == 256 && tc.bn == 128 && slab_ok(g, 256, 320, g.Cout, g.Tp, g.y_pitch, g.y_halo)) {
@@ -1508,10 +1546,11 @@ bool conv_dgrad_glu_ok(const ConvDesc& d)
            d.T == d.Tp && d.slack >= LAYOUT_SLACK_ZERO && slab_ok(d, 256, 320, d.Cout, d.Tp, d.y_pitch, d.y_halo);
 }
 
-int conv_dgrad_glu(const ConvDesc& g, const void* dy, const void* w, const void* yprev, void* dyprev, void* scratch,
+int conv_dgrad_glu(const ConvDesc& g0, const void* dy, const void* w, const void* yprev, void* dyprev, void* scratch,
                    size_t scratch_bytes, hipStream_t st)
 {
-    if (!conv_dgrad_glu_ok(g)) return W2L_ERR_SHAPE;
+    if (!conv_dgrad_glu_ok(g0)) return W2L_ERR_SHAPE;
+    ConvDesc g = g0;
     const long long F = (long long)(g.B - 1) * g.y_pitch + g.Tp;
     const long long z_end = (long long)g.B * g.y_pitch + LAYOUT_SLACK_ZERO;
     if (scratch && dgrad_split_ok(g) && scratch_bytes >= conv_dgrad_scratch_bytes(g)) {
@@ -1529,7 +1568,8 @@ int conv_dgrad_glu(const ConvDesc& g, const void* dy, const void* w, const void*
         if (rc) return rc;
         rc = set_lds(conv_dgrad_slab_k<192, 192, 256, 2, true>, bytes);
         if (rc) return rc;
-        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, true>), dim3((unsigned)tiles, 2), dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dyprev, (const bf16_t*)yprev, part, tickets, g);
+        const dim3 grid = dgrad_split_grid(g, tiles_m, (g.Cin + 191) / 192);
+        hipLaunchKernelGGL((conv_dgrad_slab_k<192, 192, 256, 2, true>), grid, dim3(512), bytes, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dyprev, (const bf16_t*)yprev, part, tickets, g);
         return launch_status();
     }
     constexpr int BM = 256, BN = 128;
