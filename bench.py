@@ -28,9 +28,8 @@ ASG_BARE_STEP_NS = 73.0
 # (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, scaled by the same counters' reading for a
 # device copy of known size).  The runs and the factor are recorded in
 # profiles/conv_kernels_config4_body_hbm_traffic.txt.
-# For conv1d_bwd_data the figure is the split-reduction tile kernel alone; its combining pass
-# moves another 47 MB per call.
-DOMINANT_KERNEL_HBM_BYTES = {"conv1d_bwd_data": 166989279, "conv1d_fwd": 236551629, "conv1d_bwd_weight": 202474160}
+# (The staging copy each entry point runs first moves another 19 to 57 MB; it is a separate kernel.)
+DOMINANT_KERNEL_HBM_BYTES = {"conv1d_bwd_data": 156499271, "conv1d_fwd": 109134230, "conv1d_bwd_weight": 202501506}
 
 
 def event_time_ms(fn, iters, warmup=None):
@@ -164,6 +163,15 @@ def main():
     hdy2 = empty((rows, L["cout"]), "bf16")
     t_glub = event_time_ms(lambda: P.w2l_glu_bwd(hy, hdh, hdy2), args.kernel_iters)
     glub_bytes = rows * L["cout"] * 2 * 2 + rows * (L["cout"] // 2) * 2
+    # what a plain device copy moving the same number of bytes achieves (half read, half written): at a few tens of
+    # megabytes a launch is a handful of microseconds and its ramp-up and tail are a visible part of it
+    def copy_rate(nbytes):
+        a = torch.empty(nbytes // 2, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        t = event_time_ms(lambda: b.copy_(a), args.kernel_iters)
+        return 2.0 * a.numel() / (t * 1e-3)
+
+    copy_glu, copy_glub = copy_rate(glu_bytes), copy_rate(glub_bytes)
     # the same two kernels rotating over 16 sets of buffers (0.44 / 0.74 GB), so that no launch finds its
     # operands in the 256 MB memory-side cache: the figure against HBM proper
     nset = 16
@@ -321,11 +329,15 @@ def main():
             "glu_fwd": {"ms": t_glu, "GBps": glu_bytes / (t_glu * 1e-3) / 1e9,
                         "frac_hbm_peak": glu_bytes / (t_glu * 1e-3) / PEAK_HBM,
                         "ms_rotating_buffers": t_glu_cold,
-                        "frac_hbm_peak_rotating_buffers": glu_bytes / (t_glu_cold * 1e-3) / PEAK_HBM},
+                        "frac_hbm_peak_rotating_buffers": glu_bytes / (t_glu_cold * 1e-3) / PEAK_HBM,
+                        "device_copy_same_bytes_GBps": copy_glu / 1e9,
+                        "frac_of_device_copy_same_bytes": glu_bytes / (t_glu * 1e-3) / copy_glu},
             "glu_bwd": {"ms": t_glub, "GBps": glub_bytes / (t_glub * 1e-3) / 1e9,
                         "frac_hbm_peak": glub_bytes / (t_glub * 1e-3) / PEAK_HBM,
                         "ms_rotating_buffers": t_glub_cold,
-                        "frac_hbm_peak_rotating_buffers": glub_bytes / (t_glub_cold * 1e-3) / PEAK_HBM},
+                        "frac_hbm_peak_rotating_buffers": glub_bytes / (t_glub_cold * 1e-3) / PEAK_HBM,
+                        "device_copy_same_bytes_GBps": copy_glub / 1e9,
+                        "frac_of_device_copy_same_bytes": glub_bytes / (t_glub * 1e-3) / copy_glub},
             "logsoftmax_fwd(24000x29)": {"ms": t_lsf, "GBps": ls_bytes_f / (t_lsf * 1e-3) / 1e9,
                                          "frac_hbm_peak": ls_bytes_f / (t_lsf * 1e-3) / PEAK_HBM},
             "logsoftmax_bwd(24000x29)": {"ms": t_lsb, "GBps": ls_bytes_b / (t_lsb * 1e-3) / 1e9,
