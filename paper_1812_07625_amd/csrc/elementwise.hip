@@ -16,7 +16,8 @@ template <typename T> struct Vec8;
 template <> struct Vec8<bf16_t> {
     static __device__ __forceinline__ void load(const bf16_t* p, float* o) {
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
-        const u4 r = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));  // streaming: each element is touched once
+        // plain load: the producer kernel has usually just written these values and they are still in the memory-side cache
+        const u4 r = *reinterpret_cast<const u4*>(p);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             o[2 * i] = bf16_to_f32((bf16_t)(r[i] & 0xffffu));
@@ -54,25 +55,28 @@ template <> struct Vec8<float> {
 struct RowMap {
     int Tp, pitch, halo;
     long long real_frames;  // B * pitch
-    __device__ __forceinline__ long long src(long long f) const
+    // IDX: long long, or unsigned where every frame index fits (the 64-bit division is slow)
+    template <typename IDX>
+    __device__ __forceinline__ long long src(IDX f) const
     {
-        if (pitch == Tp) return f < real_frames ? f : -1;
-        if (f >= real_frames) return -1;
-        const long long b = f / pitch;
-        const int t = (int)(f - b * pitch) - halo;
-        return (t >= 0 && t < Tp) ? b * Tp + t : -1;
+        if (pitch == Tp) return (long long)f < real_frames ? (long long)f : -1;
+        if ((long long)f >= real_frames) return -1;
+        const IDX b = f / (IDX)pitch;
+        const int t = (int)(f - b * (IDX)pitch) - halo;
+        return (t >= 0 && t < Tp) ? (long long)b * Tp + t : -1;
     }
 };
 
-template <typename T, int V>  // V = 8 (vector path, H % 8 == 0) or 1
+// IDX: the type of the flat element index -- unsigned where the element count fits 32 bits (the launchers
+// choose): a 64-bit division per element costs more than the rest of the element's work
+template <typename T, int V, typename IDX>  // V = 8 (vector path, H % 8 == 0) or 1
 __global__ __launch_bounds__(256) void glu_fwd_k(const T* __restrict__ y, T* __restrict__ h, long long out_rows,
                                                  int H, RowMap map)
 {
     const int hv = H / V;
-    const long long total = out_rows * hv;
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
-         i += (long long)gridDim.x * blockDim.x) {
-        const long long f = i / hv;
+    const IDX total = (IDX)(out_rows * hv);
+    for (IDX i = blockIdx.x * (IDX)blockDim.x + threadIdx.x; i < total; i += (IDX)gridDim.x * blockDim.x) {
+        const IDX f = i / (IDX)hv;
         const int c = (int)(i - f * hv) * V;
         const long long r = map.src(f);
         float o[V];
@@ -91,20 +95,19 @@ __global__ __launch_bounds__(256) void glu_fwd_k(const T* __restrict__ y, T* __r
 #pragma unroll
             for (int j = 0; j < V; ++j) o[j] = 0.f;
         }
-        if (V == 8) Vec8<T>::store(h + f * H + c, o);
-        else Elem<T>::store(h, f * H + c, o[0]);
+        if (V == 8) Vec8<T>::store(h + (size_t)f * H + c, o);
+        else Elem<T>::store(h, (size_t)f * H + c, o[0]);
     }
 }
 
-template <typename T, int V>
+template <typename T, int V, typename IDX>
 __global__ __launch_bounds__(256) void glu_bwd_k(const T* __restrict__ y, const T* __restrict__ dh,
                                                  T* __restrict__ dy, long long out_rows, int H, RowMap map)
 {
     const int hv = H / V;
-    const long long total = out_rows * hv;
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
-         i += (long long)gridDim.x * blockDim.x) {
-        const long long f = i / hv;
+    const IDX total = (IDX)(out_rows * hv);
+    for (IDX i = blockIdx.x * (IDX)blockDim.x + threadIdx.x; i < total; i += (IDX)gridDim.x * blockDim.x) {
+        const IDX f = i / (IDX)hv;
         const int c = (int)(i - f * hv) * V;
         const long long r = map.src(f);
         float da[V], dg[V];
@@ -130,11 +133,11 @@ __global__ __launch_bounds__(256) void glu_bwd_k(const T* __restrict__ y, const 
             for (int j = 0; j < V; ++j) { da[j] = 0.f; dg[j] = 0.f; }
         }
         if (V == 8) {
-            Vec8<T>::store(dy + f * 2 * H + c, da);
-            Vec8<T>::store(dy + f * 2 * H + H + c, dg);
+            Vec8<T>::store(dy + (size_t)f * 2 * H + c, da);
+            Vec8<T>::store(dy + (size_t)f * 2 * H + H + c, dg);
         } else {
-            Elem<T>::store(dy, f * 2 * H + c, da[0]);
-            Elem<T>::store(dy, f * 2 * H + H + c, dg[0]);
+            Elem<T>::store(dy, (size_t)f * 2 * H + c, da[0]);
+            Elem<T>::store(dy, (size_t)f * 2 * H + H + c, dg[0]);
         }
     }
 }
@@ -257,6 +260,19 @@ using namespace w2l;
 
 namespace w2l {
 
+namespace {
+template <typename T, int V, typename IDX>
+void launch_glu_fwd(dim3 g, hipStream_t st, const void* y, void* h, long long out_rows, int H, const RowMap& map)
+{
+    hipLaunchKernelGGL((glu_fwd_k<T, V, IDX>), g, dim3(256), 0, st, (const T*)y, (T*)h, out_rows, H, map);
+}
+template <typename T, int V, typename IDX>
+void launch_glu_bwd(dim3 g, hipStream_t st, const void* y, const void* dh, void* dy, long long out_rows, int H, const RowMap& map)
+{
+    hipLaunchKernelGGL((glu_bwd_k<T, V, IDX>), g, dim3(256), 0, st, (const T*)y, (const T*)dh, (T*)dy, out_rows, H, map);
+}
+}  // namespace
+
 int glu_fwd_layout(const void* y, void* h, int B, int Tp, int Cout, int dtype, int pitch, int halo, int slack,
                    hipStream_t st)
 {
@@ -264,14 +280,20 @@ int glu_fwd_layout(const void* y, void* h, int B, int Tp, int Cout, int dtype, i
     const bool vec = (H % 8) == 0;
     const long long out_rows = (long long)B * pitch + slack;
     const RowMap map{Tp, pitch, halo, (long long)B * pitch};
-    const dim3 g(grid_for(vec ? out_rows * (H / 8) : out_rows * H)), b(256);
-    if (dtype == W2L_BF16) {
-        if (vec) hipLaunchKernelGGL((glu_fwd_k<bf16_t, 8>), g, b, 0, st, (const bf16_t*)y, (bf16_t*)h, out_rows, H, map);
-        else hipLaunchKernelGGL((glu_fwd_k<bf16_t, 1>), g, b, 0, st, (const bf16_t*)y, (bf16_t*)h, out_rows, H, map);
-    } else {
-        if (vec) hipLaunchKernelGGL((glu_fwd_k<float, 8>), g, b, 0, st, (const float*)y, (float*)h, out_rows, H, map);
-        else hipLaunchKernelGGL((glu_fwd_k<float, 1>), g, b, 0, st, (const float*)y, (float*)h, out_rows, H, map);
+    const long long items = vec ? out_rows * (H / 8) : out_rows * H;
+    const dim3 g(grid_for(items));
+    const bool small = items < (1LL << 31);  // 32-bit element indices
+#define W2L_GLU(T_, V_)                                                                    \
+    {                                                                                      \
+        if (small) launch_glu_fwd<T_, V_, unsigned>(g, st, y, h, out_rows, H, map);        \
+        else launch_glu_fwd<T_, V_, long long>(g, st, y, h, out_rows, H, map);             \
     }
+    if (dtype == W2L_BF16) {
+        if (vec) W2L_GLU(bf16_t, 8) else W2L_GLU(bf16_t, 1)
+    } else {
+        if (vec) W2L_GLU(float, 8) else W2L_GLU(float, 1)
+    }
+#undef W2L_GLU
     return launch_status();
 }
 
@@ -282,14 +304,20 @@ int glu_bwd_layout(const void* y, const void* dh, void* dy, int B, int Tp, int C
     const bool vec = (H % 8) == 0;
     const long long out_rows = (long long)B * pitch + slack;
     const RowMap map{Tp, pitch, halo, (long long)B * pitch};
-    const dim3 g(grid_for(vec ? out_rows * (H / 8) : out_rows * H)), b(256);
-    if (dtype == W2L_BF16) {
-        if (vec) hipLaunchKernelGGL((glu_bwd_k<bf16_t, 8>), g, b, 0, st, (const bf16_t*)y, (const bf16_t*)dh, (bf16_t*)dy, out_rows, H, map);
-        else hipLaunchKernelGGL((glu_bwd_k<bf16_t, 1>), g, b, 0, st, (const bf16_t*)y, (const bf16_t*)dh, (bf16_t*)dy, out_rows, H, map);
-    } else {
-        if (vec) hipLaunchKernelGGL((glu_bwd_k<float, 8>), g, b, 0, st, (const float*)y, (const float*)dh, (float*)dy, out_rows, H, map);
-        else hipLaunchKernelGGL((glu_bwd_k<float, 1>), g, b, 0, st, (const float*)y, (const float*)dh, (float*)dy, out_rows, H, map);
+    const long long items = vec ? out_rows * (H / 8) : out_rows * H;
+    const dim3 g(grid_for(items));
+    const bool small = items < (1LL << 31);
+#define W2L_GLU(T_, V_)                                                                    \
+    {                                                                                      \
+        if (small) launch_glu_bwd<T_, V_, unsigned>(g, st, y, dh, dy, out_rows, H, map);   \
+        else launch_glu_bwd<T_, V_, long long>(g, st, y, dh, dy, out_rows, H, map);        \
     }
+    if (dtype == W2L_BF16) {
+        if (vec) W2L_GLU(bf16_t, 8) else W2L_GLU(bf16_t, 1)
+    } else {
+        if (vec) W2L_GLU(float, 8) else W2L_GLU(float, 1)
+    }
+#undef W2L_GLU
     return launch_status();
 }
 
