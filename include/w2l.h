@@ -82,7 +82,12 @@ int w2l_conv1d_fwd(const void *x, const void *w, const float *bias, void *y,
 /* Gradient with respect to the input (transpose of x -> y):
  *   dx[b,t,ci] = sum_j sum_co w[co,j,ci] * dy[b,(t+p-j)/s,co]
  * over taps j with (t+p-j) divisible by s and 0 <= (t+p-j)/s < T'.
- * dy: [B,T',Cout] (dy_dtype);  w: [Cout,k,Cin] (dtype);  dx: [B,T,Cin] (dtype). */
+ * dy: [B,T',Cout] (dy_dtype);  w: [Cout,k,Cin] (dtype);  dx: [B,T,Cin] (dtype).
+ * Given the queried workspace, bf16 problems run on the matrix cores whatever Cout is and also for
+ * a stride s > 1 with p % s == 0 and T % s == 0: dy is staged as bf16 (an fp32 dy is rounded to
+ * bf16 there) with its channels padded to a multiple of 64, the weights are copied padded and with
+ * the stride folded into the channels.  Without workspace, fp32 dy, odd channel counts and strided
+ * layers take a shape-agnostic fp32 kernel. */
 size_t w2l_conv1d_bwd_data_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype);
 int w2l_conv1d_bwd_data(const void *dy, const void *w, void *dx,
                         int B, int T, int Cin, int Cout, int k, int stride,

@@ -98,7 +98,6 @@ namespace {
 constexpr int ABI_HALO = LAYOUT_HALO, ABI_SLACK = LAYOUT_SLACK, ABI_SLACK_ZERO = LAYOUT_SLACK_ZERO;
 size_t haloed_bytes(int B, int frames, int C) { return round_up(((size_t)B * (frames + 2 * ABI_HALO) + ABI_SLACK) * C * 2, 256); }
 bool stage_fwd(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cin % 64 == 0 && Cout >= 16 && s >= 1; }
-bool stage_dgrad(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && s == 1 && k > 1 && (k - 1) / 2 <= ABI_HALO && Cout % 64 == 0 && Cin % 8 == 0 && Cin >= 64; }
 bool stage_wgrad(int Cin, int Cout, int k, int s, int dt) { return dt == W2L_BF16 && s == 1 && (k - 1) / 2 <= ABI_HALO && Cin % 8 == 0 && Cout % 8 == 0 && Cout >= 64 && (long long)k * Cin >= 64; }
 // a strided layer whose stride folds into the channels (fold_stride) is staged as the stride-1 layer it folds to
 bool stage_wgrad_folded(int B, int T, int Cin, int Cout, int k, int s, int dt, ConvDesc& f)
@@ -138,23 +137,54 @@ extern "C" int w2l_conv1d_fwd(const void* x, const void* w, const float* bias, v
     return conv_fwd(d, x, w, bias, y, dtype, y_dtype, st);
 }
 
-namespace {
-// geometry of the data gradient once dy has been staged into the haloed layout
-ConvDesc staged_dgrad_desc(int B, int T, int Cin, int Cout, int k, int stride)
+namespace w2l {
+DgradPrep dgrad_prep(int B, int T, int Cin, int Cout, int k, int s, int dt)
 {
-    ConvDesc d = dense_desc(B, T, Cin, Cout, k, stride);
-    d.y_pitch = d.Tp + 2 * ABI_HALO;
-    d.y_halo = ABI_HALO;
-    d.slack = ABI_SLACK;
-    return d;
+    DgradPrep p;
+    p.Cout = Cout; p.k = k; p.Cin = Cin; p.s = s;
+    if (dt != W2L_BF16) return p;
+    ConvDesc f = dense_desc(B, T, Cin, Cout, k, s);
+    if (s > 1 && !fold_stride(dense_desc(B, T, Cin, Cout, k, s), f)) return p;   // a stride that does not fold
+    f.w_cols = 0;
+    const int Cp = (Cout + 63) / 64 * 64;
+    p.copy_w = s > 1 || Cp != Cout;
+    f.Cout = Cp;
+    if (f.p > ABI_HALO) return p;
+    f.y_pitch = f.Tp + 2 * ABI_HALO;
+    f.y_halo = ABI_HALO;
+    f.slack = ABI_SLACK;
+    if (!conv_dgrad_mfma_ok(f)) return p;
+    p.ok = true;
+    p.d = f;
+    p.dy_bytes = haloed_bytes(B, f.Tp, Cp);
+    p.w_bytes = p.copy_w ? round_up((size_t)Cp * f.k * f.Cin * 2, 256) : 0;
+    p.split_bytes = round_up(conv_dgrad_scratch_bytes(f), 256);
+    return p;
 }
-}  // namespace
+
+int conv_dgrad_prepared(const DgradPrep& prep, const void* dy, int dydt, const void* w, void* dx, void* ws, hipStream_t st)
+{
+    if (!prep.ok) return W2L_ERR_SHAPE;
+    const ConvDesc& f = prep.d;
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    int rc = prep_dgrad_dy(dy, dydt, base, f.B, f.Tp, prep.Cout, f.Cout, f.y_pitch, f.y_halo, ABI_SLACK_ZERO, st);
+    if (rc) return rc;
+    const void* wp = w;
+    if (prep.copy_w) {
+        rc = prep_dgrad_w(w, base + prep.dy_bytes, prep.Cout, prep.k, prep.Cin, f.Cout, f.k, prep.s, st);
+        if (rc) return rc;
+        wp = base + prep.dy_bytes;
+    }
+    return conv_dgrad_mfma(f, base, wp, dx, prep.split_bytes ? base + prep.dy_bytes + prep.w_bytes : nullptr,
+                           prep.split_bytes, st);
+}
+}  // namespace w2l
 
 extern "C" size_t w2l_conv1d_bwd_data_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride, int dtype)
 {
     if (check_conv_shape(B, T, Cin, Cout, k, stride)) return 0;
-    if (!stage_dgrad(Cin, Cout, k, stride, dtype)) return 0;
-    return haloed_bytes(B, out_len(T, stride), Cout) + conv_dgrad_scratch_bytes(staged_dgrad_desc(B, T, Cin, Cout, k, stride));
+    const DgradPrep p = dgrad_prep(B, T, Cin, Cout, k, stride, dtype);
+    return p.ok ? p.total() : 0;
 }
 
 extern "C" int w2l_conv1d_bwd_data(const void* dy, const void* w, void* dx, int B, int T, int Cin, int Cout,
@@ -167,19 +197,18 @@ extern "C" int w2l_conv1d_bwd_data(const void* dy, const void* w, void* dx, int 
     if (!valid_dtype(dtype) || !valid_dtype(dy_dtype) || (dtype == W2L_F32 && dy_dtype != W2L_F32))
         return W2L_ERR_DTYPE;
     if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return W2L_ERR_ALIGN;
-    const size_t need = (dy_dtype == W2L_BF16) ? w2l_conv1d_bwd_data_workspace_bytes(B, T, Cin, Cout, k, stride, dtype) : 0;
+    const size_t need = w2l_conv1d_bwd_data_workspace_bytes(B, T, Cin, Cout, k, stride, dtype);
     if (workspace && !ws_ok(workspace, ws_bytes, need)) return W2L_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    ConvDesc d = dense_desc(B, T, Cin, Cout, k, stride);
     if (workspace && need) {
-        rc = pad_layout_bf16(dy, workspace, B, d.Tp, Cout, d.Tp + 2 * ABI_HALO, ABI_HALO, ABI_SLACK_ZERO, st);
-        if (rc) return rc;
-        d = staged_dgrad_desc(B, T, Cin, Cout, k, stride);
-        dy = workspace;
-        const size_t used = haloed_bytes(B, d.Tp, Cout);
-        return conv_dgrad(d, dy, w, dx, dtype, dy_dtype, st, static_cast<unsigned char*>(workspace) + used, need - used);
+        // dy staged as bf16 into the haloed layout (channels padded to whole blocks of 64), weights copied padded /
+        // with the stride folded where the layer needs it: every bf16 shape the MFMA kernels can be brought to.
+        // (A 1x1 layer with bf16 dy and whole channel blocks needs none of it: the kernels read its dense dy as it is.)
+        const DgradPrep p = dgrad_prep(B, T, Cin, Cout, k, stride, dtype);
+        const bool plain_1x1 = k == 1 && stride == 1 && dy_dtype == W2L_BF16 && !p.copy_w;
+        if (!plain_1x1) return conv_dgrad_prepared(p, dy, dy_dtype, w, dx, workspace, st);
     }
-    return conv_dgrad(d, dy, w, dx, dtype, dy_dtype, st);
+    return conv_dgrad(dense_desc(B, T, Cin, Cout, k, stride), dy, w, dx, dtype, dy_dtype, st);
 }
 
 extern "C" size_t w2l_conv1d_bwd_weight_workspace_bytes(int B, int T, int Cin, int Cout, int k, int stride,

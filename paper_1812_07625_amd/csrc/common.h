@@ -79,9 +79,11 @@ inline ConvDesc dense_desc(int B, int T, int Cin, int Cout, int k, int s)
 // the frames like every other layer's.  Returns false if the layer does not fold.
 inline bool fold_stride(const ConvDesc& d, ConvDesc& f)
 {
-    if (d.s <= 1 || d.p % d.s != 0 || d.T % d.s != 0) return false;
+    if (d.s <= 1 || d.p % d.s != 0 || d.T % d.s != 0 || d.x_pitch % d.s != 0 || d.x_halo % d.s != 0) return false;
     f = d;
     f.T = f.Tp = d.T / d.s;
+    f.x_pitch = d.x_pitch / d.s;  // the time layout of x in folded frames
+    f.x_halo = d.x_halo / d.s;
     f.Cin = d.Cin * d.s;
     f.k = 2 * (d.p / d.s) + 1;               // symmetric: (k - 1) / 2 = p / s frames either side
     if ((long long)f.k * f.Cin < (long long)d.k * d.Cin) return false;
@@ -163,6 +165,25 @@ int glu_bwd_layout(const void* y, const void* dh, void* dy, int B, int Tp, int C
 int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch, int halo, int slack, hipStream_t st);
 // any dtype, any channel count
 int pad_layout(const void* src, void* dst, int B, int Tp, int C, int dtype, int pitch, int halo, int slack, hipStream_t st);
+// data-gradient operand preparation (elementwise.hip): dy (fp32 or bf16, dense [B*Tp, C]) -> bf16 in the haloed layout
+// with the channels padded by zeros to Cp; w[Cout][k][Cin] -> [Cp][kf][s*Cin] with the stride folded into the
+// channels (w'[co][jj][ph*Cin+ci] = w[co][s*jj+ph][ci]) and zeros for taps and rows that do not exist
+int prep_dgrad_dy(const void* src, int src_dtype, void* dst, int B, int Tp, int C, int Cp, int pitch, int halo, int slack,
+                  hipStream_t st);
+int prep_dgrad_w(const void* w, void* dst, int Cout, int k, int Cin, int Cp, int kf, int s, hipStream_t st);
+// A data gradient brought into the form the MFMA kernels take (api.hip).  ok: the shape can be prepared; d: the
+// geometry of the prepared problem (stride 1, Cout a multiple of 64, dy haloed); copy_w: the weights need the
+// padded / folded copy.  Workspace: dy_bytes, then w_bytes, then split_bytes (conv_dgrad_scratch_bytes(d)).
+struct DgradPrep {
+    bool ok = false, copy_w = false;
+    ConvDesc d;
+    int Cout = 0, k = 0, Cin = 0, s = 1;  // the layer as the caller describes it
+    size_t dy_bytes = 0, w_bytes = 0, split_bytes = 0;
+    size_t total() const { return dy_bytes + w_bytes + split_bytes; }
+};
+DgradPrep dgrad_prep(int B, int T, int Cin, int Cout, int k, int s, int dt);
+// dy: dense [B, Tp, Cout] of dtype dydt; dx: dense [B, T, Cin] bf16; ws: prep.total() bytes, 256-byte aligned
+int conv_dgrad_prepared(const DgradPrep& prep, const void* dy, int dydt, const void* w, void* dx, void* ws, hipStream_t st);
 // the same for two tensors that share B, Tp and the layout, in one launch
 int pad_layout2_bf16(const void* src0, void* dst0, int C0, const void* src1, void* dst1, int C1, int B, int Tp, int pitch,
                      int halo, int slack, hipStream_t st);

@@ -1269,7 +1269,7 @@ __global__ __launch_bounds__(256 * KG * GN) void conv_wgrad_k(const bf16_t* __re
         const int m = m0 + mm, n = n0 + nn;
         if (m < M && n < N) {
             const size_t i = (size_t)m * N + n;
-            dw[i] = accumulate ? dw[i] + v : v;
+            __builtin_nontemporal_store(accumulate ? dw[i] + v : v, dw + i);  // 52 MB per layer that nothing reads before the step ends
         }
     });
 }

@@ -196,6 +196,39 @@ __global__ __launch_bounds__(256) void pad_layout_any_k(const T* __restrict__ sr
     }
 }
 
+// Operand preparation for data gradients the MFMA kernels do not take as they come (fp32 dy, a channel count that
+// is not a multiple of 64, a strided layer): dy -> bf16, haloed, channels padded with zeros to Cp.
+template <typename T>
+__global__ __launch_bounds__(256) void prep_dy_k(const T* __restrict__ src, bf16_t* __restrict__ dst, long long out_rows,
+                                                 int C, int Cp, RowMap map)
+{
+    const long long total = out_rows * Cp;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long f = i / Cp;
+        const int c = (int)(i - f * Cp);
+        const long long r = map.src(f);
+        dst[i] = (r >= 0 && c < C) ? f32_to_bf16(Elem<T>::load(src, r * C + c)) : (bf16_t)0;
+    }
+}
+// w[Cout][k][Cin] -> w'[Cp][kf][s * Cin]: w'[co][jj][ph * Cin + ci] = w[co][s * jj + ph][ci], zero where the tap
+// s * jj + ph does not exist or co >= Cout (s = 1: a copy with zero rows appended).
+__global__ __launch_bounds__(256) void prep_w_k(const bf16_t* __restrict__ w, bf16_t* __restrict__ dst, int Cout, int k,
+                                                int Cin, int Cp, int kf, int s)
+{
+    const long long total = (long long)Cp * kf * s * Cin;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const int ci = (int)(i % Cin);
+        const long long q = i / Cin;
+        const int ph = (int)(q % s);
+        const long long q2 = q / s;
+        const int jj = (int)(q2 % kf), co = (int)(q2 / kf);
+        const int j = s * jj + ph;
+        dst[i] = (co < Cout && j < k) ? w[((size_t)co * k + j) * Cin + ci] : (bf16_t)0;
+    }
+}
+
 inline unsigned grid_for(long long items)
 {
     long long b = (items + 255) / 256;
@@ -343,6 +376,26 @@ int pad_layout(const void* src, void* dst, int B, int Tp, int C, int dtype, int 
         hipLaunchKernelGGL(pad_layout_any_k<bf16_t>, g, b, 0, st, (const bf16_t*)src, (bf16_t*)dst, out_rows, C, map);
     else
         hipLaunchKernelGGL(pad_layout_any_k<float>, g, b, 0, st, (const float*)src, (float*)dst, out_rows, C, map);
+    return launch_status();
+}
+
+int prep_dgrad_dy(const void* src, int src_dtype, void* dst, int B, int Tp, int C, int Cp, int pitch, int halo, int slack,
+                  hipStream_t st)
+{
+    const long long out_rows = (long long)B * pitch + slack;
+    const RowMap map{Tp, pitch, halo, (long long)B * pitch};
+    const dim3 g(grid_for(out_rows * Cp)), b(256);
+    if (src_dtype == W2L_BF16)
+        hipLaunchKernelGGL(prep_dy_k<bf16_t>, g, b, 0, st, (const bf16_t*)src, (bf16_t*)dst, out_rows, C, Cp, map);
+    else
+        hipLaunchKernelGGL(prep_dy_k<float>, g, b, 0, st, (const float*)src, (bf16_t*)dst, out_rows, C, Cp, map);
+    return launch_status();
+}
+
+int prep_dgrad_w(const void* w, void* dst, int Cout, int k, int Cin, int Cp, int kf, int s, hipStream_t st)
+{
+    hipLaunchKernelGGL(prep_w_k, dim3(grid_for((long long)Cp * kf * s * Cin)), dim3(256), 0, st, (const bf16_t*)w,
+                       (bf16_t*)dst, Cout, k, Cin, Cp, kf, s);
     return launch_status();
 }
 

@@ -62,6 +62,8 @@ struct Plan {
     size_t ctc_bytes = 0, conv_bytes = 0, dgs_bytes = 0;
     size_t xfold = 0;      // haloed copy of x with the first layer's stride folded into the channels (0 bytes if unused)
     bool fold0 = false;
+    size_t cls = 0;        // operands of the last layer's data gradient prepared for the MFMA kernels (its dy is fp32)
+    DgradPrep cls_prep;
     int status = W2L_OK;
 };
 
@@ -141,6 +143,12 @@ Plan make_plan(const w2l_layer* L, int n, int B, int T, int Lmax, int dtype, int
                   L[0].cout >= 64;
         p.xfold = off;
         if (p.fold0) off += round_up(haloed_bytes(B, f0.T, f0.Cin, es), 256);
+    }
+    if (n > 1) {
+        const w2l_layer& ll = L[n - 1];
+        p.cls_prep = dgrad_prep(B, p.Tin[n - 1], ll.cin, ll.cout, ll.k, ll.stride, dtype);
+        p.cls = off;
+        if (p.cls_prep.ok) off += round_up(p.cls_prep.total(), 256);
     }
     p.total = off;
     return p;
@@ -347,7 +355,10 @@ static int train_step_impl(int criterion, const w2l_layer* layers, int n_layers,
                 if (!wait_wgrad(gdh_reader[q])) return W2L_ERR_LAUNCH;
                 gdh_reader[q] = -1;
             }
-            rc = conv_dgrad(dd, dy, weights[i], gdhb[q], dtype, dy_dt, st);
+            if (i == n - 1 && dy_dt == W2L_F32 && p.cls_prep.ok)  // the criterion's fp32 gradient: cast, pad, MFMA
+                rc = conv_dgrad_prepared(p.cls_prep, dy, dy_dt, weights[i], gdhb[q], ws + p.cls, st);
+            else
+                rc = conv_dgrad(dd, dy, weights[i], gdhb[q], dtype, dy_dt, st);
             if (rc) return rc;
             dh = gdhb[q];
             cur = q;
