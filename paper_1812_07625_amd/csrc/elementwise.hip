@@ -202,13 +202,19 @@ template <typename T>
 __global__ __launch_bounds__(256) void prep_dy_k(const T* __restrict__ src, bf16_t* __restrict__ dst, long long out_rows,
                                                  int C, int Cp, RowMap map)
 {
-    const long long total = out_rows * Cp;
+    // one thread writes 8 channels (16 bytes); Cp is a multiple of 64
+    const int cv = Cp / 8;
+    const long long total = out_rows * cv;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
          i += (long long)gridDim.x * blockDim.x) {
-        const long long f = i / Cp;
-        const int c = (int)(i - f * Cp);
+        const long long f = i / cv;
+        const int c = (int)(i - f * cv) * 8;
         const long long r = map.src(f);
-        dst[i] = (r >= 0 && c < C) ? f32_to_bf16(Elem<T>::load(src, r * C + c)) : (bf16_t)0;
+        bf16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            v[e] = (r >= 0 && c + e < C) ? f32_to_bf16(Elem<T>::load(src, r * C + c + e)) : (bf16_t)0;
+        *reinterpret_cast<uint4*>(dst + f * Cp + c) = *reinterpret_cast<const uint4*>(v);
     }
 }
 // w[Cout][k][Cin] -> w'[Cp][kf][s * Cin]: w'[co][jj][ph * Cin + ci] = w[co][s * jj + ph][ci], zero where the tap
@@ -384,7 +390,8 @@ int prep_dgrad_dy(const void* src, int src_dtype, void* dst, int B, int Tp, int 
 {
     const long long out_rows = (long long)B * pitch + slack;
     const RowMap map{Tp, pitch, halo, (long long)B * pitch};
-    const dim3 g(grid_for(out_rows * Cp)), b(256);
+    if (src_dtype == W2L_BF16 && C == Cp) return pad_layout_bf16(src, dst, B, Tp, C, pitch, halo, slack, st);
+    const dim3 g(grid_for(out_rows * (Cp / 8))), b(256);
     if (src_dtype == W2L_BF16)
         hipLaunchKernelGGL(prep_dy_k<bf16_t>, g, b, 0, st, (const bf16_t*)src, (bf16_t*)dst, out_rows, C, Cp, map);
     else
