@@ -47,6 +47,7 @@ __device__ __forceinline__ int from_left_lane_i(int v)
 }
 __device__ __forceinline__ float from_left_lane(float v) { return __int_as_float(from_left_lane_i(__float_as_int(v))); }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int LAT_PAD = 16;  // spare lattice rows at either end of an utterance = the longest block of frames
 
 // A state's exponent is kept with a bias, so that 0 can stand for "zero state" (the value a lane
@@ -55,7 +56,14 @@ constexpr int LAT_PAD = 16;  // spare lattice rows at either end of an utterance
 constexpr int EXP_BIAS = 1 << 30;
 constexpr int MAX_FRAMES = 8192;
 constexpr float MIN_LOG2 = -65535.f;               // scores are clamped to 2^+-65535; below: probability zero
-constexpr int PE_ZERO = -2147483647 - 1;           // exponent of a zero score: pulls any biased exponent below 0
+// A score enters the step as (mantissa, q) with q = EXP_DRIFT - exponent > 0, and the step takes q off a state's
+// biased exponent with one saturating unsigned subtraction: the bias of every state falls by EXP_DRIFT per frame
+// (row t of alpha carries EXP_BIAS - (t + 1) EXP_DRIFT, row t of beta EXP_BIAS - (T - t) EXP_DRIFT), a zero state
+// stays at 0, and a zero score (q = Q_ZERO) sends any state to 0.  With MAX_FRAMES frames of scores clamped to
+// 2^+-65535 a real state's biased exponent stays within (0, 2^30 + 2^16).
+constexpr int EXP_DRIFT = 65536;
+constexpr unsigned Q_ZERO = 0xffffffffu;
+__device__ __forceinline__ int sub_sat(int e, unsigned q) { return (int)__builtin_elementwise_sub_sat((unsigned)e, q); }
 
 // v * 2^e for a (v, e) pair as a double-precision base-2 log; -inf for a zero state
 __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (double)fast_log2(v) + (double)e : -INFINITY; }
@@ -77,7 +85,7 @@ __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (
 // block of BLK frames run on like the others -- their rows land in the LAT_PAD spare
 // rows that every utterance's lattice has at either end (alpha runs off the far end, beta off
 // the near one) or in rows t >= T_b that nobody reads.
-// Stored per frame and state: the pair (v, e + EXP_BIAS), the integer as the bits of the second float.
+// Stored per frame and state: the pair (v, biased e), the integer as the bits of the second float.
 // NQ > 0 (the class rows of a block of frames fit NQ values per thread): the scores do not come
 // through per-lane loads at all.  The workgroup keeps the rows lp[t, 0..C-1] of the current
 // block of BLK frames in LDS, already split into (mantissa, exponent), class-major
@@ -105,7 +113,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     __shared__ float xbuf[2][16][HALO_LANES][4 * PPT];  // [block parity][wavefront][lane - OWN_LANES][v, e of blank, label]
     __shared__ int bad_len, bad;
     extern __shared__ __align__(16) unsigned char dyn_smem[];
-    float2* const tbl = reinterpret_cast<float2*>(dyn_smem);  // TABLE: [2][C][TABLE_PITCH] (pm, pe)
+    float2* const tbl = reinterpret_cast<float2*>(dyn_smem);  // TABLE: [2][C][TABLE_PITCH] (pm, q)
     const int dir = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, NT = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int T = crit_len(in_len[b], d.len_div), L = tgt_len[b];
@@ -163,7 +171,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     const bool owner = lane >= HALO_LANES;               // not a mirror of the wavefront on the left
     int cls[PPT];        // class of the label state
     bool skip[PPT];      // label state may be entered from the label of the pair to the left
-    unsigned slot[PPT];  // lattice position of the pair (the spare pair for lanes that own no real pair)
+    unsigned slot[PPT];  // byte offset of the pair in a lattice row (the spare pair for lanes that own no real pair)
     float vb[PPT], vl[PPT];
     int eb[PPT], el[PPT];  // biased exponents; 0 for a zero state
 #pragma unroll
@@ -173,7 +181,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         const int li = dir ? L - 1 - i : i;          // label index in the target
         cls[j] = has_l ? lab[li] : d.blank;
         skip[j] = has_l && i >= 1 && lab[dir ? li + 1 : li - 1] != cls[j];
-        slot[j] = 2u * (unsigned)((real && owner) ? i : d.Lmax + 1);
+        slot[j] = 16u * (unsigned)((real && owner) ? i : d.Lmax + 1);
         // the state "before frame 0": all mass in front of pair 0, so that frame 0 comes out of the recursion itself
         const bool start = gi >= 0 && i == 0;
         vb[j] = start ? 1.f : 0.f;
@@ -190,22 +198,26 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     const int tblocks = (T + BLK - 1) / BLK;
     // running pointers instead of per-step index arithmetic: the lattice row written next
     // (and, without the table, the score row fetched next, clamped at the last frame)
-    const long long sstep = dir ? -(long long)d.C : d.C, rstep = dir ? -(long long)d.Sp : d.Sp;
-    float2* rptr = lat + (long long)frame(0) * d.Sp;
+    const long long sstep = dir ? -(long long)d.C : d.C;
+    // A lattice row is addressed as the utterance's slice (spare rows included) + the row's byte offset (uniform,
+    // advanced once per step) + the lane's byte offset: one 32-bit add per store.
+    char* const lat_slice = reinterpret_cast<char*>((dir ? beta : alpha) + (size_t)b * d.rows * d.Sp);
+    const int row_bytes = d.Sp * (int)sizeof(float2), rstep = dir ? -row_bytes : row_bytes;
+    int rptr = (LAT_PAD + frame(0)) * row_bytes;
     // exp(lp) = 2^(lp log2 e) = pm * 2^pe with pm in [1, 2); a score below 2^MIN_LOG2 (-inf included) is probability zero
-    auto split = [&](float s, float& pm, int& pe) {
+    auto split = [&](float s, float& pm, unsigned& pq) {
         const float xr = s * log2e;
         const float x = fminf(fmaxf(xr, MIN_LOG2), -MIN_LOG2);
         const float fl = floorf(x);
         const bool pos = xr >= MIN_LOG2;
-        pe = pos ? (int)fl : PE_ZERO;
+        pq = pos ? (unsigned)(EXP_DRIFT - (int)fl) : Q_ZERO;
         pm = pos ? fast_exp2(x - fl) : 0.f;
     };
     // one frame of the recursion for this lane's pairs, given the split scores.  A sum of states brings
     // them to their largest exponent (exact) and adds; a zero state (v = 0, exponent 0, far below any
     // real state's biased exponent) drops out by itself, and a sum of zeros stays at exponent 0
     // through the max() (a zero score's exponent pulls any sum below 0).
-    auto advance = [&](float2* row, float pmb, int peb, const float (&pml)[PPT], const int (&pel)[PPT]) {
+    auto advance = [&](int row, float pmb, unsigned qb, const float (&pml)[PPT], const unsigned (&ql)[PPT]) {
         // label state (previous frame) of the pair to the left of this lane's first pair
         float cv = from_left_lane(vl[PPT - 1]);
         int ce = from_left_lane_i(el[PPT - 1]);
@@ -216,19 +228,20 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
             // blank: from itself and from the label on its left
             const int E1 = max(obe, ce);
             const float s1 = __builtin_amdgcn_ldexpf(obv, obe - E1) + __builtin_amdgcn_ldexpf(cv, ce - E1);
-            // label: from itself, from its blank, and (different neighbouring labels) from the label on its left
-            const float cvs = skip[j] ? cv : 0.f;
-            const int cs = skip[j] ? ce : 0;
-            const int E2 = max(max(ole, obe), cs);
-            const float s2 = (__builtin_amdgcn_ldexpf(olv, ole - E2) + __builtin_amdgcn_ldexpf(obv, obe - E2)) +
-                             __builtin_amdgcn_ldexpf(cvs, cs - E2);
+            // label: from itself, and from its blank alone or, where the label on its left differs, from the sum
+            // just formed for the blank (its blank + that label)
+            const float xv = skip[j] ? s1 : obv;
+            const int xe = skip[j] ? E1 : obe;
+            const int E2 = max(ole, xe);
+            const float s2 = __builtin_amdgcn_ldexpf(olv, ole - E2) + __builtin_amdgcn_ldexpf(xv, xe - E2);
             cv = olv;
             ce = ole;
             vb[j] = pmb * s1;
-            eb[j] = max(E1 + peb, 0);
+            eb[j] = sub_sat(E1, qb);
             vl[j] = pml[j] * s2;
-            el[j] = max(E2 + pel[j], 0);
-            *reinterpret_cast<float4*>(row + slot[j]) = make_float4(vb[j], __int_as_float(eb[j]), vl[j], __int_as_float(el[j]));
+            el[j] = sub_sat(E2, ql[j]);
+            const u32x4 st = {__float_as_uint(vb[j]), (unsigned)eb[j], __float_as_uint(vl[j]), (unsigned)el[j]};
+            *reinterpret_cast<u32x4*>(lat_slice + (unsigned)(row + (int)slot[j])) = st;
         }
     };
     // block boundary: every lane moves the exponents of its mantissas into e; the mirror lanes
@@ -285,9 +298,9 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
                 float pm;
-                int pe;
-                split(raw[q], pm, pe);
-                if (loff[q] >= 0) tbl[buf * per_buf + loff[q]] = make_float2(pm, __int_as_float(pe));
+                unsigned pq;
+                split(raw[q], pm, pq);
+                if (loff[q] >= 0) tbl[buf * per_buf + loff[q]] = make_float2(pm, __uint_as_float(pq));
             }
         };
         const float2* tb_blank = tbl + d.blank * TABLE_PITCH;
@@ -306,11 +319,11 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
 #pragma unroll
                 for (int k = 0; k < BLK; ++k) {
                     const float pmb = nb.x;
-                    const int peb = __float_as_int(nb.y);
+                    const unsigned peb = __float_as_uint(nb.y);
                     float pml[PPT];
-                    int pel[PPT];
+                    unsigned pel[PPT];
 #pragma unroll
-                    for (int j = 0; j < PPT; ++j) { pml[j] = nl[j].x; pel[j] = __float_as_int(nl[j].y); }
+                    for (int j = 0; j < PPT; ++j) { pml[j] = nl[j].x; pel[j] = __float_as_uint(nl[j].y); }
                     if (k + 1 < BLK) {  // the next frame's scores, one step ahead
                         nb = tb_blank[cur + k + 1];
 #pragma unroll
@@ -349,7 +362,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
             for (int k = 0; k < BLK; ++k) {
                 const int step = tb * BLK + k;
                 float pmb, pml[PPT];
-                int peb, pel[PPT];
+                unsigned peb, pel[PPT];
                 split(sb[k], pmb, peb);
 #pragma unroll
                 for (int j = 0; j < PPT; ++j) split(sl[j][k], pml[j], pel[j]);
@@ -377,7 +390,7 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
             const int fle = L > 0 ? __float_as_int(__builtin_nontemporal_load(&last[2 * L - 1].y)) : 0;
             const int E = max(fbe, fle);
             const float sum = __builtin_amdgcn_ldexpf(fbv, fbe - E) + __builtin_amdgcn_ldexpf(flv, fle - E);
-            const double lp2 = pair_log2(sum, E - EXP_BIAS);
+            const double lp2 = pair_log2(sum, E - EXP_BIAS + T * EXP_DRIFT);
             logp2_out[b] = lp2;
             loss[b] = sum > 0.f ? (float)(-lp2 * LN2) : INFINITY;
         }
@@ -466,7 +479,8 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
                 if (a[u].x > 0.f && bt[u].x > 0.f) {
                     const float x = fminf(fmaxf(sc[u] * (float)LOG2E, MIN_LOG2), -MIN_LOG2), fl = floorf(x);
                     // both exponents carry the bias: taken off in wrap-around arithmetic
-                    const int ex = (int)((unsigned)__float_as_int(a[u].y) + (unsigned)__float_as_int(bt[u].y) - 2u * (unsigned)EXP_BIAS);
+                    const int ex = (int)((unsigned)__float_as_int(a[u].y) + (unsigned)__float_as_int(bt[u].y) - 2u * (unsigned)EXP_BIAS +
+                                        (unsigned)(T + 1) * (unsigned)EXP_DRIFT);
                     e = fast_exp2((fast_log2(a[u].x * bt[u].x) + (float)(ex - iref - (int)fl)) + (shift - (x - fl)));
                 }
                 if (s < S) {
