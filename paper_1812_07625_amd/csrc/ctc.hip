@@ -72,8 +72,8 @@ __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (
 // (blank 2i, label 2i+1); a lane holds PPT consecutive pairs in registers, so per frame it needs
 // exactly one value from outside: the label state of the pair to its left, which a DPP
 // whole-wavefront shift delivers from the neighbouring lane.  No value crosses a wavefront
-// boundary inside a block of BLK frames: the first BLK lanes of every wavefront
-// recompute the pairs owned by the last lanes of the wavefront on its left.  Their leftmost input
+// boundary inside a block of BLK frames: the first BLK lanes of every wavefront but the first
+// recompute the pairs owned by the last lanes of the wavefront on its left (wavefront 0 owns all 64).  Their leftmost input
 // is missing, so they go stale from the left at one pair per frame -- after BLK frames
 // the staleness has not yet reached the lanes the wavefront owns -- and once per block they are
 // refreshed through LDS, at the one barrier of the block.  States to the right of the target's
@@ -95,8 +95,8 @@ __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (
 // no vector loads and never waits on the memory counter that its own lattice stores keep busy.
 // NQ == 0 (large alphabets): the scores lp[t, blank] and lp[t, label] are gathered per lane
 // BLK frames early into a register ring.
-// BLK = 16, or 12 where that brings the target onto four wavefronts (64 - BLK owned lanes each):
-// the step is bound by instruction issue -- one wavefront alone on its SIMD issues the ~30
+// BLK = 16, or 12 where that brings the target onto four wavefronts (64 + 3 (64 - BLK) owned lanes):
+// the step is bound by instruction issue -- one wavefront alone on its SIMD issues the ~25
 // instructions of a step at the 4-cycle cadence -- so a fifth wavefront, which has to share a
 // SIMD, costs more than a hand-over between wavefronts every 12 frames instead of every 16.
 template <int PPT, int NQ, int BLK>
@@ -167,8 +167,9 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
         return;
     }
     // pair i (in this direction's order) = states q = 2i (blank), 2i+1 (label i, absent for i = L)
-    const int gi = wave * OWN_LANES + lane - HALO_LANES;  // this lane's group of PPT pairs; < 0: left of the sequence
-    const bool owner = lane >= HALO_LANES;               // not a mirror of the wavefront on the left
+    // this lane's group of PPT pairs: wavefront 0 has nobody on its left and owns all 64 of its lanes' groups
+    const int gi = wave == 0 ? lane : 64 + (wave - 1) * OWN_LANES + lane - HALO_LANES;
+    const bool owner = wave == 0 || lane >= HALO_LANES;  // not a mirror of the wavefront on the left
     int cls[PPT];        // class of the label state
     bool skip[PPT];      // label state may be entered from the label of the pair to the left
     unsigned slot[PPT];  // byte offset of the pair in a lattice row (the spare pair for lanes that own no real pair)
@@ -515,10 +516,10 @@ size_t grad_lds_bytes(int Lmax, int C)
 }
 
 // Which ctc_lattice<PPT, NQ, BLK> variant a problem takes, and its launch shape.
-// One lane per PPT (blank, label) pairs of the extended target, 64 - BLK of them per wavefront.  The step is
-// bound by instruction issue, so a wavefront wants a SIMD of its own: the smallest PPT that fits four
-// wavefronts, with blocks of 16 frames if that fits and of 12 (52 owned lanes) otherwise; targets beyond
-// 4 * 52 * 4 pairs take four pairs per lane on as many wavefronts as they need.
+// One lane per PPT (blank, label) pairs of the extended target: 64 lanes of the first wavefront, 64 - BLK of
+// every further one.  The step is bound by instruction issue, so a wavefront wants a SIMD of its own: the
+// smallest PPT that fits four wavefronts, with blocks of 16 frames if that fits (208 lanes) and of 12 (220
+// lanes) otherwise; targets beyond 220 * 4 pairs take four pairs per lane on as many wavefronts as they need.
 // NQ > 0 (score table in LDS): a block's class rows must fit 8 elements per thread and, in two buffers, 64 KB.
 struct CtcLaunch { int ppt, blk, nt, nq; size_t lds; };
 CtcLaunch ctc_launch_config(int C, int Lmax)
@@ -526,11 +527,11 @@ CtcLaunch ctc_launch_config(int C, int Lmax)
     const int pairs = Lmax + 1;
     int ppt = 4, blk = 16;
     for (int p = 1; p <= 4; p *= 2) {
-        if (pairs <= 4 * 48 * p) { ppt = p; blk = 16; break; }
-        if (pairs <= 4 * 52 * p) { ppt = p; blk = 12; break; }
+        if (pairs <= (64 + 3 * 48) * p) { ppt = p; blk = 16; break; }
+        if (pairs <= (64 + 3 * 52) * p) { ppt = p; blk = 12; break; }
     }
-    const int own = 64 - blk;
-    const int nt = 64 * (((pairs + ppt - 1) / ppt + own - 1) / own);
+    const int own = 64 - blk, groups = (pairs + ppt - 1) / ppt;
+    const int nt = 64 * (groups <= 64 ? 1 : 1 + (groups - 64 + own - 1) / own);
     const long long nel = (long long)blk * C;
     const size_t table_bytes = (size_t)2 * C * (blk + 1) * 8;
     const int nq = (nel <= 8LL * nt && table_bytes <= 64 * 1024) ? (nel <= 2LL * nt ? 2 : (nel <= 4LL * nt ? 4 : 8)) : 0;

@@ -3,10 +3,10 @@ w2l_asg_fwd_bwd launch every variant of their lattice kernels; which variant a s
 of the library's own host-side query (w2l_ctc_launch_config / w2l_asg_launch_config), the function
 the entry points dispatch through."""
 
-# CTC: (pairs per lane, frames per block) follows Lmax + 1 pairs: <= 192 -> (1,16), <= 208 -> (1,12),
-# <= 384 -> (2,16), <= 416 -> (2,12), <= 768 -> (4,16), <= 832 -> (4,12), more -> (4,16) on more wavefronts;
+# CTC: (pairs per lane, frames per block) follows Lmax + 1 pairs: <= 208 -> (1,16), <= 220 -> (1,12),
+# <= 416 -> (2,16), <= 440 -> (2,12), <= 832 -> (4,16), <= 880 -> (4,12), more -> (4,16) on more wavefronts;
 # the score-table values per thread follow frames per block * C against the workgroup size.
-CTC_LMAX = [150, 205, 380, 412, 760, 828, 1100]
+CTC_LMAX = [200, 215, 400, 436, 800, 870, 1100]
 CTC_CLASSES = [29, 50, 100, 200]
 CTC_CASES = [(c, l) for l in CTC_LMAX for c in CTC_CLASSES] + [(29, 60), (600, 20)]
 
