@@ -167,7 +167,10 @@ int conv_dgrad_prepared(const DgradPrep& prep, const void* dy, int dydt, const v
     if (!prep.ok) return W2L_ERR_SHAPE;
     const ConvDesc& f = prep.d;
     unsigned char* base = static_cast<unsigned char*>(ws);
-    int rc = prep_dgrad_dy(dy, dydt, base, f.B, f.Tp, prep.Cout, f.Cout, f.y_pitch, f.y_halo, ABI_SLACK_ZERO, st);
+    // the staging launch also zeroes the split reduction's tickets (the head of its scratch)
+    int* const tickets = prep.split_bytes ? reinterpret_cast<int*>(base + prep.dy_bytes + prep.w_bytes) : nullptr;
+    int rc = prep_dgrad_dy(dy, dydt, base, f.B, f.Tp, prep.Cout, f.Cout, f.y_pitch, f.y_halo, ABI_SLACK_ZERO, st, tickets,
+                           tickets ? (int)(DGRAD_TICKET_BYTES / 4) : 0);
     if (rc) return rc;
     const void* wp = w;
     if (prep.copy_w) {
@@ -175,8 +178,7 @@ int conv_dgrad_prepared(const DgradPrep& prep, const void* dy, int dydt, const v
         if (rc) return rc;
         wp = base + prep.dy_bytes;
     }
-    return conv_dgrad_mfma(f, base, wp, dx, prep.split_bytes ? base + prep.dy_bytes + prep.w_bytes : nullptr,
-                           prep.split_bytes, st);
+    return conv_dgrad_mfma(f, base, wp, dx, tickets, prep.split_bytes, st, tickets != nullptr);
 }
 }  // namespace w2l
 

@@ -127,8 +127,11 @@ int dbias_reduce(const void* dy, float* dbias, long long rows, int Cout, int dyd
 bool conv_fwd_mfma_ok(const ConvDesc& d);
 int conv_fwd_mfma(const ConvDesc& d, const void* x, const void* w, const float* bias, void* y, int ydt, hipStream_t st);
 bool conv_dgrad_mfma_ok(const ConvDesc& d);
+// tickets_zeroed: the first DGRAD_TICKET_BYTES of scratch are already zero on the stream (the caller's staging
+// launch cleared them), so the launch that would clear them is left out
 int conv_dgrad_mfma(const ConvDesc& d, const void* dy, const void* w, void* dx, void* scratch, size_t scratch_bytes,
-                    hipStream_t st);
+                    hipStream_t st, bool tickets_zeroed = false);
+constexpr size_t DGRAD_TICKET_BYTES = 1024;
 // forward pass fused with the layer's GLU: writes y (dense, pre-GLU, bf16) and h = GLU(y) into a
 // haloed tensor with the time layout of x (halo frames and the zeroed slack written as zeros)
 bool conv_fwd_glu_ok(const ConvDesc& d);
@@ -162,14 +165,16 @@ int glu_bwd_layout(const void* y, const void* dh, void* dy, int B, int Tp, int C
                    int slack, hipStream_t st);
 
 // dense bf16 [B*Tp, C] (C % 8 == 0) -> layout with the given pitch / halo / slack, zeros outside the real frames
-int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch, int halo, int slack, hipStream_t st);
+// (and `nclear` integers at `clear` set to zero on the way)
+int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch, int halo, int slack, hipStream_t st,
+                    int* clear = nullptr, int nclear = 0);
 // any dtype, any channel count
 int pad_layout(const void* src, void* dst, int B, int Tp, int C, int dtype, int pitch, int halo, int slack, hipStream_t st);
 // data-gradient operand preparation (elementwise.hip): dy (fp32 or bf16, dense [B*Tp, C]) -> bf16 in the haloed layout
 // with the channels padded by zeros to Cp; w[Cout][k][Cin] -> [Cp][kf][s*Cin] with the stride folded into the
 // channels (w'[co][jj][ph*Cin+ci] = w[co][s*jj+ph][ci]) and zeros for taps and rows that do not exist
 int prep_dgrad_dy(const void* src, int src_dtype, void* dst, int B, int Tp, int C, int Cp, int pitch, int halo, int slack,
-                  hipStream_t st);
+                  hipStream_t st, int* clear = nullptr, int nclear = 0);
 int prep_dgrad_w(const void* w, void* dst, int Cout, int k, int Cin, int Cp, int kf, int s, hipStream_t st);
 // A data gradient brought into the form the MFMA kernels take (api.hip).  ok: the shape can be prepared; d: the
 // geometry of the prepared problem (stride 1, Cout a multiple of 64, dy haloed); copy_w: the weights need the

@@ -1467,7 +1467,6 @@ bool conv_dgrad_mfma_ok(const ConvDesc& d)
 // writes the tile.  Taken when one workgroup per tile would leave more than a third of the CUs idle
 // and two per tile fit the chip in one round.
 // Scratch: DGRAD_TICKET_BYTES of tickets (one int per tile), then two fp32 slots of 192 x 192 per tile.
-constexpr size_t DGRAD_TICKET_BYTES = 1024;
 bool dgrad_split_ok(const ConvDesc& g)
 {
     if (!conv_dgrad_mfma_ok(g) || !halo_ok_y(g) || g.Cin % 8 != 0 || (g.Cout / 64) % 2 != 0 || g.Cout < 256) return false;
@@ -1495,7 +1494,7 @@ static dim3 dgrad_split_grid(ConvDesc& g, long long tiles_m, long long tiles_n)
 }
 
 int conv_dgrad_mfma(const ConvDesc& g0, const void* dy, const void* w, void* dx, void* scratch, size_t scratch_bytes,
-                    hipStream_t st)
+                    hipStream_t st, bool tickets_zeroed)
 {
     ConvDesc g = g0;
     const long long M = (long long)g.B * g.T, N = g.Cin;
@@ -1508,9 +1507,11 @@ int conv_dgrad_mfma(const ConvDesc& g0, const void* dy, const void* w, void* dx,
         const int tiles = (int)(((F + 191) / 192) * ((N + 191) / 192));
         int* tickets = static_cast<int*>(scratch);
         float* part = reinterpret_cast<float*>(static_cast<unsigned char*>(scratch) + DGRAD_TICKET_BYTES);
-        hipLaunchKernelGGL(zero_rows_k, dim3(1), dim3(256), 0, st, (bf16_t*)nullptr, 0LL, 0LL, 0LL, 0LL, 8, tickets, tiles);
-        rc = launch_status();
-        if (rc) return rc;
+        if (!tickets_zeroed) {
+            hipLaunchKernelGGL(zero_rows_k, dim3(1), dim3(256), 0, st, (bf16_t*)nullptr, 0LL, 0LL, 0LL, 0LL, 8, tickets, tiles);
+            rc = launch_status();
+            if (rc) return rc;
+        }
         rc = set_lds(conv_dgrad_slab_k<192, 192, 256, 2, false>, bytes);
         if (rc) return rc;
         const dim3 grid = dgrad_split_grid(g, (F + 191) / 192, (N + 191) / 192);

@@ -144,8 +144,11 @@ __global__ __launch_bounds__(256) void glu_bwd_k(const T* __restrict__ y, const 
 
 // dense [B*Tp, C] -> haloed layout (zeros in halo and slack frames); C % 8 == 0, bf16
 __global__ __launch_bounds__(256) void pad_layout_k(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
-                                                    long long out_rows, int C, RowMap map)
+                                                    long long out_rows, int C, RowMap map, int* __restrict__ clear,
+                                                    int nclear)
 {
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < nclear; i += blockDim.x) clear[i] = 0;
     const int cv = C / 8;
     const long long total = out_rows * cv;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
@@ -200,8 +203,10 @@ __global__ __launch_bounds__(256) void pad_layout_any_k(const T* __restrict__ sr
 // is not a multiple of 64, a strided layer): dy -> bf16, haloed, channels padded with zeros to Cp.
 template <typename T>
 __global__ __launch_bounds__(256) void prep_dy_k(const T* __restrict__ src, bf16_t* __restrict__ dst, long long out_rows,
-                                                 int C, int Cp, RowMap map)
+                                                 int C, int Cp, RowMap map, int* __restrict__ clear, int nclear)
 {
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < nclear; i += blockDim.x) clear[i] = 0;
     // one thread writes 8 channels (16 bytes); Cp is a multiple of 64
     const int cv = Cp / 8;
     const long long total = out_rows * cv;
@@ -363,12 +368,13 @@ int glu_bwd_layout(const void* y, const void* dh, void* dy, int B, int Tp, int C
 }  // namespace w2l
 
 namespace w2l {
-int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch, int halo, int slack, hipStream_t st)
+int pad_layout_bf16(const void* src, void* dst, int B, int Tp, int C, int pitch, int halo, int slack, hipStream_t st,
+                    int* clear, int nclear)
 {
     const long long out_rows = (long long)B * pitch + slack;
     const RowMap map{Tp, pitch, halo, (long long)B * pitch};
     hipLaunchKernelGGL(pad_layout_k, dim3(grid_for(out_rows * (C / 8))), dim3(256), 0, st, (const bf16_t*)src,
-                       (bf16_t*)dst, out_rows, C, map);
+                       (bf16_t*)dst, out_rows, C, map, clear, nclear);
     return launch_status();
 }
 
@@ -386,16 +392,16 @@ int pad_layout(const void* src, void* dst, int B, int Tp, int C, int dtype, int 
 }
 
 int prep_dgrad_dy(const void* src, int src_dtype, void* dst, int B, int Tp, int C, int Cp, int pitch, int halo, int slack,
-                  hipStream_t st)
+                  hipStream_t st, int* clear, int nclear)
 {
     const long long out_rows = (long long)B * pitch + slack;
     const RowMap map{Tp, pitch, halo, (long long)B * pitch};
-    if (src_dtype == W2L_BF16 && C == Cp) return pad_layout_bf16(src, dst, B, Tp, C, pitch, halo, slack, st);
+    if (src_dtype == W2L_BF16 && C == Cp) return pad_layout_bf16(src, dst, B, Tp, C, pitch, halo, slack, st, clear, nclear);
     const dim3 g(grid_for(out_rows * (Cp / 8))), b(256);
     if (src_dtype == W2L_BF16)
-        hipLaunchKernelGGL(prep_dy_k<bf16_t>, g, b, 0, st, (const bf16_t*)src, (bf16_t*)dst, out_rows, C, Cp, map);
+        hipLaunchKernelGGL(prep_dy_k<bf16_t>, g, b, 0, st, (const bf16_t*)src, (bf16_t*)dst, out_rows, C, Cp, map, clear, nclear);
     else
-        hipLaunchKernelGGL(prep_dy_k<float>, g, b, 0, st, (const float*)src, (bf16_t*)dst, out_rows, C, Cp, map);
+        hipLaunchKernelGGL(prep_dy_k<float>, g, b, 0, st, (const float*)src, (bf16_t*)dst, out_rows, C, Cp, map, clear, nclear);
     return launch_status();
 }
 
