@@ -20,8 +20,9 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_MFMA = 2.5e15   # dense bf16 MFMA, FLOP/s (MI355X published)
 PEAK_HBM = 8.0e12         # B/s
 # one step of the criterion recursions on one wavefront with nothing else (no memory traffic, no hand-over):
-# CTC 29 instructions at the 4-cycle issue cadence, ASG's fully connected lattice about 175 cycles, at 2.4 GHz
-CTC_BARE_STEP_NS = 46.0
+# CTC 24 instructions (21 vector, the row store, the LDS read, the row-offset add) at the 4-cycle issue cadence,
+# ASG's fully connected lattice about 175 cycles, at 2.4 GHz
+CTC_BARE_STEP_NS = 40.0
 ASG_BARE_STEP_NS = 73.0
 
 # HBM bytes per launch of the dominant kernel, from two `rocprofv3 --pmc` runs

@@ -51,8 +51,9 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int LAT_PAD = 16;  // spare lattice rows at either end of an utterance = the longest block of frames
 
 // A state's exponent is kept with a bias, so that 0 can stand for "zero state" (the value a lane
-// shift fills in at the edge) and compares below every real exponent.  Real exponents stay within
-// +-MAX_FRAMES * 65536 = +-2^29 of the bias; the exponent of a zero-valued state stays below 2^29.
+// shift fills in at the edge) and compares below every real exponent.  True exponents stay within
+// +-MAX_FRAMES * 65536 = +-2^29 of zero, and the bias (which falls by EXP_DRIFT per frame, see below) within
+// (2^29, 2^30]: a real state's biased exponent is positive and fits 31 bits.
 constexpr int EXP_BIAS = 1 << 30;
 constexpr int MAX_FRAMES = 8192;
 constexpr float MIN_LOG2 = -65535.f;               // scores are clamped to 2^+-65535; below: probability zero
