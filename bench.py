@@ -30,7 +30,7 @@ ASG_BARE_STEP_NS = 73.0
 # device copy of known size).  The runs and the factor are recorded in
 # profiles/conv_kernels_config4_body_hbm_traffic.txt.
 # (The staging copy each entry point runs first moves another 19 to 57 MB; it is a separate kernel.)
-DOMINANT_KERNEL_HBM_BYTES = {"conv1d_bwd_data": 156499271, "conv1d_fwd": 109134230, "conv1d_bwd_weight": 202501506}
+DOMINANT_KERNEL_HBM_BYTES = {"conv1d_bwd_data": 156457160, "conv1d_fwd": 109046066, "conv1d_bwd_weight": 202503374}
 
 
 def event_time_ms(fn, iters, warmup=None):
