@@ -26,7 +26,6 @@
 namespace w2l {
 namespace {
 
-constexpr double LOG2E = 1.4426950408889634074;
 constexpr double LN2 = 0.69314718055994530942;
 
 struct CtcDims {
@@ -65,6 +64,22 @@ constexpr float MIN_LOG2 = -65535.f;               // scores are clamped to 2^+-
 constexpr int EXP_DRIFT = 65536;
 constexpr unsigned Q_ZERO = 0xffffffffu;
 __device__ __forceinline__ int sub_sat(int e, unsigned q) { return (int)__builtin_elementwise_sub_sat((unsigned)e, q); }
+
+// exp(s) = 2^(s log2 e) = 2^fl * 2^frac: fl an integer in [-65535, 65535] (the product is clamped there), frac in
+// [0, 1] up to an ulp.  The rounding error of the product -- 0.004 for a score of -45000 -- and the tail of log2 e
+// are recovered with an fma, so frac is good to fp32 whatever the size of the score.  Returns false for a score
+// below 2^MIN_LOG2 (-inf included): probability zero.
+constexpr float LOG2E_HI = 1.44269502162933349609375f;   // log2 e rounded to fp32
+constexpr float LOG2E_LO = 1.92596299112661746e-8f;      // what the rounding dropped
+__device__ __forceinline__ bool score_split(float s, float& fl, float& frac)
+{
+    const float xh = s * LOG2E_HI;
+    const float xl = __builtin_fmaf(s, LOG2E_HI, -xh) + s * LOG2E_LO;
+    const float x = fminf(fmaxf(xh, MIN_LOG2), -MIN_LOG2);
+    fl = floorf(x);
+    frac = (x - fl) + xl;
+    return xh >= MIN_LOG2;
+}
 
 // v * 2^e for a (v, e) pair as a double-precision base-2 log; -inf for a zero state
 __device__ __forceinline__ double pair_log2(float v, int e) { return v > 0.f ? (double)fast_log2(v) + (double)e : -INFINITY; }
@@ -194,7 +209,6 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     const float* lpb = lp + (size_t)b * d.Tp * d.C;
     float2* lat = (dir ? beta : alpha) + ((size_t)b * d.rows + LAT_PAD) * d.Sp;  // row of frame 0
     auto frame = [&](int step) { return dir ? T - 1 - step : step; };
-    const float log2e = (float)LOG2E;
 
     const int nwaves = NT >> 6;
     const int tblocks = (T + BLK - 1) / BLK;
@@ -208,12 +222,10 @@ __global__ __launch_bounds__(1024) void ctc_lattice(const float* __restrict__ lp
     int rptr = (LAT_PAD + frame(0)) * row_bytes;
     // exp(lp) = 2^(lp log2 e) = pm * 2^pe with pm in [1, 2); a score below 2^MIN_LOG2 (-inf included) is probability zero
     auto split = [&](float s, float& pm, unsigned& pq) {
-        const float xr = s * log2e;
-        const float x = fminf(fmaxf(xr, MIN_LOG2), -MIN_LOG2);
-        const float fl = floorf(x);
-        const bool pos = xr >= MIN_LOG2;
+        float fl, frac;
+        const bool pos = score_split(s, fl, frac);
         pq = pos ? (unsigned)(EXP_DRIFT - (int)fl) : Q_ZERO;
-        pm = pos ? fast_exp2(x - fl) : 0.f;
+        pm = pos ? fast_exp2(frac) : 0.f;
     };
     // one frame of the recursion for this lane's pairs, given the split scores.  A sum of states brings
     // them to their largest exponent (exact) and adds; a zero state (v = 0, exponent 0, far below any
@@ -479,11 +491,12 @@ __global__ __launch_bounds__(256) void ctc_grad(const float* __restrict__ lp, co
                 // alpha and beta both carry the frame's own score: one of them is taken off again, split exactly
                 // as the lattice kernel split it (integer part off the integer exponents, so nothing large cancels in fp32)
                 if (a[u].x > 0.f && bt[u].x > 0.f) {
-                    const float x = fminf(fmaxf(sc[u] * (float)LOG2E, MIN_LOG2), -MIN_LOG2), fl = floorf(x);
+                    float fl, frac;
+                    score_split(sc[u], fl, frac);
                     // both exponents carry the bias: taken off in wrap-around arithmetic
                     const int ex = (int)((unsigned)__float_as_int(a[u].y) + (unsigned)__float_as_int(bt[u].y) - 2u * (unsigned)EXP_BIAS +
                                         (unsigned)(T + 1) * (unsigned)EXP_DRIFT);
-                    e = fast_exp2((fast_log2(a[u].x * bt[u].x) + (float)(ex - iref - (int)fl)) + (shift - (x - fl)));
+                    e = fast_exp2((fast_log2(a[u].x * bt[u].x) + (float)(ex - iref - (int)fl)) + (shift - frac));
                 }
                 if (s < S) {
                     ebuf[s] = e;

@@ -291,6 +291,24 @@ def test_ctc_peaked_and_impossible_scores(P):
     _check_ctc(loss, grad, loss_o, g_o)
 
 
+def test_ctc_longest_utterance_and_lowest_scores(P):
+    # 8192 frames (the size limit); utterance 0 has log-probabilities around -45000 per frame (2^-65000, just
+    # above the level that counts as probability zero), so the integer exponents of its states run through
+    # the whole range they are given; utterance 1 has ordinary scores over the same length
+    rng = np.random.default_rng(23)
+    B, Tp, Cc, Lmax = 2, 8192, 6, 30
+    lp = np.empty((B, Tp, Cc), np.float32)
+    lp[0] = (-45000.0 + 3.0 * rng.standard_normal((Tp, Cc))).astype(np.float32)
+    lp[1] = oracle.logsoftmax_fwd(rng.standard_normal((1, Tp, Cc)) * 1.5)[0].astype(np.float32)
+    tg = rng.integers(1, Cc, size=(B, Lmax)).astype(np.int32)
+    in_len = np.array([8192, 8192], np.int32)
+    tgt_len = np.array([30, 7], np.int32)
+    loss, grad = _run_ctc(P, lp, 0, tg, in_len, tgt_len, 0, 1.0)
+    loss_o, g_o = oracle.ctc(lp.astype(np.float64), tg, in_len, tgt_len, 0)
+    assert np.isfinite(loss_o).all() and loss_o[0] > 3.6e8
+    _check_ctc(loss, grad, loss_o, g_o)
+
+
 def test_ctc_bad_label_gives_nan_loss_and_zero_grad(P):
     cfg = W.config2(seed=5, B=3, T=40, in_lo=30, in_hi=40, l_lo=3, l_hi=6)
     tg = cfg["targets"].copy()
