@@ -193,9 +193,13 @@ template <typename TX, typename TDY>
 __global__ __launch_bounds__(256) void wgrad_skinny_stage1(const TX* __restrict__ x, const TDY* __restrict__ dy,
                                                            float* __restrict__ part, ConvDesc d)
 {
+    // 64 columns per workgroup; its four wavefronts take every fourth row of the chunk, so four times as many
+    // row loads are in flight per column (the kernel lives on memory latency), and add up through LDS at the end
     __shared__ float dyt[SKINNY_ROWS][32];
+    __shared__ float red[3][32][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int N = d.k * d.Cin, R = d.B * d.Tp;
-    const int n = blockIdx.x * 256 + threadIdx.x;
+    const int n = blockIdx.x * 64 + lane;
     const int per = (R + gridDim.y - 1) / gridDim.y;
     const int r_begin = per * blockIdx.y, r_end = (r_begin + per < R) ? r_begin + per : R;
     const int j = (n < N) ? n / d.Cin : 0, ci = (n < N) ? n - j * d.Cin : 0;
@@ -214,30 +218,34 @@ __global__ __launch_bounds__(256) void wgrad_skinny_stage1(const TX* __restrict_
         }
         __syncthreads();
         if (n < N) {
-            // eight rows at a time: their x values are loaded together (independent loads, one latency), a row
-            // outside the utterance or past the chunk contributes 0 (its dy row in LDS is 0 as well past the chunk)
-            for (int rr0 = 0; rr0 < SKINNY_ROWS; rr0 += 8) {
-                if (r0 + rr0 >= r_end) break;
-                float xv[8];
+            // this wavefront's eight rows of the pass: their x values are loaded together (independent loads, one
+            // latency); a row outside the utterance or past the chunk contributes 0 (its dy row in LDS is 0 as well)
+            float xv[SKINNY_ROWS / 4];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int r = min(r0 + rr0 + u, r_end - 1);
-                    const int b = r / d.Tp, tp = r - b * d.Tp;
-                    const int t = d.s * tp + j - d.p;
-                    const bool ok = t >= 0 && t < d.T && r0 + rr0 + u < r_end;
-                    const float v = Elem<TX>::load(x, ((size_t)b * d.x_pitch + d.x_halo + (ok ? t : 0)) * d.Cin + ci);
-                    xv[u] = ok ? v : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-#pragma unroll
-                    for (int c = 0; c < 32; ++c) acc[c] = fmaf(dyt[rr0 + u][c], xv[u], acc[c]);
+            for (int u = 0; u < SKINNY_ROWS / 4; ++u) {
+                const int rq = r0 + wave + 4 * u;
+                const int r = min(rq, r_end - 1);
+                const int b = r / d.Tp, tp = r - b * d.Tp;
+                const int t = d.s * tp + j - d.p;
+                const bool ok = t >= 0 && t < d.T && rq < r_end;
+                const float v = Elem<TX>::load(x, ((size_t)b * d.x_pitch + d.x_halo + (ok ? t : 0)) * d.Cin + ci);
+                xv[u] = ok ? v : 0.f;
             }
+#pragma unroll
+            for (int u = 0; u < SKINNY_ROWS / 4; ++u)
+#pragma unroll
+                for (int c = 0; c < 32; ++c) acc[c] = fmaf(dyt[wave + 4 * u][c], xv[u], acc[c]);
         }
         __syncthreads();
     }
-    if (n < N)
-        for (int c = 0; c < d.Cout; ++c) part[((size_t)blockIdx.y * d.Cout + c) * N + n] = acc[c];
+    if (wave > 0) {
+#pragma unroll
+        for (int c = 0; c < 32; ++c) red[wave - 1][c][lane] = acc[c];
+    }
+    __syncthreads();
+    if (wave == 0 && n < N)
+        for (int c = 0; c < d.Cout; ++c)
+            part[((size_t)blockIdx.y * d.Cout + c) * N + n] = ((acc[c] + red[0][c][lane]) + red[1][c][lane]) + red[2][c][lane];
 }
 __global__ __launch_bounds__(256) void wgrad_skinny_stage2(const float* __restrict__ part, float* __restrict__ dw,
                                                            int chunks, long long total, int accumulate)
@@ -357,7 +365,7 @@ int conv_wgrad_skinny(const ConvDesc& d, const void* x, const void* dy, float* d
                       float* scratch, hipStream_t st)
 {
     const long long N = (long long)d.k * d.Cin;
-    const dim3 g1((unsigned)((N + 255) / 256), SKINNY_CHUNKS);
+    const dim3 g1((unsigned)((N + 63) / 64), SKINNY_CHUNKS);
     if (dt == W2L_F32 && dydt == W2L_F32)
         hipLaunchKernelGGL((wgrad_skinny_stage1<float, float>), g1, dim3(256), 0, st, (const float*)x, (const float*)dy, scratch, d);
     else if (dt == W2L_BF16 && dydt == W2L_BF16)
