@@ -155,12 +155,14 @@ def test_logsoftmax(P, rows, Cc):
     lpb = P.w2l_logsoftmax_fwd(to_dev(zb, "bf16"), empty((rows, Cc)))
     assert np.linalg.norm(to_host(lpb) - oracle.logsoftmax_fwd(zb)) <= 1e-5 * max(np.linalg.norm(lp_o), 1.0)
 
-@pytest.mark.parametrize("n,steps,wd", [(1 << 20, 3, 0.0), (4099, 5, 1e-3), (3, 2, 0.0), (26_000_001, 1, 0.0)])
+@pytest.mark.parametrize("n,steps,wd", [(1 << 20, 3, 0.0), (4099, 5, 1e-3), (3, 2, 0.0), (26_000_001, 1, 0.0),
+                                        (6545, 2, 0.0), (2051, 1, 1e-2)])
 def test_sgd_momentum(P, n, steps, wd):
     """fp32 update vs the fp64 oracle (tolerance: a few fp32 roundings per step, 1e-6 relative to
     the tensor norm); the bf16 copy must be the round-to-nearest-even of the kernel's own fp32
     weights, bit for bit.  Sizes: several blocks, a ragged tail (n % 4 != 0), fewer values than
-    one vector, and one weight tensor of the 105M model (k=11, 768 -> 1536 plus one) at full size."""
+    one vector, one weight tensor of the 105M model (k=11, 768 -> 1536 plus one) at full size, and two sizes at
+    which only part of the last workgroup's threads have a second group of four values."""
     rng = np.random.default_rng(n)
     w0 = rng.standard_normal(n).astype(np.float32)
     v0 = (rng.standard_normal(n) * 0.1).astype(np.float32)
