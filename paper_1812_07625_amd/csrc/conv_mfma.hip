@@ -424,7 +424,9 @@ struct Core {
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const f32x4_t v = {acc[i][j][4 * r4], acc[i][j][4 * r4 + 1], acc[i][j][4 * r4 + 2], acc[i][j][4 * r4 + 3]};
                     f32x4_t* const dst = mine + (size_t)((i * TN + j) * 4 + r4) * 64;
-                    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v) : "memory");
+                    // (the wait states: a store of more than 8 bytes reads its data registers a little after issue,
+                    // and nothing tells the compiler's hazard check that this one does)
+                    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(dst), "v"(v) : "memory");
                 }
             }
         keep_apart<G>();
