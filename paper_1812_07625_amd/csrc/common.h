@@ -28,7 +28,8 @@ __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(
 // compiler selects for this cast and pairs up for neighbouring values): one instruction instead of six.
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
 
-__device__ __forceinline__ float sigmoidf_(float u) { return 1.f / (1.f + __expf(-u)); }
+// the hardware reciprocal (1 ulp) instead of an IEEE division: a quarter of the GLU kernels' instructions
+__device__ __forceinline__ float sigmoidf_(float u) { return __builtin_amdgcn_rcpf(1.f + __expf(-u)); }
 
 // Time layout of the activations the library keeps itself (train step workspace, staged
 // operands of the convolution entry points): LAYOUT_HALO zero frames on both sides of every
