@@ -53,12 +53,13 @@ def event_time_ms(fn, iters, warmup=None):
 SHORT_TIMING = {"method": "hip graph replay"}
 
 
-def graph_time_ms(calls, iters):
+def graph_time_ms(calls, iters, out=None):
     """Average milliseconds per call of launches that run for a few microseconds.  A call through the Python binding
     costs the host about 8 us, more than these kernels run, so a loop of calls measures the caller; here the calls
     (`calls`: a list of them, at least 16 go into one graph) are captured into a HIP graph on a side stream and the
-    graph is replayed, which leaves the spacing of the launches to the device.  Should capture fail, the loop of
-    calls is timed instead and SHORT_TIMING says so."""
+    graph is replayed, which leaves the spacing of the launches to the device.  `out`, if given, is a tensor the
+    calls write: what the replays leave in it must equal what the eager calls left.  Should capture fail, the loop
+    of calls is timed instead and SHORT_TIMING says so."""
     import torch
     seq = list(calls) * max(1, -(-16 // len(calls)))
     try:
@@ -68,6 +69,9 @@ def graph_time_ms(calls, iters):
             for c in seq:
                 c()
             torch.cuda.synchronize()
+            eager = out.clone() if out is not None else None
+            if out is not None:
+                out.zero_()
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
                 for c in seq:
@@ -83,7 +87,11 @@ def graph_time_ms(calls, iters):
             b.record()
             torch.cuda.synchronize()
         torch.cuda.current_stream().wait_stream(side)
+        if out is not None and not torch.equal(out, eager):
+            raise RuntimeError("bench.py: graph replays of a kernel left other values than its eager launches")
         return a.elapsed_time(b) / (reps * len(seq))
+    except RuntimeError:
+        raise
     except Exception as e:  # measured anyway, by the slower method, and reported as such
         SHORT_TIMING["method"] = "loop of calls (graph capture failed: %s)" % type(e).__name__
         torch.cuda.synchronize()
@@ -199,11 +207,11 @@ def main():
     # bandwidth-bound kernels at the same layer's shape
     rows = B * Tp
     hh = empty((rows, L["cout"] // 2), "bf16")
-    t_glu = graph_time_ms([lambda: P.w2l_glu_fwd(hy, hh)], args.kernel_iters)
+    t_glu = graph_time_ms([lambda: P.w2l_glu_fwd(hy, hh)], args.kernel_iters, out=hh)
     glu_bytes = rows * L["cout"] * 2 + rows * (L["cout"] // 2) * 2
     hdh = to_dev(W.round_to_bf16(rng.standard_normal((rows, L["cout"] // 2)).astype(np.float32)), "bf16")
     hdy2 = empty((rows, L["cout"]), "bf16")
-    t_glub = graph_time_ms([lambda: P.w2l_glu_bwd(hy, hdh, hdy2)], args.kernel_iters)
+    t_glub = graph_time_ms([lambda: P.w2l_glu_bwd(hy, hdh, hdy2)], args.kernel_iters, out=hdy2)
     glub_bytes = rows * L["cout"] * 2 * 2 + rows * (L["cout"] // 2) * 2
     # what a plain device copy moving the same number of bytes achieves (half read, half written): at a few tens of
     # megabytes a launch is a handful of microseconds and its ramp-up and tail are a visible part of it
@@ -262,8 +270,8 @@ def main():
     # per-frame log-softmax forward and backward at the criterion benchmark shape (24000 rows of 29 classes, fp32)
     lz = to_dev((rng.standard_normal((32 * 750, 29)) * 1.4).astype(np.float32))
     llp, ldz = empty((32 * 750, 29)), empty((32 * 750, 29))
-    t_lsf = graph_time_ms([lambda: P.w2l_logsoftmax_fwd(lz, llp)], args.kernel_iters)
-    t_lsb = graph_time_ms([lambda: P.w2l_logsoftmax_bwd(llp, lz, ldz)], args.kernel_iters)
+    t_lsf = graph_time_ms([lambda: P.w2l_logsoftmax_fwd(lz, llp)], args.kernel_iters, out=llp)
+    t_lsb = graph_time_ms([lambda: P.w2l_logsoftmax_bwd(llp, lz, ldz)], args.kernel_iters, out=ldz)
     ls_bytes_f, ls_bytes_b = 2 * 32 * 750 * 29 * 4, 3 * 32 * 750 * 29 * 4
 
     # CTC alone at the criterion benchmark shape (B=32, T=750, C=29)
